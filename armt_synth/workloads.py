@@ -1,0 +1,160 @@
+"""Shape table and seeded generators for synthetic ARMT workloads."""
+from __future__ import annotations
+
+import dataclasses
+from dataclasses import dataclass
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class ArmtShape:
+    """Sizes of one ARMT workload. Names follow the paper: L layers, segment of
+    seg_len tokens followed by n_mem memory tokens, associative hidden size d_mem,
+    DPFP-nu feature map (Section 2.1)."""
+    name: str
+    n_layers: int
+    d_model: int
+    n_heads: int
+    n_kv_heads: int
+    head_dim: int
+    d_ff: int
+    seg_len: int
+    n_mem: int
+    d_mem: int
+    n_tokens: int
+    dtype: str = "bf16"            # "f32" or "bf16": storage type of weights / embeddings
+    dpfp_nu: int = 3
+    rms_eps: float = 1e-5
+    rope_theta: float = 500000.0
+    assoc_eps: float = 1e-5
+
+    @property
+    def T(self) -> int:            # rows of one (layer, segment) cell
+        return self.seg_len + self.n_mem
+
+    @property
+    def phi(self) -> int:          # feature-map width 2*nu*d_mem
+        return 2 * self.dpfp_nu * self.d_mem
+
+    @property
+    def n_segments(self) -> int:
+        return self.n_tokens // self.seg_len
+
+    def replace(self, **kw) -> "ArmtShape":
+        return dataclasses.replace(self, **kw)
+
+    def flops_per_cell(self, with_read: bool = True) -> float:
+        """Algorithmic FLOPs of one (layer, segment) cell; causal attention counts
+        the lower triangle only."""
+        T, d, F, dm, P, m = self.T, self.d_model, self.d_ff, self.d_mem, self.phi, self.n_mem
+        H, Hkv, dh = self.n_heads, self.n_kv_heads, self.head_dim
+        p_lin = d * (H + 2 * Hkv) * dh + H * dh * d + 3 * d * F
+        fl = 2.0 * T * p_lin + 2.0 * T * (T + 1) * H * dh
+        if with_read:
+            fl += 2.0 * T * d * dm + 2.0 * T * P * d
+        fl += 2.0 * m * d * (dm + d + 1) + 4.0 * m * P * d
+        return fl
+
+    def flops_total(self, carry_in: bool = False) -> float:
+        N, L = self.n_segments, self.n_layers
+        n_read = N if carry_in else N - 1
+        return L * (n_read * self.flops_per_cell(True) + (N - n_read) * self.flops_per_cell(False))
+
+
+_1B = dict(n_layers=16, d_model=2048, n_heads=32, n_kv_heads=8, head_dim=64, d_ff=8192,
+           seg_len=1024, n_mem=16, d_mem=64, dtype="bf16")
+_3B = dict(n_layers=28, d_model=3072, n_heads=24, n_kv_heads=8, head_dim=128, d_ff=8192,
+           seg_len=1024, n_mem=16, d_mem=64, dtype="bf16")
+
+CONFIGS = {
+    # correctness-only fp32 case
+    "tiny": ArmtShape("tiny", n_layers=4, d_model=128, n_heads=4, n_kv_heads=2, head_dim=32,
+                      d_ff=512, seg_len=64, n_mem=8, d_mem=32, n_tokens=512, dtype="f32"),
+    "1b_8k": ArmtShape("1b_8k", n_tokens=8192, **_1B),
+    "1b_32k": ArmtShape("1b_32k", n_tokens=32768, **_1B),
+    "1b_128k": ArmtShape("1b_128k", n_tokens=131072, **_1B),
+    "1b_128k_s512": ArmtShape("1b_128k_s512", n_tokens=131072, **{**_1B, "seg_len": 512}),
+    "1b_128k_s2048": ArmtShape("1b_128k_s2048", n_tokens=131072, **{**_1B, "seg_len": 2048}),
+    "3b_128k": ArmtShape("3b_128k", n_tokens=131072, **_3B),
+}
+
+
+def get_shape(name: str) -> ArmtShape:
+    return CONFIGS[name]
+
+
+# per-layer tensors: field -> (rows, cols) as functions of the shape; row-major [out, in]
+def _layer_dims(s: ArmtShape):
+    d, H, Hkv, dh, F, dm = s.d_model, s.n_heads, s.n_kv_heads, s.head_dim, s.d_ff, s.d_mem
+    return {
+        "rms1": (d,), "wq": (H * dh, d), "wk": (Hkv * dh, d), "wv": (Hkv * dh, d), "wo": (d, H * dh),
+        "rms2": (d,), "wgate": (F, d), "wup": (F, d), "wdown": (d, F),
+        "wm_q": (dm, d), "wm_k": (dm, d), "wm_v": (d, d), "wm_b": (1, d),
+    }
+
+
+LAYER_FIELDS = ("rms1", "wq", "wk", "wv", "wo", "rms2", "wgate", "wup", "wdown",
+                "wm_q", "wm_k", "wm_v", "wm_b")
+
+
+def bf16_bits(a: np.ndarray) -> np.ndarray:
+    """fp32 array -> uint16 bf16 bit patterns, round-to-nearest-even."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    bias = ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
+    return ((u + bias) >> np.uint32(16)).astype(np.uint16)
+
+
+def from_bf16_bits(b: np.ndarray) -> np.ndarray:
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """fp32 array whose values are exactly representable in bf16."""
+    return from_bf16_bits(bf16_bits(a))
+
+
+def _normal(rng: np.random.Generator, shape, std: float, dtype: str) -> np.ndarray:
+    a = rng.standard_normal(shape, dtype=np.float32) * np.float32(std)
+    return round_to_bf16(a) if dtype == "bf16" else a
+
+
+def make_weights(shape: ArmtShape, seed: int = 0, std: float = 0.02, n_layers: int | None = None,
+                 gain_std: float = 0.0):
+    """Per-layer weights ~ N(0, std^2), norm gains = 1, memory-token embeddings
+    ~ N(0, std^2). Returned as fp32 arrays; for dtype "bf16" every value is already
+    rounded to bf16, so the oracle and the HIP path consume identical numbers.
+    Each layer draws from its own stream, so layer l is the same whatever n_layers is.
+    gain_std > 0 draws the norm gains from N(1, gain_std^2) instead (used by tests so
+    that a dropped or misplaced gain cannot go unnoticed)."""
+    L = shape.n_layers if n_layers is None else n_layers
+    layers = []
+    for l in range(L):
+        rng = np.random.default_rng([seed, 1, l])
+        lw = {}
+        for f, dims in _layer_dims(shape).items():
+            if f in ("rms1", "rms2"):
+                lw[f] = np.ones(dims, dtype=np.float32)
+                if gain_std > 0.0:
+                    lw[f] = lw[f] + _normal(rng, dims, gain_std, shape.dtype)
+                    if shape.dtype == "bf16":
+                        lw[f] = round_to_bf16(lw[f])
+            else:
+                lw[f] = _normal(rng, dims, std, shape.dtype)
+        layers.append(lw)
+    rng = np.random.default_rng([seed, 2])
+    mem_emb = _normal(rng, (shape.n_mem, shape.d_model), std, shape.dtype)
+    return layers, mem_emb
+
+
+def make_embeddings(shape: ArmtShape, seed: int = 0, n_tokens: int | None = None) -> np.ndarray:
+    """Token embeddings ~ N(0, 1), [n_tokens, d_model]; drawn segment by segment so
+    that a prefix of the sequence is the same whatever n_tokens is."""
+    n = shape.n_tokens if n_tokens is None else n_tokens
+    assert n % shape.seg_len == 0
+    out = np.empty((n, shape.d_model), dtype=np.float32)
+    for s in range(n // shape.seg_len):
+        rng = np.random.default_rng([seed, 3, s])
+        out[s * shape.seg_len:(s + 1) * shape.seg_len] = _normal(
+            rng, (shape.seg_len, shape.d_model), 1.0, shape.dtype)
+    return out
