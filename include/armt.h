@@ -1,0 +1,170 @@
+/* armt.h -- C ABI of the MI355X (gfx950) ARMT forward library.
+ *
+ * The library computes the forward pass of an Associative Recurrent Memory Transformer
+ * (paper Section 2.1, Eq. 2-6) over one long input, either cell by cell in the order the
+ * model is defined (Section 3.1: for each segment, for each layer) or with Diagonal
+ * Batching (Section 3.2, Algorithm 1, Lemma 3.1): all (layer, segment) cells of one
+ * anti-diagonal run together as one group.  Both produce the same result; only the
+ * order of independent cells differs.
+ *
+ * Conventions, valid for every call unless stated otherwise:
+ *   - every pointer is a DEVICE pointer unless marked [host];
+ *   - the caller owns all memory; the library allocates and frees no device memory and
+ *     keeps no state between calls; scratch space comes in through `workspace`;
+ *   - work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default
+ *     stream) and the call returns without waiting for the GPU, except for one small
+ *     host-to-device copy of pointer tables that is complete when the call returns;
+ *   - errors are return codes; argument errors are detected before anything is launched
+ *     and leave all outputs untouched;
+ *   - matrices are row-major; a weight W is [out_features, in_features] and is applied as
+ *     y = x W^T; there are no biases;
+ *   - the memory state A, z is always fp32, whatever the activation type.
+ */
+#ifndef ARMT_H_
+#define ARMT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ARMT_OK = 0,
+  ARMT_ERR_NULL = 1,        /* a required pointer is NULL */
+  ARMT_ERR_SHAPE = 2,       /* sizes inconsistent (n_tokens not a multiple of seg_len, heads, ...) */
+  ARMT_ERR_DTYPE = 3,       /* dtype is not one of armt_dtype */
+  ARMT_ERR_WORKSPACE = 4,   /* workspace missing, misaligned (256 B) or smaller than armt_workspace_bytes */
+  ARMT_ERR_HIP = 5,         /* a HIP runtime call failed; see armt_last_hip_error */
+  ARMT_ERR_UNSUPPORTED = 6  /* valid ARMT shape this build has no kernel for (see armt_config) */
+} armt_status;
+
+typedef enum { ARMT_F32 = 0, ARMT_BF16 = 1 } armt_dtype;   /* type of weights, embeddings, hidden_out */
+
+/* Model and segmentation sizes.  Notation of the paper: L layers, segments of seg_len tokens
+ * followed by n_mem memory tokens (a cell has T = seg_len + n_mem rows, Eq. 2 "[H, M]"),
+ * associative hidden size d_mem, feature map DPFP-nu of width Phi = 2 * dpfp_nu * d_mem
+ * (Section 2.1: A in R^{d_model x 6 d_mem} for nu = 3).
+ * Supported: n_heads * head_dim == d_model, n_heads % n_kv_heads == 0, head_dim even,
+ * 1 <= dpfp_nu < 2 * d_mem; dtype BF16 additionally needs d_model, d_ff, head_dim, d_mem
+ * multiples of 32, n_mem a multiple of 16 and head_dim in {64, 128} (ARMT_ERR_UNSUPPORTED otherwise). */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ff;
+  int32_t seg_len, n_mem, d_mem, dpfp_nu;
+  int32_t dtype;             /* armt_dtype */
+  float rms_eps;             /* RMSNorm epsilon (LLaMA-3: 1e-5) */
+  float rope_theta;          /* rotary base (LLaMA-3: 500000); positions restart at 0 in every cell */
+  float assoc_eps;           /* added to the denominators z.phi and |phi|^2 of Eq. 4 and 6; 0 = as printed */
+} armt_config;
+
+/* Weights of one layer: the decoder block (TransformerLayer of Eq. 2; LLaMA-3: pre-norm RMSNorm,
+ * grouped-query attention with rotate-half RoPE, SwiGLU) and the associative block (Eq. 3-6).
+ * All of type cfg.dtype.  A [host] array of n_layers of these is the "per-group weight pointers"
+ * of the grouped layer (Section 3.3): the weights are never copied or stacked. */
+typedef struct {
+  const void *rms1;                 /* [d_model]                      gain of the first norm   */
+  const void *wq, *wk, *wv;         /* [H*dh, d] [Hkv*dh, d] [Hkv*dh, d]                        */
+  const void *wo;                   /* [d, H*dh]                                                */
+  const void *rms2;                 /* [d_model]                      gain of the second norm  */
+  const void *wgate, *wup;          /* [d_ff, d] [d_ff, d]                                      */
+  const void *wdown;                /* [d, d_ff]                                                */
+  const void *wm_q, *wm_k;          /* [d_mem, d] [d_mem, d]          W_Q (Eq. 6), W_K (Eq. 3) */
+  const void *wm_v;                 /* [d, d]                         W_V (Eq. 3)              */
+  const void *wm_b;                 /* [1, d]                         W_beta (Eq. 3)           */
+} armt_layer_weights;
+
+/* Bytes of scratch space armt_forward_* needs for this configuration (independent of n_tokens
+ * and of the execution order); 0 if cfg is invalid.  The workspace must be 256-byte aligned.
+ * Its contents need not be initialised and are undefined afterwards. */
+size_t armt_workspace_bytes(const armt_config *cfg /* [host] */);
+
+/* Forward pass, cells visited segment by segment, layer by layer (Section 3.1; Fig. 3a):
+ * n_segments * n_layers dependent cell executions, every kernel launched for one cell.
+ *
+ *   layers      [host] array of cfg->n_layers armt_layer_weights (device pointers inside)
+ *   mem_emb     [n_mem, d_model]  memory-token embeddings appended to every segment at layer 0
+ *   x           [n_tokens, d_model] token embeddings; n_tokens must be a positive multiple of seg_len
+ *   A_in, z_in  [L, d_model, Phi], [L, Phi] fp32 memory state to start from, or both NULL for the
+ *               empty memory A_0 = z_0 = 0 (Eq. 3).  With an empty memory the first segment skips
+ *               the associative read and uses v_bar = 0 (Algorithm 1 applies Associate only from
+ *               the second group on).
+ *   hidden_out  [n_tokens, d_model] of cfg.dtype: output of the last layer at the seg_len token rows
+ *               of every segment (no final norm, no LM head)
+ *   A_out,z_out [L, d_model, Phi], [L, Phi] fp32 memory state after the last segment; may alias
+ *               A_in, z_in (state is updated in place in A_out, z_out).
+ */
+armt_status armt_forward_sequential(const armt_config *cfg, const armt_layer_weights *layers,
+                                    const void *mem_emb, const void *x, int64_t n_tokens,
+                                    const float *A_in, const float *z_in,
+                                    void *hidden_out, float *A_out, float *z_out,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Forward pass with Diagonal Batching (Algorithm 1): step t = 0 .. L + N - 2 runs every cell
+ * (layer l, segment t - l) with max(0, t - N + 1) <= l <= min(L - 1, t) in one group (Lemma 3.1):
+ * grouped GEMMs with one weight set per cell, attention batched over the cells, and the memory
+ * read / update of every live layer.  Same arguments and same result as armt_forward_sequential. */
+armt_status armt_forward_diagonal(const armt_config *cfg, const armt_layer_weights *layers,
+                                  const void *mem_emb, const void *x, int64_t n_tokens,
+                                  const float *A_in, const float *z_in,
+                                  void *hidden_out, float *A_out, float *z_out,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Anti-diagonal schedule (Lemma 3.1), host only: for step t of an L-layer model over N segments,
+ * *l_lo .. *l_hi (inclusive) are the live layers; layer l runs segment t - l.  Returns the group
+ * size, or 0 (and leaves the outputs alone) if t is outside 0 .. L + N - 2 or L, N < 1. */
+int32_t armt_diagonal_group(int32_t n_layers, int32_t n_segments, int32_t t,
+                            int32_t *l_lo /* [host] */, int32_t *l_hi /* [host] */);
+
+/* ---- single steps of the path, as the forward calls run them (for tests and micro-benchmarks).
+ * Each works on a group of g cells, like one step of Algorithm 1 does. ---- */
+
+/* Grouped GEMM (Section 3.3 item 1, Section 4.1): C_i = A_i B_i^T for i < g, every group with its
+ * own operand pointers.  a, b, c are [host] arrays of g device pointers: A_i [M, K], B_i [N, K]
+ * (a weight, [out, in]) of type dtype, C_i [M, N] fp32.  dtype BF16 needs K % 32 == 0. */
+armt_status armt_grouped_gemm(int32_t dtype, int32_t g, int32_t M, int32_t N, int32_t K,
+                              const void *const *a, const void *const *b, float *const *c,
+                              void *hip_stream);
+
+/* Segment attention batched over the group (Section 4.2): causal softmax(q k^T / sqrt(dh)) v over
+ * the T rows of each cell, grouped-query heads, rotary embedding applied to q and k first.
+ * qkv [g, T, (H + 2 Hkv) * dh] of type dtype, rows laid out as [q heads | k heads | v heads];
+ * out [g, T, H * dh] of type dtype.  qkv is modified (rotated in place).
+ * workspace: (H + 2 Hkv) * dh * (T + 64) * g * 2 bytes, 256-byte aligned, for dtype BF16; unused for F32. */
+armt_status armt_segment_attention(int32_t dtype, int32_t g, int32_t T, int32_t n_heads,
+                                   int32_t n_kv_heads, int32_t head_dim, float rope_theta,
+                                   void *qkv, void *out, void *workspace, size_t workspace_bytes,
+                                   void *hip_stream);
+
+/* Associative read of a group (Eq. 6 added to its input): for every cell i and row r,
+ * x[i][r] += A_i phi(Wq_i x[i][r]) / (z_i . phi(Wq_i x[i][r]) + eps).
+ * x [g, T, d] fp32, updated in place; wm_q [host] array of g device pointers to [d_mem, d] of type
+ * dtype; A [g, d, Phi], z [g, Phi] fp32.  workspace: g * T * (8 * d + 8 * Phi + 4 * d_mem + 16) + g * d * Phi * 2 bytes. */
+armt_status armt_assoc_read(int32_t dtype, int32_t g, int32_t T, int32_t d_model, int32_t d_mem,
+                            int32_t dpfp_nu, float eps, float *x, const void *const *wm_q,
+                            const float *A, const float *z, void *workspace, size_t workspace_bytes,
+                            void *hip_stream);
+
+/* Delta-rule memory update of a group (Eq. 3-5): for every cell i, from its m memory-token outputs
+ * ym [g, m, d] fp32: k = Wk ym, v = Wv ym, beta = sigmoid(Wb ym), v_bar = A phi(k) / (z.phi(k) + eps)
+ * (0 where empty[i] != 0), gamma = 1 - z.phi(k) / (|phi(k)|^2 + eps); then
+ * A_i += sum_j beta_j (v_j - v_bar_j) (x) phi(k_j), z_i += sum_j gamma_j phi(k_j), every j using the
+ * state from before the update.  wm_k, wm_v, wm_b: [host] arrays of g device pointers (type dtype);
+ * empty: [host] array of g flags; A [g, d, Phi], z [g, Phi] fp32 updated in place.
+ * workspace: g * m * (4 * (d + d_mem + 2 * Phi + 8) + 2 * d) + g * d * Phi * 2 bytes. */
+armt_status armt_assoc_update(int32_t dtype, int32_t g, int32_t m, int32_t d_model, int32_t d_mem,
+                              int32_t dpfp_nu, float eps, const float *ym,
+                              const void *const *wm_k, const void *const *wm_v,
+                              const void *const *wm_b, const int32_t *empty, float *A, float *z,
+                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Text for a status code (static string). */
+const char *armt_status_str(armt_status s);
+
+/* Text of the HIP error behind the last ARMT_ERR_HIP returned on the calling thread ("" if none). */
+const char *armt_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ARMT_H_ */

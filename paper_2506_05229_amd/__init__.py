@@ -1,0 +1,9 @@
+"""MI355X-native Diagonal Batching forward pass of an ARMT (arxiv 2506.05229).
+
+The product is the C-ABI shared library built from csrc/ (declared in include/armt.h);
+`binding` is a thin ctypes layer over it that marshals torch device tensors."""
+from .binding import (ArmtConfig, ArmtLayerWeights, Armt, load_library, library_path, ArmtError,
+                      diagonal_group)
+
+__all__ = ["ArmtConfig", "ArmtLayerWeights", "Armt", "load_library", "library_path", "ArmtError",
+           "diagonal_group"]

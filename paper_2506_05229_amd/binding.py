@@ -1,0 +1,136 @@
+"""ctypes binding of include/armt.h: argument marshalling only.
+
+Every step of the path runs inside the shared library; torch is used for device memory and
+the current stream.  There is no fallback: if the library is missing, loading raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+ARMT_F32, ARMT_BF16 = 0, 1
+LAYER_FIELDS = ("rms1", "wq", "wk", "wv", "wo", "rms2", "wgate", "wup", "wdown",
+                "wm_q", "wm_k", "wm_v", "wm_b")
+
+
+class ArmtError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"armt status {code}: {text}")
+        self.code = code
+
+
+class ArmtConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "n_kv_heads", "head_dim", "d_ff",
+                                         "seg_len", "n_mem", "d_mem", "dpfp_nu", "dtype")] + \
+               [(n, C.c_float) for n in ("rms_eps", "rope_theta", "assoc_eps")]
+
+    @classmethod
+    def from_shape(cls, s) -> "ArmtConfig":
+        return cls(n_layers=s.n_layers, d_model=s.d_model, n_heads=s.n_heads, n_kv_heads=s.n_kv_heads,
+                   head_dim=s.head_dim, d_ff=s.d_ff, seg_len=s.seg_len, n_mem=s.n_mem, d_mem=s.d_mem,
+                   dpfp_nu=s.dpfp_nu, dtype=ARMT_BF16 if s.dtype == "bf16" else ARMT_F32,
+                   rms_eps=s.rms_eps, rope_theta=s.rope_theta, assoc_eps=s.assoc_eps)
+
+
+class ArmtLayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in LAYER_FIELDS]
+
+
+def library_path() -> str:
+    return os.environ.get("ARMT_HIP_LIBRARY", os.path.join(HERE, "libarmt_hip.so"))
+
+
+_LIB = None
+
+
+def load_library():
+    """Load libarmt_hip.so (built in-tree by paper_2506_05229_amd.build) and declare its C ABI."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} not found: build it with `python -m paper_2506_05229_amd.build`")
+    lib = C.CDLL(path)
+    vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    fwd = [C.POINTER(ArmtConfig), C.POINTER(ArmtLayerWeights), vp, vp, i64, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.armt_workspace_bytes.argtypes = [C.POINTER(ArmtConfig)]
+    lib.armt_workspace_bytes.restype = sz
+    for name in ("armt_forward_sequential", "armt_forward_diagonal"):
+        getattr(lib, name).argtypes = fwd
+        getattr(lib, name).restype = C.c_int
+    lib.armt_diagonal_group.argtypes = [i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
+    lib.armt_diagonal_group.restype = i32
+    lib.armt_status_str.argtypes = [C.c_int]
+    lib.armt_status_str.restype = C.c_char_p
+    lib.armt_last_hip_error.argtypes = []
+    lib.armt_last_hip_error.restype = C.c_char_p
+    _LIB = lib
+    return lib
+
+
+def _check(lib, code: int):
+    if code != 0:
+        text = lib.armt_status_str(code).decode()
+        if code == 5:
+            text += " (" + lib.armt_last_hip_error().decode() + ")"
+        raise ArmtError(code, text)
+
+
+def diagonal_group(n_layers: int, n_segments: int, t: int):
+    """(l_lo, l_hi) of step t of the anti-diagonal schedule, or None outside 0 .. L+N-2."""
+    lib = load_library()
+    lo, hi = C.c_int32(-1), C.c_int32(-1)
+    g = lib.armt_diagonal_group(n_layers, n_segments, t, C.byref(lo), C.byref(hi))
+    return None if g == 0 else (lo.value, hi.value)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+class Armt:
+    """An ARMT model resident in HBM: config + per-layer weight pointers + workspace."""
+
+    def __init__(self, shape, layers, mem_emb, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.lib = load_library()
+        self.shape = shape
+        self.cfg = ArmtConfig.from_shape(shape)
+        self.device = torch.device(device)
+        self.act_dtype = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+        to = lambda a: torch.as_tensor(a).to(device=self.device, dtype=self.act_dtype).contiguous()
+        self.layers = [{f: to(lw[f]) for f in LAYER_FIELDS} for lw in layers]
+        self.mem_emb = to(mem_emb)
+        self.c_layers = (ArmtLayerWeights * shape.n_layers)()
+        for l, lw in enumerate(self.layers):
+            for f in LAYER_FIELDS:
+                setattr(self.c_layers[l], f, lw[f].data_ptr())
+        nbytes = self.lib.armt_workspace_bytes(C.byref(self.cfg))
+        if nbytes == 0:
+            raise ArmtError(2, "configuration rejected by armt_workspace_bytes")
+        self.workspace_bytes = nbytes
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+
+    def embed(self, x):
+        return self.torch.as_tensor(x).to(device=self.device, dtype=self.act_dtype).contiguous()
+
+    def forward(self, x, diagonal=True, A_in=None, z_in=None, out=None):
+        """x: [n_tokens, d] device tensor of the activation type.  Returns (hidden, A, z)."""
+        torch, s = self.torch, self.shape
+        assert x.is_cuda and x.dtype == self.act_dtype and x.is_contiguous()
+        n_tokens = x.shape[0]
+        if out is None:
+            hidden = torch.empty((n_tokens, s.d_model), dtype=self.act_dtype, device=self.device)
+            A = torch.empty((s.n_layers, s.d_model, s.phi), dtype=torch.float32, device=self.device)
+            z = torch.empty((s.n_layers, s.phi), dtype=torch.float32, device=self.device)
+        else:
+            hidden, A, z = out
+        fn = self.lib.armt_forward_diagonal if diagonal else self.lib.armt_forward_sequential
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        code = fn(C.byref(self.cfg), self.c_layers, _ptr(self.mem_emb), _ptr(x), n_tokens, _ptr(A_in), _ptr(z_in),
+                  _ptr(hidden), _ptr(A), _ptr(z), _ptr(self.workspace), self.workspace_bytes, C.c_void_p(stream))
+        _check(self.lib, code)
+        return hidden, A, z

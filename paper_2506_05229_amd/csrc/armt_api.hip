@@ -1,0 +1,409 @@
+// Host side of the ARMT forward library: argument checks, workspace carving, the per-layer
+// pointer tables ("per-group weight pointers"), the cell / anti-diagonal scheduler and the
+// kernel sequence of one step.  Everything here is plain C++ around HIP launches; the C ABI
+// is declared in include/armt.h.
+#include "../../include/armt.h"
+
+#include <cstdlib>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "attention_generic.h"
+#include "common.h"
+#include "gemm_generic.h"
+#include "rowwise_kernels.h"
+
+using namespace armt;
+
+namespace {
+
+thread_local std::string g_hip_error;
+
+#define HIP_TRY(expr)                                                                      \
+  do {                                                                                     \
+    hipError_t e_ = (expr);                                                                \
+    if (e_ != hipSuccess) {                                                                \
+      g_hip_error = std::string(#expr) + ": " + hipGetErrorString(e_);                     \
+      return ARMT_ERR_HIP;                                                                 \
+    }                                                                                      \
+  } while (0)
+
+#define ARMT_TRY(expr)                 \
+  do {                                 \
+    armt_status s_ = (expr);           \
+    if (s_ != ARMT_OK) return s_;      \
+  } while (0)
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Dims {
+  int L, d, H, Hkv, dh, F, S, m, T, dm, nu, Phi, Nqkv;
+  bool bf16;
+  float rms_eps, rope_theta, assoc_eps;
+  size_t esz;   // bytes of one activation / weight element
+};
+
+armt_status check_config(const armt_config* c, Dims* out) {
+  if (!c) return ARMT_ERR_NULL;
+  if (c->dtype != ARMT_F32 && c->dtype != ARMT_BF16) return ARMT_ERR_DTYPE;
+  if (c->n_layers < 1 || c->d_model < 1 || c->n_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 2 ||
+      c->d_ff < 1 || c->seg_len < 1 || c->n_mem < 1 || c->d_mem < 1 || c->dpfp_nu < 1)
+    return ARMT_ERR_SHAPE;
+  if (c->n_heads % c->n_kv_heads != 0 || (c->head_dim & 1) || (int64_t)c->n_heads * c->head_dim != c->d_model)
+    return ARMT_ERR_SHAPE;
+  if (c->dpfp_nu >= 2 * c->d_mem) return ARMT_ERR_SHAPE;
+  if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f) || !(c->assoc_eps >= 0.f)) return ARMT_ERR_SHAPE;
+  Dims D;
+  D.L = c->n_layers; D.d = c->d_model; D.H = c->n_heads; D.Hkv = c->n_kv_heads; D.dh = c->head_dim;
+  D.F = c->d_ff; D.S = c->seg_len; D.m = c->n_mem; D.T = D.S + D.m; D.dm = c->d_mem; D.nu = c->dpfp_nu;
+  D.Phi = 2 * D.nu * D.dm; D.Nqkv = (D.H + 2 * D.Hkv) * D.dh;
+  D.bf16 = (c->dtype == ARMT_BF16);
+  D.rms_eps = c->rms_eps; D.rope_theta = c->rope_theta; D.assoc_eps = c->assoc_eps;
+  D.esz = D.bf16 ? 2 : 4;
+  if (D.Phi > 512) return ARMT_ERR_UNSUPPORTED;          // the delta-rule kernel keeps a row of A in registers
+  if ((size_t)D.m * D.Phi * 4 + (size_t)D.m * 16 > 60000) return ARMT_ERR_UNSUPPORTED;   // phi(k_i) of a cell live in LDS
+  if (D.bf16) {
+    if (D.d % 32 || D.F % 32 || D.dh % 32 || D.dm % 32 || D.m % 16) return ARMT_ERR_UNSUPPORTED;
+    if (D.dh != 64 && D.dh != 128) return ARMT_ERR_UNSUPPORTED;
+  }
+  if (out) *out = D;
+  return ARMT_OK;
+}
+
+// GEMM kinds of one step, in launch order; each has one table entry per layer.
+enum Kind { K_MQ = 0, K_READ, K_QKV, K_O, K_GU, K_DOWN, K_MKV, K_COUNT };
+
+struct Layout {          // byte offsets into the workspace
+  size_t X, Xb, Nrm, QKV, Att, Hres, Uff, Qm, Fphi, RDen, A16, KVm, Fm, Coef, Rope, Tables, Aux, total;
+};
+
+Layout carve(const Dims& D) {
+  Layout o;
+  size_t p = 0;
+  auto take = [&](size_t bytes) { size_t at = p; p = align_up(p + bytes); return at; };
+  const size_t L = D.L, T = D.T;
+  o.X = take((L + 1) * T * D.d * 4);                              // residual stream, slot l = input of layer l
+  o.Xb = take(D.bf16 ? (L + 1) * T * D.d * 2 : 0);                // bf16 copy of the slots (GEMM operand)
+  o.Nrm = take(L * T * D.d * D.esz);
+  o.QKV = take(L * T * D.Nqkv * D.esz);
+  o.Att = take(L * T * D.d * D.esz);
+  o.Hres = take(L * T * D.d * 4);
+  o.Uff = take(L * T * D.F * D.esz);
+  o.Qm = take(L * T * D.dm * 4);
+  o.Fphi = take(L * T * D.Phi * D.esz);
+  o.RDen = take(L * T * 4);
+  o.A16 = take(D.bf16 ? L * (size_t)D.d * D.Phi * 2 : 0);
+  o.KVm = take(L * D.m * (size_t)(D.dm + D.d) * 4);
+  o.Fm = take(L * D.m * (size_t)D.Phi * 4);
+  o.Coef = take(L * D.m * 4 * 4);
+  o.Rope = take(T * (D.dh / 2) * 2 * 4);
+  o.Tables = take((size_t)K_COUNT * L * sizeof(GemmGroup));
+  o.Aux = take(L * sizeof(LayerAux));
+  o.total = p;
+  return o;
+}
+
+struct Ctx {
+  Dims D;
+  Layout o;
+  char* ws;
+  hipStream_t st;
+  const GemmGroup* tables;   // device: [K_COUNT][L]
+  const LayerAux* aux;       // device: [L]
+  GemmShape shape[K_COUNT];
+  template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
+  const GemmGroup* table(int kind) const { return tables + (size_t)kind * D.L; }
+};
+
+void fill_shapes(Ctx& c) {
+  const Dims& D = c.D;
+  auto set = [&](int k, int M, int N, int K, int lda, int ldc, int ldc2, int ldr, int n0, int n1, int epi) {
+    GemmShape s;
+    s.M = M; s.N = N; s.K = K; s.lda = lda; s.ldc = ldc; s.ldc2 = ldc2; s.ldr = ldr; s.n0 = n0; s.n1 = n1; s.epi = epi;
+    c.shape[k] = s;
+  };
+  set(K_MQ, D.T, D.dm, D.d, D.d, D.dm, 0, 0, D.dm, 0, EPI_STORE_F32);
+  set(K_READ, D.T, D.d, D.Phi, D.Phi, D.d, 0, D.d, D.d, 0, EPI_RESID_F32);
+  set(K_QKV, D.T, D.Nqkv, D.d, D.d, D.Nqkv, 0, 0, D.H * D.dh, D.Hkv * D.dh, EPI_STORE_ACT);
+  set(K_O, D.T, D.d, D.H * D.dh, D.H * D.dh, D.d, 0, D.d, D.d, 0, EPI_RESID_F32);
+  set(K_GU, D.T, D.F, D.d, D.d, D.F, 0, 0, D.F, D.F, EPI_SWIGLU);
+  set(K_DOWN, D.T, D.d, D.F, D.F, D.d, D.d, D.d, D.d, 0, EPI_RESID_F32);
+  set(K_MKV, D.m, D.dm + D.d, D.d, D.d, D.dm + D.d, 0, 0, D.dm, D.d, EPI_STORE_F32);
+}
+
+// Build the per-layer pointer tables on the host and copy them into the workspace.
+armt_status upload_tables(Ctx& c, const armt_layer_weights* W, float* A, float* z) {
+  const Dims& D = c.D;
+  const size_t L = D.L, T = D.T;
+  std::vector<GemmGroup> tab((size_t)K_COUNT * L);
+  std::vector<LayerAux> aux(L);
+  memset(tab.data(), 0, tab.size() * sizeof(GemmGroup));
+  char* X = c.ws + c.o.X;
+  char* Xop = D.bf16 ? c.ws + c.o.Xb : X;       // activation-typed view of the slots
+  const size_t slotX = T * D.d * 4, slotXop = T * D.d * D.esz;
+  for (size_t l = 0; l < L; ++l) {
+    const armt_layer_weights& w = W[l];
+    float* Al = A + l * (size_t)D.d * D.Phi;
+    bf16* A16l = D.bf16 ? c.at<bf16>(c.o.A16) + l * (size_t)D.d * D.Phi : nullptr;
+    GemmGroup* g;
+    g = &tab[K_MQ * L + l];
+    g->A = Xop + l * slotXop; g->B0 = w.wm_q; g->C = c.ws + c.o.Qm + l * T * D.dm * 4;
+    g = &tab[K_READ * L + l];
+    g->A = c.ws + c.o.Fphi + l * T * D.Phi * D.esz;
+    g->B0 = D.bf16 ? (const void*)A16l : (const void*)Al;
+    g->C = X + l * slotX; g->R = (const float*)(X + l * slotX);
+    g->rowscale = (const float*)(c.ws + c.o.RDen + l * T * 4);
+    g = &tab[K_QKV * L + l];
+    g->A = c.ws + c.o.Nrm + l * T * D.d * D.esz; g->B0 = w.wq; g->B1 = w.wk; g->B2 = w.wv;
+    g->C = c.ws + c.o.QKV + l * T * D.Nqkv * D.esz;
+    g = &tab[K_O * L + l];
+    g->A = c.ws + c.o.Att + l * T * D.d * D.esz; g->B0 = w.wo;
+    g->C = c.ws + c.o.Hres + l * T * D.d * 4; g->R = (const float*)(X + l * slotX);
+    g = &tab[K_GU * L + l];
+    g->A = c.ws + c.o.Nrm + l * T * D.d * D.esz; g->B0 = w.wgate; g->B1 = w.wup;
+    g->C = c.ws + c.o.Uff + l * T * D.F * D.esz;
+    g = &tab[K_DOWN * L + l];
+    g->A = c.ws + c.o.Uff + l * T * D.F * D.esz; g->B0 = w.wdown;
+    g->C = X + (l + 1) * slotX; g->C2 = D.bf16 ? Xop + (l + 1) * slotXop : nullptr;
+    g->R = (const float*)(c.ws + c.o.Hres + l * T * D.d * 4);
+    g = &tab[K_MKV * L + l];
+    g->A = Xop + (l + 1) * slotXop + (size_t)D.S * D.d * D.esz; g->B0 = w.wm_k; g->B1 = w.wm_v;
+    g->C = c.ws + c.o.KVm + l * D.m * (size_t)(D.dm + D.d) * 4;
+    LayerAux& a = aux[l];
+    a.rms1 = w.rms1; a.rms2 = w.rms2; a.wm_b = w.wm_b;
+    a.A = Al; a.z = z + l * (size_t)D.Phi; a.A16 = A16l;
+  }
+  // hipMemcpyAsync from pageable host memory returns once the source has been consumed.
+  HIP_TRY(hipMemcpyAsync(c.ws + c.o.Tables, tab.data(), tab.size() * sizeof(GemmGroup), hipMemcpyHostToDevice, c.st));
+  HIP_TRY(hipMemcpyAsync(c.ws + c.o.Aux, aux.data(), aux.size() * sizeof(LayerAux), hipMemcpyHostToDevice, c.st));
+  HIP_TRY(hipStreamSynchronize(c.st));
+  c.tables = c.at<GemmGroup>(c.o.Tables);
+  c.aux = c.at<LayerAux>(c.o.Aux);
+  return ARMT_OK;
+}
+
+template <typename T>
+armt_status gemm(hipStream_t st, const GemmGroup* table, int first, int g, const GemmShape& s) {
+  if (g <= 0) return ARMT_OK;
+  HIP_TRY(launch_gemm_generic<T>(table, first, g, s, st));
+  return ARMT_OK;
+}
+
+// ---- the three composite steps, shared by the forward path and the single-step entry points ----
+
+// Associative read of cells [first, first + g): x <- x + A phi(W_Q x) / (z.phi(W_Q x) + eps)   (Eq. 6)
+template <typename T>
+armt_status step_assoc_read(hipStream_t st, const GemmGroup* t_mq, const GemmShape& s_mq, const GemmGroup* t_read,
+                            const GemmShape& s_read, const LayerAux* aux, int first, int g, int Trows, int dm, int nu,
+                            float eps, float* Qm, T* Fphi, float* RDen) {
+  if (g <= 0) return ARMT_OK;
+  ARMT_TRY(gemm<T>(st, t_mq, first, g, s_mq));
+  dpfp_read_kernel<T><<<dim3(Trows, g), 128, (dm + 17) * 4, st>>>(Qm, aux, first, Trows, dm, nu, eps, Fphi, RDen);
+  HIP_TRY(hipGetLastError());
+  return gemm<T>(st, t_read, first, g, s_read);
+}
+
+// Rotary embedding of q, k and causal grouped-query attention over the rows of each cell.
+template <typename T>
+armt_status step_attention(hipStream_t st, T* QKV, T* Att, const float* rope_cs, int first, int g, int Trows, int H,
+                           int Hkv, int dh) {
+  if (g <= 0) return ARMT_OK;
+  const int ldq = (H + 2 * Hkv) * dh;
+  rope_kernel<T><<<dim3(Trows, g), 256, 0, st>>>(QKV, rope_cs, first, Trows, H + Hkv, dh, ldq);
+  HIP_TRY(hipGetLastError());
+  attention_generic_kernel<T><<<dim3(Trows, H, g), 64, (dh + Trows) * 4, st>>>(QKV, Att, first, Trows, H, Hkv, dh,
+                                                                              1.0f / sqrtf((float)dh));
+  HIP_TRY(hipGetLastError());
+  return ARMT_OK;
+}
+
+// Delta-rule update of the memories of cells [first, first + g) from their m memory-row outputs (Eq. 3-5).
+template <typename T>
+armt_status step_assoc_update(hipStream_t st, const GemmGroup* t_mkv, const GemmShape& s_mkv, const LayerAux* aux,
+                              int first, int g, int empty_layer, const T* Y0, size_t y_stride, int m, int d, int dm,
+                              int nu, float eps, float* KVm, float* Fm, float* Coef) {
+  if (g <= 0) return ARMT_OK;
+  const int Phi = 2 * nu * dm;
+  ARMT_TRY(gemm<T>(st, t_mkv, first, g, s_mkv));
+  memupd_prep_kernel<T><<<dim3(m, g), 128, (dm + 17) * 4, st>>>(KVm, Y0, y_stride, aux, first, empty_layer, m, d, dm, nu,
+                                                               eps, Fm, Coef);
+  HIP_TRY(hipGetLastError());
+  const int rows_per_block = 16;
+  delta_rule_kernel<8><<<dim3((d + rows_per_block - 1) / rows_per_block, g), 256, (size_t)m * (Phi + 4) * 4, st>>>(
+      KVm, Fm, Coef, aux, first, m, d, dm, Phi, rows_per_block);
+  HIP_TRY(hipGetLastError());
+  return ARMT_OK;
+}
+
+// One step: the cells of layers [lo, hi] (each on its own segment), as one group.
+//   read_hi: highest layer whose memory is non-empty (the associative read applies to [lo, read_hi]);
+//   empty_layer: the layer whose memory is still empty (v_bar = 0), or -1.
+template <typename T>
+armt_status run_group(const Ctx& c, int lo, int hi, int read_hi, int empty_layer) {
+  const Dims& D = c.D;
+  const int g = hi - lo + 1;
+  float* X = c.at<float>(c.o.X);
+  T* Xop = D.bf16 ? c.at<T>(c.o.Xb) : (T*)X;
+  // (1) associative read
+  ARMT_TRY(step_assoc_read<T>(c.st, c.table(K_MQ), c.shape[K_MQ], c.table(K_READ), c.shape[K_READ], c.aux, lo,
+                              read_hi - lo + 1, D.T, D.dm, D.nu, D.assoc_eps, c.at<float>(c.o.Qm), c.at<T>(c.o.Fphi),
+                              c.at<float>(c.o.RDen)));
+  // (2) decoder block (TransformerLayer of Eq. 2)
+  rmsnorm_kernel<T><<<dim3(D.T, g), 256, 0, c.st>>>(X, c.aux, lo, 0, D.T, D.d, D.rms_eps, c.at<T>(c.o.Nrm));
+  HIP_TRY(hipGetLastError());
+  ARMT_TRY(gemm<T>(c.st, c.table(K_QKV), lo, g, c.shape[K_QKV]));
+  ARMT_TRY(step_attention<T>(c.st, c.at<T>(c.o.QKV), c.at<T>(c.o.Att), c.at<float>(c.o.Rope), lo, g, D.T, D.H, D.Hkv,
+                             D.dh));
+  ARMT_TRY(gemm<T>(c.st, c.table(K_O), lo, g, c.shape[K_O]));
+  rmsnorm_kernel<T><<<dim3(D.T, g), 256, 0, c.st>>>(c.at<float>(c.o.Hres), c.aux, lo, 1, D.T, D.d, D.rms_eps,
+                                                    c.at<T>(c.o.Nrm));
+  HIP_TRY(hipGetLastError());
+  ARMT_TRY(gemm<T>(c.st, c.table(K_GU), lo, g, c.shape[K_GU]));
+  ARMT_TRY(gemm<T>(c.st, c.table(K_DOWN), lo, g, c.shape[K_DOWN]));
+  // (3) memory update from the block's output at the memory rows
+  const T* Y0 = Xop + ((size_t)D.T + D.S) * D.d;        // memory row 0 of slot 1 = output of layer 0
+  return step_assoc_update<T>(c.st, c.table(K_MKV), c.shape[K_MKV], c.aux, lo, g, empty_layer, Y0, (size_t)D.T * D.d,
+                              D.m, D.d, D.dm, D.nu, D.assoc_eps, c.at<float>(c.o.KVm), c.at<float>(c.o.Fm),
+                              c.at<float>(c.o.Coef));
+}
+
+template <typename T>
+armt_status forward_typed(Ctx& c, const void* mem_emb, const void* x, int64_t N, bool carry_in, void* hidden_out,
+                          bool diagonal) {
+  const Dims& D = c.D;
+  const int L = D.L;
+  float* X = c.at<float>(c.o.X);
+  T* Xb = D.bf16 ? c.at<T>(c.o.Xb) : nullptr;
+  {
+    const int n = D.T * (D.dh / 2);
+    rope_table_kernel<<<(n + 255) / 256, 256, 0, c.st>>>(c.at<float>(c.o.Rope), D.T, D.dh / 2, (double)D.rope_theta);
+    HIP_TRY(hipGetLastError());
+  }
+  auto ingest = [&](int64_t s) -> armt_status {       // Algorithm 1: ingest a new segment at layer 0
+    pack_segment_kernel<T><<<D.T, 256, 0, c.st>>>((const T*)x + (size_t)s * D.S * D.d, (const T*)mem_emb, D.S, D.d, X, Xb);
+    HIP_TRY(hipGetLastError());
+    return ARMT_OK;
+  };
+  auto emit = [&](int64_t s) -> armt_status {         // segment s went through all layers
+    store_hidden_kernel<T><<<D.S, 256, 0, c.st>>>(X + (size_t)L * D.T * D.d, D.d, (T*)hidden_out + (size_t)s * D.S * D.d);
+    HIP_TRY(hipGetLastError());
+    return ARMT_OK;
+  };
+  if (!diagonal) {
+    for (int64_t s = 0; s < N; ++s) {
+      ARMT_TRY(ingest(s));
+      const bool empty = (s == 0 && !carry_in);
+      for (int l = 0; l < L; ++l) ARMT_TRY(run_group<T>(c, l, l, empty ? l - 1 : l, empty ? l : -1));
+      ARMT_TRY(emit(s));
+    }
+  } else {
+    const int64_t steps = L + N - 1;
+    for (int64_t t = 0; t < steps; ++t) {
+      int32_t lo, hi;
+      armt_diagonal_group(L, (int32_t)N, (int32_t)t, &lo, &hi);
+      if (t < N) ARMT_TRY(ingest(t));
+      // only the cell of segment 0 (layer t, while t < L) can meet an empty memory
+      const bool top_empty = (!carry_in && t < L);
+      ARMT_TRY(run_group<T>(c, lo, hi, top_empty ? hi - 1 : hi, top_empty ? hi : -1));
+      if (hi == L - 1) ARMT_TRY(emit(t - (L - 1)));
+    }
+  }
+  return ARMT_OK;
+}
+
+armt_status forward_impl(const armt_config* cfg, const armt_layer_weights* layers, const void* mem_emb, const void* x,
+                         int64_t n_tokens, const float* A_in, const float* z_in, void* hidden_out, float* A_out,
+                         float* z_out, void* workspace, size_t workspace_bytes, void* hip_stream, bool diagonal) {
+  Ctx c;
+  ARMT_TRY(check_config(cfg, &c.D));
+  const Dims& D = c.D;
+  if (!layers || !mem_emb || !x || !hidden_out || !A_out || !z_out) return ARMT_ERR_NULL;
+  if ((A_in == nullptr) != (z_in == nullptr)) return ARMT_ERR_NULL;
+  for (int l = 0; l < D.L; ++l) {
+    const armt_layer_weights& w = layers[l];
+    if (!w.rms1 || !w.wq || !w.wk || !w.wv || !w.wo || !w.rms2 || !w.wgate || !w.wup || !w.wdown || !w.wm_q ||
+        !w.wm_k || !w.wm_v || !w.wm_b)
+      return ARMT_ERR_NULL;
+  }
+  if (n_tokens <= 0 || n_tokens % D.S != 0) return ARMT_ERR_SHAPE;
+  const int64_t N = n_tokens / D.S;
+  if (N + D.L > (int64_t)1 << 30) return ARMT_ERR_SHAPE;
+  c.o = carve(D);
+  if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < c.o.total) return ARMT_ERR_WORKSPACE;
+  c.ws = (char*)workspace;
+  c.st = (hipStream_t)hip_stream;
+  fill_shapes(c);
+
+  // memory state lives in A_out / z_out for the whole call
+  const size_t nA = (size_t)D.L * D.d * D.Phi, nz = (size_t)D.L * D.Phi;
+  if (A_in) {
+    if (A_in != A_out) copy_f32_kernel<<<1024, 256, 0, c.st>>>(A_out, A_in, nA);
+    if (z_in != z_out) copy_f32_kernel<<<16, 256, 0, c.st>>>(z_out, z_in, nz);
+  } else {
+    fill_f32_kernel<<<1024, 256, 0, c.st>>>(A_out, nA, 0.f);      // A_0 = 0, z_0 = 0 (Eq. 3)
+    fill_f32_kernel<<<16, 256, 0, c.st>>>(z_out, nz, 0.f);
+  }
+  HIP_TRY(hipGetLastError());
+  if (D.bf16) {
+    f32_to_bf16_kernel<<<1024, 256, 0, c.st>>>(c.at<bf16>(c.o.A16), A_out, nA);
+    HIP_TRY(hipGetLastError());
+  }
+  ARMT_TRY(upload_tables(c, layers, A_out, z_out));
+  if (D.bf16) return forward_typed<bf16>(c, mem_emb, x, N, A_in != nullptr, hidden_out, diagonal);
+  return forward_typed<float>(c, mem_emb, x, N, A_in != nullptr, hidden_out, diagonal);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t armt_workspace_bytes(const armt_config* cfg) {
+  Dims D;
+  if (check_config(cfg, &D) != ARMT_OK) return 0;
+  return carve(D).total;
+}
+
+armt_status armt_forward_sequential(const armt_config* cfg, const armt_layer_weights* layers, const void* mem_emb,
+                                    const void* x, int64_t n_tokens, const float* A_in, const float* z_in,
+                                    void* hidden_out, float* A_out, float* z_out, void* workspace,
+                                    size_t workspace_bytes, void* hip_stream) {
+  return forward_impl(cfg, layers, mem_emb, x, n_tokens, A_in, z_in, hidden_out, A_out, z_out, workspace,
+                      workspace_bytes, hip_stream, false);
+}
+
+armt_status armt_forward_diagonal(const armt_config* cfg, const armt_layer_weights* layers, const void* mem_emb,
+                                  const void* x, int64_t n_tokens, const float* A_in, const float* z_in,
+                                  void* hidden_out, float* A_out, float* z_out, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream) {
+  return forward_impl(cfg, layers, mem_emb, x, n_tokens, A_in, z_in, hidden_out, A_out, z_out, workspace,
+                      workspace_bytes, hip_stream, true);
+}
+
+int32_t armt_diagonal_group(int32_t n_layers, int32_t n_segments, int32_t t, int32_t* l_lo, int32_t* l_hi) {
+  if (n_layers < 1 || n_segments < 1 || t < 0 || (int64_t)t > (int64_t)n_layers + n_segments - 2) return 0;
+  // cell (l, s = t - l) is live iff 0 <= l < L and 0 <= t - l < N
+  const int32_t lo = t - n_segments + 1 > 0 ? t - n_segments + 1 : 0;
+  const int32_t hi = t < n_layers - 1 ? t : n_layers - 1;
+  if (l_lo) *l_lo = lo;
+  if (l_hi) *l_hi = hi;
+  return hi - lo + 1;
+}
+
+const char* armt_status_str(armt_status s) {
+  switch (s) {
+    case ARMT_OK: return "ok";
+    case ARMT_ERR_NULL: return "a required pointer is NULL";
+    case ARMT_ERR_SHAPE: return "inconsistent sizes";
+    case ARMT_ERR_DTYPE: return "unknown dtype";
+    case ARMT_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case ARMT_ERR_HIP: return "HIP runtime error";
+    case ARMT_ERR_UNSUPPORTED: return "shape not supported by this build";
+  }
+  return "unknown status";
+}
+
+const char* armt_last_hip_error(void) { return g_hip_error.c_str(); }
+
+}  // extern "C"

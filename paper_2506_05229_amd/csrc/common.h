@@ -1,0 +1,80 @@
+// Shared device/host definitions of the ARMT forward library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace armt {
+
+typedef __bf16 bf16;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;   // CDNA wavefront width
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }   // round to nearest even
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+
+// Sum over the threads of a block (blockDim.x a multiple of 64, at most 1024); every thread gets it.
+__device__ __forceinline__ float block_sum(float v, float* red /* >= 17 floats of LDS */) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float s = 0.f;
+    for (int i = 0; i < nw; ++i) s += red[i];
+    red[16] = s;
+  }
+  __syncthreads();
+  return red[16];
+}
+
+// ---------------------------------------------------------------------------------------------
+// One entry of a grouped-GEMM pointer table: the operands of ONE group (= one layer's cell).
+// The table of a GEMM kind holds one entry per layer; a launch covers entries [first, first + g).
+// This is how every group multiplies by its own layer's weights without stacking them
+// (paper Section 3.3 item 1).
+struct GemmGroup {
+  const void* A;          // [M, K] activations, row stride lda
+  const void* B0;         // weight block 0: rows [0, n0) of the logical [N, K] operand
+  const void* B1;         // weight block 1: rows [n0, n0 + n1)  (SwiGLU: the "up" weight)
+  const void* B2;         // weight block 2: the remaining rows
+  void* C;                // primary output
+  void* C2;               // optional copy of C in the activation type (or null)
+  const float* R;         // residual [M, ldr] (or null)
+  const float* rowscale;  // per-row factor applied to the accumulator (or null)
+};
+
+enum GemmEpilogue : int {
+  EPI_STORE_ACT = 0,   // C (activation type) = acc
+  EPI_STORE_F32 = 1,   // C (fp32) = acc
+  EPI_RESID_F32 = 2,   // C (fp32) = R + acc * rowscale[row]; C2 (activation type) = same, if given
+  EPI_SWIGLU = 3       // C (activation type) = silu(acc over B0) * (acc over B1); logical N = rows of B0
+};
+
+struct GemmShape {
+  int M, N, K;          // N = output columns (for EPI_SWIGLU: d_ff, each column needs two dot products)
+  int lda, ldc, ldc2, ldr;
+  int n0, n1;           // rows in weight blocks 0 and 1 (block 2 holds N - n0 - n1)
+  int epi;              // GemmEpilogue
+};
+
+}  // namespace armt

@@ -1,0 +1,251 @@
+// Row-wise kernels of one ARMT step: segment packing, RMSNorm with per-layer gain, rotary
+// embedding, DPFP feature map with the read denominator, and the delta-rule memory update.
+// All of them are bound by HBM traffic: one block (or wave) per row, coalesced row accesses.
+#pragma once
+
+#include "common.h"
+
+namespace armt {
+
+// Per-layer pointers that are not GEMM operands (device table, one entry per layer).
+struct LayerAux {
+  const void* rms1;     // [d] gain of the first norm
+  const void* rms2;     // [d] gain of the second norm
+  const void* wm_b;     // [d] W_beta
+  float* A;             // [d, Phi] associative matrix of the layer (fp32, updated in place)
+  float* z;             // [Phi]
+  bf16* A16;            // [d, Phi] bf16 shadow of A, operand of the read GEMM (bf16 configs; else null)
+};
+
+// ------------------------------------------------------------------------------------------------
+// Cell input of a new segment at layer 0: seg_len embedding rows followed by the n_mem memory-token
+// embeddings (Eq. 2, "[H, M]"; Algorithm 1, Segment).  grid: (T), block: 256.
+template <typename T>
+__global__ __launch_bounds__(256) void pack_segment_kernel(const T* __restrict__ x_seg,
+                                                           const T* __restrict__ mem_emb, int S, int d,
+                                                           float* __restrict__ X0, T* __restrict__ Xb0) {
+  const int r = blockIdx.x;
+  const T* src = (r < S) ? x_seg + (size_t)r * d : mem_emb + (size_t)(r - S) * d;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    const T v = src[c];
+    X0[(size_t)r * d + c] = to_f32(v);
+    if (Xb0) Xb0[(size_t)r * d + c] = v;
+  }
+}
+
+// Output of the last layer at the token rows of a segment -> hidden_out.  grid: (S), block: 256.
+template <typename T>
+__global__ __launch_bounds__(256) void store_hidden_kernel(const float* __restrict__ XL, int d,
+                                                           T* __restrict__ out) {
+  const size_t r = blockIdx.x;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) out[r * d + c] = from_f32<T>(XL[r * d + c]);
+}
+
+__global__ void fill_f32_kernel(float* __restrict__ p, size_t n, float v) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+__global__ void copy_f32_kernel(float* __restrict__ dst, const float* __restrict__ src, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
+__global__ void f32_to_bf16_kernel(bf16* __restrict__ dst, const float* __restrict__ src, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = (bf16)src[i];
+}
+
+// ------------------------------------------------------------------------------------------------
+// RMSNorm with the gain of the cell's own layer (Section 3.3 item 2: per-layer norm weights).
+// X: [L+1][T][d] fp32 slots (or Hres [L][T][d]); out: [L][T][d].  grid: (T, g), block: 256.
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ X, const LayerAux* __restrict__ aux,
+                                                      int first, int which, int Trows, int d, float eps,
+                                                      T* __restrict__ out) {
+  __shared__ float red[17];
+  const int l = first + blockIdx.y;
+  const size_t row = ((size_t)l * Trows + blockIdx.x) * d;
+  const T* gain = (const T*)(which == 0 ? aux[l].rms1 : aux[l].rms2);
+  float ss = 0.f;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    const float v = X[row + c];
+    ss = fmaf(v, v, ss);
+  }
+  ss = block_sum(ss, red);
+  const float rstd = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int c = threadIdx.x; c < d; c += blockDim.x) out[row + c] = from_f32<T>(X[row + c] * rstd * to_f32(gain[c]));
+}
+
+// ------------------------------------------------------------------------------------------------
+// cos / sin of p * theta^(-2j/dh), p = 0..T-1, j = 0..dh/2-1, computed in double once per call.
+__global__ void rope_table_kernel(float* __restrict__ cs, int Trows, int half, double theta) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= Trows * half) return;
+  const int p = i / half, j = i % half;
+  const double ang = (double)p * pow(theta, -(double)j / (double)half);
+  cs[2 * i] = (float)cos(ang);
+  cs[2 * i + 1] = (float)sin(ang);
+}
+
+// Rotary embedding of q and k in place, rotate-half pairing (j, j + dh/2), position = row in the cell.
+// QKV: [L][T][(H + 2 Hkv) dh].  grid: (T, g), block: 256.
+template <typename T>
+__global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ QKV, const float* __restrict__ cs, int first,
+                                                   int Trows, int n_rot_heads, int dh, int ldq) {
+  const int l = first + blockIdx.y, p = blockIdx.x, half = dh >> 1;
+  T* row = QKV + ((size_t)l * Trows + p) * ldq;
+  for (int i = threadIdx.x; i < n_rot_heads * half; i += blockDim.x) {
+    const int h = i / half, j = i % half;
+    const float c = cs[2 * (p * half + j)], s = cs[2 * (p * half + j) + 1];
+    const float a = to_f32(row[h * dh + j]), b = to_f32(row[h * dh + j + half]);
+    row[h * dh + j] = from_f32<T>(a * c - b * s);
+    row[h * dh + j + half] = from_f32<T>(b * c + a * s);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// DPFP-nu feature map (the nonlinearity phi of Section 2.1, after Schlag et al. 2021):
+// r = [relu(k), relu(-k)], phi[(j-1) 2dm + i] = r[i] r[(i-j) mod 2dm], j = 1..nu.
+__device__ __forceinline__ float dpfp_r(const float* k, int dm, int i) {
+  return i < dm ? fmaxf(k[i], 0.f) : fmaxf(-k[i - dm], 0.f);
+}
+__device__ __forceinline__ float dpfp_at(const float* k, int dm, int idx) {
+  const int n = 2 * dm, j = idx / n + 1, i = idx % n;
+  int i2 = i - j;
+  if (i2 < 0) i2 += n;
+  return dpfp_r(k, dm, i) * dpfp_r(k, dm, i2);
+}
+
+// Read side (Eq. 6): f = phi(W_Q x) for every row of the cell, 1 / (z.f + eps) for the read GEMM's
+// epilogue.  Qm: [L][T][dm] fp32; Fphi: [L][T][Phi]; RDen: [L][T].  grid: (T, g), block: 128.
+template <typename T>
+__global__ __launch_bounds__(128) void dpfp_read_kernel(const float* __restrict__ Qm, const LayerAux* __restrict__ aux,
+                                                        int first, int Trows, int dm, int nu, float eps,
+                                                        T* __restrict__ Fphi, float* __restrict__ RDen) {
+  extern __shared__ float sm[];          // dm floats + 17
+  float* k = sm;
+  float* red = sm + dm;
+  const int l = first + blockIdx.y;
+  const size_t r = (size_t)l * Trows + blockIdx.x;
+  const int Phi = 2 * nu * dm;
+  for (int c = threadIdx.x; c < dm; c += blockDim.x) k[c] = Qm[r * dm + c];
+  __syncthreads();
+  const float* z = aux[l].z;
+  float den = 0.f;
+  for (int c = threadIdx.x; c < Phi; c += blockDim.x) {
+    const float f = dpfp_at(k, dm, c);
+    den = fmaf(f, z[c], den);
+    Fphi[r * Phi + c] = from_f32<T>(f);
+  }
+  den = block_sum(den, red);
+  if (threadIdx.x == 0) RDen[r] = 1.0f / (den + eps);
+}
+
+// Write side (Eq. 3-4) for the m memory rows of each cell: f_i = phi(k_i), beta_i = sigmoid(W_beta y_i),
+// gamma_i = 1 - z.f_i / (|f_i|^2 + eps), and 1 / (z.f_i + eps) (0 for an empty memory: v_bar = 0).
+// KV: [L][m][dm + d] fp32 (k then v); Y0 + l * y_stride: the m memory rows [m][d] of layer l's output.
+// Fm: [L][m][Phi] fp32; Coef: [L][m][4] = {beta, gamma, 1/den, z.f}.  grid: (m, g), block: 128.
+template <typename T>
+__global__ __launch_bounds__(128) void memupd_prep_kernel(const float* __restrict__ KV, const T* __restrict__ Y0,
+                                                          size_t y_stride, const LayerAux* __restrict__ aux, int first,
+                                                          int empty_layer, int m, int d, int dm, int nu, float eps,
+                                                          float* __restrict__ Fm, float* __restrict__ Coef) {
+  extern __shared__ float sm[];
+  float* k = sm;
+  float* red = sm + dm;
+  const int l = first + blockIdx.y, i = blockIdx.x;
+  const int Phi = 2 * nu * dm;
+  const size_t mi = (size_t)l * m + i;
+  for (int c = threadIdx.x; c < dm; c += blockDim.x) k[c] = KV[mi * (dm + d) + c];
+  __syncthreads();
+  const float* z = aux[l].z;
+  float zf = 0.f, ff = 0.f;
+  for (int c = threadIdx.x; c < Phi; c += blockDim.x) {
+    const float f = dpfp_at(k, dm, c);
+    zf = fmaf(f, z[c], zf);
+    ff = fmaf(f, f, ff);
+    Fm[mi * Phi + c] = f;
+  }
+  const T* y = Y0 + (size_t)l * y_stride + (size_t)i * d;
+  const T* wb = (const T*)aux[l].wm_b;
+  float bl = 0.f;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) bl = fmaf(to_f32(y[c]), to_f32(wb[c]), bl);
+  zf = block_sum(zf, red);
+  ff = block_sum(ff, red);
+  bl = block_sum(bl, red);
+  if (threadIdx.x == 0) {
+    Coef[mi * 4 + 0] = 1.0f / (1.0f + expf(-bl));
+    Coef[mi * 4 + 1] = 1.0f - zf / (ff + eps);
+    Coef[mi * 4 + 2] = (l == empty_layer) ? 0.f : 1.0f / (zf + eps);
+    Coef[mi * 4 + 3] = zf;
+  }
+}
+
+// Delta rule (Eq. 5), one pass over A: row r of A needs only A[r, :], v_i[r] and the shared f_i, so
+// each wave owns rows, computes v_bar_i[r] = A[r,:].f_i / den_i for all i from the OLD row, then adds
+// sum_i beta_i (v_i[r] - v_bar_i[r]) f_i and writes the row back once (plus its bf16 shadow).
+// The block with blockIdx.x == 0 also updates z += sum_i gamma_i f_i (z is not read here).
+// grid: (ceil(d / rows_per_block), g), block: 256 (4 waves).  Phi <= 64 * NPL.
+template <int NPL>
+__global__ __launch_bounds__(256) void delta_rule_kernel(const float* __restrict__ KV, const float* __restrict__ Fm,
+                                                         const float* __restrict__ Coef,
+                                                         const LayerAux* __restrict__ aux, int first, int m, int d,
+                                                         int dm, int Phi, int rows_per_block) {
+  extern __shared__ float sm[];          // F: m * Phi, then coef: m * 4
+  float* F = sm;
+  float* cf = sm + (size_t)m * Phi;
+  const int l = first + blockIdx.y;
+  const float* Fl = Fm + (size_t)l * m * Phi;
+  for (int c = threadIdx.x; c < m * Phi; c += blockDim.x) F[c] = Fl[c];
+  for (int c = threadIdx.x; c < m * 4; c += blockDim.x) cf[c] = Coef[(size_t)l * m * 4 + c];
+  __syncthreads();
+  float* A = aux[l].A;
+  bf16* A16 = aux[l].A16;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int r0 = blockIdx.x * rows_per_block;
+  const int r1 = min(d, r0 + rows_per_block);
+  const float* V = KV + (size_t)l * m * (dm + d) + dm;      // v_i[r] = V[i * (dm + d) + r]
+  for (int r = r0 + w; r < r1; r += 4) {
+    float a[NPL];
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) {
+      const int c = lane + 64 * k;
+      a[k] = (c < Phi) ? A[(size_t)r * Phi + c] : 0.f;
+    }
+    float upd[NPL] = {};
+    for (int i = 0; i < m; ++i) {
+      float dot = 0.f;
+#pragma unroll
+      for (int k = 0; k < NPL; ++k) {
+        const int c = lane + 64 * k;
+        if (c < Phi) dot = fmaf(a[k], F[i * Phi + c], dot);
+      }
+      dot = wave_sum(dot);
+      const float coef = cf[i * 4 + 0] * (V[(size_t)i * (dm + d) + r] - dot * cf[i * 4 + 2]);
+#pragma unroll
+      for (int k = 0; k < NPL; ++k) {
+        const int c = lane + 64 * k;
+        if (c < Phi) upd[k] = fmaf(coef, F[i * Phi + c], upd[k]);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) {
+      const int c = lane + 64 * k;
+      if (c < Phi) {
+        const float v = a[k] + upd[k];
+        A[(size_t)r * Phi + c] = v;
+        if (A16) A16[(size_t)r * Phi + c] = (bf16)v;
+      }
+    }
+  }
+  if (blockIdx.x == 0) {
+    float* z = aux[l].z;
+    for (int c = threadIdx.x; c < Phi; c += blockDim.x) {
+      float s = 0.f;
+      for (int i = 0; i < m; ++i) s = fmaf(cf[i * 4 + 1], F[i * Phi + c], s);
+      z[c] += s;
+    }
+  }
+}
+
+}  // namespace armt
