@@ -116,47 +116,50 @@ armt_status armt_forward_diagonal(const armt_config *cfg, const armt_layer_weigh
 int32_t armt_diagonal_group(int32_t n_layers, int32_t n_segments, int32_t t,
                             int32_t *l_lo /* [host] */, int32_t *l_hi /* [host] */);
 
-/* ---- single steps of the path, as the forward calls run them (for tests and micro-benchmarks).
- * Each works on a group of g cells, like one step of Algorithm 1 does. ---- */
+/* ---- single steps of the path, exactly as the forward calls run them (for tests and micro-benchmarks).
+ * Each works on a group of g cells, like one step of Algorithm 1 does.  Those that take a cfg use its
+ * sizes (T = seg_len + n_mem rows per cell), need 1 <= g <= cfg->n_layers, and accept the same workspace
+ * as the forward calls (armt_workspace_bytes(cfg) bytes, 256-byte aligned). ---- */
 
-/* Grouped GEMM (Section 3.3 item 1, Section 4.1): C_i = A_i B_i^T for i < g, every group with its
- * own operand pointers.  a, b, c are [host] arrays of g device pointers: A_i [M, K], B_i [N, K]
- * (a weight, [out, in]) of type dtype, C_i [M, N] fp32.  dtype BF16 needs K % 32 == 0. */
+/* Grouped GEMM (Section 3.3 item 1, Section 4.1): C_i = A_i B_i^T for i < g, every group with its own
+ * operand pointers.  a, b, c are [host] arrays of g device pointers: A_i [M, K], B_i [N, K] (a weight,
+ * [out, in]) and C_i [M, N], all of type dtype (fp32 accumulation).  dtype BF16 needs K % 64 == 0.
+ * workspace: g * 64 bytes, 256-byte aligned (holds the pointer table). */
 armt_status armt_grouped_gemm(int32_t dtype, int32_t g, int32_t M, int32_t N, int32_t K,
-                              const void *const *a, const void *const *b, float *const *c,
-                              void *hip_stream);
+                              const void *const *a, const void *const *b, void *const *c,
+                              void *workspace, size_t workspace_bytes, void *hip_stream);
 
-/* Segment attention batched over the group (Section 4.2): causal softmax(q k^T / sqrt(dh)) v over
- * the T rows of each cell, grouped-query heads, rotary embedding applied to q and k first.
- * qkv [g, T, (H + 2 Hkv) * dh] of type dtype, rows laid out as [q heads | k heads | v heads];
- * out [g, T, H * dh] of type dtype.  qkv is modified (rotated in place).
- * workspace: (H + 2 Hkv) * dh * (T + 64) * g * 2 bytes, 256-byte aligned, for dtype BF16; unused for F32. */
-armt_status armt_segment_attention(int32_t dtype, int32_t g, int32_t T, int32_t n_heads,
-                                   int32_t n_kv_heads, int32_t head_dim, float rope_theta,
-                                   void *qkv, void *out, void *workspace, size_t workspace_bytes,
-                                   void *hip_stream);
+/* Segment attention batched over the group (Section 4.2): rotary embedding of q and k (positions
+ * 0..T-1), then causal softmax(q k^T / sqrt(dh)) v over the T rows of each cell with grouped-query
+ * heads.  qkv [g, T, (H + 2 Hkv) * dh] of cfg->dtype, each row laid out [q heads | k heads | v heads],
+ * is rotated in place; out [g, T, H * dh] of cfg->dtype. */
+armt_status armt_segment_attention(const armt_config *cfg, int32_t g, void *qkv, void *out,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
-/* Associative read of a group (Eq. 6 added to its input): for every cell i and row r,
- * x[i][r] += A_i phi(Wq_i x[i][r]) / (z_i . phi(Wq_i x[i][r]) + eps).
- * x [g, T, d] fp32, updated in place; wm_q [host] array of g device pointers to [d_mem, d] of type
- * dtype; A [g, d, Phi], z [g, Phi] fp32.  workspace: g * T * (8 * d + 8 * Phi + 4 * d_mem + 16) + g * d * Phi * 2 bytes. */
-armt_status armt_assoc_read(int32_t dtype, int32_t g, int32_t T, int32_t d_model, int32_t d_mem,
-                            int32_t dpfp_nu, float eps, float *x, const void *const *wm_q,
+/* Associative read of a group (Eq. 6, added to its input): for every cell i and row r,
+ * x[i][r] += A_i phi(Wq_i x[i][r]) / (z_i . phi(Wq_i x[i][r]) + assoc_eps).
+ * x [g, T, d] fp32, updated in place; wm_q: [host] array of g device pointers to [d_mem, d] of
+ * cfg->dtype; A [g, d, Phi], z [g, Phi] fp32 (read only). */
+armt_status armt_assoc_read(const armt_config *cfg, int32_t g, float *x, const void *const *wm_q,
                             const float *A, const float *z, void *workspace, size_t workspace_bytes,
                             void *hip_stream);
 
-/* Delta-rule memory update of a group (Eq. 3-5): for every cell i, from its m memory-token outputs
- * ym [g, m, d] fp32: k = Wk ym, v = Wv ym, beta = sigmoid(Wb ym), v_bar = A phi(k) / (z.phi(k) + eps)
- * (0 where empty[i] != 0), gamma = 1 - z.phi(k) / (|phi(k)|^2 + eps); then
- * A_i += sum_j beta_j (v_j - v_bar_j) (x) phi(k_j), z_i += sum_j gamma_j phi(k_j), every j using the
- * state from before the update.  wm_k, wm_v, wm_b: [host] arrays of g device pointers (type dtype);
- * empty: [host] array of g flags; A [g, d, Phi], z [g, Phi] fp32 updated in place.
- * workspace: g * m * (4 * (d + d_mem + 2 * Phi + 8) + 2 * d) + g * d * Phi * 2 bytes. */
-armt_status armt_assoc_update(int32_t dtype, int32_t g, int32_t m, int32_t d_model, int32_t d_mem,
-                              int32_t dpfp_nu, float eps, const float *ym,
-                              const void *const *wm_k, const void *const *wm_v,
-                              const void *const *wm_b, const int32_t *empty, float *A, float *z,
+/* Delta-rule memory update of a group (Eq. 3-5): for every cell i, from its n_mem memory-token outputs
+ * ym [g, n_mem, d] fp32: k = Wk ym, v = Wv ym, beta = sigmoid(Wb ym), v_bar = A phi(k) / (z.phi(k) + eps)
+ * (0 for the cell empty_group, whose memory is still empty; -1 = none), gamma = 1 - z.phi(k) / (|phi(k)|^2
+ * + eps); then A_i += sum_j beta_j (v_j - v_bar_j) (x) phi(k_j), z_i += sum_j gamma_j phi(k_j), every j
+ * using the state from before the update.  wm_k, wm_v, wm_b: [host] arrays of g device pointers
+ * (cfg->dtype); A [g, d, Phi], z [g, Phi] fp32, updated in place. */
+armt_status armt_assoc_update(const armt_config *cfg, int32_t g, const float *ym,
+                              const void *const *wm_k, const void *const *wm_v, const void *const *wm_b,
+                              int32_t empty_group, float *A, float *z,
                               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Benchmarking knob: force the tile configuration of the bf16 grouped GEMM for all later calls of this
+ * process (0: 256x256 tile, 8 waves; 1: 128x128, 4 waves; 2: 64x128, 4 waves; 3: 256x256, 4 waves;
+ * anything else: choose by shape, the default).  Results do not depend on it beyond rounding order.
+ * Returns the previous setting.  Not thread safe. */
+int32_t armt_set_gemm_tile_config(int32_t config);
 
 /* Text for a status code (static string). */
 const char *armt_status_str(armt_status s);

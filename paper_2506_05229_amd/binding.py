@@ -62,6 +62,17 @@ def load_library():
         getattr(lib, name).restype = C.c_int
     lib.armt_diagonal_group.argtypes = [i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
     lib.armt_diagonal_group.restype = i32
+    pp = C.POINTER(C.c_void_p)
+    lib.armt_grouped_gemm.argtypes = [i32, i32, i32, i32, i32, pp, pp, pp, vp, sz, vp]
+    lib.armt_grouped_gemm.restype = C.c_int
+    lib.armt_segment_attention.argtypes = [C.POINTER(ArmtConfig), i32, vp, vp, vp, sz, vp]
+    lib.armt_segment_attention.restype = C.c_int
+    lib.armt_assoc_read.argtypes = [C.POINTER(ArmtConfig), i32, vp, pp, vp, vp, vp, sz, vp]
+    lib.armt_assoc_read.restype = C.c_int
+    lib.armt_assoc_update.argtypes = [C.POINTER(ArmtConfig), i32, vp, pp, pp, pp, i32, vp, vp, vp, sz, vp]
+    lib.armt_assoc_update.restype = C.c_int
+    lib.armt_set_gemm_tile_config.argtypes = [i32]
+    lib.armt_set_gemm_tile_config.restype = i32
     lib.armt_status_str.argtypes = [C.c_int]
     lib.armt_status_str.restype = C.c_char_p
     lib.armt_last_hip_error.argtypes = []
@@ -134,3 +145,75 @@ class Armt:
                   _ptr(hidden), _ptr(A), _ptr(z), _ptr(self.workspace), self.workspace_bytes, C.c_void_p(stream))
         _check(self.lib, code)
         return hidden, A, z
+
+
+# ---------------------------------------------------------------- single steps (tests, micro-benchmarks)
+def _ptr_array(tensors):
+    arr = (C.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = t.data_ptr()
+    return arr
+
+
+def _stream(torch):
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def set_gemm_tile_config(config: int) -> int:
+    return load_library().armt_set_gemm_tile_config(config)
+
+
+def grouped_gemm(a_list, b_list, out_list=None, workspace=None):
+    """C_i = A_i B_i^T; lists of device tensors A_i [M, K], B_i [N, K] (fp32 or bf16)."""
+    import torch
+    lib = load_library()
+    g = len(a_list)
+    M, K = a_list[0].shape
+    N = b_list[0].shape[0]
+    dt = a_list[0].dtype
+    if out_list is None:
+        out_list = [torch.empty((M, N), dtype=dt, device=a_list[0].device) for _ in range(g)]
+    if workspace is None:
+        workspace = torch.empty(max(256, g * 64), dtype=torch.uint8, device=a_list[0].device)
+    code = lib.armt_grouped_gemm(ARMT_BF16 if dt == torch.bfloat16 else ARMT_F32, g, M, N, K, _ptr_array(a_list),
+                                 _ptr_array(b_list), _ptr_array(out_list), _ptr(workspace), workspace.numel(),
+                                 _stream(torch))
+    _check(lib, code)
+    return out_list
+
+
+class ArmtSteps:
+    """Single steps of the path on caller buffers, with the sizes of one configuration."""
+
+    def __init__(self, shape, device="cuda:0"):
+        import torch
+        self.torch, self.shape = torch, shape
+        self.lib = load_library()
+        self.cfg = ArmtConfig.from_shape(shape)
+        self.act_dtype = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+        n = self.lib.armt_workspace_bytes(C.byref(self.cfg))
+        if n == 0:
+            raise ArmtError(2, "configuration rejected by armt_workspace_bytes")
+        self.ws = torch.empty(n, dtype=torch.uint8, device=device)
+
+    def segment_attention(self, qkv):
+        """qkv [g, T, (H + 2 Hkv) dh] (rotated in place) -> out [g, T, H dh]."""
+        torch, s = self.torch, self.shape
+        g = qkv.shape[0]
+        out = torch.empty((g, s.T, s.n_heads * s.head_dim), dtype=self.act_dtype, device=qkv.device)
+        _check(self.lib, self.lib.armt_segment_attention(C.byref(self.cfg), g, _ptr(qkv), _ptr(out), _ptr(self.ws),
+                                                         self.ws.numel(), _stream(torch)))
+        return out
+
+    def assoc_read(self, x, wm_q_list, A, z):
+        """x [g, T, d] fp32, updated in place."""
+        _check(self.lib, self.lib.armt_assoc_read(C.byref(self.cfg), x.shape[0], _ptr(x), _ptr_array(wm_q_list), _ptr(A),
+                                                  _ptr(z), _ptr(self.ws), self.ws.numel(), _stream(self.torch)))
+        return x
+
+    def assoc_update(self, ym, wm_k_list, wm_v_list, wm_b_list, A, z, empty_group=-1):
+        """ym [g, m, d] fp32; A [g, d, Phi], z [g, Phi] fp32 updated in place."""
+        _check(self.lib, self.lib.armt_assoc_update(C.byref(self.cfg), ym.shape[0], _ptr(ym), _ptr_array(wm_k_list),
+                                                    _ptr_array(wm_v_list), _ptr_array(wm_b_list), empty_group, _ptr(A),
+                                                    _ptr(z), _ptr(self.ws), self.ws.numel(), _stream(self.torch)))
+        return A, z

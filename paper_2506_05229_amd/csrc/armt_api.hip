@@ -7,11 +7,13 @@
 #include <cstdlib>
 #include <cstring>
 #include <string>
+#include <type_traits>
 #include <vector>
 
 #include "attention_generic.h"
 #include "common.h"
 #include "gemm_generic.h"
+#include "gemm_mfma.h"
 #include "rowwise_kernels.h"
 
 using namespace armt;
@@ -65,7 +67,8 @@ armt_status check_config(const armt_config* c, Dims* out) {
   if (D.Phi > 512) return ARMT_ERR_UNSUPPORTED;          // the delta-rule kernel keeps a row of A in registers
   if ((size_t)D.m * D.Phi * 4 + (size_t)D.m * 16 > 60000) return ARMT_ERR_UNSUPPORTED;   // phi(k_i) of a cell live in LDS
   if (D.bf16) {
-    if (D.d % 32 || D.F % 32 || D.dh % 32 || D.dm % 32 || D.m % 16) return ARMT_ERR_UNSUPPORTED;
+    // the MFMA GEMM takes k-tiles of 64 and 16-byte rows
+    if (D.d % 64 || D.F % 64 || D.Phi % 64 || D.dm % 8 || D.m % 16) return ARMT_ERR_UNSUPPORTED;
     if (D.dh != 64 && D.dh != 128) return ARMT_ERR_UNSUPPORTED;
   }
   if (out) *out = D;
@@ -184,10 +187,22 @@ armt_status upload_tables(Ctx& c, const armt_layer_weights* W, float* A, float* 
   return ARMT_OK;
 }
 
+// ARMT_DEBUG_GENERIC=1 routes bf16 work through the plain fp32-FMA kernels (slow; for debugging only).
+bool debug_generic() {
+  static const bool v = [] { const char* e = getenv("ARMT_DEBUG_GENERIC"); return e && e[0] == '1'; }();
+  return v;
+}
+
+int g_gemm_tile_config = -1;     // armt_set_gemm_tile_config
+
 template <typename T>
 armt_status gemm(hipStream_t st, const GemmGroup* table, int first, int g, const GemmShape& s) {
   if (g <= 0) return ARMT_OK;
-  HIP_TRY(launch_gemm_generic<T>(table, first, g, s, st));
+  if (std::is_same<T, bf16>::value && !debug_generic()) {
+    HIP_TRY(launch_gemm_mfma(table, first, g, s, st, g_gemm_tile_config));
+  } else {
+    HIP_TRY(launch_gemm_generic<T>(table, first, g, s, st));
+  }
   return ARMT_OK;
 }
 
@@ -357,6 +372,38 @@ armt_status forward_impl(const armt_config* cfg, const armt_layer_weights* layer
 
 }  // namespace
 
+namespace {
+
+armt_status step_prologue(const armt_config* cfg, int32_t g, void* workspace, size_t workspace_bytes, void* stream,
+                          Ctx* c) {
+  ARMT_TRY(check_config(cfg, &c->D));
+  if (g < 1 || g > c->D.L) return ARMT_ERR_SHAPE;
+  c->o = carve(c->D);
+  if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < c->o.total) return ARMT_ERR_WORKSPACE;
+  c->ws = (char*)workspace;
+  c->st = (hipStream_t)stream;
+  fill_shapes(*c);
+  return ARMT_OK;
+}
+
+armt_status upload(Ctx& c, const std::vector<GemmGroup>& tab, const std::vector<LayerAux>& aux) {
+  if (!tab.empty())
+    HIP_TRY(hipMemcpyAsync(c.ws + c.o.Tables, tab.data(), tab.size() * sizeof(GemmGroup), hipMemcpyHostToDevice, c.st));
+  if (!aux.empty())
+    HIP_TRY(hipMemcpyAsync(c.ws + c.o.Aux, aux.data(), aux.size() * sizeof(LayerAux), hipMemcpyHostToDevice, c.st));
+  HIP_TRY(hipStreamSynchronize(c.st));
+  c.tables = c.at<GemmGroup>(c.o.Tables);
+  c.aux = c.at<LayerAux>(c.o.Aux);
+  return ARMT_OK;
+}
+
+template <typename T>
+armt_status gemm_entry(int32_t g, const GemmShape& s, const GemmGroup* table, hipStream_t st) {
+  return gemm<T>(st, table, 0, g, s);
+}
+
+}  // namespace
+
 extern "C" {
 
 size_t armt_workspace_bytes(const armt_config* cfg) {
@@ -381,6 +428,122 @@ armt_status armt_forward_diagonal(const armt_config* cfg, const armt_layer_weigh
                       workspace_bytes, hip_stream, true);
 }
 
+// ---- single-step entry points: build a small table for the caller's buffers, then run the same
+// step functions as the forward path.
+
+armt_status armt_grouped_gemm(int32_t dtype, int32_t g, int32_t M, int32_t N, int32_t K, const void* const* a,
+                              const void* const* b, void* const* c, void* workspace, size_t workspace_bytes,
+                              void* hip_stream) {
+  if (dtype != ARMT_F32 && dtype != ARMT_BF16) return ARMT_ERR_DTYPE;
+  if (!a || !b || !c) return ARMT_ERR_NULL;
+  if (g < 1 || M < 1 || N < 1 || K < 1) return ARMT_ERR_SHAPE;
+  if (dtype == ARMT_BF16 && K % 64 != 0) return ARMT_ERR_UNSUPPORTED;
+  if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < (size_t)g * sizeof(GemmGroup))
+    return ARMT_ERR_WORKSPACE;
+  std::vector<GemmGroup> tab(g);
+  memset(tab.data(), 0, tab.size() * sizeof(GemmGroup));
+  for (int i = 0; i < g; ++i) {
+    if (!a[i] || !b[i] || !c[i]) return ARMT_ERR_NULL;
+    tab[i].A = a[i]; tab[i].B0 = b[i]; tab[i].C = c[i];
+  }
+  hipStream_t st = (hipStream_t)hip_stream;
+  HIP_TRY(hipMemcpyAsync(workspace, tab.data(), tab.size() * sizeof(GemmGroup), hipMemcpyHostToDevice, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  GemmShape s;
+  s.M = M; s.N = N; s.K = K; s.lda = K; s.ldc = N; s.ldc2 = 0; s.ldr = 0; s.n0 = N; s.n1 = 0; s.epi = EPI_STORE_ACT;
+  if (dtype == ARMT_BF16) return gemm_entry<bf16>(g, s, (const GemmGroup*)workspace, st);
+  return gemm_entry<float>(g, s, (const GemmGroup*)workspace, st);
+}
+
+armt_status armt_segment_attention(const armt_config* cfg, int32_t g, void* qkv, void* out, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream) {
+  Ctx c;
+  ARMT_TRY(step_prologue(cfg, g, workspace, workspace_bytes, hip_stream, &c));
+  if (!qkv || !out) return ARMT_ERR_NULL;
+  const Dims& D = c.D;
+  const int n = D.T * (D.dh / 2);
+  rope_table_kernel<<<(n + 255) / 256, 256, 0, c.st>>>(c.at<float>(c.o.Rope), D.T, D.dh / 2, (double)D.rope_theta);
+  HIP_TRY(hipGetLastError());
+  if (D.bf16)
+    return step_attention<bf16>(c.st, (bf16*)qkv, (bf16*)out, c.at<float>(c.o.Rope), 0, g, D.T, D.H, D.Hkv, D.dh);
+  return step_attention<float>(c.st, (float*)qkv, (float*)out, c.at<float>(c.o.Rope), 0, g, D.T, D.H, D.Hkv, D.dh);
+}
+
+armt_status armt_assoc_read(const armt_config* cfg, int32_t g, float* x, const void* const* wm_q, const float* A,
+                            const float* z, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Ctx c;
+  ARMT_TRY(step_prologue(cfg, g, workspace, workspace_bytes, hip_stream, &c));
+  if (!x || !wm_q || !A || !z) return ARMT_ERR_NULL;
+  const Dims& D = c.D;
+  const size_t T = D.T, L = D.L;
+  std::vector<GemmGroup> tab((size_t)K_COUNT * L);
+  std::vector<LayerAux> aux(L);
+  memset(tab.data(), 0, tab.size() * sizeof(GemmGroup));
+  memset(aux.data(), 0, aux.size() * sizeof(LayerAux));
+  if (D.bf16) {     // bf16 operands of the two GEMMs: the rows of x and the memory matrices
+    f32_to_bf16_kernel<<<1024, 256, 0, c.st>>>(c.at<bf16>(c.o.Xb), x, (size_t)g * T * D.d);
+    f32_to_bf16_kernel<<<1024, 256, 0, c.st>>>(c.at<bf16>(c.o.A16), A, (size_t)g * D.d * D.Phi);
+    HIP_TRY(hipGetLastError());
+  }
+  for (int i = 0; i < g; ++i) {
+    if (!wm_q[i]) return ARMT_ERR_NULL;
+    GemmGroup* q = &tab[K_MQ * L + i];
+    q->A = D.bf16 ? (const void*)(c.at<bf16>(c.o.Xb) + i * T * D.d) : (const void*)(x + i * T * D.d);
+    q->B0 = wm_q[i];
+    q->C = c.ws + c.o.Qm + i * T * D.dm * 4;
+    GemmGroup* r = &tab[K_READ * L + i];
+    r->A = c.ws + c.o.Fphi + i * T * D.Phi * D.esz;
+    r->B0 = D.bf16 ? (const void*)(c.at<bf16>(c.o.A16) + (size_t)i * D.d * D.Phi) : (const void*)(A + (size_t)i * D.d * D.Phi);
+    r->C = x + i * T * D.d;
+    r->R = x + i * T * D.d;
+    r->rowscale = (const float*)(c.ws + c.o.RDen + i * T * 4);
+    aux[i].z = const_cast<float*>(z) + (size_t)i * D.Phi;
+  }
+  ARMT_TRY(upload(c, tab, aux));
+  if (D.bf16)
+    return step_assoc_read<bf16>(c.st, c.table(K_MQ), c.shape[K_MQ], c.table(K_READ), c.shape[K_READ], c.aux, 0, g, D.T,
+                                 D.dm, D.nu, D.assoc_eps, c.at<float>(c.o.Qm), c.at<bf16>(c.o.Fphi), c.at<float>(c.o.RDen));
+  return step_assoc_read<float>(c.st, c.table(K_MQ), c.shape[K_MQ], c.table(K_READ), c.shape[K_READ], c.aux, 0, g, D.T,
+                                D.dm, D.nu, D.assoc_eps, c.at<float>(c.o.Qm), c.at<float>(c.o.Fphi), c.at<float>(c.o.RDen));
+}
+
+armt_status armt_assoc_update(const armt_config* cfg, int32_t g, const float* ym, const void* const* wm_k,
+                              const void* const* wm_v, const void* const* wm_b, int32_t empty_group, float* A,
+                              float* z, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Ctx c;
+  ARMT_TRY(step_prologue(cfg, g, workspace, workspace_bytes, hip_stream, &c));
+  if (!ym || !wm_k || !wm_v || !wm_b || !A || !z) return ARMT_ERR_NULL;
+  if (empty_group < -1 || empty_group >= g) return ARMT_ERR_SHAPE;
+  const Dims& D = c.D;
+  const size_t L = D.L, md = (size_t)D.m * D.d;
+  std::vector<GemmGroup> tab((size_t)K_COUNT * L);
+  std::vector<LayerAux> aux(L);
+  memset(tab.data(), 0, tab.size() * sizeof(GemmGroup));
+  memset(aux.data(), 0, aux.size() * sizeof(LayerAux));
+  if (D.bf16) {
+    f32_to_bf16_kernel<<<256, 256, 0, c.st>>>(c.at<bf16>(c.o.Xb), ym, (size_t)g * md);
+    HIP_TRY(hipGetLastError());
+  }
+  for (int i = 0; i < g; ++i) {
+    if (!wm_k[i] || !wm_v[i] || !wm_b[i]) return ARMT_ERR_NULL;
+    GemmGroup* k = &tab[K_MKV * L + i];
+    k->A = D.bf16 ? (const void*)(c.at<bf16>(c.o.Xb) + i * md) : (const void*)(ym + i * md);
+    k->B0 = wm_k[i];
+    k->B1 = wm_v[i];
+    k->C = c.ws + c.o.KVm + (size_t)i * D.m * (D.dm + D.d) * 4;
+    aux[i].wm_b = wm_b[i];
+    aux[i].A = A + (size_t)i * D.d * D.Phi;
+    aux[i].z = z + (size_t)i * D.Phi;
+  }
+  ARMT_TRY(upload(c, tab, aux));
+  if (D.bf16)
+    return step_assoc_update<bf16>(c.st, c.table(K_MKV), c.shape[K_MKV], c.aux, 0, g, empty_group, c.at<bf16>(c.o.Xb), md,
+                                   D.m, D.d, D.dm, D.nu, D.assoc_eps, c.at<float>(c.o.KVm), c.at<float>(c.o.Fm),
+                                   c.at<float>(c.o.Coef));
+  return step_assoc_update<float>(c.st, c.table(K_MKV), c.shape[K_MKV], c.aux, 0, g, empty_group, ym, md, D.m, D.d, D.dm,
+                                  D.nu, D.assoc_eps, c.at<float>(c.o.KVm), c.at<float>(c.o.Fm), c.at<float>(c.o.Coef));
+}
+
 int32_t armt_diagonal_group(int32_t n_layers, int32_t n_segments, int32_t t, int32_t* l_lo, int32_t* l_hi) {
   if (n_layers < 1 || n_segments < 1 || t < 0 || (int64_t)t > (int64_t)n_layers + n_segments - 2) return 0;
   // cell (l, s = t - l) is live iff 0 <= l < L and 0 <= t - l < N
@@ -389,6 +552,12 @@ int32_t armt_diagonal_group(int32_t n_layers, int32_t n_segments, int32_t t, int
   if (l_lo) *l_lo = lo;
   if (l_hi) *l_hi = hi;
   return hi - lo + 1;
+}
+
+int32_t armt_set_gemm_tile_config(int32_t config) {
+  const int32_t old = g_gemm_tile_config;
+  g_gemm_tile_config = (config >= 0 && config < MF_NUM_CONFIGS) ? config : -1;
+  return old;
 }
 
 const char* armt_status_str(armt_status s) {

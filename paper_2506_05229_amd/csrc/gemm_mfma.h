@@ -1,0 +1,232 @@
+// Grouped bf16 GEMM on the CDNA4 matrix cores (paper Section 3.3 item 1, Section 4.1).
+//
+//   C_g = A_g B_g^T for every group g of the launch; A_g [M, K] activations, B_g [N, K] the
+//   weights of the group's own layer (taken from a pointer table, never stacked), fp32
+//   accumulation in v_mfma_f32_32x32x16_bf16, epilogue fused (residual add, row scale,
+//   SwiGLU, bf16 copy).
+//
+// Tiling: one workgroup per BM x BN output tile, BK = 64.  Both operands are K-contiguous, so a
+// tile row is 128 bytes = eight 16-byte chunks; chunks are XOR-swizzled inside a row so that the
+// MFMA fragment reads (one row per lane, 16 bytes) spread over all LDS banks.  Tiles are double
+// buffered in LDS and filled by direct global-to-LDS loads (no staging registers): the copies of
+// k-tile i+1 are in flight while k-tile i is multiplied.
+// The 1-D grid is laid out so that each XCD (workgroup id mod 8) owns a contiguous run of the
+// group-major tile sequence: with 16 groups every XCD streams the weights of 2 layers through its
+// own L2, and the M-tiles sharing a weight panel run back to back.
+#pragma once
+
+#include "common.h"
+#include "gemm_generic.h"
+
+namespace armt {
+
+constexpr int MF_BK = 64;                 // k-tile (bf16 elements): 128 bytes per tile row
+constexpr int MF_ROW_BYTES = MF_BK * 2;
+constexpr int MF_NUM_CONFIGS = 4;         // tile configurations of launch_gemm_mfma_epi
+
+// swizzle of the 16-byte chunk index inside a 128-byte tile row; depends on row bits 0..3 only
+__device__ __forceinline__ int mf_swz(int row) { return ((row >> 1) & 7) ^ ((row & 1) << 2); }
+
+template <int BM, int BN, int WGM, int WGN, int EPI>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGroup* __restrict__ table, int first,
+                                                                  GemmShape s, int tiles_m, int tiles_n,
+                                                                  int total_tiles) {
+  constexpr int NW = WGM * WGN;
+  constexpr int WROWS = BM / WGM, WCOLS = BN / WGN;       // wave tile
+  constexpr int TM = WROWS / 32, TN = WCOLS / 32;         // 32x32 MFMA tiles per wave
+  constexpr int A_DMA = BM / 8 / NW, B_DMA = BN / 8 / NW; // 8-row (1 KB) slabs each wave copies per k-tile
+  constexpr int A_BYTES = BM * MF_ROW_BYTES, B_BYTES = BN * MF_ROW_BYTES;
+  constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;   // output columns per tile
+  static_assert(BM % (WGM * 32) == 0 && BN % (WGN * 32) == 0, "wave tile must be a multiple of 32x32");
+  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must divide into 8-row slabs per wave");
+  static_assert(EPI != EPI_SWIGLU || TN % 2 == 0, "SwiGLU pairs gate/up 32-column tiles inside a wave");
+
+  extern __shared__ __align__(16) unsigned char smem[];   // [2][A_BYTES] then [2][B_BYTES]
+
+  // XCD-aware tile order: workgroup b runs on XCD b % 8; give each XCD a contiguous range.
+  const int per_xcd = (total_tiles + 7) >> 3;
+  const int lid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (lid >= total_tiles) return;
+  const int per_group = tiles_m * tiles_n;
+  const int grp = lid / per_group, rem = lid - grp * per_group;
+  const int tn = rem / tiles_m, tm = rem - tn * tiles_m;    // M-tiles of one weight panel are adjacent
+  const GemmGroup g = table[first + grp];
+  const int m0 = tm * BM, n0 = tn * BN_OUT;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  // ---- global -> LDS copies go straight to LDS (global_load_lds_dwordx4): one instruction moves 64 x 16
+  // bytes into 1 KB of consecutive LDS = 8 tile rows.  Lane i fills row i / 8, physical chunk i % 8 of the
+  // slab, so it fetches the logical chunk (i % 8) ^ swz(row) of that row from global memory.
+  const char* ap[A_DMA];
+  const char* bp[B_DMA];
+  {
+    const int R = lane >> 3, pc = lane & 7;
+#pragma unroll
+    for (int j = 0; j < A_DMA; ++j) {
+      const int row = (wave + j * NW) * 8 + R;
+      const int m = min(m0 + row, s.M - 1);                // rows past M re-read the last row; masked on store
+      ap[j] = (const char*)g.A + ((size_t)m * s.lda + ((pc ^ mf_swz(row)) << 3)) * 2;
+    }
+#pragma unroll
+    for (int j = 0; j < B_DMA; ++j) {
+      const int row = (wave + j * NW) * 8 + R;
+      const bf16* p;
+      if (EPI == EPI_SWIGLU) {
+        // tile rows come in 32-row blocks: even blocks from the gate weight, odd from the up weight,
+        // both for output columns n0 + (block / 2) * 32 ...
+        const int blk = row >> 5;
+        const int n = min(n0 + (blk >> 1) * 32 + (row & 31), s.N - 1);
+        p = (const bf16*)((blk & 1) ? g.B1 : g.B0) + (size_t)n * s.K;
+      } else {
+        p = weight_row<bf16>(g, s, min(n0 + row, s.N - 1));
+      }
+      bp[j] = (const char*)(p + ((pc ^ mf_swz(row)) << 3));
+    }
+  }
+  auto issue_tile = [&](int kt, int buf) {
+    typedef const __attribute__((address_space(1))) void* gptr_t;
+    typedef __attribute__((address_space(3))) void* lptr_t;
+    unsigned char* As = smem + buf * A_BYTES;
+    unsigned char* Bs = smem + 2 * A_BYTES + buf * B_BYTES;
+#pragma unroll
+    for (int j = 0; j < A_DMA; ++j)
+      __builtin_amdgcn_global_load_lds((gptr_t)(ap[j] + (size_t)kt * MF_ROW_BYTES), (lptr_t)(As + (wave + j * NW) * 1024),
+                                       16, 0, 0);
+#pragma unroll
+    for (int j = 0; j < B_DMA; ++j)
+      __builtin_amdgcn_global_load_lds((gptr_t)(bp[j] + (size_t)kt * MF_ROW_BYTES), (lptr_t)(Bs + (wave + j * NW) * 1024),
+                                       16, 0, 0);
+  };
+
+  // ---- MFMA fragment addresses: lane reads tile row (lane % 32) of each 32-row block, chunk 2*ks + lane/32
+  const int fl = mf_swz(lane & 31), half = lane >> 5;
+  int koff[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) koff[ks] = ((2 * ks + half) ^ fl) << 4;
+  const int a_frag = (wm * WROWS + (lane & 31)) * MF_ROW_BYTES;
+  const int b_frag = (wn * WCOLS + (lane & 31)) * MF_ROW_BYTES;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = s.K / MF_BK;
+  issue_tile(0, 0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's copies have landed in LDS
+  __syncthreads();                        // ... and everybody else's
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    // the other buffer was last read in iteration kt - 1, which ended with a barrier
+    if (kt + 1 < nk) issue_tile(kt + 1, cur ^ 1);
+    const unsigned char* As = smem + cur * A_BYTES + a_frag;
+    const unsigned char* Bs = smem + 2 * A_BYTES + cur * B_BYTES + b_frag;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      bf16x8 af[TM], bfr[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8*)(As + i * 32 * MF_ROW_BYTES + koff[ks]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8*)(Bs + j * 32 * MF_ROW_BYTES + koff[ks]);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+  }
+
+  // ---- epilogue.  32x32 result tile: lane holds column lane % 32, rows 8*(r/4) + 4*(lane/32) + r%4.
+  const int col_in = lane & 31;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int m = m0 + wm * WROWS + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+      if (m >= s.M) continue;
+      if (EPI == EPI_SWIGLU) {
+#pragma unroll
+        for (int j = 0; j < TN; j += 2) {
+          const int n = n0 + ((wn * TN + j) >> 1) * 32 + col_in;
+          if (n >= s.N) continue;
+          const float gt = acc[i][j][r], up = acc[i][j + 1][r];
+          ((bf16*)g.C)[(size_t)m * s.ldc + n] = (bf16)(gt / (1.f + __expf(-gt)) * up);
+        }
+      } else {
+        float rs = 1.f;
+        if (EPI == EPI_RESID_F32 && g.rowscale) rs = g.rowscale[m];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int n = n0 + wn * WCOLS + j * 32 + col_in;
+          if (n >= s.N) continue;
+          const float v = acc[i][j][r];
+          if (EPI == EPI_STORE_ACT) {
+            ((bf16*)g.C)[(size_t)m * s.ldc + n] = (bf16)v;
+          } else if (EPI == EPI_STORE_F32) {
+            ((float*)g.C)[(size_t)m * s.ldc + n] = v;
+          } else {
+            const float o = (g.R ? g.R[(size_t)m * s.ldr + n] : 0.f) + v * rs;
+            ((float*)g.C)[(size_t)m * s.ldc + n] = o;
+            if (g.C2) ((bf16*)g.C2)[(size_t)m * s.ldc2 + n] = (bf16)o;
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WGM, int WGN, int EPI>
+inline hipError_t launch_mfma_cfg(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st) {
+  constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
+  constexpr int LDS = 2 * (BM + BN) * MF_ROW_BYTES;
+  const int tiles_m = (s.M + BM - 1) / BM, tiles_n = (s.N + BN_OUT - 1) / BN_OUT;
+  const int total = g * tiles_m * tiles_n;
+  const int grid = ((total + 7) / 8) * 8;
+  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, EPI>;
+  static bool attr_set = false;            // raising the dynamic-LDS limit is a per-function, idempotent setting
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  kern<<<grid, WGM * WGN * 64, LDS, st>>>(table, first, s, tiles_m, tiles_n, total);
+  return hipGetLastError();
+}
+
+// Tile configuration by problem shape: big square tiles for the block's linears, small tiles for
+// the skinny associative-memory projections (N = d_mem columns, or M = n_mem rows).
+template <int EPI>
+inline hipError_t launch_gemm_mfma_epi(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st,
+                                       int force_cfg) {
+  int cfg = force_cfg;
+  if (cfg < 0) cfg = (s.M >= 192 && s.N >= 192) ? 0 : ((s.M >= 96 && s.N >= 96) ? 1 : 2);
+  switch (cfg) {
+    case 0: return launch_mfma_cfg<256, 256, 2, 4, EPI>(table, first, g, s, st);
+    case 1: return launch_mfma_cfg<128, 128, 2, 2, EPI>(table, first, g, s, st);
+    case 3: return launch_mfma_cfg<256, 256, 2, 2, EPI>(table, first, g, s, st);
+    default: return launch_mfma_cfg<64, 128, 2, 2, EPI>(table, first, g, s, st);
+  }
+}
+
+inline hipError_t launch_gemm_mfma(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st,
+                                   int force_cfg = -1) {
+  if (g <= 0 || s.M <= 0 || s.N <= 0) return hipSuccess;
+  switch (s.epi) {
+    case EPI_STORE_ACT: return launch_gemm_mfma_epi<EPI_STORE_ACT>(table, first, g, s, st, force_cfg);
+    case EPI_STORE_F32: return launch_gemm_mfma_epi<EPI_STORE_F32>(table, first, g, s, st, force_cfg);
+    case EPI_RESID_F32: return launch_gemm_mfma_epi<EPI_RESID_F32>(table, first, g, s, st, force_cfg);
+    case EPI_SWIGLU: return launch_gemm_mfma_epi<EPI_SWIGLU>(table, first, g, s, st, force_cfg);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace armt
