@@ -1,0 +1,128 @@
+#!/usr/bin/env python3
+"""Headline benchmark: ARMT forward with Diagonal Batching on one MI355X.
+
+One "step" is one whole forward pass (every cell of every segment: associative read, decoder block,
+memory update) over one synthetic sequence that is already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1b_128k] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense bf16 matrix-core peak (published)
+FP32_VALU_PEAK_TFLOPS = 157.3
+
+
+def cpu_baseline(shape, layers, mem_emb, x, n_seg):
+    """The oracle as it stands, timed on this machine's host cores on the first n_seg segments."""
+    import numpy as np
+    from oracle import armt_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    n_tok = n_seg * shape.seg_len
+    t0 = time.perf_counter()
+    O.armt_forward_sequential(shape, layers, mem_emb, x[:n_tok])
+    dt = time.perf_counter() - t0
+    return {"value": n_tok / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {n_seg} segments ({n_tok} tokens) of the same workload, float64 numpy, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="1b_128k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sequential", action="store_true")
+    ap.add_argument("--cpu-segments", type=int, default=2)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import armt_synth as S
+    import paper_2506_05229_amd as P
+
+    shape = S.get_shape(args.workload)
+    t_gen = time.perf_counter()
+    layers, mem_emb = S.make_weights(shape, seed=0)
+    x = S.make_embeddings(shape, seed=0)
+    t_gen = time.perf_counter() - t_gen
+    model = P.Armt(shape, layers, mem_emb)
+    xd = model.embed(x)
+    out = model.forward(xd, diagonal=True)            # allocates the outputs once
+    torch.cuda.synchronize()
+
+    def timed(diagonal, steps, warmup, profile=None):
+        for _ in range(warmup):
+            model.forward(xd, diagonal=diagonal, out=out)
+        torch.cuda.synchronize()
+        if profile:
+            P.profile_begin(profile, steps * (shape.n_layers + shape.n_segments))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            model.forward(xd, diagonal=diagonal, out=out)
+        e1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) / steps
+        prof = P.profile_end() if profile else None
+        return e0.elapsed_time(e1) / steps, wall * 1e3, prof
+
+    ms, wall_ms, prof = timed(True, args.steps, args.warmup, profile="gate_up")
+    n_tok = shape.n_tokens
+    total_flops = shape.flops_total()
+    res = {
+        "metric": "ARMT forward tokens/s, Diagonal Batching, 131072 tokens" if n_tok == 131072
+                  else f"ARMT forward tokens/s, Diagonal Batching, {n_tok} tokens",
+        "value": n_tok / (wall_ms / 1e3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall_ms, "gpu_ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": f"{shape.name}: {shape.n_layers} layers, d_model {shape.d_model}, "
+                               f"{shape.n_heads}/{shape.n_kv_heads} heads x {shape.head_dim}, d_ff {shape.d_ff}, "
+                               f"segment {shape.seg_len} + {shape.n_mem} memory tokens, d_mem {shape.d_mem}, "
+                               f"{shape.n_segments} segments, batch 1, N(0,0.02) weights, N(0,1) embeddings, seed 0",
+                   "cells": shape.n_layers * shape.n_segments,
+                   "diagonal_steps": shape.n_layers + shape.n_segments - 1,
+                   "algorithmic_tflop": total_flops / 1e12},
+        "mfma_fraction_end_to_end": total_flops / (ms / 1e3) / 1e12 / MFMA_PEAK_TFLOPS,
+    }
+    # roofline of the dominant kernel: the gate/up grouped GEMM with the SwiGLU epilogue
+    k_ms, k_launches, k_groups = prof
+    if k_launches:
+        flops_per_cell = 2.0 * shape.T * shape.d_model * 2 * shape.d_ff
+        per_launch = flops_per_cell * k_groups / k_launches
+        achieved = per_launch / (k_ms / k_launches / 1e3) / 1e12
+        res["roofline"] = {"kernel": "gemm_mfma_kernel<..., EPI_SWIGLU> (gate/up grouped GEMM + SiLU*up)",
+                           "bound": "mfma", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                           "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": None,
+                           "avg_launch_ms": k_ms / k_launches, "launches": k_launches,
+                           "avg_groups_per_launch": k_groups / k_launches,
+                           "algorithmic_gflop_per_launch": per_launch / 1e9}
+    if not args.no_sequential:
+        sms, swall, _ = timed(False, max(1, min(args.steps, 2)), 0)
+        res["sequential_tokens_per_s"] = n_tok / (swall / 1e3)
+        res["speedup_vs_sequential"] = swall / wall_ms
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(shape, layers, mem_emb, x, min(args.cpu_segments, shape.n_segments))
+    res["input_generation_s"] = t_gen
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -161,6 +161,17 @@ armt_status armt_assoc_update(const armt_config *cfg, int32_t g, const float *ym
  * Returns the previous setting.  Not thread safe. */
 int32_t armt_set_gemm_tile_config(int32_t config);
 
+/* Kernel timing for benchmarks: between armt_profile_begin and armt_profile_end every launch of one
+ * grouped GEMM of the step (up to max_launches of them) made by this process is bracketed by a pair of
+ * HIP events on the launch stream.  gemm_kind: 0 W_Q projection of the read, 1 read A phi, 2 QKV,
+ * 3 attention output, 4 gate/up with SwiGLU, 5 down, 6 W_K / W_V projections of the update.
+ * armt_profile_end waits for the recorded events and returns the summed kernel time in milliseconds,
+ * the number of launches timed and the number of groups (cells) they covered; any pointer may be NULL.
+ * Not thread safe; the events are created in begin and destroyed in end. */
+armt_status armt_profile_begin(int32_t gemm_kind, int32_t max_launches);
+armt_status armt_profile_end(double *total_ms /* [host] */, int64_t *launches /* [host] */,
+                             int64_t *groups /* [host] */);
+
 /* Text for a status code (static string). */
 const char *armt_status_str(armt_status s);
 

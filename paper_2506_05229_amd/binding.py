@@ -73,6 +73,10 @@ def load_library():
     lib.armt_assoc_update.restype = C.c_int
     lib.armt_set_gemm_tile_config.argtypes = [i32]
     lib.armt_set_gemm_tile_config.restype = i32
+    lib.armt_profile_begin.argtypes = [i32, i32]
+    lib.armt_profile_begin.restype = C.c_int
+    lib.armt_profile_end.argtypes = [C.POINTER(C.c_double), C.POINTER(i64), C.POINTER(i64)]
+    lib.armt_profile_end.restype = C.c_int
     lib.armt_status_str.argtypes = [C.c_int]
     lib.armt_status_str.restype = C.c_char_p
     lib.armt_last_hip_error.argtypes = []
@@ -161,6 +165,22 @@ def _stream(torch):
 
 def set_gemm_tile_config(config: int) -> int:
     return load_library().armt_set_gemm_tile_config(config)
+
+
+GEMM_KINDS = {"mem_q": 0, "mem_read": 1, "qkv": 2, "attn_out": 3, "gate_up": 4, "down": 5, "mem_kv": 6}
+
+
+def profile_begin(kind: str, max_launches: int):
+    lib = load_library()
+    _check(lib, lib.armt_profile_begin(GEMM_KINDS[kind], max_launches))
+
+
+def profile_end():
+    """(total kernel ms, launches, groups) of the GEMM kind selected by profile_begin."""
+    lib = load_library()
+    ms, n, g = C.c_double(0.0), C.c_int64(0), C.c_int64(0)
+    _check(lib, lib.armt_profile_end(C.byref(ms), C.byref(n), C.byref(g)))
+    return ms.value, n.value, g.value
 
 
 def grouped_gemm(a_list, b_list, out_list=None, workspace=None):

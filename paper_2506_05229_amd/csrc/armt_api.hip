@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "attention_generic.h"
+#include "attention_mfma.h"
 #include "common.h"
 #include "gemm_generic.h"
 #include "gemm_mfma.h"
@@ -69,7 +70,8 @@ armt_status check_config(const armt_config* c, Dims* out) {
   if (D.bf16) {
     // the MFMA GEMM takes k-tiles of 64 and 16-byte rows
     if (D.d % 64 || D.F % 64 || D.Phi % 64 || D.dm % 8 || D.m % 16) return ARMT_ERR_UNSUPPORTED;
-    if (D.dh != 64 && D.dh != 128) return ARMT_ERR_UNSUPPORTED;
+    // the MFMA attention kernel: head_dim 64 or 128, one wave per query head of a KV group
+    if ((D.dh != 64 && D.dh != 128) || D.H / D.Hkv > 8) return ARMT_ERR_UNSUPPORTED;
   }
   if (out) *out = D;
   return ARMT_OK;
@@ -79,7 +81,7 @@ armt_status check_config(const armt_config* c, Dims* out) {
 enum Kind { K_MQ = 0, K_READ, K_QKV, K_O, K_GU, K_DOWN, K_MKV, K_COUNT };
 
 struct Layout {          // byte offsets into the workspace
-  size_t X, Xb, Nrm, QKV, Att, Hres, Uff, Qm, Fphi, RDen, A16, KVm, Fm, Coef, Rope, Tables, Aux, total;
+  size_t X, Xb, Nrm, QKV, Vt, Att, Hres, Uff, Qm, Fphi, RDen, A16, KVm, Fm, Coef, Rope, Tables, Aux, total;
 };
 
 Layout carve(const Dims& D) {
@@ -91,6 +93,7 @@ Layout carve(const Dims& D) {
   o.Xb = take(D.bf16 ? (L + 1) * T * D.d * 2 : 0);                // bf16 copy of the slots (GEMM operand)
   o.Nrm = take(L * T * D.d * D.esz);
   o.QKV = take(L * T * D.Nqkv * D.esz);
+  o.Vt = take(D.bf16 ? attention_vt_bytes(D.L, D.T, D.Hkv, D.dh) : 0);   // V transposed, for the MFMA attention
   o.Att = take(L * T * D.d * D.esz);
   o.Hres = take(L * T * D.d * 4);
   o.Uff = take(L * T * D.F * D.esz);
@@ -125,6 +128,7 @@ void fill_shapes(Ctx& c) {
   auto set = [&](int k, int M, int N, int K, int lda, int ldc, int ldc2, int ldr, int n0, int n1, int epi) {
     GemmShape s;
     s.M = M; s.N = N; s.K = K; s.lda = lda; s.ldc = ldc; s.ldc2 = ldc2; s.ldr = ldr; s.n0 = n0; s.n1 = n1; s.epi = epi;
+    s.tag = k;
     c.shape[k] = s;
   };
   set(K_MQ, D.T, D.dm, D.d, D.d, D.dm, 0, 0, D.dm, 0, EPI_STORE_F32);
@@ -195,13 +199,28 @@ bool debug_generic() {
 
 int g_gemm_tile_config = -1;     // armt_set_gemm_tile_config
 
+// Optional timing of one GEMM kind with HIP events on the launch stream (armt_profile_*).
+struct Profile {
+  int kind = -1;
+  std::vector<hipEvent_t> ev;    // start/stop pairs
+  size_t used = 0;               // events recorded so far
+  int64_t groups = 0;            // groups (cells) covered by the recorded launches
+} g_prof;
+
 template <typename T>
 armt_status gemm(hipStream_t st, const GemmGroup* table, int first, int g, const GemmShape& s) {
   if (g <= 0) return ARMT_OK;
+  const bool timed = (g_prof.kind >= 0 && g_prof.kind == s.tag && g_prof.used + 2 <= g_prof.ev.size());
+  if (timed) HIP_TRY(hipEventRecord(g_prof.ev[g_prof.used], st));
   if (std::is_same<T, bf16>::value && !debug_generic()) {
     HIP_TRY(launch_gemm_mfma(table, first, g, s, st, g_gemm_tile_config));
   } else {
     HIP_TRY(launch_gemm_generic<T>(table, first, g, s, st));
+  }
+  if (timed) {
+    HIP_TRY(hipEventRecord(g_prof.ev[g_prof.used + 1], st));
+    g_prof.used += 2;
+    g_prof.groups += g;
   }
   return ARMT_OK;
 }
@@ -222,12 +241,16 @@ armt_status step_assoc_read(hipStream_t st, const GemmGroup* t_mq, const GemmSha
 
 // Rotary embedding of q, k and causal grouped-query attention over the rows of each cell.
 template <typename T>
-armt_status step_attention(hipStream_t st, T* QKV, T* Att, const float* rope_cs, int first, int g, int Trows, int H,
-                           int Hkv, int dh) {
+armt_status step_attention(hipStream_t st, T* QKV, T* Att, bf16* Vt, const float* rope_cs, int first, int g, int Trows,
+                           int H, int Hkv, int dh) {
   if (g <= 0) return ARMT_OK;
   const int ldq = (H + 2 * Hkv) * dh;
   rope_kernel<T><<<dim3(Trows, g), 256, 0, st>>>(QKV, rope_cs, first, Trows, H + Hkv, dh, ldq);
   HIP_TRY(hipGetLastError());
+  if (std::is_same<T, bf16>::value && !debug_generic()) {
+    HIP_TRY(launch_attention_mfma((const bf16*)QKV, Vt, (bf16*)Att, first, g, Trows, H, Hkv, dh, st));
+    return ARMT_OK;
+  }
   attention_generic_kernel<T><<<dim3(Trows, H, g), 64, (dh + Trows) * 4, st>>>(QKV, Att, first, Trows, H, Hkv, dh,
                                                                               1.0f / sqrtf((float)dh));
   HIP_TRY(hipGetLastError());
@@ -269,8 +292,8 @@ armt_status run_group(const Ctx& c, int lo, int hi, int read_hi, int empty_layer
   rmsnorm_kernel<T><<<dim3(D.T, g), 256, 0, c.st>>>(X, c.aux, lo, 0, D.T, D.d, D.rms_eps, c.at<T>(c.o.Nrm));
   HIP_TRY(hipGetLastError());
   ARMT_TRY(gemm<T>(c.st, c.table(K_QKV), lo, g, c.shape[K_QKV]));
-  ARMT_TRY(step_attention<T>(c.st, c.at<T>(c.o.QKV), c.at<T>(c.o.Att), c.at<float>(c.o.Rope), lo, g, D.T, D.H, D.Hkv,
-                             D.dh));
+  ARMT_TRY(step_attention<T>(c.st, c.at<T>(c.o.QKV), c.at<T>(c.o.Att), c.at<bf16>(c.o.Vt), c.at<float>(c.o.Rope), lo, g,
+                             D.T, D.H, D.Hkv, D.dh));
   ARMT_TRY(gemm<T>(c.st, c.table(K_O), lo, g, c.shape[K_O]));
   rmsnorm_kernel<T><<<dim3(D.T, g), 256, 0, c.st>>>(c.at<float>(c.o.Hres), c.aux, lo, 1, D.T, D.d, D.rms_eps,
                                                     c.at<T>(c.o.Nrm));
@@ -451,6 +474,7 @@ armt_status armt_grouped_gemm(int32_t dtype, int32_t g, int32_t M, int32_t N, in
   HIP_TRY(hipStreamSynchronize(st));
   GemmShape s;
   s.M = M; s.N = N; s.K = K; s.lda = K; s.ldc = N; s.ldc2 = 0; s.ldr = 0; s.n0 = N; s.n1 = 0; s.epi = EPI_STORE_ACT;
+  s.tag = -1;
   if (dtype == ARMT_BF16) return gemm_entry<bf16>(g, s, (const GemmGroup*)workspace, st);
   return gemm_entry<float>(g, s, (const GemmGroup*)workspace, st);
 }
@@ -465,8 +489,10 @@ armt_status armt_segment_attention(const armt_config* cfg, int32_t g, void* qkv,
   rope_table_kernel<<<(n + 255) / 256, 256, 0, c.st>>>(c.at<float>(c.o.Rope), D.T, D.dh / 2, (double)D.rope_theta);
   HIP_TRY(hipGetLastError());
   if (D.bf16)
-    return step_attention<bf16>(c.st, (bf16*)qkv, (bf16*)out, c.at<float>(c.o.Rope), 0, g, D.T, D.H, D.Hkv, D.dh);
-  return step_attention<float>(c.st, (float*)qkv, (float*)out, c.at<float>(c.o.Rope), 0, g, D.T, D.H, D.Hkv, D.dh);
+    return step_attention<bf16>(c.st, (bf16*)qkv, (bf16*)out, c.at<bf16>(c.o.Vt), c.at<float>(c.o.Rope), 0, g, D.T, D.H,
+                                D.Hkv, D.dh);
+  return step_attention<float>(c.st, (float*)qkv, (float*)out, nullptr, c.at<float>(c.o.Rope), 0, g, D.T, D.H, D.Hkv,
+                               D.dh);
 }
 
 armt_status armt_assoc_read(const armt_config* cfg, int32_t g, float* x, const void* const* wm_q, const float* A,
@@ -558,6 +584,48 @@ int32_t armt_set_gemm_tile_config(int32_t config) {
   const int32_t old = g_gemm_tile_config;
   g_gemm_tile_config = (config >= 0 && config < MF_NUM_CONFIGS) ? config : -1;
   return old;
+}
+
+armt_status armt_profile_begin(int32_t gemm_kind, int32_t max_launches) {
+  if (gemm_kind < 0 || gemm_kind >= K_COUNT || max_launches < 1) return ARMT_ERR_SHAPE;
+  armt_profile_end(nullptr, nullptr, nullptr);
+  g_prof.ev.resize((size_t)max_launches * 2);
+  for (size_t i = 0; i < g_prof.ev.size(); ++i) {
+    if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) {
+      for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(g_prof.ev[j]);
+      g_prof.ev.clear();
+      g_hip_error = "hipEventCreate failed";
+      return ARMT_ERR_HIP;
+    }
+  }
+  g_prof.used = 0;
+  g_prof.groups = 0;
+  g_prof.kind = gemm_kind;
+  return ARMT_OK;
+}
+
+armt_status armt_profile_end(double* total_ms, int64_t* launches, int64_t* groups) {
+  double sum = 0.0;
+  armt_status rc = ARMT_OK;
+  for (size_t i = 0; i + 1 < g_prof.used; i += 2) {
+    float ms = 0.f;
+    if (hipEventSynchronize(g_prof.ev[i + 1]) != hipSuccess ||
+        hipEventElapsedTime(&ms, g_prof.ev[i], g_prof.ev[i + 1]) != hipSuccess) {
+      g_hip_error = "hipEventElapsedTime failed";
+      rc = ARMT_ERR_HIP;
+      break;
+    }
+    sum += ms;
+  }
+  if (total_ms) *total_ms = sum;
+  if (launches) *launches = (int64_t)(g_prof.used / 2);
+  if (groups) *groups = g_prof.groups;
+  for (hipEvent_t e : g_prof.ev) (void)hipEventDestroy(e);
+  g_prof.ev.clear();
+  g_prof.used = 0;
+  g_prof.groups = 0;
+  g_prof.kind = -1;
+  return rc;
 }
 
 const char* armt_status_str(armt_status s) {

@@ -1,0 +1,232 @@
+// Segment attention on the CDNA4 matrix cores (paper Section 4.2): causal softmax(q k^T / sqrt(dh)) v
+// over the T rows of each cell, grouped-query heads, batched over the cells of the group.
+//
+// One workgroup = one KV head of one cell x 32 query rows; wave w handles query head (kv * GROUP + w),
+// so all waves share the K / V tiles in LDS and have the same causal extent.  Per 64-key tile a wave
+// computes S^T = K Q^T with v_mfma_f32_32x32x16_bf16 (keys along the rows, so a lane holds ONE query
+// column: the running max / sum of the online softmax are per-lane scalars and need a single exchange
+// between the two half-waves), turns it into P^T in registers -- the MFMA result layout is directly the
+// B-operand layout of the second product -- and accumulates O^T += V^T P^T.  V is needed with the key
+// index contiguous, so a pre-pass stores it transposed ([dh][T]) next to rotating q and k.
+// K / V^T tiles are double buffered and filled with direct global-to-LDS loads.
+#pragma once
+
+#include "common.h"
+#include "gemm_mfma.h"
+
+namespace armt {
+
+constexpr int AT_KT = 64;      // keys per tile
+constexpr int AT_QT = 32;      // query rows per wave / workgroup
+
+// V of every cell transposed: Vt[l][kvh][c][j] = V[l][j][kvh*dh + c], j padded with zeros to Tp.
+// grid: (Tp / 64, Hkv, g), block: 256.
+__global__ __launch_bounds__(256) void v_transpose_kernel(const bf16* __restrict__ QKV, bf16* __restrict__ Vt,
+                                                          int first, int Trows, int Tp, int H, int Hkv, int dh) {
+  extern __shared__ __align__(16) unsigned char smraw[];
+  bf16* tile = (bf16*)smraw;                   // [64][dh + 2]
+  const int l = first + blockIdx.z, kvh = blockIdx.y, j0 = blockIdx.x * 64;
+  const int ldq = (H + 2 * Hkv) * dh, ldt = dh + 2;
+  const bf16* src = QKV + (size_t)l * Trows * ldq + (H + Hkv) * dh + kvh * dh;
+  for (int idx = threadIdx.x; idx < 64 * dh; idx += blockDim.x) {
+    const int jr = idx / dh, c = idx - jr * dh;
+    tile[jr * ldt + c] = (j0 + jr < Trows) ? src[(size_t)(j0 + jr) * ldq + c] : (bf16)0.f;
+  }
+  __syncthreads();
+  bf16* dst = Vt + ((size_t)(l * Hkv + kvh) * dh) * Tp + j0;
+  for (int idx = threadIdx.x; idx < 64 * dh; idx += blockDim.x) {
+    const int c = idx >> 6, jr = idx & 63;
+    dst[(size_t)c * Tp + jr] = tile[jr * ldt + c];
+  }
+}
+
+// QKV: [L][T][(H + 2 Hkv) dh] with q, k already rotated; Vt as above; Out: [L][T][H dh].
+// grid: (ceil(T / 32), Hkv, g), block: GROUP * 64 with GROUP = H / Hkv.
+template <int DH>
+__global__ __launch_bounds__(512) void attention_mfma_kernel(const bf16* __restrict__ QKV, const bf16* __restrict__ Vt,
+                                                             bf16* __restrict__ Out, int first, int Trows, int Tp,
+                                                             int H, int Hkv, float scale_log2e) {
+  // a K tile is DH / 64 sub-tiles [64 keys][64 dims] with 128-byte rows
+  constexpr int K_BYTES = AT_KT * DH * 2;
+  constexpr int V_BYTES = DH * AT_KT * 2;          // V^T tile: [DH dims][64 keys], 128-byte rows
+  constexpr int STAGE = K_BYTES + V_BYTES;
+  constexpr int K_SLABS = K_BYTES / 1024, V_SLABS = V_BYTES / 1024;
+  constexpr int KS = DH / 16;                      // k-steps of the first product
+  constexpr int OT = DH / 32;                      // 32-row tiles of O^T
+  extern __shared__ __align__(16) unsigned char smem[];   // [2][STAGE]
+
+  const int nqt = gridDim.x;
+  const int qt = nqt - 1 - blockIdx.x;             // long (late) query tiles first
+  const int kvh = blockIdx.y, l = first + blockIdx.z;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int nw = blockDim.x >> 6, group = H / Hkv;
+  const int head = kvh * group + wave;
+  const int ldq = (H + 2 * Hkv) * DH;
+  const int q0 = qt * AT_QT;
+  const int qcol = lane & 31, half = lane >> 5;
+
+  const bf16* cell = QKV + (size_t)l * Trows * ldq;
+  const char* kbase = (const char*)(cell + H * DH + kvh * DH);
+  const char* vbase = (const char*)(Vt + (size_t)(l * Hkv + kvh) * DH * Tp);
+
+  // ---- Q fragments (B operand: lane holds query row qcol, 8 consecutive dims per k-step)
+  bf16x8 qf[KS];
+  {
+    const int qrow = min(q0 + qcol, Trows - 1);
+    const bf16* qp = cell + (size_t)qrow * ldq + head * DH + half * 8;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(qp + ks * 16);
+  }
+
+  // ---- tile copies: slab = 8 rows x 128 bytes; lane i fills row i/8, physical chunk i%8
+  const int R = lane >> 3, pc = lane & 7;
+  auto issue_tile = [&](int kt, int buf) {
+    typedef const __attribute__((address_space(1))) void* gptr_t;
+    typedef __attribute__((address_space(3))) void* lptr_t;
+    unsigned char* Ks = smem + buf * STAGE;
+    unsigned char* Vs = Ks + K_BYTES;
+    const int k0 = kt * AT_KT;
+    for (int sl = wave; sl < K_SLABS + V_SLABS; sl += nw) {
+      if (sl < K_SLABS) {
+        const int sub = sl >> 3, row = (sl & 7) * 8 + R;               // key row inside the tile
+        const int key = min(k0 + row, Trows - 1);                      // keys past T are masked by causality
+        const char* src = kbase + ((size_t)key * ldq + sub * 64 + ((pc ^ mf_swz(row)) << 3)) * 2;
+        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(Ks + sl * 1024), 16, 0, 0);
+      } else {
+        const int vs = sl - K_SLABS, row = vs * 8 + R;                 // dim row of V^T
+        const char* src = vbase + ((size_t)row * Tp + k0 + ((pc ^ mf_swz(row)) << 3)) * 2;
+        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(Vs + vs * 1024), 16, 0, 0);
+      }
+    }
+  };
+
+  const int fl = mf_swz(lane & 31);
+  f32x16 o[OT];
+#pragma unroll
+  for (int t = 0; t < OT; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[t][r] = 0.f;
+  float m = -INFINITY, lsum = 0.f;
+
+  const int nkt = (min(q0 + AT_QT, Trows) + AT_KT - 1) / AT_KT;
+  issue_tile(0, 0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  __syncthreads();
+
+  for (int kt = 0; kt < nkt; ++kt) {
+    const int cur = kt & 1, k0 = kt * AT_KT;
+    if (kt + 1 < nkt) issue_tile(kt + 1, cur ^ 1);
+    const unsigned char* Ks = smem + cur * STAGE;
+    const unsigned char* Vs = Ks + K_BYTES;
+
+    // S^T[key][query] for the two 32-key halves of the tile
+    f32x16 s[2];
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[jj][r] = 0.f;
+      const unsigned char* krow = Ks + (jj * 32 + (lane & 31)) * MF_ROW_BYTES;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 kf = *(const bf16x8*)(krow + (ks >> 2) * (AT_KT * MF_ROW_BYTES) + (((2 * (ks & 3) + half) ^ fl) << 4));
+        s[jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[jj], 0, 0, 0);
+      }
+    }
+    if (k0 + AT_KT - 1 > q0) {     // tile crosses the diagonal: mask keys after the query
+      const int qi = q0 + qcol;
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = k0 + jj * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+          if (key > qi) s[jj][r] = -INFINITY;
+        }
+    }
+    // online softmax: every lane owns one query column; its 32 keys here, the other 32 in lane ^ 32
+    float mx = s[0][0];
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[jj][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+    const float m_new = fmaxf(m, mx);
+    const float alpha = __builtin_amdgcn_exp2f((m - m_new) * scale_log2e);
+    m = m_new;
+    const float mc = m * scale_log2e;
+    lsum *= alpha;
+#pragma unroll
+    for (int t = 0; t < OT; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[t][r] *= alpha;
+    bf16x8 pf[2][2];
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(s[jj][r], scale_log2e, -mc));
+        lsum += p;
+        pf[jj][r >> 3][r & 7] = (bf16)p;
+      }
+    // O^T[dim][query] += V^T[dim][key] P^T[key][query]; k-step ss of half jj covers keys
+    // jj*32 + 16*ss + {4*half + 0..3, 8 + 4*half + 0..3}: exactly what registers 8*ss .. 8*ss+7 of s[jj] hold
+#pragma unroll
+    for (int t = 0; t < OT; ++t) {
+      const unsigned char* vrow = Vs + (t * 32 + (lane & 31)) * MF_ROW_BYTES + 8 * half;
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int ss = 0; ss < 2; ++ss) {
+          const int ch = jj * 4 + 2 * ss;
+          const bf16x4 lo = *(const bf16x4*)(vrow + ((ch ^ fl) << 4));
+          const bf16x4 hi = *(const bf16x4*)(vrow + (((ch + 1) ^ fl) << 4));
+          bf16x8 vf;
+          vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
+          vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
+          o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[jj][ss], o[t], 0, 0, 0);
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+  }
+
+  lsum += __shfl_xor(lsum, 32, kWave);
+  const float inv = 1.0f / lsum;
+  const int qi = q0 + qcol;
+  if (qi < Trows) {
+    bf16* dst = Out + ((size_t)l * Trows + qi) * (H * DH) + head * DH;
+#pragma unroll
+    for (int t = 0; t < OT; ++t)
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {         // registers 4*rg .. 4*rg+3 hold 4 consecutive dims
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[t][4 * rg + e] * inv);
+        *(bf16x4*)(dst + t * 32 + 8 * rg + 4 * half) = v;
+      }
+  }
+}
+
+inline int attention_tp(int Trows) { return (Trows + AT_KT - 1) / AT_KT * AT_KT; }
+
+// bytes of V^T scratch for g cells
+inline size_t attention_vt_bytes(int g, int Trows, int Hkv, int dh) {
+  return (size_t)g * Hkv * dh * attention_tp(Trows) * 2;
+}
+
+inline hipError_t launch_attention_mfma(const bf16* QKV, bf16* Vt, bf16* Out, int first, int g, int Trows, int H,
+                                        int Hkv, int dh, hipStream_t st) {
+  const int Tp = attention_tp(Trows), group = H / Hkv;
+  v_transpose_kernel<<<dim3(Tp / 64, Hkv, g), 256, 64 * (dh + 2) * 2, st>>>(QKV, Vt, first, Trows, Tp, H, Hkv, dh);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)dh);
+  const dim3 grid((Trows + AT_QT - 1) / AT_QT, Hkv, g);
+  if (dh == 64)
+    attention_mfma_kernel<64><<<grid, group * 64, 2 * (64 * 64 * 2 * 2), st>>>(QKV, Vt, Out, first, Trows, Tp, H, Hkv, scale_log2e);
+  else
+    attention_mfma_kernel<128><<<grid, group * 64, 2 * (64 * 128 * 2 * 2), st>>>(QKV, Vt, Out, first, Trows, Tp, H, Hkv, scale_log2e);
+  return hipGetLastError();
+}
+
+}  // namespace armt

@@ -75,6 +75,7 @@ struct GemmShape {
   int lda, ldc, ldc2, ldr;
   int n0, n1;           // rows in weight blocks 0 and 1 (block 2 holds N - n0 - n1)
   int epi;              // GemmEpilogue
+  int tag;              // which GEMM of the step this is (profiling only)
 };
 
 }  // namespace armt
