@@ -1,0 +1,159 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the header
+declares, implements the anti-diagonal schedule of Lemma 3.1, sizes its workspace, and turns bad
+arguments into error codes before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import armt_synth as S
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2506_05229_amd as P
+    if not os.path.exists(P.library_path()):
+        from paper_2506_05229_amd.build import build
+        build()
+    return P.load_library()
+
+
+def _cfg(shape):
+    import paper_2506_05229_amd as P
+    return P.ArmtConfig.from_shape(shape)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "armt.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = sorted(set(re.findall(r"\b(armt_[a-z0-9_]+)\s*\(", header)))
+    assert {"armt_forward_sequential", "armt_forward_diagonal", "armt_workspace_bytes", "armt_grouped_gemm",
+            "armt_segment_attention", "armt_assoc_read", "armt_assoc_update", "armt_diagonal_group"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_diagonal_schedule_matches_lemma_fixture(lib):
+    for line in open(os.path.join(GOLDEN, "lemma31_groups.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        lhs, rhs = line.split(":")
+        L, N = (int(v) for v in lhs.split())
+        sizes = [int(v) for v in rhs.split()]
+        seen = set()
+        for t, want in enumerate(sizes):
+            lo, hi = C.c_int32(-7), C.c_int32(-7)
+            g = lib.armt_diagonal_group(L, N, t, C.byref(lo), C.byref(hi))
+            assert g == want == hi.value - lo.value + 1
+            for l in range(lo.value, hi.value + 1):
+                s = t - l
+                assert 0 <= l < L and 0 <= s < N          # node (segment s, layer l) sits in group s + l
+                seen.add((l, s))
+        assert len(seen) == L * N                          # every cell exactly once, in L + N - 1 groups
+        lo, hi = C.c_int32(-7), C.c_int32(-7)
+        for t in (-1, L + N - 1, L + N + 5):
+            assert lib.armt_diagonal_group(L, N, t, C.byref(lo), C.byref(hi)) == 0
+            assert lo.value == -7 and hi.value == -7
+    assert lib.armt_diagonal_group(0, 3, 0, None, None) == 0
+    assert lib.armt_diagonal_group(3, 0, 0, None, None) == 0
+    assert lib.armt_diagonal_group(16, 128, 20, None, None) == 16
+
+
+def test_earliest_group_property(lib):
+    """Each cell's group index s + l is one more than the latest of its two predecessors (s, l-1),
+    (s-1, l): no cell could run earlier (Lemma 3.1)."""
+    L, N = 5, 7
+    group_of = {}
+    for t in range(L + N - 1):
+        lo, hi = C.c_int32(), C.c_int32()
+        lib.armt_diagonal_group(L, N, t, C.byref(lo), C.byref(hi))
+        for l in range(lo.value, hi.value + 1):
+            group_of[(l, t - l)] = t
+    for (l, s), t in group_of.items():
+        preds = [group_of[p] for p in ((l - 1, s), (l, s - 1)) if p in group_of]
+        assert t == (max(preds) + 1 if preds else 0)
+
+
+def test_workspace_bytes(lib):
+    for name in S.CONFIGS:
+        assert lib.armt_workspace_bytes(C.byref(_cfg(S.get_shape(name)))) > 0
+    big = lib.armt_workspace_bytes(C.byref(_cfg(S.get_shape("1b_128k"))))
+    assert big == lib.armt_workspace_bytes(C.byref(_cfg(S.get_shape("1b_8k"))))     # independent of n_tokens
+    assert big < 2 * 2 ** 30
+    assert lib.armt_workspace_bytes(None) == 0
+    tiny = S.get_shape("tiny")
+    for bad in (dict(n_heads=3), dict(head_dim=31, d_model=124), dict(n_layers=0), dict(n_kv_heads=3), dict(d_mem=0),
+                dict(dpfp_nu=64)):
+        assert lib.armt_workspace_bytes(C.byref(_cfg(tiny.replace(**bad)))) == 0, bad
+    c = _cfg(tiny)
+    c.dtype = 7
+    assert lib.armt_workspace_bytes(C.byref(c)) == 0
+
+
+def test_forward_argument_errors_come_before_any_launch(lib):
+    """All of these return before touching the GPU, so they run without one; the fake pointers are never
+    dereferenced."""
+    import paper_2506_05229_amd as P
+    shape = S.get_shape("tiny")
+    cfg = _cfg(shape)
+    L = shape.n_layers
+    layers = (P.ArmtLayerWeights * L)()
+    fake = 0x1000
+    for l in range(L):
+        for f, _ in P.ArmtLayerWeights._fields_:
+            setattr(layers[l], f, fake)
+    ws_bytes = lib.armt_workspace_bytes(C.byref(cfg))
+    ok_args = dict(cfg=C.byref(cfg), layers=layers, mem=fake, x=fake, n=shape.n_tokens, A_in=None, z_in=None,
+                   hid=fake, A=fake, z=fake, ws=0x10000, wsb=ws_bytes, st=None)
+
+    def call(fn, **kw):
+        a = dict(ok_args, **kw)
+        return fn(a["cfg"], a["layers"], a["mem"], a["x"], a["n"], a["A_in"], a["z_in"], a["hid"], a["A"], a["z"],
+                  a["ws"], a["wsb"], a["st"])
+
+    for fn in (lib.armt_forward_sequential, lib.armt_forward_diagonal):
+        assert call(fn, cfg=None) == 1
+        assert call(fn, mem=None) == 1 and call(fn, x=None) == 1 and call(fn, hid=None) == 1
+        assert call(fn, A=None) == 1 and call(fn, z=None) == 1 and call(fn, layers=None) == 1
+        assert call(fn, A_in=fake) == 1                     # A_in without z_in
+        assert call(fn, n=0) == 2 and call(fn, n=-64) == 2 and call(fn, n=shape.n_tokens + 1) == 2
+        assert call(fn, ws=None) == 4 and call(fn, wsb=ws_bytes - 1) == 4 and call(fn, ws=0x10001) == 4
+        bad = _cfg(shape)
+        bad.dtype = 9
+        assert call(fn, cfg=C.byref(bad)) == 3
+        assert call(fn, cfg=C.byref(_cfg(shape.replace(n_heads=3)))) == 2
+        # bf16 shapes the matrix-core kernels do not cover are refused, not run slowly
+        assert call(fn, cfg=C.byref(_cfg(shape.replace(dtype="bf16")))) == 6
+        missing = (P.ArmtLayerWeights * L)()
+        for l in range(L):
+            for f, _ in P.ArmtLayerWeights._fields_:
+                setattr(missing[l], f, fake)
+        missing[L - 1].wm_b = None
+        assert call(fn, layers=missing) == 1
+    for code in range(0, 7):
+        assert lib.armt_status_str(code)
+    assert lib.armt_last_hip_error() is not None
+
+
+def test_step_entry_argument_errors(lib):
+    shape = S.get_shape("tiny")
+    cfg = _cfg(shape)
+    n = lib.armt_workspace_bytes(C.byref(cfg))
+    fake = 0x1000
+    assert lib.armt_segment_attention(C.byref(cfg), 0, fake, fake, 0x10000, n, None) == 2
+    assert lib.armt_segment_attention(C.byref(cfg), shape.n_layers + 1, fake, fake, 0x10000, n, None) == 2
+    assert lib.armt_segment_attention(C.byref(cfg), 1, fake, fake, 0x10000, n - 1, None) == 4
+    assert lib.armt_segment_attention(C.byref(cfg), 1, None, fake, 0x10000, n, None) == 1
+    arr = (C.c_void_p * 1)(fake)
+    assert lib.armt_grouped_gemm(0, 1, 8, 8, 8, arr, arr, arr, None, 0, None) == 4
+    assert lib.armt_grouped_gemm(1, 1, 8, 8, 40, arr, arr, arr, 0x10000, 4096, None) == 6      # bf16 needs K % 64 == 0
+    assert lib.armt_grouped_gemm(5, 1, 8, 8, 8, arr, arr, arr, 0x10000, 4096, None) == 3
+    assert lib.armt_grouped_gemm(0, 0, 8, 8, 8, arr, arr, arr, 0x10000, 4096, None) == 2
+    assert lib.armt_assoc_update(C.byref(cfg), 1, fake, arr, arr, arr, 3, fake, fake, 0x10000, n, None) == 2
+    assert lib.armt_profile_begin(99, 4) == 2
+    assert lib.armt_set_gemm_tile_config(-1) == -1
