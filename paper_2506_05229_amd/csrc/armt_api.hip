@@ -129,6 +129,7 @@ void fill_shapes(Ctx& c) {
     GemmShape s;
     s.M = M; s.N = N; s.K = K; s.lda = lda; s.ldc = ldc; s.ldc2 = ldc2; s.ldr = ldr; s.n0 = n0; s.n1 = n1; s.epi = epi;
     s.tag = k;
+    s.dbg = 0;
     c.shape[k] = s;
   };
   set(K_MQ, D.T, D.dm, D.d, D.d, D.dm, 0, 0, D.dm, 0, EPI_STORE_F32);
@@ -198,6 +199,7 @@ bool debug_generic() {
 }
 
 int g_gemm_tile_config = -1;     // armt_set_gemm_tile_config
+int g_gemm_dbg = 0;              // diagnosis variants of armt_grouped_gemm (tile config / 100)
 
 // Optional timing of one GEMM kind with HIP events on the launch stream (armt_profile_*).
 struct Profile {
@@ -475,6 +477,7 @@ armt_status armt_grouped_gemm(int32_t dtype, int32_t g, int32_t M, int32_t N, in
   GemmShape s;
   s.M = M; s.N = N; s.K = K; s.lda = K; s.ldc = N; s.ldc2 = 0; s.ldr = 0; s.n0 = N; s.n1 = 0; s.epi = EPI_STORE_ACT;
   s.tag = -1;
+  s.dbg = g_gemm_dbg;
   if (dtype == ARMT_BF16) return gemm_entry<bf16>(g, s, (const GemmGroup*)workspace, st);
   return gemm_entry<float>(g, s, (const GemmGroup*)workspace, st);
 }
@@ -582,6 +585,8 @@ int32_t armt_diagonal_group(int32_t n_layers, int32_t n_segments, int32_t t, int
 
 int32_t armt_set_gemm_tile_config(int32_t config) {
   const int32_t old = g_gemm_tile_config;
+  g_gemm_dbg = config >= 100 ? config / 100 : 0;
+  if (config >= 100) config %= 100;
   g_gemm_tile_config = (config >= 0 && config < MF_NUM_CONFIGS) ? config : -1;
   return old;
 }

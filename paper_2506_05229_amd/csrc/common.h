@@ -76,6 +76,7 @@ struct GemmShape {
   int n0, n1;           // rows in weight blocks 0 and 1 (block 2 holds N - n0 - n1)
   int epi;              // GemmEpilogue
   int tag;              // which GEMM of the step this is (profiling only)
+  int dbg;              // diagnosis only: bit 0 freezes the k offset of B, bit 1 that of A (wrong results)
 };
 
 }  // namespace armt

@@ -27,7 +27,10 @@ constexpr int MF_NUM_CONFIGS = 4;         // tile configurations of launch_gemm_
 // swizzle of the 16-byte chunk index inside a 128-byte tile row; depends on row bits 0..3 only
 __device__ __forceinline__ int mf_swz(int row) { return ((row >> 1) & 7) ^ ((row & 1) << 2); }
 
-template <int BM, int BN, int WGM, int WGN, int EPI>
+// TAIL: the last M-tile of every group also owns the 16 rows that follow it (M = tiles_m * BM + 16).  With
+// T = seg_len + 16 memory rows and seg_len a multiple of BM this removes the nearly empty fifth tile a
+// 1040-row cell would otherwise need: the 16 memory rows ride along as one extra strip of 16x16x32 MFMAs.
+template <int BM, int BN, int WGM, int WGN, int EPI, bool TAIL>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGroup* __restrict__ table, int first,
                                                                   GemmShape s, int tiles_m, int tiles_n,
                                                                   int total_tiles) {
@@ -35,11 +38,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   constexpr int WROWS = BM / WGM, WCOLS = BN / WGN;       // wave tile
   constexpr int TM = WROWS / 32, TN = WCOLS / 32;         // 32x32 MFMA tiles per wave
   constexpr int A_DMA = BM / 8 / NW, B_DMA = BN / 8 / NW; // 8-row (1 KB) slabs each wave copies per k-tile
-  constexpr int A_BYTES = BM * MF_ROW_BYTES, B_BYTES = BN * MF_ROW_BYTES;
+  constexpr int A_ROWS = TAIL ? BM + 16 : BM;
+  constexpr int A_BYTES = A_ROWS * MF_ROW_BYTES, B_BYTES = BN * MF_ROW_BYTES;
   constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;   // output columns per tile
   static_assert(BM % (WGM * 32) == 0 && BN % (WGN * 32) == 0, "wave tile must be a multiple of 32x32");
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must divide into 8-row slabs per wave");
   static_assert(EPI != EPI_SWIGLU || TN % 2 == 0, "SwiGLU pairs gate/up 32-column tiles inside a wave");
+  static_assert(!TAIL || (BN == NW * 32 && NW >= 2), "the tail strip gives every wave two 16-column tiles");
 
   extern __shared__ __align__(16) unsigned char smem[];   // [2][A_BYTES] then [2][B_BYTES]
 
@@ -52,6 +57,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   const int tn = rem / tiles_m, tm = rem - tn * tiles_m;    // M-tiles of one weight panel are adjacent
   const GemmGroup g = table[first + grp];
   const int m0 = tm * BM, n0 = tn * BN_OUT;
+  const bool tail = TAIL && (tm == tiles_m - 1);            // block-uniform
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -62,6 +68,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   // slab, so it fetches the logical chunk (i % 8) ^ swz(row) of that row from global memory.
   const char* ap[A_DMA];
   const char* bp[B_DMA];
+  const char* tp = nullptr;      // tail rows: waves 0 and 1 copy one extra slab each
   {
     const int R = lane >> 3, pc = lane & 7;
 #pragma unroll
@@ -69,6 +76,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       const int row = (wave + j * NW) * 8 + R;
       const int m = min(m0 + row, s.M - 1);                // rows past M re-read the last row; masked on store
       ap[j] = (const char*)g.A + ((size_t)m * s.lda + ((pc ^ mf_swz(row)) << 3)) * 2;
+    }
+    if (TAIL) {
+      const int row = BM + (wave & 1) * 8 + R;
+      const int m = min(m0 + row, s.M - 1);
+      tp = (const char*)g.A + ((size_t)m * s.lda + ((pc ^ mf_swz(row)) << 3)) * 2;
     }
 #pragma unroll
     for (int j = 0; j < B_DMA; ++j) {
@@ -93,12 +105,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
     unsigned char* Bs = smem + 2 * A_BYTES + buf * B_BYTES;
 #pragma unroll
     for (int j = 0; j < A_DMA; ++j)
-      __builtin_amdgcn_global_load_lds((gptr_t)(ap[j] + (size_t)kt * MF_ROW_BYTES), (lptr_t)(As + (wave + j * NW) * 1024),
-                                       16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(ap[j] + (size_t)((s.dbg & 2) ? 0 : kt) * MF_ROW_BYTES),
+                                       (lptr_t)(As + (wave + j * NW) * 1024), 16, 0, 0);
+    if (TAIL && tail && wave < 2)
+      __builtin_amdgcn_global_load_lds((gptr_t)(tp + (size_t)kt * MF_ROW_BYTES),
+                                       (lptr_t)(As + BM * MF_ROW_BYTES + wave * 1024), 16, 0, 0);
 #pragma unroll
     for (int j = 0; j < B_DMA; ++j)
-      __builtin_amdgcn_global_load_lds((gptr_t)(bp[j] + (size_t)kt * MF_ROW_BYTES), (lptr_t)(Bs + (wave + j * NW) * 1024),
-                                       16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(bp[j] + (size_t)((s.dbg & 1) ? 0 : kt) * MF_ROW_BYTES),
+                                       (lptr_t)(Bs + (wave + j * NW) * 1024), 16, 0, 0);
   };
 
   // ---- MFMA fragment addresses: lane reads tile row (lane % 32) of each 32-row block, chunk 2*ks + lane/32
@@ -108,6 +123,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   for (int ks = 0; ks < 4; ++ks) koff[ks] = ((2 * ks + half) ^ fl) << 4;
   const int a_frag = (wm * WROWS + (lane & 31)) * MF_ROW_BYTES;
   const int b_frag = (wn * WCOLS + (lane & 31)) * MF_ROW_BYTES;
+  // tail strip (16x16x32 MFMA): lane reads row (lane % 16), chunk 4*ks2 + lane/16.  Wave w owns two 16-column
+  // tiles whose B rows lie 32 apart, so that for SwiGLU tile 0 is the gate and tile 1 the up projection of the
+  // same 16 output columns: B tile rows ((w / 2) * 2 + t) * 32 + (w % 2) * 16 + lane % 16.
+  const int t_sw = mf_swz(lane & 15), t_q = lane >> 4;
+  const int t_a = (BM + (lane & 15)) * MF_ROW_BYTES;
+  const int t_brow = ((wave >> 1) * 2) * 32 + (wave & 1) * 16 + (lane & 15);
+  const int t_b = t_brow * MF_ROW_BYTES;
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -116,6 +138,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  f32x4 tacc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 
   const int nk = s.K / MF_BK;
   issue_tile(0, 0);
@@ -126,26 +149,52 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
     const int cur = kt & 1;
     // the other buffer was last read in iteration kt - 1, which ended with a barrier
     if (kt + 1 < nk) issue_tile(kt + 1, cur ^ 1);
-    const unsigned char* As = smem + cur * A_BYTES + a_frag;
-    const unsigned char* Bs = smem + 2 * A_BYTES + cur * B_BYTES + b_frag;
+    const unsigned char* As = smem + cur * A_BYTES;
+    const unsigned char* Bs = smem + 2 * A_BYTES + cur * B_BYTES;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       bf16x8 af[TM], bfr[TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8*)(As + i * 32 * MF_ROW_BYTES + koff[ks]);
+      for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8*)(As + a_frag + i * 32 * MF_ROW_BYTES + koff[ks]);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8*)(Bs + j * 32 * MF_ROW_BYTES + koff[ks]);
+      for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8*)(Bs + b_frag + j * 32 * MF_ROW_BYTES + koff[ks]);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
+    if (TAIL && tail) {
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2) {
+        const int ko = ((4 * ks2 + t_q) ^ t_sw) << 4;
+        const bf16x8 ta = *(const bf16x8*)(As + t_a + ko);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const bf16x8 tb = *(const bf16x8*)(Bs + t_b + t * 32 * MF_ROW_BYTES + ko);
+          tacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ta, tb, tacc[t], 0, 0, 0);
+        }
+      }
+    }
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
   }
 
   // ---- epilogue.  32x32 result tile: lane holds column lane % 32, rows 8*(r/4) + 4*(lane/32) + r%4.
+  auto store = [&](int m, int n, float v, float rs) {
+    if (EPI == EPI_STORE_ACT) {
+      ((bf16*)g.C)[(size_t)m * s.ldc + n] = (bf16)v;
+    } else if (EPI == EPI_STORE_F32) {
+      ((float*)g.C)[(size_t)m * s.ldc + n] = v;
+    } else {
+      const float o = (g.R ? g.R[(size_t)m * s.ldr + n] : 0.f) + v * rs;
+      ((float*)g.C)[(size_t)m * s.ldc + n] = o;
+      if (g.C2) ((bf16*)g.C2)[(size_t)m * s.ldc2 + n] = (bf16)o;
+    }
+  };
+  auto swiglu = [&](int m, int n, float gt, float up) {
+    ((bf16*)g.C)[(size_t)m * s.ldc + n] = (bf16)(gt / (1.f + __expf(-gt)) * up);
+  };
   const int col_in = lane & 31;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
@@ -157,9 +206,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
 #pragma unroll
         for (int j = 0; j < TN; j += 2) {
           const int n = n0 + ((wn * TN + j) >> 1) * 32 + col_in;
-          if (n >= s.N) continue;
-          const float gt = acc[i][j][r], up = acc[i][j + 1][r];
-          ((bf16*)g.C)[(size_t)m * s.ldc + n] = (bf16)(gt / (1.f + __expf(-gt)) * up);
+          if (n < s.N) swiglu(m, n, acc[i][j][r], acc[i][j + 1][r]);
         }
       } else {
         float rs = 1.f;
@@ -167,31 +214,40 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           const int n = n0 + wn * WCOLS + j * 32 + col_in;
-          if (n >= s.N) continue;
-          const float v = acc[i][j][r];
-          if (EPI == EPI_STORE_ACT) {
-            ((bf16*)g.C)[(size_t)m * s.ldc + n] = (bf16)v;
-          } else if (EPI == EPI_STORE_F32) {
-            ((float*)g.C)[(size_t)m * s.ldc + n] = v;
-          } else {
-            const float o = (g.R ? g.R[(size_t)m * s.ldr + n] : 0.f) + v * rs;
-            ((float*)g.C)[(size_t)m * s.ldc + n] = o;
-            if (g.C2) ((bf16*)g.C2)[(size_t)m * s.ldc2 + n] = (bf16)o;
-          }
+          if (n < s.N) store(m, n, acc[i][j][r], rs);
+        }
+      }
+    }
+  }
+  if (TAIL && tail) {     // 16x16 result tile: lane holds column lane % 16, rows 4*(lane/16) + r
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int m = m0 + BM + 4 * t_q + r;
+      if (m >= s.M) continue;
+      if (EPI == EPI_SWIGLU) {
+        const int n = n0 + (wave >> 1) * 32 + (wave & 1) * 16 + (lane & 15);
+        if (n < s.N) swiglu(m, n, tacc[0][r], tacc[1][r]);
+      } else {
+        float rs = 1.f;
+        if (EPI == EPI_RESID_F32 && g.rowscale) rs = g.rowscale[m];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const int n = n0 + t_brow + t * 32;
+          if (n < s.N) store(m, n, tacc[t][r], rs);
         }
       }
     }
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI>
-inline hipError_t launch_mfma_cfg(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st) {
+template <int BM, int BN, int WGM, int WGN, int EPI, bool TAIL>
+inline hipError_t launch_mfma_tail(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st) {
   constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
-  constexpr int LDS = 2 * (BM + BN) * MF_ROW_BYTES;
-  const int tiles_m = (s.M + BM - 1) / BM, tiles_n = (s.N + BN_OUT - 1) / BN_OUT;
+  constexpr int LDS = 2 * ((TAIL ? BM + 16 : BM) + BN) * MF_ROW_BYTES;
+  const int tiles_m = TAIL ? s.M / BM : (s.M + BM - 1) / BM, tiles_n = (s.N + BN_OUT - 1) / BN_OUT;
   const int total = g * tiles_m * tiles_n;
   const int grid = ((total + 7) / 8) * 8;
-  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, EPI>;
+  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, EPI, TAIL>;
   static bool attr_set = false;            // raising the dynamic-LDS limit is a per-function, idempotent setting
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -200,6 +256,16 @@ inline hipError_t launch_mfma_cfg(const GemmGroup* table, int first, int g, cons
   }
   kern<<<grid, WGM * WGN * 64, LDS, st>>>(table, first, s, tiles_m, tiles_n, total);
   return hipGetLastError();
+}
+
+// M = tiles * BM + 16 (a cell: seg_len rows + 16 memory rows) takes the tail variant.
+template <int BM, int BN, int WGM, int WGN, int EPI>
+inline hipError_t launch_mfma_cfg(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st) {
+  if constexpr (BN == WGM * WGN * 32) {
+    if (s.M > BM && s.M % BM == 16 && !(s.dbg & 32))
+      return launch_mfma_tail<BM, BN, WGM, WGN, EPI, true>(table, first, g, s, st);
+  }
+  return launch_mfma_tail<BM, BN, WGM, WGN, EPI, false>(table, first, g, s, st);
 }
 
 // Tile configuration by problem shape: big square tiles for the block's linears, small tiles for
@@ -212,7 +278,7 @@ inline hipError_t launch_gemm_mfma_epi(const GemmGroup* table, int first, int g,
   switch (cfg) {
     case 0: return launch_mfma_cfg<256, 256, 2, 4, EPI>(table, first, g, s, st);
     case 1: return launch_mfma_cfg<128, 128, 2, 2, EPI>(table, first, g, s, st);
-    case 3: return launch_mfma_cfg<256, 256, 2, 2, EPI>(table, first, g, s, st);
+    case 3: return launch_mfma_cfg<128, 256, 2, 4, EPI>(table, first, g, s, st);
     default: return launch_mfma_cfg<64, 128, 2, 2, EPI>(table, first, g, s, st);
   }
 }
