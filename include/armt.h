@@ -156,7 +156,7 @@ armt_status armt_assoc_update(const armt_config *cfg, int32_t g, const float *ym
                               void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Benchmarking knob: force the tile configuration of the bf16 grouped GEMM for all later calls of this
- * process (0: 256x256 tile, 8 waves; 1: 128x128, 4 waves; 2: 64x128, 4 waves; 3: 128x256, 8 waves;
+ * process (0: 256x256 tile, 8 waves; 1: 128x128, 4 waves; 2: 64x128, 4 waves; 3: 128x256, 8 waves; 4: 256x256, 16 waves;
  * anything else: choose by shape, the default).  Results do not depend on it beyond rounding order.
  * Returns the previous setting.  Not thread safe. */
 int32_t armt_set_gemm_tile_config(int32_t config);

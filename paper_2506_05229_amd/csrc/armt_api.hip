@@ -111,6 +111,9 @@ Layout carve(const Dims& D) {
   return o;
 }
 
+int g_gemm_tile_config = -1;     // armt_set_gemm_tile_config
+int g_gemm_dbg = 0;              // diagnosis variants (tile config / 100)
+
 struct Ctx {
   Dims D;
   Layout o;
@@ -129,7 +132,7 @@ void fill_shapes(Ctx& c) {
     GemmShape s;
     s.M = M; s.N = N; s.K = K; s.lda = lda; s.ldc = ldc; s.ldc2 = ldc2; s.ldr = ldr; s.n0 = n0; s.n1 = n1; s.epi = epi;
     s.tag = k;
-    s.dbg = 0;
+    s.dbg = g_gemm_dbg;
     c.shape[k] = s;
   };
   set(K_MQ, D.T, D.dm, D.d, D.d, D.dm, 0, 0, D.dm, 0, EPI_STORE_F32);
@@ -198,8 +201,6 @@ bool debug_generic() {
   return v;
 }
 
-int g_gemm_tile_config = -1;     // armt_set_gemm_tile_config
-int g_gemm_dbg = 0;              // diagnosis variants of armt_grouped_gemm (tile config / 100)
 
 // Optional timing of one GEMM kind with HIP events on the launch stream (armt_profile_*).
 struct Profile {
@@ -270,9 +271,21 @@ armt_status step_assoc_update(hipStream_t st, const GemmGroup* t_mkv, const Gemm
   memupd_prep_kernel<T><<<dim3(m, g), 128, (dm + 17) * 4, st>>>(KVm, Y0, y_stride, aux, first, empty_layer, m, d, dm, nu,
                                                                eps, Fm, Coef);
   HIP_TRY(hipGetLastError());
-  const int rows_per_block = 16;
-  delta_rule_kernel<8><<<dim3((d + rows_per_block - 1) / rows_per_block, g), 256, (size_t)m * (Phi + 4) * 4, st>>>(
-      KVm, Fm, Coef, aux, first, m, d, dm, Phi, rows_per_block);
+  if (m == 16 && Phi % 64 == 0 && Phi <= 512) {
+    const int rows_per_block = 32;
+    const dim3 grid((d + rows_per_block - 1) / rows_per_block, g);
+#define ARMT_DELTA16(NPL) \
+  case NPL: delta_rule16_kernel<NPL><<<grid, 256, 0, st>>>(KVm, Fm, Coef, aux, first, d, dm, rows_per_block); break;
+    switch (Phi / 64) {
+      ARMT_DELTA16(1) ARMT_DELTA16(2) ARMT_DELTA16(3) ARMT_DELTA16(4) ARMT_DELTA16(5) ARMT_DELTA16(6) ARMT_DELTA16(7)
+      ARMT_DELTA16(8)
+    }
+#undef ARMT_DELTA16
+  } else {
+    const int rows_per_block = 16;
+    delta_rule_kernel<8><<<dim3((d + rows_per_block - 1) / rows_per_block, g), 256, (size_t)m * (Phi + 4) * 4, st>>>(
+        KVm, Fm, Coef, aux, first, m, d, dm, Phi, rows_per_block);
+  }
   HIP_TRY(hipGetLastError());
   return ARMT_OK;
 }

@@ -22,10 +22,11 @@ namespace armt {
 
 constexpr int MF_BK = 64;                 // k-tile (bf16 elements): 128 bytes per tile row
 constexpr int MF_ROW_BYTES = MF_BK * 2;
-constexpr int MF_NUM_CONFIGS = 4;         // tile configurations of launch_gemm_mfma_epi
+constexpr int MF_NUM_CONFIGS = 5;         // tile configurations of launch_gemm_mfma_epi
 
 // swizzle of the 16-byte chunk index inside a 128-byte tile row; depends on row bits 0..3 only
 __device__ __forceinline__ int mf_swz(int row) { return ((row >> 1) & 7) ^ ((row & 1) << 2); }
+
 
 // TAIL: the last M-tile of every group also owns the 16 rows that follow it (M = tiles_m * BM + 16).  With
 // T = seg_len + 16 memory rows and seg_len a multiple of BM this removes the nearly empty fifth tile a
@@ -44,7 +45,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   static_assert(BM % (WGM * 32) == 0 && BN % (WGN * 32) == 0, "wave tile must be a multiple of 32x32");
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must divide into 8-row slabs per wave");
   static_assert(EPI != EPI_SWIGLU || TN % 2 == 0, "SwiGLU pairs gate/up 32-column tiles inside a wave");
-  static_assert(!TAIL || (BN == NW * 32 && NW >= 2), "the tail strip gives every wave two 16-column tiles");
+  static_assert(!TAIL || (BN <= NW * 32 && NW >= 2), "the tail strip gives each of the first BN / 32 waves two 16-column tiles");
+  constexpr int TAIL_WAVES = BN / 32;
 
   extern __shared__ __align__(16) unsigned char smem[];   // [2][A_BYTES] then [2][B_BYTES]
 
@@ -57,11 +59,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   const int tn = rem / tiles_m, tm = rem - tn * tiles_m;    // M-tiles of one weight panel are adjacent
   const GemmGroup g = table[first + grp];
   const int m0 = tm * BM, n0 = tn * BN_OUT;
-  const bool tail = TAIL && (tm == tiles_m - 1);            // block-uniform
+  const bool tail_blk = TAIL && (tm == tiles_m - 1);        // block-uniform
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WGN, wn = wave % WGN;
+  const bool tail = tail_blk && wave < (TAIL ? BN / 32 : 0);   // wave-uniform: this wave computes part of the strip
 
   // ---- global -> LDS copies go straight to LDS (global_load_lds_dwordx4): one instruction moves 64 x 16
   // bytes into 1 KB of consecutive LDS = 8 tile rows.  Lane i fills row i / 8, physical chunk i % 8 of the
@@ -107,7 +110,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
     for (int j = 0; j < A_DMA; ++j)
       __builtin_amdgcn_global_load_lds((gptr_t)(ap[j] + (size_t)((s.dbg & 2) ? 0 : kt) * MF_ROW_BYTES),
                                        (lptr_t)(As + (wave + j * NW) * 1024), 16, 0, 0);
-    if (TAIL && tail && wave < 2)
+    if (TAIL && tail_blk && wave < 2)
       __builtin_amdgcn_global_load_lds((gptr_t)(tp + (size_t)kt * MF_ROW_BYTES),
                                        (lptr_t)(As + BM * MF_ROW_BYTES + wave * 1024), 16, 0, 0);
 #pragma unroll
@@ -140,49 +143,55 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
   f32x4 tacc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 
-  const int nk = s.K / MF_BK;
-  issue_tile(0, 0);
-  __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's copies have landed in LDS
-  __syncthreads();                        // ... and everybody else's
-
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    // the other buffer was last read in iteration kt - 1, which ended with a barrier
-    if (kt + 1 < nk) issue_tile(kt + 1, cur ^ 1);
-    const unsigned char* As = smem + cur * A_BYTES;
-    const unsigned char* Bs = smem + 2 * A_BYTES + cur * B_BYTES;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 af[TM], bfr[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8*)(As + a_frag + i * 32 * MF_ROW_BYTES + koff[ks]);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8*)(Bs + b_frag + j * 32 * MF_ROW_BYTES + koff[ks]);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
-    if (TAIL && tail) {
-#pragma unroll
-      for (int ks2 = 0; ks2 < 2; ++ks2) {
-        const int ko = ((4 * ks2 + t_q) ^ t_sw) << 4;
-        const bf16x8 ta = *(const bf16x8*)(As + t_a + ko);
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const bf16x8 tb = *(const bf16x8*)(Bs + t_b + t * 32 * MF_ROW_BYTES + ko);
-          tacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ta, tb, tacc[t], 0, 0, 0);
-        }
-      }
-    }
+  {
+    // main loop: the copy of k-tile kt+1 is in flight while k-tile kt is multiplied; one barrier per k-tile
+    const int nk = s.K / MF_BK;
+    issue_tile(0, 0);
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+      const int cur = kt & 1;
+      if (kt + 1 < nk) issue_tile(kt + 1, cur ^ 1);
+      const unsigned char* As = smem + cur * A_BYTES;
+      const unsigned char* Bs = smem + 2 * A_BYTES + cur * B_BYTES;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        bf16x8 af[TM], bfr[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8*)(As + a_frag + i * 32 * MF_ROW_BYTES + koff[ks]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8*)(Bs + b_frag + j * 32 * MF_ROW_BYTES + koff[ks]);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+      }
+      if (TAIL && tail) {
+#pragma unroll
+        for (int ks2 = 0; ks2 < 2; ++ks2) {
+          const int ko = ((4 * ks2 + t_q) ^ t_sw) << 4;
+          const bf16x8 ta = *(const bf16x8*)(As + t_a + ko);
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            const bf16x8 tb = *(const bf16x8*)(Bs + t_b + t * 32 * MF_ROW_BYTES + ko);
+            tacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ta, tb, tacc[t], 0, 0, 0);
+          }
+        }
+      }
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      __syncthreads();
+    }
   }
 
-  // ---- epilogue.  32x32 result tile: lane holds column lane % 32, rows 8*(r/4) + 4*(lane/32) + r%4.
-  auto store = [&](int m, int n, float v, float rs) {
-    if (EPI == EPI_STORE_ACT) {
+  // ---- epilogue, staged through LDS so that global memory sees whole rows: a 32x32 result tile has lane =
+  // column (lane % 32) and registers = rows 8*(r/4) + 4*(lane/32) + r%4, which written directly would touch
+  // global memory in 128-byte pieces.  Instead, in TM * 2 passes every wave drops 16 rows of its tile into a
+  // fp32 staging tile [WGM * 16][BN_OUT + 8] (the +8 keeps the two half-waves on different banks), and all
+  // threads then walk the staging tile row-major, one wave per row: 16-byte accesses, full rows of R, C, C2.
+  // The tile buffers are free here: the main loop ended with a barrier.
+  auto store1 = [&](int m, int n, float v, float rs) {
+    if (EPI == EPI_STORE_ACT || EPI == EPI_SWIGLU) {
       ((bf16*)g.C)[(size_t)m * s.ldc + n] = (bf16)v;
     } else if (EPI == EPI_STORE_F32) {
       ((float*)g.C)[(size_t)m * s.ldc + n] = v;
@@ -192,31 +201,62 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       if (g.C2) ((bf16*)g.C2)[(size_t)m * s.ldc2 + n] = (bf16)o;
     }
   };
-  auto swiglu = [&](int m, int n, float gt, float up) {
-    ((bf16*)g.C)[(size_t)m * s.ldc + n] = (bf16)(gt / (1.f + __expf(-gt)) * up);
-  };
-  const int col_in = lane & 31;
+  auto silu_mul = [](float gt, float up) { return gt / (1.f + __expf(-gt)) * up; };
+  {
+    constexpr int SLD = BN_OUT + 8, SR = WGM * 16, C4 = BN_OUT / 4, CHUNKS = SR * C4, NT = NW * 64;
+    static_assert(SR * SLD * 4 <= 2 * (A_BYTES + B_BYTES), "staging tile must fit in the tile buffers");
+    float* stg = (float*)smem;
+    const bool vec_ok = ((s.N | s.ldc | s.ldr | s.ldc2) & 3) == 0;
+    const int col_in = lane & 31;
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
+    for (int pass = 0; pass < TM * 2; ++pass) {
+      const int i = pass >> 1, rh = pass & 1;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int m = m0 + wm * WROWS + i * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-      if (m >= s.M) continue;
-      if (EPI == EPI_SWIGLU) {
+      for (int q = 0; q < 8; ++q) {
+        const int r = rh * 8 + q;
+        float* dst = stg + (wm * 16 + 8 * (q >> 2) + 4 * half + (q & 3)) * SLD + col_in;
+        if (EPI == EPI_SWIGLU) {
 #pragma unroll
-        for (int j = 0; j < TN; j += 2) {
-          const int n = n0 + ((wn * TN + j) >> 1) * 32 + col_in;
-          if (n < s.N) swiglu(m, n, acc[i][j][r], acc[i][j + 1][r]);
-        }
-      } else {
-        float rs = 1.f;
-        if (EPI == EPI_RESID_F32 && g.rowscale) rs = g.rowscale[m];
+          for (int j = 0; j < TN; j += 2) dst[((wn * TN + j) >> 1) * 32] = silu_mul(acc[i][j][r], acc[i][j + 1][r]);
+        } else {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int n = n0 + wn * WCOLS + j * 32 + col_in;
-          if (n < s.N) store(m, n, acc[i][j][r], rs);
+          for (int j = 0; j < TN; ++j) dst[wn * WCOLS + j * 32] = acc[i][j][r];
         }
       }
+      __syncthreads();
+      for (int q = tid; q < CHUNKS; q += NT) {
+        const int sr = q / C4, c4 = q - sr * C4;
+        const int m = m0 + (sr >> 4) * WROWS + i * 32 + rh * 16 + (sr & 15), n = n0 + c4 * 4;
+        if (m >= s.M || n >= s.N) continue;
+        const f32x4 v = *(const f32x4*)(stg + sr * SLD + c4 * 4);
+        float rs = 1.f;
+        if (EPI == EPI_RESID_F32 && g.rowscale) rs = g.rowscale[m];
+        if (vec_ok) {
+          if (EPI == EPI_STORE_ACT || EPI == EPI_SWIGLU) {
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
+            *(bf16x4*)((bf16*)g.C + (size_t)m * s.ldc + n) = o;
+          } else if (EPI == EPI_STORE_F32) {
+            *(f32x4*)((float*)g.C + (size_t)m * s.ldc + n) = v;
+          } else {
+            f32x4 o = v * rs;
+            if (g.R) o += *(const f32x4*)(g.R + (size_t)m * s.ldr + n);
+            *(f32x4*)((float*)g.C + (size_t)m * s.ldc + n) = o;
+            if (g.C2) {
+              bf16x4 ob;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) ob[e] = (bf16)o[e];
+              *(bf16x4*)((bf16*)g.C2 + (size_t)m * s.ldc2 + n) = ob;
+            }
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (n + e < s.N) store1(m, n + e, v[e], rs);
+        }
+      }
+      __syncthreads();
     }
   }
   if (TAIL && tail) {     // 16x16 result tile: lane holds column lane % 16, rows 4*(lane/16) + r
@@ -226,14 +266,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       if (m >= s.M) continue;
       if (EPI == EPI_SWIGLU) {
         const int n = n0 + (wave >> 1) * 32 + (wave & 1) * 16 + (lane & 15);
-        if (n < s.N) swiglu(m, n, tacc[0][r], tacc[1][r]);
+        if (n < s.N) store1(m, n, silu_mul(tacc[0][r], tacc[1][r]), 1.f);
       } else {
         float rs = 1.f;
         if (EPI == EPI_RESID_F32 && g.rowscale) rs = g.rowscale[m];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           const int n = n0 + t_brow + t * 32;
-          if (n < s.N) store(m, n, tacc[t][r], rs);
+          if (n < s.N) store1(m, n, tacc[t][r], rs);
         }
       }
     }
@@ -261,7 +301,7 @@ inline hipError_t launch_mfma_tail(const GemmGroup* table, int first, int g, con
 // M = tiles * BM + 16 (a cell: seg_len rows + 16 memory rows) takes the tail variant.
 template <int BM, int BN, int WGM, int WGN, int EPI>
 inline hipError_t launch_mfma_cfg(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st) {
-  if constexpr (BN == WGM * WGN * 32) {
+  if constexpr (BN <= WGM * WGN * 32) {
     if (s.M > BM && s.M % BM == 16 && !(s.dbg & 32))
       return launch_mfma_tail<BM, BN, WGM, WGN, EPI, true>(table, first, g, s, st);
   }
@@ -274,11 +314,12 @@ template <int EPI>
 inline hipError_t launch_gemm_mfma_epi(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st,
                                        int force_cfg) {
   int cfg = force_cfg;
-  if (cfg < 0) cfg = (s.M >= 192 && s.N >= 192) ? 0 : ((s.M >= 96 && s.N >= 96) ? 1 : 2);
+  if (cfg < 0) cfg = (s.M >= 192 && s.N >= 192) ? 4 : ((s.M >= 96 && s.N >= 96) ? 1 : 2);
   switch (cfg) {
     case 0: return launch_mfma_cfg<256, 256, 2, 4, EPI>(table, first, g, s, st);
     case 1: return launch_mfma_cfg<128, 128, 2, 2, EPI>(table, first, g, s, st);
     case 3: return launch_mfma_cfg<128, 256, 2, 4, EPI>(table, first, g, s, st);
+    case 4: return launch_mfma_cfg<256, 256, 4, 4, EPI>(table, first, g, s, st);
     default: return launch_mfma_cfg<64, 128, 2, 2, EPI>(table, first, g, s, st);
   }
 }

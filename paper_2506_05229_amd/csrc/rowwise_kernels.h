@@ -248,4 +248,80 @@ __global__ __launch_bounds__(256) void delta_rule_kernel(const float* __restrict
   }
 }
 
+// Fast path of the delta rule for n_mem = 16 and Phi = 64 * NPL: phi(k_i) lives in registers (lane owns columns
+// lane + 64 k), the 16 dot products of a row are reduced with a transposing butterfly (17 exchanges instead of
+// 16 full wave reductions; afterwards lane L holds the complete dot product for i = (L >> 2) & 15), and the 16
+// coefficients are broadcast through scalar registers.  grid: (ceil(d / rows_per_block), g), block: 256.
+template <int NPL>
+__global__ __launch_bounds__(256) void delta_rule16_kernel(const float* __restrict__ KV, const float* __restrict__ Fm,
+                                                           const float* __restrict__ Coef,
+                                                           const LayerAux* __restrict__ aux, int first, int d, int dm,
+                                                           int rows_per_block) {
+  constexpr int M = 16, Phi = 64 * NPL;
+  const int l = first + blockIdx.y;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const float* Fl = Fm + (size_t)l * M * Phi;
+  const float* cf = Coef + (size_t)l * M * 4;
+  float f[M][NPL];
+#pragma unroll
+  for (int i = 0; i < M; ++i)
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) f[i][k] = Fl[i * Phi + lane + 64 * k];
+  const int mi = (lane >> 2) & 15;                 // the memory token whose dot product this lane ends up with
+  const float beta = cf[mi * 4 + 0], rden = cf[mi * 4 + 2];
+  const float* Vmi = KV + (size_t)l * M * (dm + d) + (size_t)mi * (dm + d) + dm;
+  float* A = aux[l].A;
+  bf16* A16 = aux[l].A16;
+  const bool b5 = lane & 32, b4 = lane & 16, b3 = lane & 8, b2 = lane & 4;
+  const int r0 = blockIdx.x * rows_per_block, r1 = min(d, r0 + rows_per_block);
+  for (int r = r0 + w; r < r1; r += 4) {
+    float a[NPL];
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) a[k] = A[(size_t)r * Phi + lane + 64 * k];
+    const float vr = Vmi[r];
+    float p[M];
+#pragma unroll
+    for (int i = 0; i < M; ++i) {
+      float t = 0.f;
+#pragma unroll
+      for (int k = 0; k < NPL; ++k) t = fmaf(a[k], f[i][k], t);
+      p[i] = t;
+    }
+    float q8[8], q4[4], q2[2];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) q8[j] = (b5 ? p[j + 8] : p[j]) + __shfl_xor(b5 ? p[j] : p[j + 8], 32, kWave);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) q4[j] = (b4 ? q8[j + 4] : q8[j]) + __shfl_xor(b4 ? q8[j] : q8[j + 4], 16, kWave);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) q2[j] = (b3 ? q4[j + 2] : q4[j]) + __shfl_xor(b3 ? q4[j] : q4[j + 2], 8, kWave);
+    float dot = (b2 ? q2[1] : q2[0]) + __shfl_xor(b2 ? q2[0] : q2[1], 4, kWave);
+    dot += __shfl_xor(dot, 2, kWave);
+    dot += __shfl_xor(dot, 1, kWave);
+    const float coef = beta * (vr - dot * rden);      // beta_i (v_i[r] - v_bar_i[r])
+    float upd[NPL] = {};
+#pragma unroll
+    for (int i = 0; i < M; ++i) {
+      const float ci = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, coef), i * 4));
+#pragma unroll
+      for (int k = 0; k < NPL; ++k) upd[k] = fmaf(ci, f[i][k], upd[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) {
+      const float v = a[k] + upd[k];
+      A[(size_t)r * Phi + lane + 64 * k] = v;
+      if (A16) A16[(size_t)r * Phi + lane + 64 * k] = (bf16)v;
+    }
+  }
+  if (blockIdx.x == 0 && w == 0) {
+    float* z = aux[l].z;
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) {
+      float s = 0.f;
+#pragma unroll
+      for (int i = 0; i < M; ++i) s = fmaf(cf[i * 4 + 1], f[i][k], s);
+      z[lane + 64 * k] += s;
+    }
+  }
+}
+
 }  // namespace armt
