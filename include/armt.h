@@ -124,7 +124,7 @@ int32_t armt_diagonal_group(int32_t n_layers, int32_t n_segments, int32_t t,
 /* Grouped GEMM (Section 3.3 item 1, Section 4.1): C_i = A_i B_i^T for i < g, every group with its own
  * operand pointers.  a, b, c are [host] arrays of g device pointers: A_i [M, K], B_i [N, K] (a weight,
  * [out, in]) and C_i [M, N], all of type dtype (fp32 accumulation).  dtype BF16 needs K % 64 == 0.
- * workspace: g * 64 bytes, 256-byte aligned (holds the pointer table). */
+ * workspace: g * 128 bytes, 256-byte aligned (holds the pointer table). */
 armt_status armt_grouped_gemm(int32_t dtype, int32_t g, int32_t M, int32_t N, int32_t K,
                               const void *const *a, const void *const *b, void *const *c,
                               void *workspace, size_t workspace_bytes, void *hip_stream);

@@ -194,7 +194,7 @@ def grouped_gemm(a_list, b_list, out_list=None, workspace=None):
     if out_list is None:
         out_list = [torch.empty((M, N), dtype=dt, device=a_list[0].device) for _ in range(g)]
     if workspace is None:
-        workspace = torch.empty(max(256, g * 64), dtype=torch.uint8, device=a_list[0].device)
+        workspace = torch.empty(max(256, g * 128), dtype=torch.uint8, device=a_list[0].device)
     code = lib.armt_grouped_gemm(ARMT_BF16 if dt == torch.bfloat16 else ARMT_F32, g, M, N, K, _ptr_array(a_list),
                                  _ptr_array(b_list), _ptr_array(out_list), _ptr(workspace), workspace.numel(),
                                  _stream(torch))

@@ -81,7 +81,7 @@ armt_status check_config(const armt_config* c, Dims* out) {
 enum Kind { K_MQ = 0, K_READ, K_QKV, K_O, K_GU, K_DOWN, K_MKV, K_COUNT };
 
 struct Layout {          // byte offsets into the workspace
-  size_t X, Xb, Nrm, QKV, Vt, Att, Hres, Uff, Qm, Fphi, RDen, A16, KVm, Fm, Coef, Rope, Tables, Aux, total;
+  size_t X, Xb, Nrm, QKV, Vt, Att, Hres, Uff, Qm, Fphi, RDen, A16, KVm, Fm, Coef, Rope, Ssq, RStd, Tables, Aux, total;
 };
 
 Layout carve(const Dims& D) {
@@ -105,11 +105,20 @@ Layout carve(const Dims& D) {
   o.Fm = take(L * D.m * (size_t)D.Phi * 4);
   o.Coef = take(L * D.m * 4 * 4);
   o.Rope = take(T * (D.dh / 2) * 2 * 4);
+  o.Ssq = take(D.bf16 ? L * T * (size_t)((D.d + 63) / 64) * 4 : 0);   // per-tile sums of squares (fused RMSNorm)
+  o.RStd = take(D.bf16 ? L * T * 4 : 0);
   o.Tables = take((size_t)K_COUNT * L * sizeof(GemmGroup));
   o.Aux = take(L * sizeof(LayerAux));
   o.total = p;
   return o;
 }
+
+// ARMT_DEBUG_GENERIC=1 routes bf16 work through the plain fp32-FMA kernels (slow; for debugging only).
+bool debug_generic() {
+  static const bool v = [] { const char* e = getenv("ARMT_DEBUG_GENERIC"); return e && e[0] == '1'; }();
+  return v;
+}
+
 
 int g_gemm_tile_config = -1;     // armt_set_gemm_tile_config
 int g_gemm_dbg = 0;              // diagnosis variants (tile config / 100)
@@ -122,6 +131,8 @@ struct Ctx {
   const GemmGroup* tables;   // device: [K_COUNT][L]
   const LayerAux* aux;       // device: [L]
   GemmShape shape[K_COUNT];
+  bool fused_norm;           // bf16 MFMA path: RMSNorm folded into the GEMM epilogues around it
+  int ssq_parts;             // N-tiles of the GEMMs that produce a normalised row (d / tile width)
   template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
   const GemmGroup* table(int kind) const { return tables + (size_t)kind * D.L; }
 };
@@ -142,6 +153,11 @@ void fill_shapes(Ctx& c) {
   set(K_GU, D.T, D.F, D.d, D.d, D.F, 0, 0, D.F, D.F, EPI_SWIGLU);
   set(K_DOWN, D.T, D.d, D.F, D.F, D.d, D.d, D.d, D.d, 0, EPI_RESID_F32);
   set(K_MKV, D.m, D.dm + D.d, D.d, D.d, D.dm + D.d, 0, 0, D.dm, D.d, EPI_STORE_F32);
+  c.fused_norm = D.bf16 && !debug_generic();
+  if (c.fused_norm) c.shape[K_READ].ldc2 = c.shape[K_O].ldc2 = D.d;
+  // the read GEMM and the attention-output GEMM both have N = d and pick the same tile configuration
+  const int tile_n = mfma_tile_n(mfma_pick_config(c.shape[K_O], g_gemm_tile_config));
+  c.ssq_parts = (D.d + tile_n - 1) / tile_n;
 }
 
 // Build the per-layer pointer tables on the host and copy them into the workspace.
@@ -166,15 +182,22 @@ armt_status upload_tables(Ctx& c, const armt_layer_weights* W, float* A, float* 
     g->B0 = D.bf16 ? (const void*)A16l : (const void*)Al;
     g->C = X + l * slotX; g->R = (const float*)(X + l * slotX);
     g->rowscale = (const float*)(c.ws + c.o.RDen + l * T * 4);
+    void* nrm = c.ws + c.o.Nrm + l * T * D.d * D.esz;
+    float* ssq = (float*)(c.ws + c.o.Ssq) + l * T * c.ssq_parts;
+    const float* rstd = (const float*)(c.ws + c.o.RStd) + l * T;
+    if (c.fused_norm) { g->C2 = nrm; g->gain = w.rms1; g->ssq_out = ssq; }   // input of the first norm
     g = &tab[K_QKV * L + l];
-    g->A = c.ws + c.o.Nrm + l * T * D.d * D.esz; g->B0 = w.wq; g->B1 = w.wk; g->B2 = w.wv;
+    g->A = nrm; g->B0 = w.wq; g->B1 = w.wk; g->B2 = w.wv;
     g->C = c.ws + c.o.QKV + l * T * D.Nqkv * D.esz;
+    if (c.fused_norm) g->rowscale = rstd;
     g = &tab[K_O * L + l];
     g->A = c.ws + c.o.Att + l * T * D.d * D.esz; g->B0 = w.wo;
     g->C = c.ws + c.o.Hres + l * T * D.d * 4; g->R = (const float*)(X + l * slotX);
+    if (c.fused_norm) { g->C2 = nrm; g->gain = w.rms2; g->ssq_out = ssq; }   // input of the second norm
     g = &tab[K_GU * L + l];
-    g->A = c.ws + c.o.Nrm + l * T * D.d * D.esz; g->B0 = w.wgate; g->B1 = w.wup;
+    g->A = nrm; g->B0 = w.wgate; g->B1 = w.wup;
     g->C = c.ws + c.o.Uff + l * T * D.F * D.esz;
+    if (c.fused_norm) g->rowscale = rstd;
     g = &tab[K_DOWN * L + l];
     g->A = c.ws + c.o.Uff + l * T * D.F * D.esz; g->B0 = w.wdown;
     g->C = X + (l + 1) * slotX; g->C2 = D.bf16 ? Xop + (l + 1) * slotXop : nullptr;
@@ -194,13 +217,6 @@ armt_status upload_tables(Ctx& c, const armt_layer_weights* W, float* A, float* 
   c.aux = c.at<LayerAux>(c.o.Aux);
   return ARMT_OK;
 }
-
-// ARMT_DEBUG_GENERIC=1 routes bf16 work through the plain fp32-FMA kernels (slow; for debugging only).
-bool debug_generic() {
-  static const bool v = [] { const char* e = getenv("ARMT_DEBUG_GENERIC"); return e && e[0] == '1'; }();
-  return v;
-}
-
 
 // Optional timing of one GEMM kind with HIP events on the launch stream (armt_profile_*).
 struct Profile {
@@ -303,15 +319,34 @@ armt_status run_group(const Ctx& c, int lo, int hi, int read_hi, int empty_layer
   ARMT_TRY(step_assoc_read<T>(c.st, c.table(K_MQ), c.shape[K_MQ], c.table(K_READ), c.shape[K_READ], c.aux, lo,
                               read_hi - lo + 1, D.T, D.dm, D.nu, D.assoc_eps, c.at<float>(c.o.Qm), c.at<T>(c.o.Fphi),
                               c.at<float>(c.o.RDen)));
-  // (2) decoder block (TransformerLayer of Eq. 2)
-  rmsnorm_kernel<T><<<dim3(D.T, g), 256, 0, c.st>>>(X, c.aux, lo, 0, D.T, D.d, D.rms_eps, c.at<T>(c.o.Nrm));
-  HIP_TRY(hipGetLastError());
+  // (2) decoder block (TransformerLayer of Eq. 2).  On the bf16 path both RMSNorms are folded into the GEMMs
+  // around them: the producer of a row (read GEMM, attention-output GEMM) also writes bf16(row * gain) and the
+  // row's sum of squares per N-tile; the consumer GEMM multiplies its result rows by 1 / rms.
+  float* rstd = c.at<float>(c.o.RStd);
+  if (c.fused_norm) {
+    const int gr = read_hi - lo + 1;
+    if (gr > 0) {
+      rstd_kernel<<<dim3((D.T + 255) / 256, gr), 256, 0, c.st>>>(c.at<float>(c.o.Ssq), lo, D.T, c.ssq_parts, D.d, D.rms_eps, rstd);
+      HIP_TRY(hipGetLastError());
+    }
+    if (gr < g) {      // cells that met an empty memory had no read GEMM in front of the norm
+      rmsnorm_kernel<T><<<dim3(D.T, g - gr), 256, 0, c.st>>>(X, c.aux, lo + gr, 0, D.T, D.d, D.rms_eps, c.at<T>(c.o.Nrm), rstd);
+      HIP_TRY(hipGetLastError());
+    }
+  } else {
+    rmsnorm_kernel<T><<<dim3(D.T, g), 256, 0, c.st>>>(X, c.aux, lo, 0, D.T, D.d, D.rms_eps, c.at<T>(c.o.Nrm), nullptr);
+    HIP_TRY(hipGetLastError());
+  }
   ARMT_TRY(gemm<T>(c.st, c.table(K_QKV), lo, g, c.shape[K_QKV]));
   ARMT_TRY(step_attention<T>(c.st, c.at<T>(c.o.QKV), c.at<T>(c.o.Att), c.at<bf16>(c.o.Vt), c.at<float>(c.o.Rope), lo, g,
                              D.T, D.H, D.Hkv, D.dh));
   ARMT_TRY(gemm<T>(c.st, c.table(K_O), lo, g, c.shape[K_O]));
-  rmsnorm_kernel<T><<<dim3(D.T, g), 256, 0, c.st>>>(c.at<float>(c.o.Hres), c.aux, lo, 1, D.T, D.d, D.rms_eps,
-                                                    c.at<T>(c.o.Nrm));
+  if (c.fused_norm) {
+    rstd_kernel<<<dim3((D.T + 255) / 256, g), 256, 0, c.st>>>(c.at<float>(c.o.Ssq), lo, D.T, c.ssq_parts, D.d, D.rms_eps, rstd);
+  } else {
+    rmsnorm_kernel<T><<<dim3(D.T, g), 256, 0, c.st>>>(c.at<float>(c.o.Hres), c.aux, lo, 1, D.T, D.d, D.rms_eps,
+                                                      c.at<T>(c.o.Nrm), nullptr);
+  }
   HIP_TRY(hipGetLastError());
   ARMT_TRY(gemm<T>(c.st, c.table(K_GU), lo, g, c.shape[K_GU]));
   ARMT_TRY(gemm<T>(c.st, c.table(K_DOWN), lo, g, c.shape[K_DOWN]));

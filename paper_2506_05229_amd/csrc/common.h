@@ -61,13 +61,17 @@ struct GemmGroup {
   void* C2;               // optional copy of C in the activation type (or null)
   const float* R;         // residual [M, ldr] (or null)
   const float* rowscale;  // per-row factor applied to the accumulator (or null)
+  const void* gain;       // EPI_RESID_F32: C2 = (bf16)(result * gain[col]) instead of (bf16)result (or null)
+  float* ssq_out;         // EPI_RESID_F32: [M][tiles_n] per-row sums of squares of the result, one per N-tile (or null)
+  const void* pad_[6];    // keep entries at 128 bytes
 };
+static_assert(sizeof(GemmGroup) == 128, "pointer-table entries are 128 bytes");
 
 enum GemmEpilogue : int {
-  EPI_STORE_ACT = 0,   // C (activation type) = acc
-  EPI_STORE_F32 = 1,   // C (fp32) = acc
+  EPI_STORE_ACT = 0,   // C (activation type) = acc * rowscale[row]
+  EPI_STORE_F32 = 1,   // C (fp32) = acc * rowscale[row]
   EPI_RESID_F32 = 2,   // C (fp32) = R + acc * rowscale[row]; C2 (activation type) = same, if given
-  EPI_SWIGLU = 3       // C (activation type) = silu(acc over B0) * (acc over B1); logical N = rows of B0
+  EPI_SWIGLU = 3       // C (activation type) = silu(rs * acc over B0) * (rs * acc over B1), rs = rowscale[row]; N = rows of B0
 };
 
 struct GemmShape {

@@ -82,23 +82,23 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const GemmGroup* __re
   for (int i = 0; i < 4; ++i) {
     const int m = m0 + ty * 4 + i;
     if (m >= s.M) continue;
-    const float rs = (s.epi == EPI_RESID_F32 && g.rowscale) ? g.rowscale[m] : 1.f;
+    const float rs = g.rowscale ? g.rowscale[m] : 1.f;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int n = n0 + tx * 4 + j;
       if (n >= s.N) continue;
       const float v = acc[i][j];
       switch (s.epi) {
-        case EPI_STORE_ACT: ((T*)g.C)[(size_t)m * s.ldc + n] = from_f32<T>(v); break;
-        case EPI_STORE_F32: ((float*)g.C)[(size_t)m * s.ldc + n] = v; break;
+        case EPI_STORE_ACT: ((T*)g.C)[(size_t)m * s.ldc + n] = from_f32<T>(v * rs); break;
+        case EPI_STORE_F32: ((float*)g.C)[(size_t)m * s.ldc + n] = v * rs; break;
         case EPI_RESID_F32: {
           const float r = (g.R ? g.R[(size_t)m * s.ldr + n] : 0.f) + v * rs;
           ((float*)g.C)[(size_t)m * s.ldc + n] = r;
-          if (g.C2) ((T*)g.C2)[(size_t)m * s.ldc2 + n] = from_f32<T>(r);
+          if (g.C2) ((T*)g.C2)[(size_t)m * s.ldc2 + n] = from_f32<T>(g.gain ? r * to_f32(((const T*)g.gain)[n]) : r);
         } break;
         case EPI_SWIGLU: {
-          const float sg = v / (1.f + expf(-v));
-          ((T*)g.C)[(size_t)m * s.ldc + n] = from_f32<T>(sg * acu[i][j]);
+          const float gv = v * rs, sg = gv / (1.f + expf(-gv));
+          ((T*)g.C)[(size_t)m * s.ldc + n] = from_f32<T>(sg * (acu[i][j] * rs));
         } break;
       }
     }

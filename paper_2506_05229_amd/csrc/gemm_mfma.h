@@ -48,7 +48,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   static_assert(!TAIL || (BN <= NW * 32 && NW >= 2), "the tail strip gives each of the first BN / 32 waves two 16-column tiles");
   constexpr int TAIL_WAVES = BN / 32;
 
-  extern __shared__ __align__(16) unsigned char smem[];   // [2][A_BYTES] then [2][B_BYTES]
+  extern __shared__ __align__(16) unsigned char smem[];   // [2][A_BYTES], [2][B_BYTES], then A_ROWS row scales
 
   // XCD-aware tile order: workgroup b runs on XCD b % 8; give each XCD a contiguous range.
   const int per_xcd = (total_tiles + 7) >> 3;
@@ -63,6 +63,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // per-row scale of the result (1 / rms of a fused RMSNorm, or 1 / denominator of the associative read),
+  // fetched once; visible to everybody after the first barrier of the main loop
+  float* rs_lds = (float*)(smem + 2 * A_BYTES + 2 * B_BYTES);
+  for (int r = tid; r < A_ROWS; r += NW * 64) rs_lds[r] = (g.rowscale && m0 + r < s.M) ? g.rowscale[m0 + r] : 1.f;
   const int wm = wave / WGN, wn = wave % WGN;
   const bool tail = tail_blk && wave < (TAIL ? BN / 32 : 0);   // wave-uniform: this wave computes part of the strip
 
@@ -188,102 +192,126 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   // column (lane % 32) and registers = rows 8*(r/4) + 4*(lane/32) + r%4, which written directly would touch
   // global memory in 128-byte pieces.  Instead, in TM * 2 passes every wave drops 16 rows of its tile into a
   // fp32 staging tile [WGM * 16][BN_OUT + 8] (the +8 keeps the two half-waves on different banks), and all
-  // threads then walk the staging tile row-major, one wave per row: 16-byte accesses, full rows of R, C, C2.
+  // threads then walk the staging tile row-major, C4 = BN_OUT / 4 lanes per row: 16-byte accesses, full rows
+  // of R, C, C2.  The tail strip goes through the same path as one more pass of 16 rows.
   // The tile buffers are free here: the main loop ended with a barrier.
-  auto store1 = [&](int m, int n, float v, float rs) {
-    if (EPI == EPI_STORE_ACT || EPI == EPI_SWIGLU) {
-      ((bf16*)g.C)[(size_t)m * s.ldc + n] = (bf16)v;
-    } else if (EPI == EPI_STORE_F32) {
-      ((float*)g.C)[(size_t)m * s.ldc + n] = v;
-    } else {
-      const float o = (g.R ? g.R[(size_t)m * s.ldr + n] : 0.f) + v * rs;
-      ((float*)g.C)[(size_t)m * s.ldc + n] = o;
-      if (g.C2) ((bf16*)g.C2)[(size_t)m * s.ldc2 + n] = (bf16)o;
-    }
-  };
+  constexpr int SLD = BN_OUT + 8, SR = WGM * 16, C4 = BN_OUT / 4, NT = NW * 64;
+  static_assert(SR * SLD * 4 <= 2 * (A_BYTES + B_BYTES), "staging tile must fit in the tile buffers");
+  static_assert(C4 == 16 || C4 == 32 || C4 == 64, "a staged row is handled by 16, 32 or 64 consecutive lanes");
+  float* stg = (float*)smem;
+  const bool vec_ok = ((s.N | s.ldc | s.ldr | s.ldc2) & 3) == 0;
   auto silu_mul = [](float gt, float up) { return gt / (1.f + __expf(-gt)) * up; };
-  {
-    constexpr int SLD = BN_OUT + 8, SR = WGM * 16, C4 = BN_OUT / 4, CHUNKS = SR * C4, NT = NW * 64;
-    static_assert(SR * SLD * 4 <= 2 * (A_BYTES + B_BYTES), "staging tile must fit in the tile buffers");
-    float* stg = (float*)smem;
-    const bool vec_ok = ((s.N | s.ldc | s.ldr | s.ldc2) & 3) == 0;
-    const int col_in = lane & 31;
+  auto row_scale = [&](int m) { return rs_lds[m - m0]; };
+  // walk nrows staged rows; staged row sr is output row m_of(sr)
+  auto drain = [&](int nrows, auto m_of) {
+    for (int q = tid; q < nrows * C4; q += NT) {
+      const int sr = q / C4, c4 = q - sr * C4;
+      const int m = m_of(sr), n = n0 + c4 * 4;
+      const bool valid = m < s.M && n < s.N;
+      f32x4 o = {0.f, 0.f, 0.f, 0.f};
+      if (valid) {
+        o = *(const f32x4*)(stg + sr * SLD + c4 * 4);
+        if (EPI != EPI_SWIGLU) o *= row_scale(m);        // SwiGLU applied it before the nonlinearity
+        if (EPI == EPI_RESID_F32 && g.R) {
+          if (vec_ok) {
+            o += *(const f32x4*)(g.R + (size_t)m * s.ldr + n);
+          } else {
 #pragma unroll
-    for (int pass = 0; pass < TM * 2; ++pass) {
-      const int i = pass >> 1, rh = pass & 1;
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        const int r = rh * 8 + q;
-        float* dst = stg + (wm * 16 + 8 * (q >> 2) + 4 * half + (q & 3)) * SLD + col_in;
-        if (EPI == EPI_SWIGLU) {
-#pragma unroll
-          for (int j = 0; j < TN; j += 2) dst[((wn * TN + j) >> 1) * 32] = silu_mul(acc[i][j][r], acc[i][j + 1][r]);
-        } else {
-#pragma unroll
-          for (int j = 0; j < TN; ++j) dst[wn * WCOLS + j * 32] = acc[i][j][r];
+            for (int e = 0; e < 4; ++e)
+              if (n + e < s.N) o[e] += g.R[(size_t)m * s.ldr + n + e];
+          }
         }
-      }
-      __syncthreads();
-      for (int q = tid; q < CHUNKS; q += NT) {
-        const int sr = q / C4, c4 = q - sr * C4;
-        const int m = m0 + (sr >> 4) * WROWS + i * 32 + rh * 16 + (sr & 15), n = n0 + c4 * 4;
-        if (m >= s.M || n >= s.N) continue;
-        const f32x4 v = *(const f32x4*)(stg + sr * SLD + c4 * 4);
-        float rs = 1.f;
-        if (EPI == EPI_RESID_F32 && g.rowscale) rs = g.rowscale[m];
+        if (!vec_ok) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (n + e >= s.N) o[e] = 0.f;
+        }
+        bf16x4 ob, og;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ob[e] = (bf16)o[e];
+        if (EPI == EPI_RESID_F32 && g.C2) {
+          if (g.gain) {      // the copy is the un-normalised input of the next RMSNorm: x * gain
+#pragma unroll
+            for (int e = 0; e < 4; ++e) og[e] = (bf16)(o[e] * (float)((const bf16*)g.gain)[min(n + e, s.N - 1)]);
+          } else {
+            og = ob;
+          }
+        }
         if (vec_ok) {
           if (EPI == EPI_STORE_ACT || EPI == EPI_SWIGLU) {
-            bf16x4 o;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
-            *(bf16x4*)((bf16*)g.C + (size_t)m * s.ldc + n) = o;
-          } else if (EPI == EPI_STORE_F32) {
-            *(f32x4*)((float*)g.C + (size_t)m * s.ldc + n) = v;
+            *(bf16x4*)((bf16*)g.C + (size_t)m * s.ldc + n) = ob;
           } else {
-            f32x4 o = v * rs;
-            if (g.R) o += *(const f32x4*)(g.R + (size_t)m * s.ldr + n);
             *(f32x4*)((float*)g.C + (size_t)m * s.ldc + n) = o;
-            if (g.C2) {
-              bf16x4 ob;
-#pragma unroll
-              for (int e = 0; e < 4; ++e) ob[e] = (bf16)o[e];
-              *(bf16x4*)((bf16*)g.C2 + (size_t)m * s.ldc2 + n) = ob;
-            }
+            if (EPI == EPI_RESID_F32 && g.C2) *(bf16x4*)((bf16*)g.C2 + (size_t)m * s.ldc2 + n) = og;
           }
         } else {
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (n + e < s.N) store1(m, n + e, v[e], rs);
+          for (int e = 0; e < 4; ++e) {
+            if (n + e >= s.N) continue;
+            if (EPI == EPI_STORE_ACT || EPI == EPI_SWIGLU) {
+              ((bf16*)g.C)[(size_t)m * s.ldc + n + e] = ob[e];
+            } else {
+              ((float*)g.C)[(size_t)m * s.ldc + n + e] = o[e];
+              if (EPI == EPI_RESID_F32 && g.C2) ((bf16*)g.C2)[(size_t)m * s.ldc2 + n + e] = og[e];
+            }
+          }
         }
       }
-      __syncthreads();
-    }
-  }
-  if (TAIL && tail) {     // 16x16 result tile: lane holds column lane % 16, rows 4*(lane/16) + r
+      if (EPI == EPI_RESID_F32 && g.ssq_out) {
+        // sum of squares of this row over the tile's columns, for the RMSNorm that consumes the row:
+        // one partial per (row, N-tile), summed later in tile order (deterministic, no atomics)
+        float part = o[0] * o[0] + o[1] * o[1] + o[2] * o[2] + o[3] * o[3];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int m = m0 + BM + 4 * t_q + r;
-      if (m >= s.M) continue;
+        for (int off = C4 / 2; off > 0; off >>= 1) part += __shfl_xor(part, off, kWave);
+        if (c4 == 0 && m < s.M) g.ssq_out[(size_t)m * tiles_n + tn] = part;
+      }
+    }
+  };
+  const int col_in = lane & 31;
+#pragma unroll
+  for (int pass = 0; pass < TM * 2; ++pass) {
+    const int i = pass >> 1, rh = pass & 1;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int r = rh * 8 + q, row16 = 8 * (q >> 2) + 4 * half + (q & 3);
+      float* dst = stg + (wm * 16 + row16) * SLD + col_in;
       if (EPI == EPI_SWIGLU) {
-        const int n = n0 + (wave >> 1) * 32 + (wave & 1) * 16 + (lane & 15);
-        if (n < s.N) store1(m, n, silu_mul(tacc[0][r], tacc[1][r]), 1.f);
-      } else {
-        float rs = 1.f;
-        if (EPI == EPI_RESID_F32 && g.rowscale) rs = g.rowscale[m];
+        const float rs = row_scale(m0 + wm * WROWS + i * 32 + rh * 16 + row16);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const int n = n0 + t_brow + t * 32;
-          if (n < s.N) store1(m, n, tacc[t][r], rs);
+        for (int j = 0; j < TN; j += 2)
+          dst[((wn * TN + j) >> 1) * 32] = silu_mul(rs * acc[i][j][r], rs * acc[i][j + 1][r]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) dst[wn * WCOLS + j * 32] = acc[i][j][r];
+      }
+    }
+    __syncthreads();
+    drain(SR, [&](int sr) { return m0 + (sr >> 4) * WROWS + i * 32 + rh * 16 + (sr & 15); });
+    __syncthreads();
+  }
+  if (TAIL && tail_blk) {     // 16x16 result tile: lane holds column lane % 16, rows 4*(lane/16) + r
+    if (tail) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float* dst = stg + (4 * t_q + r) * SLD;
+        if (EPI == EPI_SWIGLU) {
+          const float rs = row_scale(m0 + BM + 4 * t_q + r);
+          dst[(wave >> 1) * 32 + (wave & 1) * 16 + (lane & 15)] = silu_mul(rs * tacc[0][r], rs * tacc[1][r]);
+        } else {
+          dst[t_brow] = tacc[0][r];
+          dst[t_brow + 32] = tacc[1][r];
         }
       }
     }
+    __syncthreads();
+    drain(16, [&](int sr) { return m0 + BM + sr; });
   }
 }
 
 template <int BM, int BN, int WGM, int WGN, int EPI, bool TAIL>
 inline hipError_t launch_mfma_tail(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st) {
   constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
-  constexpr int LDS = 2 * ((TAIL ? BM + 16 : BM) + BN) * MF_ROW_BYTES;
+  constexpr int LDS = 2 * ((TAIL ? BM + 16 : BM) + BN) * MF_ROW_BYTES + (BM + 16) * 4;
   const int tiles_m = TAIL ? s.M / BM : (s.M + BM - 1) / BM, tiles_n = (s.N + BN_OUT - 1) / BN_OUT;
   const int total = g * tiles_m * tiles_n;
   const int grid = ((total + 7) / 8) * 8;
@@ -308,13 +336,19 @@ inline hipError_t launch_mfma_cfg(const GemmGroup* table, int first, int g, cons
   return launch_mfma_tail<BM, BN, WGM, WGN, EPI, false>(table, first, g, s, st);
 }
 
+inline int mfma_pick_config(const GemmShape& s, int force_cfg) {
+  if (force_cfg >= 0 && force_cfg < MF_NUM_CONFIGS) return force_cfg;
+  return (s.M >= 192 && s.N >= 192) ? 4 : ((s.M >= 96 && s.N >= 96) ? 1 : 2);
+}
+// output columns per tile of a configuration (the SwiGLU epilogue halves it)
+inline int mfma_tile_n(int cfg) { return (cfg == 1 || cfg == 2) ? 128 : 256; }
+
 // Tile configuration by problem shape: big square tiles for the block's linears, small tiles for
 // the skinny associative-memory projections (N = d_mem columns, or M = n_mem rows).
 template <int EPI>
 inline hipError_t launch_gemm_mfma_epi(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st,
                                        int force_cfg) {
-  int cfg = force_cfg;
-  if (cfg < 0) cfg = (s.M >= 192 && s.N >= 192) ? 4 : ((s.M >= 96 && s.N >= 96) ? 1 : 2);
+  const int cfg = mfma_pick_config(s, force_cfg);
   switch (cfg) {
     case 0: return launch_mfma_cfg<256, 256, 2, 4, EPI>(table, first, g, s, st);
     case 1: return launch_mfma_cfg<128, 128, 2, 2, EPI>(table, first, g, s, st);

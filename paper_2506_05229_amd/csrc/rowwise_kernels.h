@@ -58,10 +58,12 @@ __global__ void f32_to_bf16_kernel(bf16* __restrict__ dst, const float* __restri
 // ------------------------------------------------------------------------------------------------
 // RMSNorm with the gain of the cell's own layer (Section 3.3 item 2: per-layer norm weights).
 // X: [L+1][T][d] fp32 slots (or Hres [L][T][d]); out: [L][T][d].  grid: (T, g), block: 256.
+// With rstd_out the row is written as x * gain only and 1 / rms goes to rstd_out [L][T]: the following GEMM
+// applies it as a per-row scale of its result, (x * gain * rstd) W^T = rstd * ((x * gain) W^T).
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ X, const LayerAux* __restrict__ aux,
                                                       int first, int which, int Trows, int d, float eps,
-                                                      T* __restrict__ out) {
+                                                      T* __restrict__ out, float* __restrict__ rstd_out) {
   __shared__ float red[17];
   const int l = first + blockIdx.y;
   const size_t row = ((size_t)l * Trows + blockIdx.x) * d;
@@ -73,7 +75,21 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
   }
   ss = block_sum(ss, red);
   const float rstd = 1.0f / sqrtf(ss / (float)d + eps);
-  for (int c = threadIdx.x; c < d; c += blockDim.x) out[row + c] = from_f32<T>(X[row + c] * rstd * to_f32(gain[c]));
+  const float f = rstd_out ? 1.0f : rstd;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) out[row + c] = from_f32<T>(X[row + c] * f * to_f32(gain[c]));
+  if (rstd_out && threadIdx.x == 0) rstd_out[(size_t)l * Trows + blockIdx.x] = rstd;
+}
+
+// 1 / rms of every row from the per-tile sums of squares a GEMM epilogue left behind.
+// ssq: [L][T][parts]; rstd: [L][T].  grid: (ceil(T / 256), g), block: 256.
+__global__ __launch_bounds__(256) void rstd_kernel(const float* __restrict__ ssq, int first, int Trows, int parts,
+                                                   int d, float eps, float* __restrict__ rstd) {
+  const int l = first + blockIdx.y, r = blockIdx.x * 256 + threadIdx.x;
+  if (r >= Trows) return;
+  const float* p = ssq + ((size_t)l * Trows + r) * parts;
+  float s = 0.f;
+  for (int i = 0; i < parts; ++i) s += p[i];
+  rstd[(size_t)l * Trows + r] = 1.0f / sqrtf(s / (float)d + eps);
 }
 
 // ------------------------------------------------------------------------------------------------
