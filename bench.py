@@ -18,7 +18,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense bf16 matrix-core peak (published)
-FP32_VALU_PEAK_TFLOPS = 157.3
+# HBM bytes per cell of the gate/up GEMM at the 1B shape, from the two rocprofv3 --pmc runs summarised in
+# profiles/gate_up_gemm_1b_128k_hbm_traffic.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from the copy
+# calibration): (1.379 GB + 0.232 GB) / 13.6 cells per launch.  Algorithmic: 88.4 MB per cell.
+GATE_UP_HBM_BYTES_PER_CELL = {"1b": 118.5e6}
 
 
 def cpu_baseline(shape, layers, mem_emb, x, n_seg):
@@ -47,6 +50,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sequential", action="store_true")
     ap.add_argument("--cpu-segments", type=int, default=2)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain device copy of known size (the memory-state carry-in copy), so that a "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled against it")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
@@ -110,7 +116,12 @@ def main():
         achieved = per_launch / (k_ms / k_launches / 1e3) / 1e12
         res["roofline"] = {"kernel": "gemm_mfma_kernel<..., EPI_SWIGLU> (gate/up grouped GEMM + SiLU*up)",
                            "bound": "mfma", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                           "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": None,
+                           "frac": achieved / MFMA_PEAK_TFLOPS,
+                           "traffic": (GATE_UP_HBM_BYTES_PER_CELL["1b"] * k_groups / k_launches
+                                       if shape.name.startswith("1b_") and shape.seg_len == 1024 else None),
+                           "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated)",
+                           "algorithmic_bytes_per_launch": (2 * shape.d_ff * shape.d_model * 2 + shape.T * shape.d_model * 2
+                                                            + shape.T * shape.d_ff * 2) * k_groups / k_launches,
                            "avg_launch_ms": k_ms / k_launches, "launches": k_launches,
                            "avg_groups_per_launch": k_groups / k_launches,
                            "algorithmic_gflop_per_launch": per_launch / 1e9}
@@ -118,6 +129,12 @@ def main():
         sms, swall, _ = timed(False, max(1, min(args.steps, 2)), 0)
         res["sequential_tokens_per_s"] = n_tok / (swall / 1e3)
         res["speedup_vs_sequential"] = swall / wall_ms
+    if args.calibrate_copy:
+        # copy_f32_kernel moves the whole memory state A_in -> A_out: n_layers * d_model * Phi floats read and written
+        A_src, z_src = out[1].clone(), out[2].clone()
+        model.forward(xd[:shape.seg_len].contiguous(), diagonal=True, A_in=A_src, z_in=z_src)
+        torch.cuda.synchronize()
+        res["calibration_copy_bytes"] = int(A_src.numel() * 4)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(shape, layers, mem_emb, x, min(args.cpu_segments, shape.n_segments))
     res["input_generation_s"] = t_gen
