@@ -22,7 +22,7 @@ namespace armt {
 
 constexpr int MF_BK = 64;                 // k-tile (bf16 elements): 128 bytes per tile row
 constexpr int MF_ROW_BYTES = MF_BK * 2;
-constexpr int MF_NUM_CONFIGS = 5;         // tile configurations of launch_gemm_mfma_epi
+constexpr int MF_NUM_CONFIGS = 7;         // tile configurations of launch_gemm_mfma_epi
 
 // swizzle of the 16-byte chunk index inside a 128-byte tile row; depends on row bits 0..3 only
 __device__ __forceinline__ int mf_swz(int row) { return ((row >> 1) & 7) ^ ((row & 1) << 2); }
@@ -31,24 +31,35 @@ __device__ __forceinline__ int mf_swz(int row) { return ((row >> 1) & 7) ^ ((row
 // TAIL: the last M-tile of every group also owns the 16 rows that follow it (M = tiles_m * BM + 16).  With
 // T = seg_len + 16 memory rows and seg_len a multiple of BM this removes the nearly empty fifth tile a
 // 1040-row cell would otherwise need: the 16 memory rows ride along as one extra strip of 16x16x32 MFMAs.
-template <int BM, int BN, int WGM, int WGN, int EPI, bool TAIL>
-__global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGroup* __restrict__ table, int first,
-                                                                  GemmShape s, int tiles_m, int tiles_n,
-                                                                  int total_tiles) {
-  constexpr int NW = WGM * WGN;
+template <int N>
+__device__ __forceinline__ void mf_wait_vmcnt() {      // s_waitcnt vmcnt(N) only (N <= 63)
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
+
+// PW > 0: PW extra waves do nothing but the global -> LDS copies (and help with the epilogue's stores), the
+// WGM x WGN waves that multiply never issue a memory instruction in the main loop.  The copy path accepts a
+// limited number of outstanding instructions per CU; a wave that hits the limit stalls at issue, in order, with
+// its MFMAs queued behind the stalled copy.  With separate copy waves that stall costs no matrix-core time.
+template <int BM, int BN, int WGM, int WGN, int PW, bool REG, int EPI, bool TAIL, int NS>
+__global__ __launch_bounds__((WGM * WGN + PW) * 64) void gemm_mfma_kernel(const GemmGroup* __restrict__ table,
+                                                                           int first, GemmShape s, int tiles_m,
+                                                                           int tiles_n, int total_tiles) {
+  constexpr int NWC = WGM * WGN;                          // waves that multiply
+  constexpr int NW = NWC + PW;                            // all waves of the block
+  constexpr int DW = PW ? PW : NWC;                       // waves that copy
   constexpr int WROWS = BM / WGM, WCOLS = BN / WGN;       // wave tile
   constexpr int TM = WROWS / 32, TN = WCOLS / 32;         // 32x32 MFMA tiles per wave
-  constexpr int A_DMA = BM / 8 / NW, B_DMA = BN / 8 / NW; // 8-row (1 KB) slabs each wave copies per k-tile
+  constexpr int A_DMA = BM / 8 / DW, B_DMA = BN / 8 / DW; // 8-row (1 KB) slabs each copying wave moves per k-tile
   constexpr int A_ROWS = TAIL ? BM + 16 : BM;
   constexpr int A_BYTES = A_ROWS * MF_ROW_BYTES, B_BYTES = BN * MF_ROW_BYTES;
   constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;   // output columns per tile
   static_assert(BM % (WGM * 32) == 0 && BN % (WGN * 32) == 0, "wave tile must be a multiple of 32x32");
-  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must divide into 8-row slabs per wave");
+  static_assert(BM % (8 * DW) == 0 && BN % (8 * DW) == 0, "tile rows must divide into 8-row slabs per copying wave");
   static_assert(EPI != EPI_SWIGLU || TN % 2 == 0, "SwiGLU pairs gate/up 32-column tiles inside a wave");
-  static_assert(!TAIL || (BN <= NW * 32 && NW >= 2), "the tail strip gives each of the first BN / 32 waves two 16-column tiles");
+  static_assert(!TAIL || (BN <= NWC * 32 && DW >= 2), "the tail strip gives each of the first BN / 32 waves two 16-column tiles");
   constexpr int TAIL_WAVES = BN / 32;
 
-  extern __shared__ __align__(16) unsigned char smem[];   // [2][A_BYTES], [2][B_BYTES], then A_ROWS row scales
+  extern __shared__ __align__(16) unsigned char smem[];   // [NS][A_BYTES], [NS][B_BYTES], then A_ROWS row scales
 
   // XCD-aware tile order: workgroup b runs on XCD b % 8; give each XCD a contiguous range.
   const int per_xcd = (total_tiles + 7) >> 3;
@@ -65,62 +76,108 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // per-row scale of the result (1 / rms of a fused RMSNorm, or 1 / denominator of the associative read),
   // fetched once; visible to everybody after the first barrier of the main loop
-  float* rs_lds = (float*)(smem + 2 * A_BYTES + 2 * B_BYTES);
+  float* rs_lds = (float*)(smem + NS * A_BYTES + NS * B_BYTES);
   for (int r = tid; r < A_ROWS; r += NW * 64) rs_lds[r] = (g.rowscale && m0 + r < s.M) ? g.rowscale[m0 + r] : 1.f;
+  const bool is_prod = PW > 0 && wave >= NWC;                  // wave-uniform roles
+  const bool does_dma = PW == 0 || is_prod;
+  const int dw = PW ? wave - NWC : wave;                       // index among the copying waves
   const int wm = wave / WGN, wn = wave % WGN;
   const bool tail = tail_blk && wave < (TAIL ? BN / 32 : 0);   // wave-uniform: this wave computes part of the strip
 
   // ---- global -> LDS copies go straight to LDS (global_load_lds_dwordx4): one instruction moves 64 x 16
   // bytes into 1 KB of consecutive LDS = 8 tile rows.  Lane i fills row i / 8, physical chunk i % 8 of the
   // slab, so it fetches the logical chunk (i % 8) ^ swz(row) of that row from global memory.
-  const char* ap[A_DMA];
-  const char* bp[B_DMA];
-  const char* tp = nullptr;      // tail rows: waves 0 and 1 copy one extra slab each
-  {
-    const int R = lane >> 3, pc = lane & 7;
+  // first element of row `row` of this block's weight tile
+  auto b_row = [&](int row) -> const bf16* {
+    if (EPI == EPI_SWIGLU) {
+      // tile rows come in 32-row blocks: even blocks from the gate weight, odd from the up weight,
+      // both for output columns n0 + (block / 2) * 32 ...
+      const int blk = row >> 5;
+      const int n = min(n0 + (blk >> 1) * 32 + (row & 31), s.N - 1);
+      return (const bf16*)((blk & 1) ? g.B1 : g.B0) + (size_t)n * s.K;
+    }
+    return weight_row<bf16>(g, s, min(n0 + row, s.N - 1));
+  };
+  const int dR = lane >> 3, dpc = lane & 7;
+  // source of this lane for A slab j / the tail slab / B slab j, at k = 0
+  auto a_src = [&](int j) -> const char* {
+    const int row = (dw + j * DW) * 8 + dR;
+    const int m = min(m0 + row, s.M - 1);                  // rows past M re-read the last row; masked on store
+    return (const char*)g.A + ((size_t)m * s.lda + ((dpc ^ mf_swz(row)) << 3)) * 2;
+  };
+  auto t_src = [&]() -> const char* {                      // tail rows: copying waves 0 and 1 move one extra slab each
+    const int row = BM + (dw & 1) * 8 + dR;
+    const int m = min(m0 + row, s.M - 1);
+    return (const char*)g.A + ((size_t)m * s.lda + ((dpc ^ mf_swz(row)) << 3)) * 2;
+  };
+  auto b_src = [&](int j) -> const char* {
+    const int row = (dw + j * DW) * 8 + dR;
+    return (const char*)(b_row(row) + ((dpc ^ mf_swz(row)) << 3));
+  };
+  // Two ways to address the sources.
+  // General shapes: every lane keeps one 64-bit pointer per slab (rows past M or N are clamped per lane).
+  // Regular shapes (REG: no ragged M or N, weight blocks that end on tile boundaries): all sources of a lane
+  // differ by wave-uniform amounts, because the swizzle of row 8 * slab + lane / 8 depends on the slab's parity
+  // only and the copying wave's slabs dw + DW * j all have the parity of dw.  One 32-bit lane offset per operand
+  // plus a scalar base per slab then address everything, and issuing a copy takes scalar instructions only.
+  // That matters: a wave's vector-ALU instructions are not issued while other waves keep the SIMD's
+  // matrix core busy with back-to-back MFMAs, scalar and memory instructions are.  Address arithmetic in the
+  // vector ALU would hold the copies back until the multiplying waves pause.
+  constexpr bool KEEP_PTRS = !REG;
+  static_assert(!REG || DW % 2 == 0, "slabs of a copying wave must share their parity");
+  static_assert(REG || PW == 0, "copy waves only exist for regular shapes");
+  const char* ap[KEEP_PTRS ? A_DMA : 1];
+  const char* bp[KEEP_PTRS ? B_DMA : 1];
+  const char* tp = nullptr;
+  unsigned a_off0 = 0, b_off0 = 0;
+  if (KEEP_PTRS) {
 #pragma unroll
-    for (int j = 0; j < A_DMA; ++j) {
-      const int row = (wave + j * NW) * 8 + R;
-      const int m = min(m0 + row, s.M - 1);                // rows past M re-read the last row; masked on store
-      ap[j] = (const char*)g.A + ((size_t)m * s.lda + ((pc ^ mf_swz(row)) << 3)) * 2;
-    }
-    if (TAIL) {
-      const int row = BM + (wave & 1) * 8 + R;
-      const int m = min(m0 + row, s.M - 1);
-      tp = (const char*)g.A + ((size_t)m * s.lda + ((pc ^ mf_swz(row)) << 3)) * 2;
-    }
+    for (int j = 0; j < (KEEP_PTRS ? A_DMA : 0); ++j) ap[j] = a_src(j);
+    if (TAIL) tp = t_src();
 #pragma unroll
-    for (int j = 0; j < B_DMA; ++j) {
-      const int row = (wave + j * NW) * 8 + R;
-      const bf16* p;
-      if (EPI == EPI_SWIGLU) {
-        // tile rows come in 32-row blocks: even blocks from the gate weight, odd from the up weight,
-        // both for output columns n0 + (block / 2) * 32 ...
-        const int blk = row >> 5;
-        const int n = min(n0 + (blk >> 1) * 32 + (row & 31), s.N - 1);
-        p = (const bf16*)((blk & 1) ? g.B1 : g.B0) + (size_t)n * s.K;
-      } else {
-        p = weight_row<bf16>(g, s, min(n0 + row, s.N - 1));
-      }
-      bp[j] = (const char*)(p + ((pc ^ mf_swz(row)) << 3));
-    }
+    for (int j = 0; j < (KEEP_PTRS ? B_DMA : 0); ++j) bp[j] = b_src(j);
+  } else {
+    const int chunk = (dpc ^ mf_swz((dw & 1) * 8 + dR)) << 4;
+    a_off0 = (unsigned)dR * (unsigned)s.lda * 2u + chunk;
+    b_off0 = (unsigned)dR * (unsigned)s.K * 2u + chunk;
   }
+  // scalar source of the first row of slab `slab` (REG only)
+  auto a_base = [&](int slab) -> const char* { return (const char*)g.A + (size_t)(m0 + 8 * slab) * s.lda * 2; };
+  auto b_base = [&](int slab) -> const char* {
+    if (EPI == EPI_SWIGLU) {   // tile rows 32 * blk ..: blk even from the gate, odd from the up weight, columns n0 + 32 * (blk / 2) ..
+      const int n = n0 + (slab >> 3) * 32 + (slab & 3) * 8;
+      return (const char*)(((slab >> 2) & 1) ? g.B1 : g.B0) + (size_t)n * s.K * 2;
+    }
+    return (const char*)weight_row<bf16>(g, s, n0 + 8 * slab);
+  };
+  const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) void*)smem;
+  // one copy: 64 lanes x 16 bytes from base + lane offset to LDS address `lds` (M0) onwards; scalar operands only
+  auto dma = [&](const char* base, unsigned voff, unsigned lds) {
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(lds) : "memory", "m0");
+  };
   auto issue_tile = [&](int kt, int buf) {
     typedef const __attribute__((address_space(1))) void* gptr_t;
     typedef __attribute__((address_space(3))) void* lptr_t;
-    unsigned char* As = smem + buf * A_BYTES;
-    unsigned char* Bs = smem + 2 * A_BYTES + buf * B_BYTES;
+    const size_t ka = (size_t)((s.dbg & 2) ? 0 : kt) * MF_ROW_BYTES, kb = (size_t)((s.dbg & 1) ? 0 : kt) * MF_ROW_BYTES;
+    if (KEEP_PTRS) {
+      unsigned char* As = smem + buf * A_BYTES;
+      unsigned char* Bs = smem + NS * A_BYTES + buf * B_BYTES;
 #pragma unroll
-    for (int j = 0; j < A_DMA; ++j)
-      __builtin_amdgcn_global_load_lds((gptr_t)(ap[j] + (size_t)((s.dbg & 2) ? 0 : kt) * MF_ROW_BYTES),
-                                       (lptr_t)(As + (wave + j * NW) * 1024), 16, 0, 0);
-    if (TAIL && tail_blk && wave < 2)
-      __builtin_amdgcn_global_load_lds((gptr_t)(tp + (size_t)kt * MF_ROW_BYTES),
-                                       (lptr_t)(As + BM * MF_ROW_BYTES + wave * 1024), 16, 0, 0);
+      for (int j = 0; j < A_DMA; ++j)
+        __builtin_amdgcn_global_load_lds((gptr_t)(ap[KEEP_PTRS ? j : 0] + ka), (lptr_t)(As + (dw + j * DW) * 1024), 16, 0, 0);
+      if (TAIL && tail_blk && dw < 2)
+        __builtin_amdgcn_global_load_lds((gptr_t)(tp + ka), (lptr_t)(As + BM * MF_ROW_BYTES + dw * 1024), 16, 0, 0);
 #pragma unroll
-    for (int j = 0; j < B_DMA; ++j)
-      __builtin_amdgcn_global_load_lds((gptr_t)(bp[j] + (size_t)((s.dbg & 1) ? 0 : kt) * MF_ROW_BYTES),
-                                       (lptr_t)(Bs + (wave + j * NW) * 1024), 16, 0, 0);
+      for (int j = 0; j < B_DMA; ++j)
+        __builtin_amdgcn_global_load_lds((gptr_t)(bp[KEEP_PTRS ? j : 0] + kb), (lptr_t)(Bs + (dw + j * DW) * 1024), 16, 0, 0);
+    } else {
+      const unsigned As = lds0 + buf * A_BYTES, Bs = lds0 + NS * A_BYTES + buf * B_BYTES;
+#pragma unroll
+      for (int j = 0; j < A_DMA; ++j) dma(a_base(dw + j * DW) + ka, a_off0, As + (dw + j * DW) * 1024);
+      if (TAIL && tail_blk && dw < 2) dma(a_base(BM / 8 + dw) + ka, a_off0, As + BM * MF_ROW_BYTES + dw * 1024);
+#pragma unroll
+      for (int j = 0; j < B_DMA; ++j) dma(b_base(dw + j * DW) + kb, b_off0, Bs + (dw + j * DW) * 1024);
+    }
   };
 
   // ---- MFMA fragment addresses: lane reads tile row (lane % 32) of each 32-row block, chunk 2*ks + lane/32
@@ -148,16 +205,28 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   f32x4 tacc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 
   {
-    // main loop: the copy of k-tile kt+1 is in flight while k-tile kt is multiplied; one barrier per k-tile
+    // main loop: NS tile buffers; the copies of k-tiles kt+1 .. kt+NS-1 are in flight while k-tile kt is
+    // multiplied (copies complete in issue order, so waiting for tile kt+1 leaves the younger ones outstanding);
+    // one barrier per k-tile
+    constexpr int CNT = A_DMA + B_DMA;                 // copy instructions per wave and tile (+1 on the tail waves)
+    const bool extra = TAIL && tail_blk && dw < 2;
     const int nk = s.K / MF_BK;
-    issue_tile(0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);
+#pragma unroll
+    for (int p = 0; p < NS - 1; ++p)
+      if (p < nk && does_dma) issue_tile(p, p);
+    if (NS > 2 && nk > NS - 2) {
+      if (extra) mf_wait_vmcnt<(NS - 2) * (CNT + 1)>(); else mf_wait_vmcnt<(NS - 2) * CNT>();
+    } else {
+      mf_wait_vmcnt<0>();
+    }
     __syncthreads();
+    int cur = 0, nxt = NS - 1;                           // buffers of tile kt and of tile kt + NS - 1
     for (int kt = 0; kt < nk; ++kt) {
-      const int cur = kt & 1;
-      if (kt + 1 < nk) issue_tile(kt + 1, cur ^ 1);
+      // buffer nxt was last read in iteration kt - 1, which ended with a barrier
+      if (kt + NS - 1 < nk && does_dma) issue_tile(kt + NS - 1, nxt);
       const unsigned char* As = smem + cur * A_BYTES;
-      const unsigned char* Bs = smem + 2 * A_BYTES + cur * B_BYTES;
+      const unsigned char* Bs = smem + NS * A_BYTES + cur * B_BYTES;
+      if (!is_prod) {
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         bf16x8 af[TM], bfr[TN];
@@ -171,6 +240,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
           for (int j = 0; j < TN; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
       }
+      }
       if (TAIL && tail) {
 #pragma unroll
         for (int ks2 = 0; ks2 < 2; ++ks2) {
@@ -183,8 +253,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
           }
         }
       }
-      __builtin_amdgcn_s_waitcnt(0x0F70);
+      // tile kt+1 must have landed; tiles kt+2 .. kt+NS-1 (if they were issued) may stay in flight
+      if (NS > 2 && kt + NS - 1 < nk) {
+        if (extra) mf_wait_vmcnt<(NS - 2) * (CNT + 1)>(); else mf_wait_vmcnt<(NS - 2) * CNT>();
+      } else {
+        mf_wait_vmcnt<0>();
+      }
       __syncthreads();
+      cur = (cur + 1 == NS) ? 0 : cur + 1;
+      nxt = (nxt + 1 == NS) ? 0 : nxt + 1;
     }
   }
 
@@ -196,7 +273,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   // of R, C, C2.  The tail strip goes through the same path as one more pass of 16 rows.
   // The tile buffers are free here: the main loop ended with a barrier.
   constexpr int SLD = BN_OUT + 8, SR = WGM * 16, C4 = BN_OUT / 4, NT = NW * 64;
-  static_assert(SR * SLD * 4 <= 2 * (A_BYTES + B_BYTES), "staging tile must fit in the tile buffers");
+  static_assert(SR * SLD * 4 <= NS * (A_BYTES + B_BYTES), "staging tile must fit in the tile buffers");
   static_assert(C4 == 16 || C4 == 32 || C4 == 64, "a staged row is handled by 16, 32 or 64 consecutive lanes");
   float* stg = (float*)smem;
   const bool vec_ok = ((s.N | s.ldc | s.ldr | s.ldc2) & 3) == 0;
@@ -271,6 +348,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
 #pragma unroll
   for (int pass = 0; pass < TM * 2; ++pass) {
     const int i = pass >> 1, rh = pass & 1;
+    if (!is_prod) {
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
       const int r = rh * 8 + q, row16 = 8 * (q >> 2) + 4 * half + (q & 3);
@@ -284,6 +362,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
 #pragma unroll
         for (int j = 0; j < TN; ++j) dst[wn * WCOLS + j * 32] = acc[i][j][r];
       }
+    }
     }
     __syncthreads();
     drain(SR, [&](int sr) { return m0 + (sr >> 4) * WROWS + i * 32 + rh * 16 + (sr & 15); });
@@ -308,37 +387,47 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, bool TAIL>
+template <int BM, int BN, int WGM, int WGN, int PW, bool REG, int EPI, bool TAIL, int NS>
 inline hipError_t launch_mfma_tail(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st) {
   constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
-  constexpr int LDS = 2 * ((TAIL ? BM + 16 : BM) + BN) * MF_ROW_BYTES + (BM + 16) * 4;
+  constexpr int LDS = NS * ((TAIL ? BM + 16 : BM) + BN) * MF_ROW_BYTES + (BM + 16) * 4;
   const int tiles_m = TAIL ? s.M / BM : (s.M + BM - 1) / BM, tiles_n = (s.N + BN_OUT - 1) / BN_OUT;
   const int total = g * tiles_m * tiles_n;
   const int grid = ((total + 7) / 8) * 8;
-  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, EPI, TAIL>;
+  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, PW, REG, EPI, TAIL, NS>;
   static bool attr_set = false;            // raising the dynamic-LDS limit is a per-function, idempotent setting
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  kern<<<grid, WGM * WGN * 64, LDS, st>>>(table, first, s, tiles_m, tiles_n, total);
+  kern<<<grid, (WGM * WGN + PW) * 64, LDS, st>>>(table, first, s, tiles_m, tiles_n, total);
   return hipGetLastError();
 }
 
 // M = tiles * BM + 16 (a cell: seg_len rows + 16 memory rows) takes the tail variant.
-template <int BM, int BN, int WGM, int WGN, int EPI>
+// shapes the copy-wave variant addresses with one lane offset per operand
+template <int BM, int BN, int EPI>
+inline bool mfma_regular_shape(const GemmShape& s) {
+  constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
+  const bool m_ok = s.M % BM == 0 || (s.M > BM && s.M % BM == 16 && !(s.dbg & 32));
+  const int e0 = s.n0, e1 = s.n0 + s.n1;      // ends of weight blocks 0 and 1
+  const bool w_ok = EPI == EPI_SWIGLU || ((e0 >= s.N || e0 % BN == 0) && (e1 >= s.N || e1 % BN == 0));
+  return m_ok && s.N % BN_OUT == 0 && w_ok && s.K % MF_BK == 0;
+}
+
+template <int BM, int BN, int WGM, int WGN, int EPI, int PW = 0, bool REG = false, int NS = 2>
 inline hipError_t launch_mfma_cfg(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st) {
   if constexpr (BN <= WGM * WGN * 32) {
     if (s.M > BM && s.M % BM == 16 && !(s.dbg & 32))
-      return launch_mfma_tail<BM, BN, WGM, WGN, EPI, true>(table, first, g, s, st);
+      return launch_mfma_tail<BM, BN, WGM, WGN, PW, REG, EPI, true, NS>(table, first, g, s, st);
   }
-  return launch_mfma_tail<BM, BN, WGM, WGN, EPI, false>(table, first, g, s, st);
+  return launch_mfma_tail<BM, BN, WGM, WGN, PW, REG, EPI, false, NS>(table, first, g, s, st);
 }
 
 inline int mfma_pick_config(const GemmShape& s, int force_cfg) {
   if (force_cfg >= 0 && force_cfg < MF_NUM_CONFIGS) return force_cfg;
-  return (s.M >= 192 && s.N >= 192) ? 4 : ((s.M >= 96 && s.N >= 96) ? 1 : 2);
+  return (s.M >= 192 && s.N >= 192) ? 6 : ((s.M >= 96 && s.N >= 96) ? 1 : 2);
 }
 // output columns per tile of a configuration (the SwiGLU epilogue halves it)
 inline int mfma_tile_n(int cfg) { return (cfg == 1 || cfg == 2) ? 128 : 256; }
@@ -354,8 +443,15 @@ inline hipError_t launch_gemm_mfma_epi(const GemmGroup* table, int first, int g,
     case 1: return launch_mfma_cfg<128, 128, 2, 2, EPI>(table, first, g, s, st);
     case 3: return launch_mfma_cfg<128, 256, 2, 4, EPI>(table, first, g, s, st);
     case 4: return launch_mfma_cfg<256, 256, 4, 4, EPI>(table, first, g, s, st);
-    default: return launch_mfma_cfg<64, 128, 2, 2, EPI>(table, first, g, s, st);
+    case 5:   // 8 multiplying + 4 copy waves
+      if (mfma_regular_shape<256, 256, EPI>(s)) return launch_mfma_cfg<256, 256, 2, 4, EPI, 4, true>(table, first, g, s, st);
+      return launch_mfma_cfg<256, 256, 4, 4, EPI>(table, first, g, s, st);
+    case 6:   // 16 waves, scalar-addressed copies
+      if (mfma_regular_shape<256, 256, EPI>(s)) return launch_mfma_cfg<256, 256, 4, 4, EPI, 0, true>(table, first, g, s, st);
+      return launch_mfma_cfg<256, 256, 4, 4, EPI>(table, first, g, s, st);
+    default: break;
   }
+  return launch_mfma_cfg<64, 128, 2, 2, EPI>(table, first, g, s, st);
 }
 
 inline hipError_t launch_gemm_mfma(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st,
