@@ -132,7 +132,7 @@ struct Ctx {
   const LayerAux* aux;       // device: [L]
   GemmShape shape[K_COUNT];
   bool fused_norm;           // bf16 MFMA path: RMSNorm folded into the GEMM epilogues around it
-  int ssq_parts;             // N-tiles of the GEMMs that produce a normalised row (d / tile width)
+  int ssq_parts;             // partial sums of squares per row written by the GEMMs that produce a normalised row
   template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
   const GemmGroup* table(int kind) const { return tables + (size_t)kind * D.L; }
 };
@@ -155,9 +155,7 @@ void fill_shapes(Ctx& c) {
   set(K_MKV, D.m, D.dm + D.d, D.d, D.d, D.dm + D.d, 0, 0, D.dm, D.d, EPI_STORE_F32);
   c.fused_norm = D.bf16 && !debug_generic();
   if (c.fused_norm) c.shape[K_READ].ldc2 = c.shape[K_O].ldc2 = D.d;
-  // the read GEMM and the attention-output GEMM both have N = d and pick the same tile configuration
-  const int tile_n = mfma_tile_n(mfma_pick_config(c.shape[K_O], g_gemm_tile_config));
-  c.ssq_parts = (D.d + tile_n - 1) / tile_n;
+  c.ssq_parts = (D.d + 127) / 128;   // the GEMM epilogue writes one partial sum of squares per 128 columns
 }
 
 // Build the per-layer pointer tables on the host and copy them into the workspace.

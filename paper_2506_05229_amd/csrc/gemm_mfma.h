@@ -36,27 +36,21 @@ __device__ __forceinline__ void mf_wait_vmcnt() {      // s_waitcnt vmcnt(N) onl
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
 }
 
-// PW > 0: PW extra waves do nothing but the global -> LDS copies (and help with the epilogue's stores), the
-// WGM x WGN waves that multiply never issue a memory instruction in the main loop.  The copy path accepts a
-// limited number of outstanding instructions per CU; a wave that hits the limit stalls at issue, in order, with
-// its MFMAs queued behind the stalled copy.  With separate copy waves that stall costs no matrix-core time.
-template <int BM, int BN, int WGM, int WGN, int PW, bool REG, int EPI, bool TAIL, int NS>
-__global__ __launch_bounds__((WGM * WGN + PW) * 64) void gemm_mfma_kernel(const GemmGroup* __restrict__ table,
-                                                                           int first, GemmShape s, int tiles_m,
-                                                                           int tiles_n, int total_tiles) {
-  constexpr int NWC = WGM * WGN;                          // waves that multiply
-  constexpr int NW = NWC + PW;                            // all waves of the block
-  constexpr int DW = PW ? PW : NWC;                       // waves that copy
+template <int BM, int BN, int WGM, int WGN, bool REG, int EPI, bool TAIL, int NS>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGroup* __restrict__ table, int first,
+                                                                  GemmShape s, int tiles_m, int tiles_n,
+                                                                  int total_tiles) {
+  constexpr int NW = WGM * WGN;
   constexpr int WROWS = BM / WGM, WCOLS = BN / WGN;       // wave tile
   constexpr int TM = WROWS / 32, TN = WCOLS / 32;         // 32x32 MFMA tiles per wave
-  constexpr int A_DMA = BM / 8 / DW, B_DMA = BN / 8 / DW; // 8-row (1 KB) slabs each copying wave moves per k-tile
+  constexpr int A_DMA = BM / 8 / NW, B_DMA = BN / 8 / NW; // 8-row (1 KB) slabs each wave copies per k-tile
   constexpr int A_ROWS = TAIL ? BM + 16 : BM;
   constexpr int A_BYTES = A_ROWS * MF_ROW_BYTES, B_BYTES = BN * MF_ROW_BYTES;
   constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;   // output columns per tile
   static_assert(BM % (WGM * 32) == 0 && BN % (WGN * 32) == 0, "wave tile must be a multiple of 32x32");
-  static_assert(BM % (8 * DW) == 0 && BN % (8 * DW) == 0, "tile rows must divide into 8-row slabs per copying wave");
+  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must divide into 8-row slabs per wave");
   static_assert(EPI != EPI_SWIGLU || TN % 2 == 0, "SwiGLU pairs gate/up 32-column tiles inside a wave");
-  static_assert(!TAIL || (BN <= NWC * 32 && DW >= 2), "the tail strip gives each of the first BN / 32 waves two 16-column tiles");
+  static_assert(!TAIL || (BN <= NW * 32 && NW >= 2), "the tail strip gives each of the first BN / 32 waves two 16-column tiles");
   constexpr int TAIL_WAVES = BN / 32;
 
   extern __shared__ __align__(16) unsigned char smem[];   // [NS][A_BYTES], [NS][B_BYTES], then A_ROWS row scales
@@ -78,9 +72,6 @@ __global__ __launch_bounds__((WGM * WGN + PW) * 64) void gemm_mfma_kernel(const 
   // fetched once; visible to everybody after the first barrier of the main loop
   float* rs_lds = (float*)(smem + NS * A_BYTES + NS * B_BYTES);
   for (int r = tid; r < A_ROWS; r += NW * 64) rs_lds[r] = (g.rowscale && m0 + r < s.M) ? g.rowscale[m0 + r] : 1.f;
-  const bool is_prod = PW > 0 && wave >= NWC;                  // wave-uniform roles
-  const bool does_dma = PW == 0 || is_prod;
-  const int dw = PW ? wave - NWC : wave;                       // index among the copying waves
   const int wm = wave / WGN, wn = wave % WGN;
   const bool tail = tail_blk && wave < (TAIL ? BN / 32 : 0);   // wave-uniform: this wave computes part of the strip
 
@@ -101,31 +92,30 @@ __global__ __launch_bounds__((WGM * WGN + PW) * 64) void gemm_mfma_kernel(const 
   const int dR = lane >> 3, dpc = lane & 7;
   // source of this lane for A slab j / the tail slab / B slab j, at k = 0
   auto a_src = [&](int j) -> const char* {
-    const int row = (dw + j * DW) * 8 + dR;
+    const int row = (wave + j * NW) * 8 + dR;
     const int m = min(m0 + row, s.M - 1);                  // rows past M re-read the last row; masked on store
     return (const char*)g.A + ((size_t)m * s.lda + ((dpc ^ mf_swz(row)) << 3)) * 2;
   };
   auto t_src = [&]() -> const char* {                      // tail rows: copying waves 0 and 1 move one extra slab each
-    const int row = BM + (dw & 1) * 8 + dR;
+    const int row = BM + (wave & 1) * 8 + dR;
     const int m = min(m0 + row, s.M - 1);
     return (const char*)g.A + ((size_t)m * s.lda + ((dpc ^ mf_swz(row)) << 3)) * 2;
   };
   auto b_src = [&](int j) -> const char* {
-    const int row = (dw + j * DW) * 8 + dR;
+    const int row = (wave + j * NW) * 8 + dR;
     return (const char*)(b_row(row) + ((dpc ^ mf_swz(row)) << 3));
   };
   // Two ways to address the sources.
   // General shapes: every lane keeps one 64-bit pointer per slab (rows past M or N are clamped per lane).
   // Regular shapes (REG: no ragged M or N, weight blocks that end on tile boundaries): all sources of a lane
   // differ by wave-uniform amounts, because the swizzle of row 8 * slab + lane / 8 depends on the slab's parity
-  // only and the copying wave's slabs dw + DW * j all have the parity of dw.  One 32-bit lane offset per operand
+  // only and a wave's slabs wave + NW * j all have the parity of the wave.  One 32-bit lane offset per operand
   // plus a scalar base per slab then address everything, and issuing a copy takes scalar instructions only.
   // That matters: a wave's vector-ALU instructions are not issued while other waves keep the SIMD's
   // matrix core busy with back-to-back MFMAs, scalar and memory instructions are.  Address arithmetic in the
   // vector ALU would hold the copies back until the multiplying waves pause.
   constexpr bool KEEP_PTRS = !REG;
-  static_assert(!REG || DW % 2 == 0, "slabs of a copying wave must share their parity");
-  static_assert(REG || PW == 0, "copy waves only exist for regular shapes");
+  static_assert(!REG || NW % 2 == 0, "slabs of a wave must share their parity");
   const char* ap[KEEP_PTRS ? A_DMA : 1];
   const char* bp[KEEP_PTRS ? B_DMA : 1];
   const char* tp = nullptr;
@@ -137,7 +127,7 @@ __global__ __launch_bounds__((WGM * WGN + PW) * 64) void gemm_mfma_kernel(const 
 #pragma unroll
     for (int j = 0; j < (KEEP_PTRS ? B_DMA : 0); ++j) bp[j] = b_src(j);
   } else {
-    const int chunk = (dpc ^ mf_swz((dw & 1) * 8 + dR)) << 4;
+    const int chunk = (dpc ^ mf_swz((wave & 1) * 8 + dR)) << 4;
     a_off0 = (unsigned)dR * (unsigned)s.lda * 2u + chunk;
     b_off0 = (unsigned)dR * (unsigned)s.K * 2u + chunk;
   }
@@ -164,19 +154,19 @@ __global__ __launch_bounds__((WGM * WGN + PW) * 64) void gemm_mfma_kernel(const 
       unsigned char* Bs = smem + NS * A_BYTES + buf * B_BYTES;
 #pragma unroll
       for (int j = 0; j < A_DMA; ++j)
-        __builtin_amdgcn_global_load_lds((gptr_t)(ap[KEEP_PTRS ? j : 0] + ka), (lptr_t)(As + (dw + j * DW) * 1024), 16, 0, 0);
-      if (TAIL && tail_blk && dw < 2)
-        __builtin_amdgcn_global_load_lds((gptr_t)(tp + ka), (lptr_t)(As + BM * MF_ROW_BYTES + dw * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gptr_t)(ap[KEEP_PTRS ? j : 0] + ka), (lptr_t)(As + (wave + j * NW) * 1024), 16, 0, 0);
+      if (TAIL && tail_blk && wave < 2)
+        __builtin_amdgcn_global_load_lds((gptr_t)(tp + ka), (lptr_t)(As + BM * MF_ROW_BYTES + wave * 1024), 16, 0, 0);
 #pragma unroll
       for (int j = 0; j < B_DMA; ++j)
-        __builtin_amdgcn_global_load_lds((gptr_t)(bp[KEEP_PTRS ? j : 0] + kb), (lptr_t)(Bs + (dw + j * DW) * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gptr_t)(bp[KEEP_PTRS ? j : 0] + kb), (lptr_t)(Bs + (wave + j * NW) * 1024), 16, 0, 0);
     } else {
       const unsigned As = lds0 + buf * A_BYTES, Bs = lds0 + NS * A_BYTES + buf * B_BYTES;
 #pragma unroll
-      for (int j = 0; j < A_DMA; ++j) dma(a_base(dw + j * DW) + ka, a_off0, As + (dw + j * DW) * 1024);
-      if (TAIL && tail_blk && dw < 2) dma(a_base(BM / 8 + dw) + ka, a_off0, As + BM * MF_ROW_BYTES + dw * 1024);
+      for (int j = 0; j < A_DMA; ++j) dma(a_base(wave + j * NW) + ka, a_off0, As + (wave + j * NW) * 1024);
+      if (TAIL && tail_blk && wave < 2) dma(a_base(BM / 8 + wave) + ka, a_off0, As + BM * MF_ROW_BYTES + wave * 1024);
 #pragma unroll
-      for (int j = 0; j < B_DMA; ++j) dma(b_base(dw + j * DW) + kb, b_off0, Bs + (dw + j * DW) * 1024);
+      for (int j = 0; j < B_DMA; ++j) dma(b_base(wave + j * NW) + kb, b_off0, Bs + (wave + j * NW) * 1024);
     }
   };
 
@@ -209,11 +199,11 @@ __global__ __launch_bounds__((WGM * WGN + PW) * 64) void gemm_mfma_kernel(const 
     // multiplied (copies complete in issue order, so waiting for tile kt+1 leaves the younger ones outstanding);
     // one barrier per k-tile
     constexpr int CNT = A_DMA + B_DMA;                 // copy instructions per wave and tile (+1 on the tail waves)
-    const bool extra = TAIL && tail_blk && dw < 2;
+    const bool extra = TAIL && tail_blk && wave < 2;
     const int nk = s.K / MF_BK;
 #pragma unroll
     for (int p = 0; p < NS - 1; ++p)
-      if (p < nk && does_dma) issue_tile(p, p);
+      if (p < nk) issue_tile(p, p);
     if (NS > 2 && nk > NS - 2) {
       if (extra) mf_wait_vmcnt<(NS - 2) * (CNT + 1)>(); else mf_wait_vmcnt<(NS - 2) * CNT>();
     } else {
@@ -223,10 +213,9 @@ __global__ __launch_bounds__((WGM * WGN + PW) * 64) void gemm_mfma_kernel(const 
     int cur = 0, nxt = NS - 1;                           // buffers of tile kt and of tile kt + NS - 1
     for (int kt = 0; kt < nk; ++kt) {
       // buffer nxt was last read in iteration kt - 1, which ended with a barrier
-      if (kt + NS - 1 < nk && does_dma) issue_tile(kt + NS - 1, nxt);
+      if (kt + NS - 1 < nk) issue_tile(kt + NS - 1, nxt);
       const unsigned char* As = smem + cur * A_BYTES;
       const unsigned char* Bs = smem + NS * A_BYTES + cur * B_BYTES;
-      if (!is_prod) {
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         bf16x8 af[TM], bfr[TN];
@@ -239,7 +228,6 @@ __global__ __launch_bounds__((WGM * WGN + PW) * 64) void gemm_mfma_kernel(const 
 #pragma unroll
           for (int j = 0; j < TN; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-      }
       }
       if (TAIL && tail) {
 #pragma unroll
@@ -335,12 +323,15 @@ __global__ __launch_bounds__((WGM * WGN + PW) * 64) void gemm_mfma_kernel(const 
         }
       }
       if (EPI == EPI_RESID_F32 && g.ssq_out) {
-        // sum of squares of this row over the tile's columns, for the RMSNorm that consumes the row:
-        // one partial per (row, N-tile), summed later in tile order (deterministic, no atomics)
+        // sum of squares of this row for the RMSNorm that consumes the row: one partial per (row, 128 columns),
+        // summed later in column order (deterministic, no atomics).  The granularity is fixed, not the tile
+        // width, so that every tile configuration produces the same partials bit for bit.
+        static_assert(EPI != EPI_RESID_F32 || BN_OUT % 128 == 0, "partials cover 128 columns = 32 lanes");
         float part = o[0] * o[0] + o[1] * o[1] + o[2] * o[2] + o[3] * o[3];
 #pragma unroll
-        for (int off = C4 / 2; off > 0; off >>= 1) part += __shfl_xor(part, off, kWave);
-        if (c4 == 0 && m < s.M) g.ssq_out[(size_t)m * tiles_n + tn] = part;
+        for (int off = 16; off > 0; off >>= 1) part += __shfl_xor(part, off, kWave);
+        if ((c4 & 31) == 0 && m < s.M)
+          g.ssq_out[(size_t)m * ((s.N + 127) >> 7) + tn * (BN_OUT / 128) + (c4 >> 5)] = part;
       }
     }
   };
@@ -348,7 +339,6 @@ __global__ __launch_bounds__((WGM * WGN + PW) * 64) void gemm_mfma_kernel(const 
 #pragma unroll
   for (int pass = 0; pass < TM * 2; ++pass) {
     const int i = pass >> 1, rh = pass & 1;
-    if (!is_prod) {
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
       const int r = rh * 8 + q, row16 = 8 * (q >> 2) + 4 * half + (q & 3);
@@ -362,7 +352,6 @@ __global__ __launch_bounds__((WGM * WGN + PW) * 64) void gemm_mfma_kernel(const 
 #pragma unroll
         for (int j = 0; j < TN; ++j) dst[wn * WCOLS + j * 32] = acc[i][j][r];
       }
-    }
     }
     __syncthreads();
     drain(SR, [&](int sr) { return m0 + (sr >> 4) * WROWS + i * 32 + rh * 16 + (sr & 15); });
@@ -387,21 +376,21 @@ __global__ __launch_bounds__((WGM * WGN + PW) * 64) void gemm_mfma_kernel(const 
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, int PW, bool REG, int EPI, bool TAIL, int NS>
+template <int BM, int BN, int WGM, int WGN, bool REG, int EPI, bool TAIL, int NS>
 inline hipError_t launch_mfma_tail(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st) {
   constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   constexpr int LDS = NS * ((TAIL ? BM + 16 : BM) + BN) * MF_ROW_BYTES + (BM + 16) * 4;
   const int tiles_m = TAIL ? s.M / BM : (s.M + BM - 1) / BM, tiles_n = (s.N + BN_OUT - 1) / BN_OUT;
   const int total = g * tiles_m * tiles_n;
   const int grid = ((total + 7) / 8) * 8;
-  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, PW, REG, EPI, TAIL, NS>;
+  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, REG, EPI, TAIL, NS>;
   static bool attr_set = false;            // raising the dynamic-LDS limit is a per-function, idempotent setting
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  kern<<<grid, (WGM * WGN + PW) * 64, LDS, st>>>(table, first, s, tiles_m, tiles_n, total);
+  kern<<<grid, WGM * WGN * 64, LDS, st>>>(table, first, s, tiles_m, tiles_n, total);
   return hipGetLastError();
 }
 
@@ -416,39 +405,43 @@ inline bool mfma_regular_shape(const GemmShape& s) {
   return m_ok && s.N % BN_OUT == 0 && w_ok && s.K % MF_BK == 0;
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, int PW = 0, bool REG = false, int NS = 2>
+template <int BM, int BN, int WGM, int WGN, int EPI, bool REG = false, int NS = 2>
 inline hipError_t launch_mfma_cfg(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st) {
   if constexpr (BN <= WGM * WGN * 32) {
     if (s.M > BM && s.M % BM == 16 && !(s.dbg & 32))
-      return launch_mfma_tail<BM, BN, WGM, WGN, PW, REG, EPI, true, NS>(table, first, g, s, st);
+      return launch_mfma_tail<BM, BN, WGM, WGN, REG, EPI, true, NS>(table, first, g, s, st);
   }
-  return launch_mfma_tail<BM, BN, WGM, WGN, PW, REG, EPI, false, NS>(table, first, g, s, st);
+  return launch_mfma_tail<BM, BN, WGM, WGN, REG, EPI, false, NS>(table, first, g, s, st);
 }
 
-inline int mfma_pick_config(const GemmShape& s, int force_cfg) {
+// Big tiles move the fewest bytes per flop, but a launch needs about one tile per CU to use the chip: a single
+// cell (sequential order, or the first and last steps of the diagonal order) has too few 256x256 tiles.
+inline int mfma_pick_config(const GemmShape& s, int g, int force_cfg) {
   if (force_cfg >= 0 && force_cfg < MF_NUM_CONFIGS) return force_cfg;
-  return (s.M >= 192 && s.N >= 192) ? 6 : ((s.M >= 96 && s.N >= 96) ? 1 : 2);
+  if (s.M < 96 || s.N < 96) return 2;
+  const int tm = (s.M > 256 && s.M % 256 == 16) ? s.M / 256 : (s.M + 255) / 256;
+  const int bn_out = (s.epi == EPI_SWIGLU) ? 128 : 256;
+  const long tiles = (long)g * tm * ((s.N + bn_out - 1) / bn_out);
+  return (s.M >= 192 && s.N >= 192 && tiles >= 224) ? 5 : 6;
 }
-// output columns per tile of a configuration (the SwiGLU epilogue halves it)
-inline int mfma_tile_n(int cfg) { return (cfg == 1 || cfg == 2) ? 128 : 256; }
 
 // Tile configuration by problem shape: big square tiles for the block's linears, small tiles for
 // the skinny associative-memory projections (N = d_mem columns, or M = n_mem rows).
 template <int EPI>
 inline hipError_t launch_gemm_mfma_epi(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st,
                                        int force_cfg) {
-  const int cfg = mfma_pick_config(s, force_cfg);
+  const int cfg = mfma_pick_config(s, g, force_cfg);
   switch (cfg) {
     case 0: return launch_mfma_cfg<256, 256, 2, 4, EPI>(table, first, g, s, st);
     case 1: return launch_mfma_cfg<128, 128, 2, 2, EPI>(table, first, g, s, st);
     case 3: return launch_mfma_cfg<128, 256, 2, 4, EPI>(table, first, g, s, st);
     case 4: return launch_mfma_cfg<256, 256, 4, 4, EPI>(table, first, g, s, st);
-    case 5:   // 8 multiplying + 4 copy waves
-      if (mfma_regular_shape<256, 256, EPI>(s)) return launch_mfma_cfg<256, 256, 2, 4, EPI, 4, true>(table, first, g, s, st);
+    case 5:   // as 4, copies addressed by scalar base + lane offset
+      if (mfma_regular_shape<256, 256, EPI>(s)) return launch_mfma_cfg<256, 256, 4, 4, EPI, true>(table, first, g, s, st);
       return launch_mfma_cfg<256, 256, 4, 4, EPI>(table, first, g, s, st);
-    case 6:   // 16 waves, scalar-addressed copies
-      if (mfma_regular_shape<256, 256, EPI>(s)) return launch_mfma_cfg<256, 256, 4, 4, EPI, 0, true>(table, first, g, s, st);
-      return launch_mfma_cfg<256, 256, 4, 4, EPI>(table, first, g, s, st);
+    case 6:   // as 1, copies addressed by scalar base + lane offset
+      if (mfma_regular_shape<128, 128, EPI>(s)) return launch_mfma_cfg<128, 128, 2, 2, EPI, true>(table, first, g, s, st);
+      return launch_mfma_cfg<128, 128, 2, 2, EPI>(table, first, g, s, st);
     default: break;
   }
   return launch_mfma_cfg<64, 128, 2, 2, EPI>(table, first, g, s, st);
