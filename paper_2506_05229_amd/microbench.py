@@ -1,0 +1,118 @@
+"""Operation-level scaling of the two batched primitives of Diagonal Batching (paper Section 4.1-4.2,
+the figures on grouped-GEMM FLOPS vs group size and attention vs batch size), on synthetic data.
+
+    python -m paper_2506_05229_amd.microbench gemm      [--workload 1b_128k] [--data randn|zeros] [--iters 30]
+    python -m paper_2506_05229_amd.microbench attention [--workload 1b_128k] [--iters 30]
+
+`gemm` times the four big linear shapes of one cell (QKV, attention output, gate/up as one N = 2 d_ff problem,
+down) as one grouped launch of g = 1, 2, 4, 8, n_layers groups, every group with its own weight, through the
+library's armt_grouped_gemm entry point (plain store epilogue).  `--data zeros` multiplies zero matrices:
+the arithmetic is the same but nothing toggles, which shows how much of the rate the chip's power limit takes
+(the sustained clock under random data is lower than under constant data).
+`attention` times the fused segment attention (RoPE + GQA + causal softmax) for g = 1 ... n_layers cells.
+
+Everything is timed with device events after a warm-up in the same process; one JSON line per measurement.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+
+
+def _time(torch, fn, iters: int, warmup: int) -> float:
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def _groups(n_layers: int):
+    gs = [g for g in (1, 2, 4, 8) if g < n_layers]
+    return gs + [n_layers]
+
+
+def bench_gemm(shape, data: str, iters: int, warmup: int):
+    import torch
+    from . import grouped_gemm
+
+    s = shape
+    qkv = (s.n_heads + 2 * s.n_kv_heads) * s.head_dim
+    kinds = [("qkv", qkv, s.d_model), ("attn_out", s.d_model, s.n_heads * s.head_dim),
+             ("gate_up", 2 * s.d_ff, s.d_model), ("down", s.d_model, s.d_ff)]
+    gen = torch.Generator(device="cuda").manual_seed(0)
+
+    def mat(r, c, std):
+        if data == "zeros":
+            return torch.zeros(r, c, device="cuda", dtype=torch.bfloat16)
+        return (torch.randn(r, c, device="cuda", generator=gen) * std).to(torch.bfloat16)
+
+    for name, N, K in kinds:
+        for g in _groups(s.n_layers):
+            a = [mat(s.T, K, 1.0) for _ in range(g)]
+            b = [mat(N, K, 0.02) for _ in range(g)]
+            out = [torch.empty(s.T, N, device="cuda", dtype=torch.bfloat16) for _ in range(g)]
+            ws = torch.empty(max(256, g * 128), dtype=torch.uint8, device="cuda")
+            ms = _time(torch, lambda: grouped_gemm(a, b, out, ws), iters, warmup)
+            print(json.dumps({"op": "grouped_gemm", "kind": name, "data": data, "groups": g, "M": s.T, "N": N, "K": K,
+                              "ms": round(ms, 4), "tflops": round(2.0 * g * s.T * N * K / ms / 1e9, 1)}), flush=True)
+            del a, b, out
+
+
+def bench_attention(shape, iters: int, warmup: int):
+    import torch
+    from . import ArmtSteps
+
+    s = shape
+    steps = ArmtSteps(s)
+    width = (s.n_heads + 2 * s.n_kv_heads) * s.head_dim
+    gen = torch.Generator(device="cuda").manual_seed(0)
+    for g in _groups(s.n_layers):
+        src = torch.randn(g, s.T, width, device="cuda", generator=gen).to(steps.act_dtype)
+        qkv = src.clone()
+
+        def run():
+            qkv.copy_(src)          # the kernel rotates q and k in place
+            steps.segment_attention(qkv)
+
+        ms_copy = _time(torch, lambda: qkv.copy_(src), iters, warmup)
+        ms = _time(torch, run, iters, warmup) - ms_copy
+        # causal: T (T + 1) / 2 score pairs per head, 2 matmuls of 2 dh flops each
+        flops = g * s.n_heads * (s.T * (s.T + 1) / 2) * 4.0 * s.head_dim
+        print(json.dumps({"op": "segment_attention", "groups": g, "T": s.T, "heads": s.n_heads, "kv_heads": s.n_kv_heads,
+                          "head_dim": s.head_dim, "ms": round(ms, 4), "tflops": round(flops / ms / 1e9, 1)}), flush=True)
+
+
+def main(argv=None) -> int:
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("op", choices=["gemm", "attention"])
+    ap.add_argument("--workload", default="1b_128k")
+    ap.add_argument("--data", choices=["randn", "zeros"], default="randn")
+    ap.add_argument("--iters", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=100)
+    args = ap.parse_args(argv)
+    import torch
+    from armt_synth import CONFIGS
+
+    if not torch.cuda.is_available():
+        print("microbench needs the GPU: the library has no CPU path", file=sys.stderr)
+        return 2
+    shape = CONFIGS[args.workload]
+    if shape.dtype != "bf16":
+        print("microbench times the bf16 path", file=sys.stderr)
+        return 2
+    if args.op == "gemm":
+        bench_gemm(shape, args.data, args.iters, args.warmup)
+    else:
+        bench_attention(shape, args.iters, args.warmup)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
