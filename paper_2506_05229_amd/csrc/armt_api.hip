@@ -132,6 +132,7 @@ struct Ctx {
   const LayerAux* aux;       // device: [L]
   GemmShape shape[K_COUNT];
   bool fused_norm;           // bf16 MFMA path: RMSNorm folded into the GEMM epilogues around it
+  bool fused_rope;           // bf16 MFMA path: rotary embedding applied by the QKV GEMM epilogue
   int ssq_parts;             // partial sums of squares per row written by the GEMMs that produce a normalised row
   template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
   const GemmGroup* table(int kind) const { return tables + (size_t)kind * D.L; }
@@ -154,6 +155,9 @@ void fill_shapes(Ctx& c) {
   set(K_DOWN, D.T, D.d, D.F, D.F, D.d, D.d, D.d, D.d, 0, EPI_RESID_F32);
   set(K_MKV, D.m, D.dm + D.d, D.d, D.d, D.dm + D.d, 0, 0, D.dm, D.d, EPI_STORE_F32);
   c.fused_norm = D.bf16 && !debug_generic();
+  // rotary embedding as the epilogue of the QKV GEMM: heads must not straddle its output tiles
+  c.fused_rope = D.bf16 && !debug_generic() && 128 % D.dh == 0;
+  if (c.fused_rope) { c.shape[K_QKV].epi = EPI_QKV_ROPE; c.shape[K_QKV].ldr = D.dh; }
   if (c.fused_norm) c.shape[K_READ].ldc2 = c.shape[K_O].ldc2 = D.d;
   c.ssq_parts = (D.d + 127) / 128;   // the GEMM epilogue writes one partial sum of squares per 128 columns
 }
@@ -186,6 +190,7 @@ armt_status upload_tables(Ctx& c, const armt_layer_weights* W, float* A, float* 
     if (c.fused_norm) { g->C2 = nrm; g->gain = w.rms1; g->ssq_out = ssq; }   // input of the first norm
     g = &tab[K_QKV * L + l];
     g->A = nrm; g->B0 = w.wq; g->B1 = w.wk; g->B2 = w.wv;
+    if (c.fused_rope) g->R = (const float*)(c.ws + c.o.Rope);
     g->C = c.ws + c.o.QKV + l * T * D.Nqkv * D.esz;
     if (c.fused_norm) g->rowscale = rstd;
     g = &tab[K_O * L + l];
@@ -259,11 +264,13 @@ armt_status step_assoc_read(hipStream_t st, const GemmGroup* t_mq, const GemmSha
 // Rotary embedding of q, k and causal grouped-query attention over the rows of each cell.
 template <typename T>
 armt_status step_attention(hipStream_t st, T* QKV, T* Att, bf16* Vt, const float* rope_cs, int first, int g, int Trows,
-                           int H, int Hkv, int dh) {
+                           int H, int Hkv, int dh, bool rotated) {
   if (g <= 0) return ARMT_OK;
   const int ldq = (H + 2 * Hkv) * dh;
-  rope_kernel<T><<<dim3(Trows, g), 256, 0, st>>>(QKV, rope_cs, first, Trows, H + Hkv, dh, ldq);
-  HIP_TRY(hipGetLastError());
+  if (!rotated) {      // q and k not yet rotated by the producer of QKV
+    rope_kernel<T><<<dim3(Trows, g), 256, 0, st>>>(QKV, rope_cs, first, Trows, H + Hkv, dh, ldq);
+    HIP_TRY(hipGetLastError());
+  }
   if (std::is_same<T, bf16>::value && !debug_generic()) {
     HIP_TRY(launch_attention_mfma((const bf16*)QKV, Vt, (bf16*)Att, first, g, Trows, H, Hkv, dh, st));
     return ARMT_OK;
@@ -337,7 +344,7 @@ armt_status run_group(const Ctx& c, int lo, int hi, int read_hi, int empty_layer
   }
   ARMT_TRY(gemm<T>(c.st, c.table(K_QKV), lo, g, c.shape[K_QKV]));
   ARMT_TRY(step_attention<T>(c.st, c.at<T>(c.o.QKV), c.at<T>(c.o.Att), c.at<bf16>(c.o.Vt), c.at<float>(c.o.Rope), lo, g,
-                             D.T, D.H, D.Hkv, D.dh));
+                             D.T, D.H, D.Hkv, D.dh, c.fused_rope));
   ARMT_TRY(gemm<T>(c.st, c.table(K_O), lo, g, c.shape[K_O]));
   if (c.fused_norm) {
     rstd_kernel<<<dim3((D.T + 255) / 256, g), 256, 0, c.st>>>(c.at<float>(c.o.Ssq), lo, D.T, c.ssq_parts, D.d, D.rms_eps, rstd);
@@ -539,9 +546,9 @@ armt_status armt_segment_attention(const armt_config* cfg, int32_t g, void* qkv,
   HIP_TRY(hipGetLastError());
   if (D.bf16)
     return step_attention<bf16>(c.st, (bf16*)qkv, (bf16*)out, c.at<bf16>(c.o.Vt), c.at<float>(c.o.Rope), 0, g, D.T, D.H,
-                                D.Hkv, D.dh);
+                                D.Hkv, D.dh, false);
   return step_attention<float>(c.st, (float*)qkv, (float*)out, nullptr, c.at<float>(c.o.Rope), 0, g, D.T, D.H, D.Hkv,
-                               D.dh);
+                               D.dh, false);
 }
 
 armt_status armt_assoc_read(const armt_config* cfg, int32_t g, float* x, const void* const* wm_q, const float* A,

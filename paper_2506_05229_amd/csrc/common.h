@@ -59,7 +59,7 @@ struct GemmGroup {
   const void* B2;         // weight block 2: the remaining rows
   void* C;                // primary output
   void* C2;               // optional copy of C in the activation type (or null)
-  const float* R;         // residual [M, ldr] (or null)
+  const float* R;         // residual [M, ldr] (or null); EPI_QKV_ROPE: cos/sin table
   const float* rowscale;  // per-row factor applied to the accumulator (or null)
   const void* gain;       // EPI_RESID_F32: C2 = (bf16)(result * gain[col]) instead of (bf16)result (or null)
   float* ssq_out;         // EPI_RESID_F32: [M][tiles_n] per-row sums of squares of the result, one per N-tile (or null)
@@ -71,12 +71,15 @@ enum GemmEpilogue : int {
   EPI_STORE_ACT = 0,   // C (activation type) = acc * rowscale[row]
   EPI_STORE_F32 = 1,   // C (fp32) = acc * rowscale[row]
   EPI_RESID_F32 = 2,   // C (fp32) = R + acc * rowscale[row]; C2 (activation type) = same, if given
-  EPI_SWIGLU = 3       // C (activation type) = silu(rs * acc over B0) * (rs * acc over B1), rs = rowscale[row]; N = rows of B0
+  EPI_SWIGLU = 3,      // C (activation type) = silu(rs * acc over B0) * (rs * acc over B1), rs = rowscale[row]; N = rows of B0
+  EPI_QKV_ROPE = 4     // EPI_STORE_ACT of the fused q | k | v projection with the rotary embedding applied to the q and k
+                       // columns [0, n0 + n1): heads of ldr columns, rotate-half pairing, position = row; R = cos/sin table
+                       // [M][ldr / 2][2].  Heads must not straddle output tiles (tile width a multiple of ldr).
 };
 
 struct GemmShape {
   int M, N, K;          // N = output columns (for EPI_SWIGLU: d_ff, each column needs two dot products)
-  int lda, ldc, ldc2, ldr;
+  int lda, ldc, ldc2, ldr;   // ldr: row stride of R; EPI_QKV_ROPE: head dimension
   int n0, n1;           // rows in weight blocks 0 and 1 (block 2 holds N - n0 - n1)
   int epi;              // GemmEpilogue
   int tag;              // which GEMM of the step this is (profiling only)

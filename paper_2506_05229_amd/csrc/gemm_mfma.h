@@ -277,6 +277,19 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       if (valid) {
         o = *(const f32x4*)(stg + sr * SLD + c4 * 4);
         if (EPI != EPI_SWIGLU) o *= row_scale(m);        // SwiGLU applied it before the nonlinearity
+        if (EPI == EPI_QKV_ROPE && n < s.n0 + s.n1) {
+          // rotary embedding (rotate-half): column j of a head pairs with j +- dh/2, which lies in the same
+          // staged row; out_j = x_j cos_j' - x_{j+h} sin_j' (j < h), x_j cos_j' + x_{j-h} sin_j' (j >= h), j' = j mod h
+          const int dh = s.ldr, hd = dh >> 1, j = n % dh, lo = j < hd;
+          const f32x4 p = *(const f32x4*)(stg + sr * SLD + c4 * 4 + (lo ? hd : -hd)) * row_scale(m);
+          const float* cs = g.R + 2 * ((size_t)m * hd + (j - (lo ? 0 : hd)));
+          const f32x4 cs0 = *(const f32x4*)cs, cs1 = *(const f32x4*)(cs + 4);     // c0 s0 c1 s1 | c2 s2 c3 s3
+          const float sg = lo ? -1.f : 1.f;
+          o[0] = o[0] * cs0[0] + sg * p[0] * cs0[1];
+          o[1] = o[1] * cs0[2] + sg * p[1] * cs0[3];
+          o[2] = o[2] * cs1[0] + sg * p[2] * cs1[1];
+          o[3] = o[3] * cs1[2] + sg * p[3] * cs1[3];
+        }
         if (EPI == EPI_RESID_F32 && g.R) {
           if (vec_ok) {
             o += *(const f32x4*)(g.R + (size_t)m * s.ldr + n);
@@ -303,7 +316,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
           }
         }
         if (vec_ok) {
-          if (EPI == EPI_STORE_ACT || EPI == EPI_SWIGLU) {
+          if (EPI == EPI_STORE_ACT || EPI == EPI_SWIGLU || EPI == EPI_QKV_ROPE) {
             *(bf16x4*)((bf16*)g.C + (size_t)m * s.ldc + n) = ob;
           } else {
             *(f32x4*)((float*)g.C + (size_t)m * s.ldc + n) = o;
@@ -313,7 +326,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             if (n + e >= s.N) continue;
-            if (EPI == EPI_STORE_ACT || EPI == EPI_SWIGLU) {
+            if (EPI == EPI_STORE_ACT || EPI == EPI_SWIGLU || EPI == EPI_QKV_ROPE) {
               ((bf16*)g.C)[(size_t)m * s.ldc + n + e] = ob[e];
             } else {
               ((float*)g.C)[(size_t)m * s.ldc + n + e] = o[e];
@@ -455,6 +468,10 @@ inline hipError_t launch_gemm_mfma(const GemmGroup* table, int first, int g, con
     case EPI_STORE_F32: return launch_gemm_mfma_epi<EPI_STORE_F32>(table, first, g, s, st, force_cfg);
     case EPI_RESID_F32: return launch_gemm_mfma_epi<EPI_RESID_F32>(table, first, g, s, st, force_cfg);
     case EPI_SWIGLU: return launch_gemm_mfma_epi<EPI_SWIGLU>(table, first, g, s, st, force_cfg);
+    case EPI_QKV_ROPE:
+      // the rotation reads its partner column from the staged tile: heads must not straddle tiles (128 or 256 wide)
+      if (s.ldr <= 0 || 128 % s.ldr != 0 || (s.N & 3) || (s.ldc & 3)) return hipErrorInvalidValue;
+      return launch_gemm_mfma_epi<EPI_QKV_ROPE>(table, first, g, s, st, force_cfg);
   }
   return hipErrorInvalidValue;
 }
