@@ -133,6 +133,7 @@ struct Ctx {
   GemmShape shape[K_COUNT];
   bool fused_norm;           // bf16 MFMA path: RMSNorm folded into the GEMM epilogues around it
   bool fused_rope;           // bf16 MFMA path: rotary embedding applied by the QKV GEMM epilogue
+  bool fused_vt;             // ... which also writes V transposed
   int ssq_parts;             // partial sums of squares per row written by the GEMMs that produce a normalised row
   template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
   const GemmGroup* table(int kind) const { return tables + (size_t)kind * D.L; }
@@ -156,8 +157,11 @@ void fill_shapes(Ctx& c) {
   set(K_MKV, D.m, D.dm + D.d, D.d, D.d, D.dm + D.d, 0, 0, D.dm, D.d, EPI_STORE_F32);
   c.fused_norm = D.bf16 && !debug_generic();
   // rotary embedding as the epilogue of the QKV GEMM: heads must not straddle its output tiles
-  c.fused_rope = D.bf16 && !debug_generic() && 128 % D.dh == 0;
+  c.fused_rope = D.bf16 && !debug_generic() && 128 % D.dh == 0 && !(g_gemm_dbg & 128);
   if (c.fused_rope) { c.shape[K_QKV].epi = EPI_QKV_ROPE; c.shape[K_QKV].ldr = D.dh; }
+  // ... and V written transposed for the attention kernel, if the v columns start on a tile boundary
+  c.fused_vt = c.fused_rope && ((D.H + D.Hkv) * D.dh) % 256 == 0 && D.T % 8 == 0 && !(g_gemm_dbg & 64);
+  if (c.fused_vt) c.shape[K_QKV].ldc2 = attention_tp(D.T);
   if (c.fused_norm) c.shape[K_READ].ldc2 = c.shape[K_O].ldc2 = D.d;
   c.ssq_parts = (D.d + 127) / 128;   // the GEMM epilogue writes one partial sum of squares per 128 columns
 }
@@ -191,6 +195,7 @@ armt_status upload_tables(Ctx& c, const armt_layer_weights* W, float* A, float* 
     g = &tab[K_QKV * L + l];
     g->A = nrm; g->B0 = w.wq; g->B1 = w.wk; g->B2 = w.wv;
     if (c.fused_rope) g->R = (const float*)(c.ws + c.o.Rope);
+    if (c.fused_vt) g->C2 = c.ws + c.o.Vt + l * (size_t)D.Hkv * D.dh * attention_tp(D.T) * 2;
     g->C = c.ws + c.o.QKV + l * T * D.Nqkv * D.esz;
     if (c.fused_norm) g->rowscale = rstd;
     g = &tab[K_O * L + l];
@@ -264,7 +269,7 @@ armt_status step_assoc_read(hipStream_t st, const GemmGroup* t_mq, const GemmSha
 // Rotary embedding of q, k and causal grouped-query attention over the rows of each cell.
 template <typename T>
 armt_status step_attention(hipStream_t st, T* QKV, T* Att, bf16* Vt, const float* rope_cs, int first, int g, int Trows,
-                           int H, int Hkv, int dh, bool rotated) {
+                           int H, int Hkv, int dh, bool rotated, bool vt_ready) {
   if (g <= 0) return ARMT_OK;
   const int ldq = (H + 2 * Hkv) * dh;
   if (!rotated) {      // q and k not yet rotated by the producer of QKV
@@ -272,7 +277,7 @@ armt_status step_attention(hipStream_t st, T* QKV, T* Att, bf16* Vt, const float
     HIP_TRY(hipGetLastError());
   }
   if (std::is_same<T, bf16>::value && !debug_generic()) {
-    HIP_TRY(launch_attention_mfma((const bf16*)QKV, Vt, (bf16*)Att, first, g, Trows, H, Hkv, dh, st));
+    HIP_TRY(launch_attention_mfma((const bf16*)QKV, Vt, (bf16*)Att, first, g, Trows, H, Hkv, dh, vt_ready, st));
     return ARMT_OK;
   }
   attention_generic_kernel<T><<<dim3(Trows, H, g), 64, (dh + Trows) * 4, st>>>(QKV, Att, first, Trows, H, Hkv, dh,
@@ -344,7 +349,7 @@ armt_status run_group(const Ctx& c, int lo, int hi, int read_hi, int empty_layer
   }
   ARMT_TRY(gemm<T>(c.st, c.table(K_QKV), lo, g, c.shape[K_QKV]));
   ARMT_TRY(step_attention<T>(c.st, c.at<T>(c.o.QKV), c.at<T>(c.o.Att), c.at<bf16>(c.o.Vt), c.at<float>(c.o.Rope), lo, g,
-                             D.T, D.H, D.Hkv, D.dh, c.fused_rope));
+                             D.T, D.H, D.Hkv, D.dh, c.fused_rope, c.fused_vt));
   ARMT_TRY(gemm<T>(c.st, c.table(K_O), lo, g, c.shape[K_O]));
   if (c.fused_norm) {
     rstd_kernel<<<dim3((D.T + 255) / 256, g), 256, 0, c.st>>>(c.at<float>(c.o.Ssq), lo, D.T, c.ssq_parts, D.d, D.rms_eps, rstd);
@@ -373,6 +378,11 @@ armt_status forward_typed(Ctx& c, const void* mem_emb, const void* x, int64_t N,
     const int n = D.T * (D.dh / 2);
     rope_table_kernel<<<(n + 255) / 256, 256, 0, c.st>>>(c.at<float>(c.o.Rope), D.T, D.dh / 2, (double)D.rope_theta);
     HIP_TRY(hipGetLastError());
+    if (c.fused_vt) {      // the QKV epilogue never writes the padding columns [T, Tp) of V^T, which must read as zero
+      const size_t nf = attention_vt_bytes(D.L, D.T, D.Hkv, D.dh) / 4;
+      fill_f32_kernel<<<(unsigned)((nf + 255) / 256), 256, 0, c.st>>>(c.at<float>(c.o.Vt), nf, 0.f);
+      HIP_TRY(hipGetLastError());
+    }
   }
   auto ingest = [&](int64_t s) -> armt_status {       // Algorithm 1: ingest a new segment at layer 0
     pack_segment_kernel<T><<<D.T, 256, 0, c.st>>>((const T*)x + (size_t)s * D.S * D.d, (const T*)mem_emb, D.S, D.d, X, Xb);
@@ -546,9 +556,9 @@ armt_status armt_segment_attention(const armt_config* cfg, int32_t g, void* qkv,
   HIP_TRY(hipGetLastError());
   if (D.bf16)
     return step_attention<bf16>(c.st, (bf16*)qkv, (bf16*)out, c.at<bf16>(c.o.Vt), c.at<float>(c.o.Rope), 0, g, D.T, D.H,
-                                D.Hkv, D.dh, false);
+                                D.Hkv, D.dh, false, false);
   return step_attention<float>(c.st, (float*)qkv, (float*)out, nullptr, c.at<float>(c.o.Rope), 0, g, D.T, D.H, D.Hkv,
-                               D.dh, false);
+                               D.dh, false, false);
 }
 
 armt_status armt_assoc_read(const armt_config* cfg, int32_t g, float* x, const void* const* wm_q, const float* A,

@@ -215,11 +215,14 @@ inline size_t attention_vt_bytes(int g, int Trows, int Hkv, int dh) {
 }
 
 inline hipError_t launch_attention_mfma(const bf16* QKV, bf16* Vt, bf16* Out, int first, int g, int Trows, int H,
-                                        int Hkv, int dh, hipStream_t st) {
+                                        int Hkv, int dh, bool vt_ready, hipStream_t st) {
   const int Tp = attention_tp(Trows), group = H / Hkv;
-  v_transpose_kernel<<<dim3(Tp / 64, Hkv, g), 256, 64 * (dh + 2) * 2, st>>>(QKV, Vt, first, Trows, Tp, H, Hkv, dh);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  hipError_t e = hipSuccess;
+  if (!vt_ready) {      // V^T not yet written by the producer of QKV
+    v_transpose_kernel<<<dim3(Tp / 64, Hkv, g), 256, 64 * (dh + 2) * 2, st>>>(QKV, Vt, first, Trows, Tp, H, Hkv, dh);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)dh);
   const dim3 grid((Trows + AT_QT - 1) / AT_QT, Hkv, g);
   if (dh == 64)

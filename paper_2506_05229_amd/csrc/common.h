@@ -75,6 +75,8 @@ enum GemmEpilogue : int {
   EPI_QKV_ROPE = 4     // EPI_STORE_ACT of the fused q | k | v projection with the rotary embedding applied to the q and k
                        // columns [0, n0 + n1): heads of ldr columns, rotate-half pairing, position = row; R = cos/sin table
                        // [M][ldr / 2][2].  Heads must not straddle output tiles (tile width a multiple of ldr).
+                       // With ldc2 > 0 the v columns [n0 + n1, N) are not stored in C but transposed in C2:
+                       // C2[(n - n0 - n1) * ldc2 + m]; n0 + n1 must then be a multiple of the tile width.
 };
 
 struct GemmShape {

@@ -348,6 +348,22 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       }
     }
   };
+  // EPI_QKV_ROPE, tiles of the v columns: the attention kernel wants V transposed ([column][row], row stride ldc2),
+  // so these tiles are drained column-wise: a thread takes 8 consecutive rows of one column, 16 bytes per store.
+  const bool vt_tile = EPI == EPI_QKV_ROPE && s.ldc2 > 0 && n0 >= s.n0 + s.n1;      // block-uniform
+  auto drain_vt = [&](int nrows, auto m_of) {
+    bf16* vt = (bf16*)g.C2 + (size_t)(n0 - (s.n0 + s.n1)) * s.ldc2;
+    for (int u = tid; u < (nrows >> 3) * BN_OUT; u += NT) {
+      const int rg = u / BN_OUT, col = u - rg * BN_OUT;
+      const int m = m_of(rg * 8);          // rows rg * 8 .. + 7 of the staging tile are consecutive output rows
+      if (m >= s.M || n0 + col >= s.N) continue;
+      bf16x8 v;
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        v[i] = (m + i < s.M) ? (bf16)(stg[(rg * 8 + i) * SLD + col] * rs_lds[m + i - m0]) : (bf16)0.f;
+      *(bf16x8*)(vt + (size_t)col * s.ldc2 + m) = v;
+    }
+  };
   const int col_in = lane & 31;
 #pragma unroll
   for (int pass = 0; pass < TM * 2; ++pass) {
@@ -367,7 +383,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       }
     }
     __syncthreads();
-    drain(SR, [&](int sr) { return m0 + (sr >> 4) * WROWS + i * 32 + rh * 16 + (sr & 15); });
+    auto pass_row = [&](int sr) { return m0 + (sr >> 4) * WROWS + i * 32 + rh * 16 + (sr & 15); };
+    if (vt_tile) drain_vt(SR, pass_row);
+    else drain(SR, pass_row);
     __syncthreads();
   }
   if (TAIL && tail_blk) {     // 16x16 result tile: lane holds column lane % 16, rows 4*(lane/16) + r
@@ -385,7 +403,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       }
     }
     __syncthreads();
-    drain(16, [&](int sr) { return m0 + BM + sr; });
+    auto tail_row = [&](int sr) { return m0 + BM + sr; };
+    if (vt_tile) drain_vt(16, tail_row);
+    else drain(16, tail_row);
   }
 }
 
