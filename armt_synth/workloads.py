@@ -173,3 +173,30 @@ def make_embeddings(shape: ArmtShape, seed: int = 0, n_tokens: int | None = None
         out[s * shape.seg_len:(s + 1) * shape.seg_len] = _normal(
             rng, (shape.seg_len, shape.d_model), 1.0, shape.dtype)
     return out
+
+
+LLAMA3_VOCAB = 128256      # vocabulary of the LLaMA-3 family the paper's models come from
+
+
+def make_token_ends(shape: ArmtShape, vocab: int, seed: int = 0, n_tokens: int | None = None,
+                    gain_std: float = 0.0):
+    """Inputs of the token-level ends of Algorithm 1: token ids uniform over the vocabulary
+    [n_tokens] int32 (drawn segment by segment, so a prefix is the same whatever n_tokens is),
+    an embedding table ~ N(0, 1) [vocab, d_model] (so that gathered rows have the distribution of
+    make_embeddings), the gain of the final norm (ones, or N(1, gain_std^2)) and a separate head
+    weight ~ N(0, 0.02^2) [vocab, d_model]. Values are bf16-exact for dtype "bf16"."""
+    n = shape.n_tokens if n_tokens is None else n_tokens
+    assert n % shape.seg_len == 0
+    ids = np.empty(n, dtype=np.int32)
+    for s in range(n // shape.seg_len):
+        rng = np.random.default_rng([seed, 5, s])
+        ids[s * shape.seg_len:(s + 1) * shape.seg_len] = rng.integers(0, vocab, shape.seg_len, dtype=np.int32)
+    rng = np.random.default_rng([seed, 6])
+    emb_table = _normal(rng, (vocab, shape.d_model), 1.0, shape.dtype)
+    w_lm = _normal(rng, (vocab, shape.d_model), 0.02, shape.dtype)
+    if gain_std > 0.0:
+        g = 1.0 + rng.standard_normal(shape.d_model, dtype=np.float32) * np.float32(gain_std)
+        final_gain = round_to_bf16(g) if shape.dtype == "bf16" else g
+    else:
+        final_gain = np.ones(shape.d_model, dtype=np.float32)
+    return ids, emb_table, final_gain, w_lm

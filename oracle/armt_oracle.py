@@ -22,6 +22,10 @@ Parity status of each function (what pins it, in tests/test_oracle_*.py):
   armt_forward_sequential  brute-force pure-python recomputation on tiny sizes, prefix and
                            carry-in invariants, perturbation (causality over segments)
   armt_forward_diagonal_order   bit-identical to the sequential order (exact recurrence)
+  embed_tokens             row identity with the table, error on ids outside the vocabulary
+  lm_head                  identity head (logits = g * h / rms(h)), scale invariance, library
+                           rms_norm + matmul, pure-python loops on tiny sizes
+  armt_forward_tokens      composition of the three (no arithmetic of its own)
 Absolute values of the hidden states on the LLaMA-shaped workloads are not printed
 anywhere in the paper; they are pinned only through the checks above.
 
@@ -38,7 +42,10 @@ Readings of the paper taken here (each is listed with its reason in the design n
   * positions restart at 0 in every segment; the transformer layer is a LLaMA-3 decoder
     block (pre-norm RMSNorm, GQA, rotate-half RoPE, SwiGLU, no biases);
   * the result is the last layer's hidden state at the token rows (no final norm, no
-    LM head), plus the final memory state of every layer.
+    LM head), plus the final memory state of every layer;
+  * the token-level ends of Algorithm 1 (token ids in, logits out) are the LLaMA ones: a
+    row gather from the embedding table in front, a final RMSNorm (same eps as the
+    block's) and a bias-free linear head behind; the head may share the table.
 """
 from __future__ import annotations
 
@@ -228,3 +235,27 @@ def armt_forward_diagonal_order(cfg, layers, mem_emb, x, A_in=None, z_in=None):
                 hidden[s * S:(s + 1) * S] = Y[:S]   # segment went through all layers
         cell_in = nxt
     return hidden, np.stack(A), np.stack(z)
+
+
+# --------------------------------------------------------------------------- token-level ends (Algorithm 1)
+def embed_tokens(ids: np.ndarray, emb_table: np.ndarray) -> np.ndarray:
+    """x[i] = emb_table[ids[i]]: Algorithm 1 starts from token ids, the cells from embeddings."""
+    ids = np.asarray(ids)
+    E = np.asarray(emb_table, dtype=F64)
+    if ids.size and (ids.min() < 0 or ids.max() >= E.shape[0]):
+        raise ValueError("token id outside the vocabulary")
+    return E[ids]
+
+
+def lm_head(hidden: np.ndarray, final_gain: np.ndarray, w_lm: np.ndarray, eps: float) -> np.ndarray:
+    """logits = rmsnorm(hidden, final_gain) W_lm^T, W_lm [vocab, d] (Algorithm 1 returns logits)."""
+    return rmsnorm(hidden, final_gain, eps) @ np.asarray(w_lm, dtype=F64).T
+
+
+def armt_forward_tokens(cfg, layers, mem_emb, emb_table, ids, final_gain, w_lm, last_rows=None):
+    """Token ids -> logits: gather, the ARMT forward, final norm + head on all rows or on the last
+    `last_rows` rows. Returns (logits, hidden, A, z)."""
+    x = embed_tokens(ids, emb_table)
+    hidden, A, z = armt_forward_sequential(cfg, layers, mem_emb, x)
+    rows = hidden if last_rows is None else hidden[-last_rows:]
+    return lm_head(rows, final_gain, w_lm, cfg.rms_eps), hidden, A, z
