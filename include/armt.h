@@ -155,9 +155,28 @@ armt_status armt_assoc_update(const armt_config *cfg, int32_t g, const float *ym
                               int32_t empty_group, float *A, float *z,
                               void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* ---- token-level ends of Algorithm 1 (token ids in, logits out), to be called around a forward call. ---- */
+
+/* Embedding gather: x_out[i] = emb_table[ids[i]] for i < n_tokens.  emb_table [vocab, d_model] and x_out
+ * [n_tokens, d_model] of cfg->dtype, ids [n_tokens] int32 (device).  Ids must lie in [0, vocab); the kernel
+ * clamps them into that range instead of reading outside the table.  No workspace. */
+armt_status armt_embed_tokens(const armt_config *cfg, const void *emb_table, int32_t vocab,
+                              const int32_t *ids, int64_t n_tokens, void *x_out, void *hip_stream);
+
+/* Final RMSNorm + linear head (Algorithm 1 returns logits): logits = rmsnorm(hidden; final_gain, cfg->rms_eps)
+ * w_lm^T.  hidden [n_rows, d_model] of cfg->dtype (e.g. hidden_out of a forward call, or its last rows),
+ * final_gain [d_model] and w_lm [vocab, d_model] of cfg->dtype (w_lm may be the embedding table), logits
+ * [n_rows, vocab] fp32.  workspace: armt_lm_head_workspace_bytes(cfg, n_rows) bytes, 256-byte aligned
+ * (normalised operand, row scales, pointer table).  Returns ARMT_ERR_SHAPE for n_rows < 1 or vocab < 1. */
+size_t armt_lm_head_workspace_bytes(const armt_config *cfg, int64_t n_rows);
+armt_status armt_lm_head(const armt_config *cfg, const void *hidden, int64_t n_rows, const void *final_gain,
+                         const void *w_lm, int32_t vocab, float *logits,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Benchmarking knob: force the tile configuration of the bf16 grouped GEMM for all later calls of this
- * process (0: 256x256 tile, 8 waves; 1: 128x128, 4 waves; 2: 64x128, 4 waves; 3: 128x256, 8 waves; 4: 256x256, 16 waves;
- * anything else: choose by shape, the default).  Results do not depend on it beyond rounding order.
+ * process (0: 256x256 tile, 8 waves; 1: 128x128, 4 waves; 2: 64x128, 4 waves; 3: 128x256, 8 waves; 4: 256x256,
+ * 16 waves; 5 / 6: as 4 / 1 with the tile copies addressed by scalar base + lane offset where the shape allows;
+ * anything else: choose by shape and tile count, the default).  Results do not depend on it beyond rounding order.
  * Returns the previous setting.  Not thread safe. */
 int32_t armt_set_gemm_tile_config(int32_t config);
 

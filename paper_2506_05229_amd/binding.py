@@ -71,6 +71,12 @@ def load_library():
     lib.armt_assoc_read.restype = C.c_int
     lib.armt_assoc_update.argtypes = [C.POINTER(ArmtConfig), i32, vp, pp, pp, pp, i32, vp, vp, vp, sz, vp]
     lib.armt_assoc_update.restype = C.c_int
+    lib.armt_embed_tokens.argtypes = [C.POINTER(ArmtConfig), vp, i32, vp, i64, vp, vp]
+    lib.armt_embed_tokens.restype = C.c_int
+    lib.armt_lm_head_workspace_bytes.argtypes = [C.POINTER(ArmtConfig), i64]
+    lib.armt_lm_head_workspace_bytes.restype = sz
+    lib.armt_lm_head.argtypes = [C.POINTER(ArmtConfig), vp, i64, vp, vp, i32, vp, vp, sz, vp]
+    lib.armt_lm_head.restype = C.c_int
     lib.armt_set_gemm_tile_config.argtypes = [i32]
     lib.armt_set_gemm_tile_config.restype = i32
     lib.armt_profile_begin.argtypes = [i32, i32]
@@ -237,3 +243,43 @@ class ArmtSteps:
                                                     _ptr_array(wm_v_list), _ptr_array(wm_b_list), empty_group, _ptr(A),
                                                     _ptr(z), _ptr(self.ws), self.ws.numel(), _stream(self.torch)))
         return A, z
+
+
+class TokenEnds:
+    """Token-level ends of Algorithm 1 around a forward call: ids -> embeddings, hidden states -> logits."""
+
+    def __init__(self, shape, emb_table, final_gain, w_lm, device="cuda:0"):
+        import torch
+        self.torch, self.shape = torch, shape
+        self.lib = load_library()
+        self.cfg = ArmtConfig.from_shape(shape)
+        self.dt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+        dev = lambda a: a if isinstance(a, torch.Tensor) else torch.from_numpy(a).to(device=device, dtype=self.dt)
+        self.emb_table, self.final_gain, self.w_lm = dev(emb_table), dev(final_gain), dev(w_lm)
+        self.vocab = int(self.emb_table.shape[0])
+        self.ws = None
+
+    def embed(self, ids):
+        """ids [n] int32 device tensor -> x [n, d_model]."""
+        torch = self.torch
+        x = torch.empty((ids.numel(), self.shape.d_model), dtype=self.dt, device=ids.device)
+        _check(self.lib, self.lib.armt_embed_tokens(C.byref(self.cfg), _ptr(self.emb_table), self.vocab, _ptr(ids),
+                                                    ids.numel(), _ptr(x), _stream(torch)))
+        return x
+
+    def logits(self, hidden, out=None):
+        """hidden [n, d_model] -> logits [n, vocab] fp32."""
+        torch = self.torch
+        n = hidden.shape[0]
+        need = self.lib.armt_lm_head_workspace_bytes(C.byref(self.cfg), n)
+        if need == 0:
+            raise ArmtError(2, "configuration or row count rejected by armt_lm_head_workspace_bytes")
+        if self.ws is None or self.ws.numel() < need:
+            self.ws = torch.empty(need, dtype=torch.uint8, device=hidden.device)
+        V = int(self.w_lm.shape[0])
+        if out is None:
+            out = torch.empty((n, V), dtype=torch.float32, device=hidden.device)
+        _check(self.lib, self.lib.armt_lm_head(C.byref(self.cfg), _ptr(hidden), n, _ptr(self.final_gain),
+                                               _ptr(self.w_lm), V, _ptr(out), _ptr(self.ws), self.ws.numel(),
+                                               _stream(torch)))
+        return out

@@ -16,6 +16,7 @@
 #include "gemm_generic.h"
 #include "gemm_mfma.h"
 #include "rowwise_kernels.h"
+#include "token_ends.h"
 
 using namespace armt;
 
@@ -492,6 +493,53 @@ armt_status gemm_entry(int32_t g, const GemmShape& s, const GemmGroup* table, hi
 
 }  // namespace
 
+namespace {
+constexpr int64_t kHeadRows = 1024;    // rows per group of the head GEMM: 4 tiles of 256, like a cell
+struct HeadLayout { size_t xg, rstd, table, total; int64_t groups, rem; };
+HeadLayout head_layout(const Dims& D, int64_t n_rows) {
+  HeadLayout h;
+  h.groups = n_rows / kHeadRows;
+  h.rem = n_rows % kHeadRows;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t at = off; off += (bytes + kAlign - 1) / kAlign * kAlign; return at; };
+  h.xg = take((size_t)n_rows * D.d * D.esz);
+  h.rstd = take((size_t)n_rows * 4);
+  h.table = take((size_t)(h.groups + 1) * sizeof(GemmGroup));
+  h.total = off;
+  return h;
+}
+
+template <typename T>
+armt_status lm_head_typed(const Dims& D, const HeadLayout& h, const void* hidden, int64_t n_rows, const void* gain,
+                          const void* w_lm, int32_t vocab, float* logits, char* ws, hipStream_t st) {
+  T* xg = (T*)(ws + h.xg);
+  float* rstd = (float*)(ws + h.rstd);
+  final_norm_kernel<T><<<(unsigned)n_rows, 256, 0, st>>>((const T*)hidden, (const T*)gain, D.d, D.rms_eps, xg, rstd);
+  HIP_TRY(hipGetLastError());
+  // the rows go through the grouped GEMM in groups of kHeadRows that all point at the same weight: the
+  // tile order then keeps the four M-tiles of a weight panel side by side, as for a cell
+  std::vector<GemmGroup> tab(h.groups + 1);
+  memset(tab.data(), 0, tab.size() * sizeof(GemmGroup));
+  for (int64_t i = 0; i <= h.groups; ++i) {
+    const size_t r0 = (size_t)i * kHeadRows;
+    tab[i].A = xg + r0 * D.d; tab[i].B0 = w_lm; tab[i].C = logits + r0 * (size_t)vocab; tab[i].rowscale = rstd + r0;
+  }
+  HIP_TRY(hipMemcpyAsync(ws + h.table, tab.data(), tab.size() * sizeof(GemmGroup), hipMemcpyHostToDevice, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  GemmShape s;
+  s.M = (int)kHeadRows; s.N = vocab; s.K = D.d; s.lda = D.d; s.ldc = vocab; s.ldc2 = 0; s.ldr = 0; s.n0 = vocab; s.n1 = 0;
+  s.epi = EPI_STORE_F32; s.tag = -1; s.dbg = g_gemm_dbg;
+  const GemmGroup* table = (const GemmGroup*)(ws + h.table);
+  for (int64_t g0 = 0; g0 < h.groups; g0 += 256)          // at most 256 groups per launch
+    ARMT_TRY(gemm<T>(st, table, (int)g0, (int)std::min<int64_t>(256, h.groups - g0), s));
+  if (h.rem) {
+    s.M = (int)h.rem;
+    ARMT_TRY(gemm<T>(st, table, (int)h.groups, 1, s));
+  }
+  return ARMT_OK;
+}
+}  // namespace
+
 extern "C" {
 
 size_t armt_workspace_bytes(const armt_config* cfg) {
@@ -543,6 +591,43 @@ armt_status armt_grouped_gemm(int32_t dtype, int32_t g, int32_t M, int32_t N, in
   s.dbg = g_gemm_dbg;
   if (dtype == ARMT_BF16) return gemm_entry<bf16>(g, s, (const GemmGroup*)workspace, st);
   return gemm_entry<float>(g, s, (const GemmGroup*)workspace, st);
+}
+
+// ---- token-level ends of Algorithm 1
+armt_status armt_embed_tokens(const armt_config* cfg, const void* emb_table, int32_t vocab, const int32_t* ids,
+                              int64_t n_tokens, void* x_out, void* hip_stream) {
+  Dims D;
+  ARMT_TRY(check_config(cfg, &D));
+  if (!emb_table || !ids || !x_out) return ARMT_ERR_NULL;
+  if (vocab < 1 || n_tokens < 1 || n_tokens > 0x7fffffff) return ARMT_ERR_SHAPE;
+  const int row_bytes = D.d * D.esz;
+  if (row_bytes % 16 != 0) return ARMT_ERR_UNSUPPORTED;
+  embed_rows_kernel<<<(unsigned)n_tokens, 256, 0, (hipStream_t)hip_stream>>>(
+      (const unsigned char*)emb_table, ids, vocab, row_bytes, (unsigned char*)x_out);
+  HIP_TRY(hipGetLastError());
+  return ARMT_OK;
+}
+
+
+size_t armt_lm_head_workspace_bytes(const armt_config* cfg, int64_t n_rows) {
+  Dims D;
+  if (check_config(cfg, &D) != ARMT_OK || n_rows < 1) return 0;
+  return head_layout(D, n_rows).total;
+}
+
+armt_status armt_lm_head(const armt_config* cfg, const void* hidden, int64_t n_rows, const void* final_gain,
+                         const void* w_lm, int32_t vocab, float* logits, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+  Dims D;
+  ARMT_TRY(check_config(cfg, &D));
+  if (!hidden || !final_gain || !w_lm || !logits) return ARMT_ERR_NULL;
+  if (n_rows < 1 || n_rows > 0x7fffffff || vocab < 1) return ARMT_ERR_SHAPE;
+  const HeadLayout h = head_layout(D, n_rows);
+  if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < h.total) return ARMT_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (D.bf16)
+    return lm_head_typed<bf16>(D, h, hidden, n_rows, final_gain, w_lm, vocab, logits, (char*)workspace, st);
+  return lm_head_typed<float>(D, h, hidden, n_rows, final_gain, w_lm, vocab, logits, (char*)workspace, st);
 }
 
 armt_status armt_segment_attention(const armt_config* cfg, int32_t g, void* qkv, void* out, void* workspace,

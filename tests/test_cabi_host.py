@@ -157,3 +157,26 @@ def test_step_entry_argument_errors(lib):
     assert lib.armt_assoc_update(C.byref(cfg), 1, fake, arr, arr, arr, 3, fake, fake, 0x10000, n, None) == 2
     assert lib.armt_profile_begin(99, 4) == 2
     assert lib.armt_set_gemm_tile_config(-1) == -1
+
+
+def test_token_end_entry_argument_errors(lib):
+    shape = S.get_shape("tiny")
+    cfg = _cfg(shape)
+    fake = 0x1000
+    # embedding gather: null pointers, empty vocabulary, no tokens
+    assert lib.armt_embed_tokens(C.byref(cfg), None, 10, fake, 4, fake, None) == 1
+    assert lib.armt_embed_tokens(C.byref(cfg), fake, 0, fake, 4, fake, None) == 2
+    assert lib.armt_embed_tokens(C.byref(cfg), fake, 10, fake, 0, fake, None) == 2
+    # head: workspace grows with the rows (operand copy + row scales + pointer table), 0 for bad arguments
+    n1, n2 = lib.armt_lm_head_workspace_bytes(C.byref(cfg), 1), lib.armt_lm_head_workspace_bytes(C.byref(cfg), 5000)
+    assert n1 >= shape.d_model * 4 + 4 + 128 and n2 >= 5000 * (shape.d_model * 4 + 4) + 5 * 128 and n2 % 256 == 0
+    assert lib.armt_lm_head_workspace_bytes(C.byref(cfg), 0) == 0
+    assert lib.armt_lm_head(C.byref(cfg), None, 4, fake, fake, 10, fake, 0x10000, n1, None) == 1
+    assert lib.armt_lm_head(C.byref(cfg), fake, 0, fake, fake, 10, fake, 0x10000, n1, None) == 2
+    assert lib.armt_lm_head(C.byref(cfg), fake, 4, fake, fake, 0, fake, 0x10000, n1, None) == 2
+    assert lib.armt_lm_head(C.byref(cfg), fake, 5000, fake, fake, 10, fake, 0x10000, n2 - 1, None) == 4
+    assert lib.armt_lm_head(C.byref(cfg), fake, 4, fake, fake, 10, fake, 0x10010, n1, None) == 4     # misaligned
+    bad = _cfg(shape)
+    bad.head_dim = 31
+    assert lib.armt_lm_head_workspace_bytes(C.byref(bad), 4) == 0
+    assert lib.armt_embed_tokens(C.byref(bad), fake, 10, fake, 4, fake, None) != 0

@@ -1,0 +1,90 @@
+"""Parity of the token-level ends of Algorithm 1 (embedding gather; final RMSNorm + linear head) against
+the oracle, through the C-ABI entry points armt_embed_tokens / armt_lm_head."""
+import numpy as np
+import pytest
+import torch
+
+import armt_synth as S
+from gpu_util import rel_fro
+
+pytestmark = pytest.mark.gpu
+
+
+def _ends(shape, vocab, seed, n_tokens):
+    import paper_2506_05229_amd as P
+    ids, E, gf, W = S.make_token_ends(shape, vocab=vocab, seed=seed, n_tokens=n_tokens, gain_std=0.1)
+    return ids, E, gf, W, P.TokenEnds(shape, E, gf, W)
+
+
+@pytest.mark.parametrize("name,vocab", [("tiny", 301), ("1b_8k", 1000)])
+def test_embedding_gather_is_exact(name, vocab):
+    shape = S.get_shape(name)
+    ids, E, gf, W, te = _ends(shape, vocab, 3, 2 * shape.seg_len)
+    from oracle import armt_oracle as O
+    x = te.embed(torch.from_numpy(ids).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(x.float().cpu().numpy().astype(np.float64), O.embed_tokens(ids, E))      # a copy: bit-exact
+
+
+@pytest.mark.parametrize("name,vocab,rows,tol", [
+    ("tiny", 301, 72, None),          # fp32: ragged vocabulary, fewer rows than one group
+    ("tiny", 64, 2500, None),         # fp32: two groups of 1024 rows and a remainder
+    ("1b_8k", 1000, 1040, 2e-2),      # bf16: one group + 16 rows, vocabulary not a multiple of the tile
+    ("1b_8k", 2048, 2048, 2e-2),      # bf16: regular shape (scalar-addressed tiles)
+])
+def test_lm_head_matches_oracle(name, vocab, rows, tol):
+    from oracle import armt_oracle as O
+    shape = S.get_shape(name)
+    ids, E, gf, W, te = _ends(shape, vocab, 4, shape.seg_len)
+    rng = np.random.default_rng(5)
+    h = (rng.standard_normal((rows, shape.d_model)) * 2.0).astype(np.float32)
+    if shape.dtype == "bf16":
+        h = S.round_to_bf16(h)
+    got = te.logits(torch.from_numpy(h).to("cuda", te.dt))
+    torch.cuda.synchronize()
+    got = got.cpu().numpy().astype(np.float64)
+    want = O.lm_head(h, gf, W, shape.rms_eps)
+    assert got.shape == want.shape
+    if tol is None:
+        assert np.abs(got - want).max() <= 1e-4 * max(1.0, np.abs(want).max())
+    else:
+        assert rel_fro(got, want) <= tol, rel_fro(got, want)
+        assert np.abs(got - want).max() <= 5e-2 * np.abs(want).max()
+
+
+def test_tokens_to_logits_tiny_end_to_end():
+    """ids -> embeddings -> diagonal forward -> logits of the last rows, all through the library, vs the oracle."""
+    import paper_2506_05229_amd as P
+    from oracle import armt_oracle as O
+    shape = S.get_shape("tiny")
+    layers, mem_emb = S.make_weights(shape, seed=2, gain_std=0.1)
+    n_tok = 3 * shape.seg_len
+    ids, E, gf, W, te = _ends(shape, 97, 2, n_tok)
+    model = P.Armt(shape, layers, mem_emb)
+    x = te.embed(torch.from_numpy(ids).cuda())
+    hidden, A, z = model.forward(x, diagonal=True)
+    got = te.logits(hidden[-shape.seg_len:].contiguous())
+    torch.cuda.synchronize()
+    want, h_ref, _, _ = O.armt_forward_tokens(shape, layers, mem_emb, E, ids, gf, W, last_rows=shape.seg_len)
+    assert np.abs(hidden.cpu().numpy() - h_ref).max() <= 1e-4
+    assert np.abs(got.cpu().numpy() - want).max() <= 1e-4 * max(1.0, np.abs(want).max())
+
+
+def test_lm_head_full_vocabulary_sampled():
+    """LLaMA-3 vocabulary (128256 = 501 tiles of 256) on the last segment of the 1B shape: sampled logits,
+    each recomputed by the oracle from its own row and weight row."""
+    from oracle import armt_oracle as O
+    shape = S.get_shape("1b_128k")
+    V = S.LLAMA3_VOCAB
+    ids, E, gf, W, te = _ends(shape, V, 6, shape.seg_len)
+    rng = np.random.default_rng(7)
+    rows = shape.seg_len
+    h = S.round_to_bf16(rng.standard_normal((rows, shape.d_model)).astype(np.float32))
+    got = te.logits(torch.from_numpy(h).to("cuda", te.dt))
+    torch.cuda.synchronize()
+    r = np.concatenate([[0, rows - 1], rng.integers(0, rows, 30)])
+    c = np.concatenate([[0, V - 1, 255, 256], rng.integers(0, V, 60)])
+    sub = got[torch.from_numpy(r).cuda()][:, torch.from_numpy(c).cuda()].cpu().numpy().astype(np.float64)
+    want = O.lm_head(h[r], gf, W[c], shape.rms_eps)
+    assert rel_fro(sub, want) <= 2e-2, rel_fro(sub, want)
+    assert np.isfinite(got.sum().item())
