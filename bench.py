@@ -49,6 +49,8 @@ def main():
     ap.add_argument("--workload", default="1b_128k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sequential", action="store_true")
+    ap.add_argument("--no-lm-head", action="store_true",
+                    help="skip the extra timing of the token-level ends (embedding gather, final norm + head)")
     ap.add_argument("--cpu-segments", type=int, default=2)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of known size (the memory-state carry-in copy), so that a "
@@ -129,6 +131,41 @@ def main():
         sms, swall, _ = timed(False, max(1, min(args.steps, 2)), 0)
         res["sequential_tokens_per_s"] = n_tok / (swall / 1e3)
         res["speedup_vs_sequential"] = swall / wall_ms
+    if not args.no_lm_head:
+        # Token-level ends of Algorithm 1 (not part of `value`, which is the BASELINE metric on hidden states):
+        # embedding gather for the whole sequence, final norm + LLaMA-3-sized head on the last segment and on
+        # 16 segments, the latter extrapolated to all rows (the head's cost is linear in the rows).
+        ids, E, gf, Wlm = S.make_token_ends(shape, vocab=S.LLAMA3_VOCAB, seed=0)
+        te = P.TokenEnds(shape, E, gf, Wlm)
+        ids_d = torch.from_numpy(ids).cuda()
+        hid = out[0]
+
+        def ev(fn, reps=3):
+            fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps
+
+        ms_embed = ev(lambda: te.embed(ids_d))
+        rows_big = min(16 * shape.seg_len, n_tok)
+        lg_last = torch.empty((shape.seg_len, S.LLAMA3_VOCAB), dtype=torch.float32, device="cuda")
+        lg_big = torch.empty((rows_big, S.LLAMA3_VOCAB), dtype=torch.float32, device="cuda")
+        ms_last = ev(lambda: te.logits(hid[-shape.seg_len:], out=lg_last))
+        ms_big = ev(lambda: te.logits(hid[:rows_big], out=lg_big))
+        fl = lambda r: 2.0 * r * S.LLAMA3_VOCAB * shape.d_model
+        ms_all = ms_big * n_tok / rows_big
+        res["token_ends"] = {
+            "vocab": S.LLAMA3_VOCAB, "embed_ms_all_tokens": ms_embed,
+            "lm_head_last_segment_ms": ms_last, "lm_head_last_segment_tflops": fl(shape.seg_len) / ms_last / 1e9,
+            "lm_head_rows_timed": rows_big, "lm_head_ms": ms_big, "lm_head_tflops": fl(rows_big) / ms_big / 1e9,
+            "tokens_per_s_ids_to_last_segment_logits": n_tok / ((wall_ms + ms_embed + ms_last) / 1e3),
+            "tokens_per_s_ids_to_all_logits_extrapolated": n_tok / ((wall_ms + ms_embed + ms_all) / 1e3)}
+        del lg_last, lg_big, te
     if args.calibrate_copy:
         # copy_f32_kernel moves the whole memory state A_in -> A_out: n_layers * d_model * Phi floats read and written
         A_src, z_src = out[1].clone(), out[2].clone()

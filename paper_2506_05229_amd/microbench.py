@@ -3,6 +3,7 @@ the figures on grouped-GEMM FLOPS vs group size and attention vs batch size), on
 
     python -m paper_2506_05229_amd.microbench gemm      [--workload 1b_128k] [--data randn|zeros] [--iters 30]
     python -m paper_2506_05229_amd.microbench attention [--workload 1b_128k] [--iters 30]
+    python -m paper_2506_05229_amd.microbench head      [--workload 1b_128k] [--iters 10]
 
 `gemm` times the four big linear shapes of one cell (QKV, attention output, gate/up as one N = 2 d_ff problem,
 down) as one grouped launch of g = 1, 2, 4, 8, n_layers groups, every group with its own weight, through the
@@ -10,6 +11,8 @@ library's armt_grouped_gemm entry point (plain store epilogue).  `--data zeros` 
 the arithmetic is the same but nothing toggles, which shows how much of the rate the chip's power limit takes
 (the sustained clock under random data is lower than under constant data).
 `attention` times the fused segment attention (RoPE + GQA + causal softmax) for g = 1 ... n_layers cells.
+
+`head` times the final RMSNorm + linear head over the LLaMA-3 vocabulary (128256) for 1, 4 and 16 segments of rows.
 
 Everything is timed with device events after a warm-up in the same process; one JSON line per measurement.
 """
@@ -89,9 +92,28 @@ def bench_attention(shape, iters: int, warmup: int):
                           "head_dim": s.head_dim, "ms": round(ms, 4), "tflops": round(flops / ms / 1e9, 1)}), flush=True)
 
 
+def bench_head(shape, iters: int, warmup: int):
+    import torch
+    import armt_synth as S
+    from . import TokenEnds
+
+    s = shape
+    ids, E, gf, W = S.make_token_ends(s, vocab=S.LLAMA3_VOCAB, seed=0, n_tokens=s.seg_len)
+    te = TokenEnds(s, E, gf, W)
+    gen = torch.Generator(device="cuda").manual_seed(0)
+    for segs in (1, 4, 16):
+        rows = segs * s.seg_len
+        h = torch.randn(rows, s.d_model, device="cuda", generator=gen).to(te.dt)
+        out = torch.empty((rows, S.LLAMA3_VOCAB), dtype=torch.float32, device="cuda")
+        ms = _time(torch, lambda: te.logits(h, out=out), iters, min(warmup, 5))
+        print(json.dumps({"op": "lm_head", "rows": rows, "vocab": S.LLAMA3_VOCAB, "d_model": s.d_model, "ms": round(ms, 4),
+                          "tflops": round(2.0 * rows * S.LLAMA3_VOCAB * s.d_model / ms / 1e9, 1)}), flush=True)
+        del h, out
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("op", choices=["gemm", "attention"])
+    ap.add_argument("op", choices=["gemm", "attention", "head"])
     ap.add_argument("--workload", default="1b_128k")
     ap.add_argument("--data", choices=["randn", "zeros"], default="randn")
     ap.add_argument("--iters", type=int, default=30)
@@ -109,8 +131,10 @@ def main(argv=None) -> int:
         return 2
     if args.op == "gemm":
         bench_gemm(shape, args.data, args.iters, args.warmup)
-    else:
+    elif args.op == "attention":
         bench_attention(shape, args.iters, args.warmup)
+    else:
+        bench_head(shape, min(args.iters, 10), args.warmup)
     return 0
 
 
