@@ -90,6 +90,8 @@ CONFIGS = {
     "1b_128k_s512": ArmtShape("1b_128k_s512", n_tokens=131072, **{**_1B, "seg_len": 512}),
     "1b_128k_s2048": ArmtShape("1b_128k_s2048", n_tokens=131072, **{**_1B, "seg_len": 2048}),
     "3b_128k": ArmtShape("3b_128k", n_tokens=131072, **_3B),
+    # the shape of the paper's timing tables: 4096-token segments with 128 memory tokens
+    "1b_128k_s4096_m128": ArmtShape("1b_128k_s4096_m128", n_tokens=131072, **{**_1B, "seg_len": 4096, "n_mem": 128}),
 }
 
 

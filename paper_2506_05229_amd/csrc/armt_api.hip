@@ -67,7 +67,6 @@ armt_status check_config(const armt_config* c, Dims* out) {
   D.rms_eps = c->rms_eps; D.rope_theta = c->rope_theta; D.assoc_eps = c->assoc_eps;
   D.esz = D.bf16 ? 2 : 4;
   if (D.Phi > 512) return ARMT_ERR_UNSUPPORTED;          // the delta-rule kernel keeps a row of A in registers
-  if ((size_t)D.m * D.Phi * 4 + (size_t)D.m * 16 > 60000) return ARMT_ERR_UNSUPPORTED;   // phi(k_i) of a cell live in LDS
   if (D.bf16) {
     // the MFMA GEMM takes k-tiles of 64 and 16-byte rows
     if (D.d % 64 || D.F % 64 || D.Phi % 64 || D.dm % 8 || D.m % 16) return ARMT_ERR_UNSUPPORTED;
@@ -309,9 +308,10 @@ armt_status step_assoc_update(hipStream_t st, const GemmGroup* t_mkv, const Gemm
     }
 #undef ARMT_DELTA16
   } else {
-    const int rows_per_block = 16;
-    delta_rule_kernel<8><<<dim3((d + rows_per_block - 1) / rows_per_block, g), 256, (size_t)m * (Phi + 4) * 4, st>>>(
-        KVm, Fm, Coef, aux, first, m, d, dm, Phi, rows_per_block);
+    const int rows_per_block = 4 * DR_ROWS;
+    const size_t lds = (size_t)std::min(m, DR_CHUNK) * (Phi + 4) * 4;
+    delta_rule_kernel<8><<<dim3((d + rows_per_block - 1) / rows_per_block, g), 256, lds, st>>>(KVm, Fm, Coef, aux, first,
+                                                                                             m, d, dm, Phi);
   }
   HIP_TRY(hipGetLastError());
   return ARMT_OK;

@@ -198,68 +198,91 @@ __global__ __launch_bounds__(128) void memupd_prep_kernel(const float* __restric
 }
 
 // Delta rule (Eq. 5), one pass over A: row r of A needs only A[r, :], v_i[r] and the shared f_i, so
-// each wave owns rows, computes v_bar_i[r] = A[r,:].f_i / den_i for all i from the OLD row, then adds
-// sum_i beta_i (v_i[r] - v_bar_i[r]) f_i and writes the row back once (plus its bf16 shadow).
+// each wave owns DR_ROWS rows, keeps them in registers, computes v_bar_i[r] = A[r,:].f_i / den_i for all i
+// from the OLD rows, accumulates sum_i beta_i (v_i[r] - v_bar_i[r]) f_i and writes each row back once (plus its
+// bf16 shadow).  The f_i pass through LDS in chunks of DR_CHUNK memory tokens, so any n_mem fits.
 // The block with blockIdx.x == 0 also updates z += sum_i gamma_i f_i (z is not read here).
-// grid: (ceil(d / rows_per_block), g), block: 256 (4 waves).  Phi <= 64 * NPL.
+// grid: (ceil(d / (4 * DR_ROWS)), g), block: 256 (4 waves).  Phi <= 64 * NPL.
+// dynamic LDS: min(m, DR_CHUNK) * (Phi + 4) floats.
+constexpr int DR_ROWS = 4, DR_CHUNK = 32;
 template <int NPL>
 __global__ __launch_bounds__(256) void delta_rule_kernel(const float* __restrict__ KV, const float* __restrict__ Fm,
                                                          const float* __restrict__ Coef,
                                                          const LayerAux* __restrict__ aux, int first, int m, int d,
-                                                         int dm, int Phi, int rows_per_block) {
-  extern __shared__ float sm[];          // F: m * Phi, then coef: m * 4
+                                                         int dm, int Phi) {
+  extern __shared__ float sm[];          // F: chunk * Phi, then coef: chunk * 4
+  const int chunk = min(m, DR_CHUNK);
   float* F = sm;
-  float* cf = sm + (size_t)m * Phi;
+  float* cf = sm + (size_t)chunk * Phi;
   const int l = first + blockIdx.y;
   const float* Fl = Fm + (size_t)l * m * Phi;
-  for (int c = threadIdx.x; c < m * Phi; c += blockDim.x) F[c] = Fl[c];
-  for (int c = threadIdx.x; c < m * 4; c += blockDim.x) cf[c] = Coef[(size_t)l * m * 4 + c];
-  __syncthreads();
   float* A = aux[l].A;
   bf16* A16 = aux[l].A16;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int r0 = blockIdx.x * rows_per_block;
-  const int r1 = min(d, r0 + rows_per_block);
-  const float* V = KV + (size_t)l * m * (dm + d) + dm;      // v_i[r] = V[i * (dm + d) + r]
-  for (int r = r0 + w; r < r1; r += 4) {
-    float a[NPL];
+  const int r0 = blockIdx.x * (4 * DR_ROWS) + w * DR_ROWS;      // this wave's rows r0 .. r0 + DR_ROWS - 1
+  const float* V = KV + (size_t)l * m * (dm + d) + dm;          // v_i[r] = V[i * (dm + d) + r]
+  float a[DR_ROWS][NPL], upd[DR_ROWS][NPL];
+#pragma unroll
+  for (int q = 0; q < DR_ROWS; ++q)
 #pragma unroll
     for (int k = 0; k < NPL; ++k) {
       const int c = lane + 64 * k;
-      a[k] = (c < Phi) ? A[(size_t)r * Phi + c] : 0.f;
+      a[q][k] = (r0 + q < d && c < Phi) ? A[(size_t)(r0 + q) * Phi + c] : 0.f;
+      upd[q][k] = 0.f;
     }
-    float upd[NPL] = {};
-    for (int i = 0; i < m; ++i) {
-      float dot = 0.f;
+  float zs[2] = {0.f, 0.f};              // z columns threadIdx.x and threadIdx.x + 256 (Phi <= 512)
+  for (int i0 = 0; i0 < m; i0 += chunk) {
+    const int n = min(chunk, m - i0);
+    __syncthreads();                     // the previous chunk is no longer read
+    for (int c = threadIdx.x; c < n * Phi; c += blockDim.x) F[c] = Fl[(size_t)i0 * Phi + c];
+    for (int c = threadIdx.x; c < n * 4; c += blockDim.x) cf[c] = Coef[((size_t)l * m + i0) * 4 + c];
+    __syncthreads();
 #pragma unroll
-      for (int k = 0; k < NPL; ++k) {
-        const int c = lane + 64 * k;
-        if (c < Phi) dot = fmaf(a[k], F[i * Phi + c], dot);
-      }
-      dot = wave_sum(dot);
-      const float coef = cf[i * 4 + 0] * (V[(size_t)i * (dm + d) + r] - dot * cf[i * 4 + 2]);
+    for (int q = 0; q < DR_ROWS; ++q) {
+      const int r = r0 + q;
+      if (r >= d) break;                 // wave-uniform
+      for (int i = 0; i < n; ++i) {
+        float dot = 0.f;
 #pragma unroll
-      for (int k = 0; k < NPL; ++k) {
-        const int c = lane + 64 * k;
-        if (c < Phi) upd[k] = fmaf(coef, F[i * Phi + c], upd[k]);
+        for (int k = 0; k < NPL; ++k) {
+          const int c = lane + 64 * k;
+          if (c < Phi) dot = fmaf(a[q][k], F[i * Phi + c], dot);
+        }
+        dot = wave_sum(dot);
+        const float coef = cf[i * 4 + 0] * (V[(size_t)(i0 + i) * (dm + d) + r] - dot * cf[i * 4 + 2]);
+#pragma unroll
+        for (int k = 0; k < NPL; ++k) {
+          const int c = lane + 64 * k;
+          if (c < Phi) upd[q][k] = fmaf(coef, F[i * Phi + c], upd[q][k]);
+        }
       }
     }
+    if (blockIdx.x == 0) {
 #pragma unroll
-    for (int k = 0; k < NPL; ++k) {
-      const int c = lane + 64 * k;
-      if (c < Phi) {
-        const float v = a[k] + upd[k];
-        A[(size_t)r * Phi + c] = v;
-        if (A16) A16[(size_t)r * Phi + c] = (bf16)v;
+      for (int h = 0; h < 2; ++h) {
+        const int c = threadIdx.x + 256 * h;
+        if (c < Phi)
+          for (int i = 0; i < n; ++i) zs[h] = fmaf(cf[i * 4 + 1], F[i * Phi + c], zs[h]);
       }
     }
   }
+#pragma unroll
+  for (int q = 0; q < DR_ROWS; ++q)
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) {
+      const int c = lane + 64 * k;
+      if (r0 + q < d && c < Phi) {
+        const float v = a[q][k] + upd[q][k];
+        A[(size_t)(r0 + q) * Phi + c] = v;
+        if (A16) A16[(size_t)(r0 + q) * Phi + c] = (bf16)v;
+      }
+    }
   if (blockIdx.x == 0) {
     float* z = aux[l].z;
-    for (int c = threadIdx.x; c < Phi; c += blockDim.x) {
-      float s = 0.f;
-      for (int i = 0; i < m; ++i) s = fmaf(cf[i * 4 + 1], F[i * Phi + c], s);
-      z[c] += s;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int c = threadIdx.x + 256 * h;
+      if (c < Phi) z[c] += zs[h];
     }
   }
 }

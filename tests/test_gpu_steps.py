@@ -109,6 +109,9 @@ MEM_SHAPES = [
     ("f32", dict(d_model=120, n_heads=6, head_dim=20, n_kv_heads=3, seg_len=37, n_mem=5, d_mem=12, dpfp_nu=2)),
     ("bf16", dict(d_model=256, n_heads=4, head_dim=64, n_kv_heads=2, d_ff=512, seg_len=144, n_mem=16, d_mem=32)),
     ("bf16", dict(d_model=512, n_heads=8, head_dim=64, n_kv_heads=2, d_ff=512, seg_len=1024, n_mem=16, d_mem=64)),
+    # memory tokens in several LDS chunks of the generic delta rule: 32 + 8, and the 128 of the paper's tables
+    ("f32", dict(n_mem=40)),
+    ("bf16", dict(d_model=256, n_heads=4, head_dim=64, n_kv_heads=2, d_ff=512, seg_len=128, n_mem=128, d_mem=64)),
 ]
 
 
