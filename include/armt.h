@@ -110,6 +110,26 @@ armt_status armt_forward_diagonal(const armt_config *cfg, const armt_layer_weigh
                                   void *hidden_out, float *A_out, float *z_out,
                                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Batch of B independent sequences of the same length (the paper's batched setting, Section 4.3): step t
+ * runs the cells (layer l, segment t - l) of all B sequences as one group of up to B * n_layers cells; the B
+ * cells of a layer share its weights.  The sequential variant runs, per (segment, layer), the B cells of that
+ * layer as one group: ordinary batching, the baseline of the paper's batch-size comparison.
+ * x, hidden_out: [B][n_tokens][d_model]; A_in, A_out: [B][n_layers][d_model][Phi]; z_in, z_out: [B][n_layers][Phi];
+ * workspace: armt_workspace_bytes_batched(cfg, B) bytes (0 = configuration or batch rejected; B * n_layers
+ * must not exceed 32768).  Everything else as in the calls above, which are the case B = 1; sequence b of a
+ * batched call gets bit for bit the result of a call on sequence b alone. */
+size_t armt_workspace_bytes_batched(const armt_config *cfg, int32_t batch);
+armt_status armt_forward_sequential_batched(const armt_config *cfg, const armt_layer_weights *layers,
+                                            const void *mem_emb, const void *x, int32_t batch, int64_t n_tokens,
+                                            const float *A_in, const float *z_in,
+                                            void *hidden_out, float *A_out, float *z_out,
+                                            void *workspace, size_t workspace_bytes, void *hip_stream);
+armt_status armt_forward_diagonal_batched(const armt_config *cfg, const armt_layer_weights *layers,
+                                          const void *mem_emb, const void *x, int32_t batch, int64_t n_tokens,
+                                          const float *A_in, const float *z_in,
+                                          void *hidden_out, float *A_out, float *z_out,
+                                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Anti-diagonal schedule (Lemma 3.1), host only: for step t of an L-layer model over N segments,
  * *l_lo .. *l_hi (inclusive) are the live layers; layer l runs segment t - l.  Returns the group
  * size, or 0 (and leaves the outputs alone) if t is outside 0 .. L + N - 2 or L, N < 1. */

@@ -26,6 +26,7 @@ Parity status of each function (what pins it, in tests/test_oracle_*.py):
   lm_head                  identity head (logits = g * h / rms(h)), scale invariance, library
                            rms_norm + matmul, pure-python loops on tiny sizes
   armt_forward_tokens      composition of the three (no arithmetic of its own)
+  armt_forward_batched     a loop over the sequences (no arithmetic of its own)
 Absolute values of the hidden states on the LLaMA-shaped workloads are not printed
 anywhere in the paper; they are pinned only through the checks above.
 
@@ -259,3 +260,11 @@ def armt_forward_tokens(cfg, layers, mem_emb, emb_table, ids, final_gain, w_lm, 
     hidden, A, z = armt_forward_sequential(cfg, layers, mem_emb, x)
     rows = hidden if last_rows is None else hidden[-last_rows:]
     return lm_head(rows, final_gain, w_lm, cfg.rms_eps), hidden, A, z
+
+
+# --------------------------------------------------------------------------- batch (Section 4.3)
+def armt_forward_batched(cfg, layers, mem_emb, x):
+    """B independent sequences x [B, n_tokens, d]: by definition each one's own sequential result.
+    Returns (hidden [B, n_tokens, d], A [B, L, d, Phi], z [B, L, Phi])."""
+    outs = [armt_forward_sequential(cfg, layers, mem_emb, xb) for xb in x]
+    return tuple(np.stack([o[i] for o in outs]) for i in range(3))

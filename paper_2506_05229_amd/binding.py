@@ -60,6 +60,12 @@ def load_library():
     for name in ("armt_forward_sequential", "armt_forward_diagonal"):
         getattr(lib, name).argtypes = fwd
         getattr(lib, name).restype = C.c_int
+    fwdb = fwd[:4] + [i32] + fwd[4:]
+    for name in ("armt_forward_sequential_batched", "armt_forward_diagonal_batched"):
+        getattr(lib, name).argtypes = fwdb
+        getattr(lib, name).restype = C.c_int
+    lib.armt_workspace_bytes_batched.argtypes = [C.POINTER(ArmtConfig), i32]
+    lib.armt_workspace_bytes_batched.restype = sz
     lib.armt_diagonal_group.argtypes = [i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
     lib.armt_diagonal_group.restype = i32
     pp = C.POINTER(C.c_void_p)
@@ -153,6 +159,30 @@ class Armt:
         stream = torch.cuda.current_stream(self.device).cuda_stream
         code = fn(C.byref(self.cfg), self.c_layers, _ptr(self.mem_emb), _ptr(x), n_tokens, _ptr(A_in), _ptr(z_in),
                   _ptr(hidden), _ptr(A), _ptr(z), _ptr(self.workspace), self.workspace_bytes, C.c_void_p(stream))
+        _check(self.lib, code)
+        return hidden, A, z
+
+    def forward_batched(self, x, diagonal=True, A_in=None, z_in=None, out=None):
+        """x: [B, n_tokens, d] device tensor: B independent sequences.  Returns (hidden [B, n_tokens, d],
+        A [B, L, d, Phi], z [B, L, Phi])."""
+        torch, s = self.torch, self.shape
+        assert x.is_cuda and x.dtype == self.act_dtype and x.is_contiguous() and x.dim() == 3
+        B, n_tokens = x.shape[0], x.shape[1]
+        need = self.lib.armt_workspace_bytes_batched(C.byref(self.cfg), B)
+        if need == 0:
+            raise ArmtError(2, "configuration or batch rejected by armt_workspace_bytes_batched")
+        if self.workspace.numel() < need:
+            self.workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
+        if out is None:
+            hidden = torch.empty((B, n_tokens, s.d_model), dtype=self.act_dtype, device=self.device)
+            A = torch.empty((B, s.n_layers, s.d_model, s.phi), dtype=torch.float32, device=self.device)
+            z = torch.empty((B, s.n_layers, s.phi), dtype=torch.float32, device=self.device)
+        else:
+            hidden, A, z = out
+        fn = self.lib.armt_forward_diagonal_batched if diagonal else self.lib.armt_forward_sequential_batched
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        code = fn(C.byref(self.cfg), self.c_layers, _ptr(self.mem_emb), _ptr(x), B, n_tokens, _ptr(A_in), _ptr(z_in),
+                  _ptr(hidden), _ptr(A), _ptr(z), _ptr(self.workspace), self.workspace.numel(), C.c_void_p(stream))
         _check(self.lib, code)
         return hidden, A, z
 

@@ -43,7 +43,9 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Dims {
-  int L, d, H, Hkv, dh, F, S, m, T, dm, nu, Phi, Nqkv;
+  // L counts the cells that can be live in one step: n_layers * batch ("virtual layers": index v = layer * B + b;
+  // all per-layer scratch, tables and kernels are indexed by v).  Lr = n_layers, B = batch (1 outside the batched calls).
+  int L, Lr, B, d, H, Hkv, dh, F, S, m, T, dm, nu, Phi, Nqkv;
   bool bf16;
   float rms_eps, rope_theta, assoc_eps;
   size_t esz;   // bytes of one activation / weight element
@@ -60,7 +62,7 @@ armt_status check_config(const armt_config* c, Dims* out) {
   if (c->dpfp_nu >= 2 * c->d_mem) return ARMT_ERR_SHAPE;
   if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f) || !(c->assoc_eps >= 0.f)) return ARMT_ERR_SHAPE;
   Dims D;
-  D.L = c->n_layers; D.d = c->d_model; D.H = c->n_heads; D.Hkv = c->n_kv_heads; D.dh = c->head_dim;
+  D.L = D.Lr = c->n_layers; D.B = 1; D.d = c->d_model; D.H = c->n_heads; D.Hkv = c->n_kv_heads; D.dh = c->head_dim;
   D.F = c->d_ff; D.S = c->seg_len; D.m = c->n_mem; D.T = D.S + D.m; D.dm = c->d_mem; D.nu = c->dpfp_nu;
   D.Phi = 2 * D.nu * D.dm; D.Nqkv = (D.H + 2 * D.Hkv) * D.dh;
   D.bf16 = (c->dtype == ARMT_BF16);
@@ -89,8 +91,8 @@ Layout carve(const Dims& D) {
   size_t p = 0;
   auto take = [&](size_t bytes) { size_t at = p; p = align_up(p + bytes); return at; };
   const size_t L = D.L, T = D.T;
-  o.X = take((L + 1) * T * D.d * 4);                              // residual stream, slot l = input of layer l
-  o.Xb = take(D.bf16 ? (L + 1) * T * D.d * 2 : 0);                // bf16 copy of the slots (GEMM operand)
+  o.X = take((L + D.B) * T * D.d * 4);                            // residual stream, slot v = input of cell v; output in v + B
+  o.Xb = take(D.bf16 ? (L + D.B) * T * D.d * 2 : 0);              // bf16 copy of the slots (GEMM operand)
   o.Nrm = take(L * T * D.d * D.esz);
   o.QKV = take(L * T * D.Nqkv * D.esz);
   o.Vt = take(D.bf16 ? attention_vt_bytes(D.L, D.T, D.Hkv, D.dh) : 0);   // V transposed, for the MFMA attention
@@ -176,10 +178,12 @@ armt_status upload_tables(Ctx& c, const armt_layer_weights* W, float* A, float* 
   char* X = c.ws + c.o.X;
   char* Xop = D.bf16 ? c.ws + c.o.Xb : X;       // activation-typed view of the slots
   const size_t slotX = T * D.d * 4, slotXop = T * D.d * D.esz;
-  for (size_t l = 0; l < L; ++l) {
-    const armt_layer_weights& w = W[l];
-    float* Al = A + l * (size_t)D.d * D.Phi;
-    bf16* A16l = D.bf16 ? c.at<bf16>(c.o.A16) + l * (size_t)D.d * D.Phi : nullptr;
+  const size_t B = D.B;
+  for (size_t l = 0; l < L; ++l) {                 // l = virtual layer: real layer l / B of sequence l % B
+    const armt_layer_weights& w = W[l / B];
+    const size_t state = (l % B) * D.Lr + l / B;    // the caller's memory state is [B][n_layers][...]
+    float* Al = A + state * (size_t)D.d * D.Phi;
+    bf16* A16l = D.bf16 ? c.at<bf16>(c.o.A16) + state * (size_t)D.d * D.Phi : nullptr;
     GemmGroup* g;
     g = &tab[K_MQ * L + l];
     g->A = Xop + l * slotXop; g->B0 = w.wm_q; g->C = c.ws + c.o.Qm + l * T * D.dm * 4;
@@ -208,14 +212,14 @@ armt_status upload_tables(Ctx& c, const armt_layer_weights* W, float* A, float* 
     if (c.fused_norm) g->rowscale = rstd;
     g = &tab[K_DOWN * L + l];
     g->A = c.ws + c.o.Uff + l * T * D.F * D.esz; g->B0 = w.wdown;
-    g->C = X + (l + 1) * slotX; g->C2 = D.bf16 ? Xop + (l + 1) * slotXop : nullptr;
+    g->C = X + (l + B) * slotX; g->C2 = D.bf16 ? Xop + (l + B) * slotXop : nullptr;
     g->R = (const float*)(c.ws + c.o.Hres + l * T * D.d * 4);
     g = &tab[K_MKV * L + l];
-    g->A = Xop + (l + 1) * slotXop + (size_t)D.S * D.d * D.esz; g->B0 = w.wm_k; g->B1 = w.wm_v;
+    g->A = Xop + (l + B) * slotXop + (size_t)D.S * D.d * D.esz; g->B0 = w.wm_k; g->B1 = w.wm_v;
     g->C = c.ws + c.o.KVm + l * D.m * (size_t)(D.dm + D.d) * 4;
     LayerAux& a = aux[l];
     a.rms1 = w.rms1; a.rms2 = w.rms2; a.wm_b = w.wm_b;
-    a.A = Al; a.z = z + l * (size_t)D.Phi; a.A16 = A16l;
+    a.A = Al; a.z = z + state * (size_t)D.Phi; a.A16 = A16l;
   }
   // hipMemcpyAsync from pageable host memory returns once the source has been consumed.
   HIP_TRY(hipMemcpyAsync(c.ws + c.o.Tables, tab.data(), tab.size() * sizeof(GemmGroup), hipMemcpyHostToDevice, c.st));
@@ -289,12 +293,12 @@ armt_status step_attention(hipStream_t st, T* QKV, T* Att, bf16* Vt, const float
 // Delta-rule update of the memories of cells [first, first + g) from their m memory-row outputs (Eq. 3-5).
 template <typename T>
 armt_status step_assoc_update(hipStream_t st, const GemmGroup* t_mkv, const GemmShape& s_mkv, const LayerAux* aux,
-                              int first, int g, int empty_layer, const T* Y0, size_t y_stride, int m, int d, int dm,
+                              int first, int g, int empty_lo, int empty_hi, const T* Y0, size_t y_stride, int m, int d, int dm,
                               int nu, float eps, float* KVm, float* Fm, float* Coef) {
   if (g <= 0) return ARMT_OK;
   const int Phi = 2 * nu * dm;
   ARMT_TRY(gemm<T>(st, t_mkv, first, g, s_mkv));
-  memupd_prep_kernel<T><<<dim3(m, g), 128, (dm + 17) * 4, st>>>(KVm, Y0, y_stride, aux, first, empty_layer, m, d, dm, nu,
+  memupd_prep_kernel<T><<<dim3(m, g), 128, (dm + 17) * 4, st>>>(KVm, Y0, y_stride, aux, first, empty_lo, empty_hi, m, d, dm, nu,
                                                                eps, Fm, Coef);
   HIP_TRY(hipGetLastError());
   if (m == 16 && Phi % 64 == 0 && Phi <= 512) {
@@ -323,19 +327,21 @@ armt_status step_assoc_update(hipStream_t st, const GemmGroup* t_mkv, const Gemm
 template <typename T>
 armt_status run_group(const Ctx& c, int lo, int hi, int read_hi, int empty_layer) {
   const Dims& D = c.D;
-  const int g = hi - lo + 1;
+  // real layers -> cells: layer l of the B sequences = cells l * B .. l * B + B - 1
+  const int g = (hi - lo + 1) * D.B, gr = (read_hi - lo + 1) * D.B;
+  const int e0 = empty_layer < 0 ? -1 : empty_layer * D.B, e1 = empty_layer < 0 ? -1 : e0 + D.B;
+  lo *= D.B;
   float* X = c.at<float>(c.o.X);
   T* Xop = D.bf16 ? c.at<T>(c.o.Xb) : (T*)X;
   // (1) associative read
   ARMT_TRY(step_assoc_read<T>(c.st, c.table(K_MQ), c.shape[K_MQ], c.table(K_READ), c.shape[K_READ], c.aux, lo,
-                              read_hi - lo + 1, D.T, D.dm, D.nu, D.assoc_eps, c.at<float>(c.o.Qm), c.at<T>(c.o.Fphi),
+                              gr, D.T, D.dm, D.nu, D.assoc_eps, c.at<float>(c.o.Qm), c.at<T>(c.o.Fphi),
                               c.at<float>(c.o.RDen)));
   // (2) decoder block (TransformerLayer of Eq. 2).  On the bf16 path both RMSNorms are folded into the GEMMs
   // around them: the producer of a row (read GEMM, attention-output GEMM) also writes bf16(row * gain) and the
   // row's sum of squares per N-tile; the consumer GEMM multiplies its result rows by 1 / rms.
   float* rstd = c.at<float>(c.o.RStd);
   if (c.fused_norm) {
-    const int gr = read_hi - lo + 1;
     if (gr > 0) {
       rstd_kernel<<<dim3((D.T + 255) / 256, gr), 256, 0, c.st>>>(c.at<float>(c.o.Ssq), lo, D.T, c.ssq_parts, D.d, D.rms_eps, rstd);
       HIP_TRY(hipGetLastError());
@@ -362,8 +368,8 @@ armt_status run_group(const Ctx& c, int lo, int hi, int read_hi, int empty_layer
   ARMT_TRY(gemm<T>(c.st, c.table(K_GU), lo, g, c.shape[K_GU]));
   ARMT_TRY(gemm<T>(c.st, c.table(K_DOWN), lo, g, c.shape[K_DOWN]));
   // (3) memory update from the block's output at the memory rows
-  const T* Y0 = Xop + ((size_t)D.T + D.S) * D.d;        // memory row 0 of slot 1 = output of layer 0
-  return step_assoc_update<T>(c.st, c.table(K_MKV), c.shape[K_MKV], c.aux, lo, g, empty_layer, Y0, (size_t)D.T * D.d,
+  const T* Y0 = Xop + ((size_t)D.B * D.T + D.S) * D.d;  // memory row 0 of slot B = output of cell 0
+  return step_assoc_update<T>(c.st, c.table(K_MKV), c.shape[K_MKV], c.aux, lo, g, e0, e1, Y0, (size_t)D.T * D.d,
                               D.m, D.d, D.dm, D.nu, D.assoc_eps, c.at<float>(c.o.KVm), c.at<float>(c.o.Fm),
                               c.at<float>(c.o.Coef));
 }
@@ -372,7 +378,8 @@ template <typename T>
 armt_status forward_typed(Ctx& c, const void* mem_emb, const void* x, int64_t N, bool carry_in, void* hidden_out,
                           bool diagonal) {
   const Dims& D = c.D;
-  const int L = D.L;
+  const int L = D.Lr;
+  const size_t seq = (size_t)N * D.S * D.d;      // elements of one sequence of x / hidden_out
   float* X = c.at<float>(c.o.X);
   T* Xb = D.bf16 ? c.at<T>(c.o.Xb) : nullptr;
   {
@@ -386,12 +393,18 @@ armt_status forward_typed(Ctx& c, const void* mem_emb, const void* x, int64_t N,
     }
   }
   auto ingest = [&](int64_t s) -> armt_status {       // Algorithm 1: ingest a new segment at layer 0
-    pack_segment_kernel<T><<<D.T, 256, 0, c.st>>>((const T*)x + (size_t)s * D.S * D.d, (const T*)mem_emb, D.S, D.d, X, Xb);
+    for (int b = 0; b < D.B; ++b) {                  // sequence b enters at cell b (layer 0)
+      const size_t slot = (size_t)b * D.T * D.d;
+      pack_segment_kernel<T><<<D.T, 256, 0, c.st>>>((const T*)x + b * seq + (size_t)s * D.S * D.d, (const T*)mem_emb, D.S, D.d,
+                                                    X + slot, Xb ? Xb + slot : nullptr);
+    }
     HIP_TRY(hipGetLastError());
     return ARMT_OK;
   };
   auto emit = [&](int64_t s) -> armt_status {         // segment s went through all layers
-    store_hidden_kernel<T><<<D.S, 256, 0, c.st>>>(X + (size_t)L * D.T * D.d, D.d, (T*)hidden_out + (size_t)s * D.S * D.d);
+    for (int b = 0; b < D.B; ++b)                    // output of the last layer's cell of sequence b: slot L * B + b
+      store_hidden_kernel<T><<<D.S, 256, 0, c.st>>>(X + (size_t)(D.L + b) * D.T * D.d, D.d,
+                                                    (T*)hidden_out + b * seq + (size_t)s * D.S * D.d);
     HIP_TRY(hipGetLastError());
     return ARMT_OK;
   };
@@ -418,11 +431,12 @@ armt_status forward_typed(Ctx& c, const void* mem_emb, const void* x, int64_t N,
 }
 
 armt_status forward_impl(const armt_config* cfg, const armt_layer_weights* layers, const void* mem_emb, const void* x,
-                         int64_t n_tokens, const float* A_in, const float* z_in, void* hidden_out, float* A_out,
+                         int32_t batch, int64_t n_tokens, const float* A_in, const float* z_in, void* hidden_out, float* A_out,
                          float* z_out, void* workspace, size_t workspace_bytes, void* hip_stream, bool diagonal) {
   Ctx c;
   ARMT_TRY(check_config(cfg, &c.D));
   const Dims& D = c.D;
+  if (batch < 1 || (int64_t)batch * D.L > 32768) return ARMT_ERR_SHAPE;      // cells of a step index a launch grid
   if (!layers || !mem_emb || !x || !hidden_out || !A_out || !z_out) return ARMT_ERR_NULL;
   if ((A_in == nullptr) != (z_in == nullptr)) return ARMT_ERR_NULL;
   for (int l = 0; l < D.L; ++l) {
@@ -434,6 +448,8 @@ armt_status forward_impl(const armt_config* cfg, const armt_layer_weights* layer
   if (n_tokens <= 0 || n_tokens % D.S != 0) return ARMT_ERR_SHAPE;
   const int64_t N = n_tokens / D.S;
   if (N + D.L > (int64_t)1 << 30) return ARMT_ERR_SHAPE;
+  c.D.B = batch;
+  c.D.L = D.Lr * batch;                    // from here on L counts cells per step (see Dims)
   c.o = carve(D);
   if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < c.o.total) return ARMT_ERR_WORKSPACE;
   c.ws = (char*)workspace;
@@ -552,7 +568,7 @@ armt_status armt_forward_sequential(const armt_config* cfg, const armt_layer_wei
                                     const void* x, int64_t n_tokens, const float* A_in, const float* z_in,
                                     void* hidden_out, float* A_out, float* z_out, void* workspace,
                                     size_t workspace_bytes, void* hip_stream) {
-  return forward_impl(cfg, layers, mem_emb, x, n_tokens, A_in, z_in, hidden_out, A_out, z_out, workspace,
+  return forward_impl(cfg, layers, mem_emb, x, 1, n_tokens, A_in, z_in, hidden_out, A_out, z_out, workspace,
                       workspace_bytes, hip_stream, false);
 }
 
@@ -560,7 +576,31 @@ armt_status armt_forward_diagonal(const armt_config* cfg, const armt_layer_weigh
                                   const void* x, int64_t n_tokens, const float* A_in, const float* z_in,
                                   void* hidden_out, float* A_out, float* z_out, void* workspace,
                                   size_t workspace_bytes, void* hip_stream) {
-  return forward_impl(cfg, layers, mem_emb, x, n_tokens, A_in, z_in, hidden_out, A_out, z_out, workspace,
+  return forward_impl(cfg, layers, mem_emb, x, 1, n_tokens, A_in, z_in, hidden_out, A_out, z_out, workspace,
+                      workspace_bytes, hip_stream, true);
+}
+
+size_t armt_workspace_bytes_batched(const armt_config* cfg, int32_t batch) {
+  Dims D;
+  if (check_config(cfg, &D) != ARMT_OK || batch < 1 || (int64_t)batch * D.L > 32768) return 0;
+  D.B = batch;
+  D.L = D.Lr * batch;
+  return carve(D).total;
+}
+
+armt_status armt_forward_sequential_batched(const armt_config* cfg, const armt_layer_weights* layers,
+                                            const void* mem_emb, const void* x, int32_t batch, int64_t n_tokens,
+                                            const float* A_in, const float* z_in, void* hidden_out, float* A_out,
+                                            float* z_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return forward_impl(cfg, layers, mem_emb, x, batch, n_tokens, A_in, z_in, hidden_out, A_out, z_out, workspace,
+                      workspace_bytes, hip_stream, false);
+}
+
+armt_status armt_forward_diagonal_batched(const armt_config* cfg, const armt_layer_weights* layers,
+                                          const void* mem_emb, const void* x, int32_t batch, int64_t n_tokens,
+                                          const float* A_in, const float* z_in, void* hidden_out, float* A_out,
+                                          float* z_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return forward_impl(cfg, layers, mem_emb, x, batch, n_tokens, A_in, z_in, hidden_out, A_out, z_out, workspace,
                       workspace_bytes, hip_stream, true);
 }
 
@@ -714,10 +754,10 @@ armt_status armt_assoc_update(const armt_config* cfg, int32_t g, const float* ym
   }
   ARMT_TRY(upload(c, tab, aux));
   if (D.bf16)
-    return step_assoc_update<bf16>(c.st, c.table(K_MKV), c.shape[K_MKV], c.aux, 0, g, empty_group, c.at<bf16>(c.o.Xb), md,
+    return step_assoc_update<bf16>(c.st, c.table(K_MKV), c.shape[K_MKV], c.aux, 0, g, empty_group, empty_group + 1, c.at<bf16>(c.o.Xb), md,
                                    D.m, D.d, D.dm, D.nu, D.assoc_eps, c.at<float>(c.o.KVm), c.at<float>(c.o.Fm),
                                    c.at<float>(c.o.Coef));
-  return step_assoc_update<float>(c.st, c.table(K_MKV), c.shape[K_MKV], c.aux, 0, g, empty_group, ym, md, D.m, D.d, D.dm,
+  return step_assoc_update<float>(c.st, c.table(K_MKV), c.shape[K_MKV], c.aux, 0, g, empty_group, empty_group + 1, ym, md, D.m, D.d, D.dm,
                                   D.nu, D.assoc_eps, c.at<float>(c.o.KVm), c.at<float>(c.o.Fm), c.at<float>(c.o.Coef));
 }
 

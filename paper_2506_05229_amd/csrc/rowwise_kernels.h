@@ -158,13 +158,15 @@ __global__ __launch_bounds__(128) void dpfp_read_kernel(const float* __restrict_
 }
 
 // Write side (Eq. 3-4) for the m memory rows of each cell: f_i = phi(k_i), beta_i = sigmoid(W_beta y_i),
-// gamma_i = 1 - z.f_i / (|f_i|^2 + eps), and 1 / (z.f_i + eps) (0 for an empty memory: v_bar = 0).
+// gamma_i = 1 - z.f_i / (|f_i|^2 + eps), and 1 / (z.f_i + eps) (0 for the cells [empty_lo, empty_hi), whose
+// memory is still empty: v_bar = 0).
 // KV: [L][m][dm + d] fp32 (k then v); Y0 + l * y_stride: the m memory rows [m][d] of layer l's output.
 // Fm: [L][m][Phi] fp32; Coef: [L][m][4] = {beta, gamma, 1/den, z.f}.  grid: (m, g), block: 128.
 template <typename T>
 __global__ __launch_bounds__(128) void memupd_prep_kernel(const float* __restrict__ KV, const T* __restrict__ Y0,
                                                           size_t y_stride, const LayerAux* __restrict__ aux, int first,
-                                                          int empty_layer, int m, int d, int dm, int nu, float eps,
+                                                          int empty_lo, int empty_hi, int m, int d, int dm, int nu,
+                                                          float eps,
                                                           float* __restrict__ Fm, float* __restrict__ Coef) {
   extern __shared__ float sm[];
   float* k = sm;
@@ -192,7 +194,7 @@ __global__ __launch_bounds__(128) void memupd_prep_kernel(const float* __restric
   if (threadIdx.x == 0) {
     Coef[mi * 4 + 0] = 1.0f / (1.0f + expf(-bl));
     Coef[mi * 4 + 1] = 1.0f - zf / (ff + eps);
-    Coef[mi * 4 + 2] = (l == empty_layer) ? 0.f : 1.0f / (zf + eps);
+    Coef[mi * 4 + 2] = (l >= empty_lo && l < empty_hi) ? 0.f : 1.0f / (zf + eps);
     Coef[mi * 4 + 3] = zf;
   }
 }
