@@ -49,6 +49,8 @@ def main():
     ap.add_argument("--workload", default="1b_128k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sequential", action="store_true")
+    ap.add_argument("--batch", type=int, default=1,
+                    help="B independent sequences per call (default 1 = the headline metric); tokens/s counts all B")
     ap.add_argument("--no-lm-head", action="store_true",
                     help="skip the extra timing of the token-level ends (embedding gather, final norm + head)")
     ap.add_argument("--cpu-segments", type=int, default=2)
@@ -71,13 +73,19 @@ def main():
     x = S.make_embeddings(shape, seed=0)
     t_gen = time.perf_counter() - t_gen
     model = P.Armt(shape, layers, mem_emb)
-    xd = model.embed(x)
-    out = model.forward(xd, diagonal=True)            # allocates the outputs once
+    B = max(1, args.batch)
+    if B == 1:
+        xd = model.embed(x)
+        fwd = model.forward
+    else:       # sequence b = the embeddings of seed b
+        xd = model.embed(np.stack([x] + [S.make_embeddings(shape, seed=b) for b in range(1, B)]))
+        fwd = model.forward_batched
+    out = fwd(xd, diagonal=True)            # allocates the outputs once
     torch.cuda.synchronize()
 
     def timed(diagonal, steps, warmup, profile=None):
         for _ in range(warmup):
-            model.forward(xd, diagonal=diagonal, out=out)
+            fwd(xd, diagonal=diagonal, out=out)
         torch.cuda.synchronize()
         if profile:
             P.profile_begin(profile, steps * (shape.n_layers + shape.n_segments))
@@ -85,7 +93,7 @@ def main():
         t0 = time.perf_counter()
         e0.record()
         for _ in range(steps):
-            model.forward(xd, diagonal=diagonal, out=out)
+            fwd(xd, diagonal=diagonal, out=out)
         e1.record()
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) / steps
@@ -93,19 +101,19 @@ def main():
         return e0.elapsed_time(e1) / steps, wall * 1e3, prof
 
     ms, wall_ms, prof = timed(True, args.steps, args.warmup, profile="gate_up")
-    n_tok = shape.n_tokens
-    total_flops = shape.flops_total()
+    n_tok = shape.n_tokens * B
+    total_flops = shape.flops_total() * B
     res = {
-        "metric": "ARMT forward tokens/s, Diagonal Batching, 131072 tokens" if n_tok == 131072
-                  else f"ARMT forward tokens/s, Diagonal Batching, {n_tok} tokens",
+        "metric": "ARMT forward tokens/s, Diagonal Batching, 131072 tokens" if (n_tok == 131072 and B == 1)
+                  else f"ARMT forward tokens/s, Diagonal Batching, {B} x {shape.n_tokens} tokens",
         "value": n_tok / (wall_ms / 1e3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall_ms, "gpu_ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": shape.dtype, "data": "synthetic",
         "config": {"workload": f"{shape.name}: {shape.n_layers} layers, d_model {shape.d_model}, "
                                f"{shape.n_heads}/{shape.n_kv_heads} heads x {shape.head_dim}, d_ff {shape.d_ff}, "
                                f"segment {shape.seg_len} + {shape.n_mem} memory tokens, d_mem {shape.d_mem}, "
-                               f"{shape.n_segments} segments, batch 1, N(0,0.02) weights, N(0,1) embeddings, seed 0",
-                   "cells": shape.n_layers * shape.n_segments,
+                               f"{shape.n_segments} segments, batch {B}, N(0,0.02) weights, N(0,1) embeddings, seed 0",
+                   "cells": shape.n_layers * shape.n_segments * B,
                    "diagonal_steps": shape.n_layers + shape.n_segments - 1,
                    "algorithmic_tflop": total_flops / 1e12},
         "mfma_fraction_end_to_end": total_flops / (ms / 1e3) / 1e12 / MFMA_PEAK_TFLOPS,
@@ -131,7 +139,7 @@ def main():
         sms, swall, _ = timed(False, max(1, min(args.steps, 2)), 0)
         res["sequential_tokens_per_s"] = n_tok / (swall / 1e3)
         res["speedup_vs_sequential"] = swall / wall_ms
-    if not args.no_lm_head:
+    if not args.no_lm_head and B == 1:
         # Token-level ends of Algorithm 1 (not part of `value`, which is the BASELINE metric on hidden states):
         # embedding gather for the whole sequence, final norm + LLaMA-3-sized head on the last segment and on
         # 16 segments, the latter extrapolated to all rows (the head's cost is linear in the rows).
@@ -172,7 +180,7 @@ def main():
         model.forward(xd[:shape.seg_len].contiguous(), diagonal=True, A_in=A_src, z_in=z_src)
         torch.cuda.synchronize()
         res["calibration_copy_bytes"] = int(A_src.numel() * 4)
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and B == 1:
         res["cpu_baseline"] = cpu_baseline(shape, layers, mem_emb, x, min(args.cpu_segments, shape.n_segments))
     res["input_generation_s"] = t_gen
     print(json.dumps(res))
