@@ -20,8 +20,8 @@ sys.path.insert(0, ROOT)
 MFMA_PEAK_TFLOPS = 2500.0          # MI355X dense bf16 matrix-core peak (published)
 # HBM bytes per cell of the gate/up GEMM at the 1B shape, from the two rocprofv3 --pmc runs summarised in
 # profiles/gate_up_gemm_1b_128k_hbm_traffic.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from the copy
-# calibration): (1.379 GB + 0.232 GB) / 13.6 cells per launch.  Algorithmic: 88.4 MB per cell.
-GATE_UP_HBM_BYTES_PER_CELL = {"1b": 118.5e6}
+# calibration): (1.383 GB + 0.232 GB) / 13.6 cells per launch.  Algorithmic: 88.4 MB per cell.
+GATE_UP_HBM_BYTES_PER_CELL = {"1b": 118.7e6}
 
 
 def cpu_baseline(shape, layers, mem_emb, x, n_seg):
