@@ -180,3 +180,35 @@ def test_token_end_entry_argument_errors(lib):
     bad.head_dim = 31
     assert lib.armt_lm_head_workspace_bytes(C.byref(bad), 4) == 0
     assert lib.armt_embed_tokens(C.byref(bad), fake, 10, fake, 4, fake, None) != 0
+
+
+def test_batched_workspace_and_argument_errors(lib):
+    shape = S.get_shape("tiny")
+    cfg = _cfg(shape)
+    n1 = lib.armt_workspace_bytes(C.byref(cfg))
+    lib.armt_workspace_bytes_batched.restype = C.c_size_t
+    assert lib.armt_workspace_bytes_batched(C.byref(cfg), 1) == n1
+    n3 = lib.armt_workspace_bytes_batched(C.byref(cfg), 3)
+    assert 2 * n1 < n3 <= 3 * n1 + 4096                       # per-cell scratch grows with the batch, tables do not shrink
+    assert lib.armt_workspace_bytes_batched(C.byref(cfg), 0) == 0
+    assert lib.armt_workspace_bytes_batched(C.byref(cfg), 32768) == 0        # batch * n_layers beyond a launch grid
+    layers = (__import__("paper_2506_05229_amd").ArmtLayerWeights * shape.n_layers)()
+    fake = 0x1000
+    args = lambda batch, ws_bytes: (C.byref(cfg), layers, fake, fake, batch, shape.seg_len, None, None, fake, fake, fake,
+                                    0x10000, ws_bytes, None)
+    assert lib.armt_forward_diagonal_batched(*args(0, n3)) == 2
+    assert lib.armt_forward_diagonal_batched(*args(3, n3)) == 1          # null weight pointers
+    for f in ("rms1", "wq", "wk", "wv", "wo", "rms2", "wgate", "wup", "wdown", "wm_q", "wm_k", "wm_v", "wm_b"):
+        for l in range(shape.n_layers):
+            setattr(layers[l], f, fake)
+    assert lib.armt_forward_diagonal_batched(*args(3, n3 - 1)) == 4
+    assert lib.armt_forward_sequential_batched(*args(3, n1)) == 4
+
+
+def test_microbench_needs_a_gpu_and_says_so(capsys):
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("this checks the behaviour without a GPU")
+    from paper_2506_05229_amd import microbench
+    assert microbench.main(["gemm", "--iters", "1"]) == 2
+    assert "GPU" in capsys.readouterr().err

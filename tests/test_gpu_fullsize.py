@@ -61,10 +61,10 @@ def test_1b_131072_tokens_bench_configuration():
 
 @pytest.mark.timeout(900)
 @pytest.mark.parametrize("name,n_seg_gpu", [("1b_128k_s512", 6), ("1b_128k_s2048", 3), ("3b_128k", 3),
-                                            ("1b_128k_s4096_m128", 3)])
+                                            ("1b_128k_s4096_m128", 3), ("160m_128k", 4)])
 def test_other_shapes_prefix_against_oracle(name, n_seg_gpu):
     """Segment sweep (512 / 2048 + 16 memory tokens), the 3B shape (head_dim 128, 3 query heads per KV head) and
-    the shape of the paper's timing tables (4096 + 128 memory tokens):
+    the shape of the paper's timing tables (4096 + 128 memory tokens), the 160M model (no head grouping):
     a few segments on the GPU, the first two checked against the oracle, diagonal == sequential."""
     shape = S.get_shape(name)
     model, layers, mem_emb = _model(shape)
