@@ -84,6 +84,10 @@ _3B = dict(n_layers=28, d_model=3072, n_heads=24, n_kv_heads=8, head_dim=128, d_
 _160M = dict(n_layers=12, d_model=768, n_heads=12, n_kv_heads=12, head_dim=64, d_ff=3072,
              seg_len=1024, n_mem=16, d_mem=64, dtype="bf16", **_MEM_SCALES)
 
+# LLaMA-3.1-8B: 32 layers of width 4096, 32 / 8 heads of 128, d_ff 14336 (the large model of the paper's tables)
+_8B = dict(n_layers=32, d_model=4096, n_heads=32, n_kv_heads=8, head_dim=128, d_ff=14336,
+           seg_len=1024, n_mem=16, d_mem=64, dtype="bf16", **_MEM_SCALES)
+
 CONFIGS = {
     # correctness-only fp32 case
     "tiny": ArmtShape("tiny", n_layers=4, d_model=128, n_heads=4, n_kv_heads=2, head_dim=32,
@@ -94,6 +98,7 @@ CONFIGS = {
     "1b_128k_s512": ArmtShape("1b_128k_s512", n_tokens=131072, **{**_1B, "seg_len": 512}),
     "1b_128k_s2048": ArmtShape("1b_128k_s2048", n_tokens=131072, **{**_1B, "seg_len": 2048}),
     "3b_128k": ArmtShape("3b_128k", n_tokens=131072, **_3B),
+    "8b_128k": ArmtShape("8b_128k", n_tokens=131072, **_8B),
     "160m_128k": ArmtShape("160m_128k", n_tokens=131072, **_160M),
     # the shape of the paper's timing tables: 4096-token segments with 128 memory tokens
     "1b_128k_s4096_m128": ArmtShape("1b_128k_s4096_m128", n_tokens=131072, **{**_1B, "seg_len": 4096, "n_mem": 128}),

@@ -85,3 +85,22 @@ def test_other_shapes_prefix_against_oracle(name, n_seg_gpu):
     eA, ez = rel_fro(A2.cpu().numpy(), oA), rel_fro(z2.cpu().numpy(), oz)
     print(f"{name}: memory state after 2 segments: rel A {eA:.3e}, rel z {ez:.3e}", flush=True)
     assert eA <= MEM_A_REL and ez <= MEM_Z_REL
+
+
+@pytest.mark.timeout(900)
+def test_8b_width_two_layers_against_oracle():
+    """The 8B shape's widths (d_model 4096, d_ff 14336, 32 / 8 heads of 128) on 2 of its 32 layers, so that the
+    oracle finishes in a minute or two: 3 segments on the GPU, the first two against the oracle."""
+    shape = S.get_shape("8b_128k").replace(n_layers=2)
+    model, layers, mem_emb = _model(shape)
+    x = S.make_embeddings(shape, seed=0, n_tokens=3 * shape.seg_len)
+    xd = model.embed(x)
+    hd, Ad, zd = model.forward(xd, diagonal=True)
+    hs, As, zs = model.forward(xd, diagonal=False)
+    torch.cuda.synchronize()
+    assert torch.equal(hs, hd) and torch.equal(As, Ad) and torch.equal(zs, zd)
+    k = 2 * shape.seg_len
+    oh, oA, oz = O.armt_forward_sequential(shape, layers, mem_emb, x[:k])
+    err = rel_fro(hd[:k].float().cpu().numpy(), oh)
+    print(f"8b width, 2 layers: rel. Frobenius error vs oracle on the first 2 segments {err:.3e}", flush=True)
+    assert err <= BF16_REL
