@@ -46,9 +46,10 @@ typedef enum { ARMT_F32 = 0, ARMT_BF16 = 1 } armt_dtype;   /* type of weights, e
  * followed by n_mem memory tokens (a cell has T = seg_len + n_mem rows, Eq. 2 "[H, M]"),
  * associative hidden size d_mem, feature map DPFP-nu of width Phi = 2 * dpfp_nu * d_mem
  * (Section 2.1: A in R^{d_model x 6 d_mem} for nu = 3).
- * Supported: n_heads * head_dim == d_model, n_heads % n_kv_heads == 0, head_dim even,
- * 1 <= dpfp_nu < 2 * d_mem; dtype BF16 additionally needs d_model, d_ff, head_dim, d_mem
- * multiples of 32, n_mem a multiple of 16 and head_dim in {64, 128} (ARMT_ERR_UNSUPPORTED otherwise). */
+ * Valid (else ARMT_ERR_SHAPE): all sizes >= 1, n_heads * head_dim == d_model, n_heads % n_kv_heads == 0,
+ * head_dim even, 1 <= dpfp_nu < 2 * d_mem.  Of the valid shapes this build has kernels for (else
+ * ARMT_ERR_UNSUPPORTED): Phi <= 512; dtype BF16 additionally needs d_model, d_ff and Phi multiples of 64, d_mem a
+ * multiple of 8, n_mem a multiple of 16, head_dim 64 or 128 and at most 8 query heads per KV head. */
 typedef struct {
   int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ff;
   int32_t seg_len, n_mem, d_mem, dpfp_nu;
