@@ -3,16 +3,22 @@
 //   C_g = A_g B_g^T for every group g of the launch; A_g [M, K] activations, B_g [N, K] the
 //   weights of the group's own layer (taken from a pointer table, never stacked), fp32
 //   accumulation in v_mfma_f32_32x32x16_bf16, epilogue fused (residual add, row scale,
-//   SwiGLU, bf16 copy).
+//   SwiGLU, bf16 copy and sums of squares for the next RMSNorm, rotary embedding and transposed
+//   V for the QKV projection).
 //
 // Tiling: one workgroup per BM x BN output tile, BK = 64.  Both operands are K-contiguous, so a
 // tile row is 128 bytes = eight 16-byte chunks; chunks are XOR-swizzled inside a row so that the
 // MFMA fragment reads (one row per lane, 16 bytes) spread over all LDS banks.  Tiles are double
-// buffered in LDS and filled by direct global-to-LDS loads (no staging registers): the copies of
-// k-tile i+1 are in flight while k-tile i is multiplied.
+// buffered in LDS (NS = 2 stages; more are possible for small tiles) and filled by direct
+// global-to-LDS loads (no staging registers): the copies of k-tile i+1 are in flight while k-tile i
+// is multiplied.  For regular shapes (template flag REG) the copies are addressed by a scalar base
+// and one lane offset per operand, so that issuing them needs no vector-ALU instruction.
 // The 1-D grid is laid out so that each XCD (workgroup id mod 8) owns a contiguous run of the
 // group-major tile sequence: with 16 groups every XCD streams the weights of 2 layers through its
 // own L2, and the M-tiles sharing a weight panel run back to back.
+// Template parameters of the kernel: BM x BN tile, WGM x WGN waves, REG (see above), EPI (GemmEpilogue),
+// TAIL (see below), NS (LDS stages).  The launcher picks the configuration from the shape and the
+// number of tiles of the launch (mfma_pick_config).
 #pragma once
 
 #include "common.h"
@@ -27,15 +33,14 @@ constexpr int MF_NUM_CONFIGS = 7;         // tile configurations of launch_gemm_
 // swizzle of the 16-byte chunk index inside a 128-byte tile row; depends on row bits 0..3 only
 __device__ __forceinline__ int mf_swz(int row) { return ((row >> 1) & 7) ^ ((row & 1) << 2); }
 
-
-// TAIL: the last M-tile of every group also owns the 16 rows that follow it (M = tiles_m * BM + 16).  With
-// T = seg_len + 16 memory rows and seg_len a multiple of BM this removes the nearly empty fifth tile a
-// 1040-row cell would otherwise need: the 16 memory rows ride along as one extra strip of 16x16x32 MFMAs.
 template <int N>
 __device__ __forceinline__ void mf_wait_vmcnt() {      // s_waitcnt vmcnt(N) only (N <= 63)
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
 }
 
+// TAIL: the last M-tile of every group also owns the 16 rows that follow it (M = tiles_m * BM + 16).  With
+// T = seg_len + 16 memory rows and seg_len a multiple of BM this removes the nearly empty fifth tile a
+// 1040-row cell would otherwise need: the 16 memory rows ride along as one extra strip of 16x16x32 MFMAs.
 template <int BM, int BN, int WGM, int WGN, bool REG, int EPI, bool TAIL, int NS>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGroup* __restrict__ table, int first,
                                                                   GemmShape s, int tiles_m, int tiles_n,
