@@ -53,7 +53,7 @@ def main():
                     help="B independent sequences per call (default 1 = the headline metric); tokens/s counts all B")
     ap.add_argument("--no-lm-head", action="store_true",
                     help="skip the extra timing of the token-level ends (embedding gather, final norm + head)")
-    ap.add_argument("--cpu-segments", type=int, default=2)
+    ap.add_argument("--cpu-segments", type=int, default=4)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of known size (the memory-state carry-in copy), so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled against it")
