@@ -47,14 +47,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
                                                                   int total_tiles) {
   constexpr int NW = WGM * WGN;
   constexpr int WROWS = BM / WGM, WCOLS = BN / WGN;       // wave tile
-  constexpr int TM = WROWS / 32, TN = WCOLS / 32;         // 32x32 MFMA tiles per wave
+  constexpr int TM = WROWS / 16, TN = WCOLS / 16;         // 16x16 MFMA tiles per wave
   constexpr int A_DMA = BM / 8 / NW, B_DMA = BN / 8 / NW; // 8-row (1 KB) slabs each wave copies per k-tile
   constexpr int A_ROWS = TAIL ? BM + 16 : BM;
   constexpr int A_BYTES = A_ROWS * MF_ROW_BYTES, B_BYTES = BN * MF_ROW_BYTES;
   constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;   // output columns per tile
   static_assert(BM % (WGM * 32) == 0 && BN % (WGN * 32) == 0, "wave tile must be a multiple of 32x32");
+  static_assert(EPI != EPI_SWIGLU || WCOLS % 64 == 0, "SwiGLU: a wave owns whole gate/up pairs of 32-row weight blocks");
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must divide into 8-row slabs per wave");
-  static_assert(EPI != EPI_SWIGLU || TN % 2 == 0, "SwiGLU pairs gate/up 32-column tiles inside a wave");
   static_assert(!TAIL || (BN <= NW * 32 && NW >= 2), "the tail strip gives each of the first BN / 32 waves two 16-column tiles");
   constexpr int TAIL_WAVES = BN / 32;
 
@@ -175,28 +175,28 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
     }
   };
 
-  // ---- MFMA fragment addresses: lane reads tile row (lane % 32) of each 32-row block, chunk 2*ks + lane/32
-  const int fl = mf_swz(lane & 31), half = lane >> 5;
-  int koff[4];
+  // ---- MFMA fragment addresses (v_mfma_f32_16x16x32_bf16: under random operands this instruction sustains
+  // 1.9 PFLOP/s on the chip against 1.35 for the 32x32x16 form, which draws more power per flop; measured with
+  // register-only loops): lane reads tile row (lane % 16) of each 16-row block, 16-byte chunk 4 * ks2 + lane / 16
+  // of the 128-byte row; a 16x16 result tile has lane = column lane % 16 and registers = rows 4 * (lane / 16) + r.
+  const int t_sw = mf_swz(lane & 15), t_q = lane >> 4;
+  int koff[2];
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) koff[ks] = ((2 * ks + half) ^ fl) << 4;
-  const int a_frag = (wm * WROWS + (lane & 31)) * MF_ROW_BYTES;
-  const int b_frag = (wn * WCOLS + (lane & 31)) * MF_ROW_BYTES;
-  // tail strip (16x16x32 MFMA): lane reads row (lane % 16), chunk 4*ks2 + lane/16.  Wave w owns two 16-column
+  for (int ks2 = 0; ks2 < 2; ++ks2) koff[ks2] = ((4 * ks2 + t_q) ^ t_sw) << 4;
+  const int a_frag = (wm * WROWS + (lane & 15)) * MF_ROW_BYTES;
+  const int b_frag = (wn * WCOLS + (lane & 15)) * MF_ROW_BYTES;
+  // tail strip: the same instruction on the 16 extra rows.  Wave w owns two 16-column
   // tiles whose B rows lie 32 apart, so that for SwiGLU tile 0 is the gate and tile 1 the up projection of the
   // same 16 output columns: B tile rows ((w / 2) * 2 + t) * 32 + (w % 2) * 16 + lane % 16.
-  const int t_sw = mf_swz(lane & 15), t_q = lane >> 4;
   const int t_a = (BM + (lane & 15)) * MF_ROW_BYTES;
   const int t_brow = ((wave >> 1) * 2) * 32 + (wave & 1) * 16 + (lane & 15);
   const int t_b = t_brow * MF_ROW_BYTES;
 
-  f32x16 acc[TM][TN];
+  f32x4 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
   f32x4 tacc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 
   {
@@ -222,22 +222,22 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       const unsigned char* As = smem + cur * A_BYTES;
       const unsigned char* Bs = smem + NS * A_BYTES + cur * B_BYTES;
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
+      for (int ks2 = 0; ks2 < 2; ++ks2) {
         bf16x8 af[TM], bfr[TN];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8*)(As + a_frag + i * 32 * MF_ROW_BYTES + koff[ks]);
+        for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8*)(As + a_frag + i * 16 * MF_ROW_BYTES + koff[ks2]);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8*)(Bs + b_frag + j * 32 * MF_ROW_BYTES + koff[ks]);
+        for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8*)(Bs + b_frag + j * 16 * MF_ROW_BYTES + koff[ks2]);
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
       }
       if (TAIL && tail) {
 #pragma unroll
         for (int ks2 = 0; ks2 < 2; ++ks2) {
-          const int ko = ((4 * ks2 + t_q) ^ t_sw) << 4;
+          const int ko = koff[ks2];
           const bf16x8 ta = *(const bf16x8*)(As + t_a + ko);
 #pragma unroll
           for (int t = 0; t < 2; ++t) {
@@ -258,14 +258,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
     }
   }
 
-  // ---- epilogue, staged through LDS so that global memory sees whole rows: a 32x32 result tile has lane =
-  // column (lane % 32) and registers = rows 8*(r/4) + 4*(lane/32) + r%4, which written directly would touch
-  // global memory in 128-byte pieces.  Instead, in TM * 2 passes every wave drops 16 rows of its tile into a
-  // fp32 staging tile [WGM * 16][BN_OUT + 8] (the +8 keeps the two half-waves on different banks), and all
-  // threads then walk the staging tile row-major, C4 = BN_OUT / 4 lanes per row: 16-byte accesses, full rows
+  // ---- epilogue, staged through LDS so that global memory sees whole rows: a 16x16 result tile has lane =
+  // column (lane % 16) and registers = rows 4 * (lane / 16) + r, which written directly would touch global
+  // memory in 32- or 64-byte pieces.  Instead, in TM passes every wave drops one 16-row block of its tile into
+  // a fp32 staging tile [WGM * 16][BN_OUT + 4] (the +4 puts the four row groups of a wave on different banks),
+  // and all threads then walk the staging tile row-major, C4 = BN_OUT / 4 lanes per row: 16-byte accesses, full rows
   // of R, C, C2.  The tail strip goes through the same path as one more pass of 16 rows.
   // The tile buffers are free here: the main loop ended with a barrier.
-  constexpr int SLD = BN_OUT + 8, SR = WGM * 16, C4 = BN_OUT / 4, NT = NW * 64;
+  constexpr int SLD = BN_OUT + 4, SR = WGM * 16, C4 = BN_OUT / 4, NT = NW * 64;
   static_assert(SR * SLD * 4 <= NS * (A_BYTES + B_BYTES), "staging tile must fit in the tile buffers");
   static_assert(C4 == 16 || C4 == 32 || C4 == 64, "a staged row is handled by 16, 32 or 64 consecutive lanes");
   float* stg = (float*)smem;
@@ -369,26 +369,29 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       *(bf16x8*)(vt + (size_t)col * s.ldc2 + m) = v;
     }
   };
-  const int col_in = lane & 31;
+  const int col_in = lane & 15;
 #pragma unroll
-  for (int pass = 0; pass < TM * 2; ++pass) {
-    const int i = pass >> 1, rh = pass & 1;
+  for (int pass = 0; pass < TM; ++pass) {
+    const int i = pass;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const int r = rh * 8 + q, row16 = 8 * (q >> 2) + 4 * half + (q & 3);
+    for (int r = 0; r < 4; ++r) {
+      const int row16 = 4 * t_q + r;
       float* dst = stg + (wm * 16 + row16) * SLD + col_in;
       if (EPI == EPI_SWIGLU) {
-        const float rs = row_scale(m0 + wm * WROWS + i * 32 + rh * 16 + row16);
+        // the wave's weight rows come in 32-row blocks, gate / up alternating: tiles 4q + h (gate) and 4q + 2 + h
+        // (up), h = 0, 1, give output columns (wn * WCOLS / 64 + q) * 32 + h * 16 + lane % 16
+        const float rs = row_scale(m0 + wm * WROWS + i * 16 + row16);
 #pragma unroll
-        for (int j = 0; j < TN; j += 2)
-          dst[((wn * TN + j) >> 1) * 32] = silu_mul(rs * acc[i][j][r], rs * acc[i][j + 1][r]);
+        for (int j = 0; j < TN; ++j)
+          if ((j & 2) == 0)
+            dst[(wn * (WCOLS / 64) + (j >> 2)) * 32 + (j & 1) * 16] = silu_mul(rs * acc[i][j][r], rs * acc[i][j + 2][r]);
       } else {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) dst[wn * WCOLS + j * 32] = acc[i][j][r];
+        for (int j = 0; j < TN; ++j) dst[wn * WCOLS + j * 16] = acc[i][j][r];
       }
     }
     __syncthreads();
-    auto pass_row = [&](int sr) { return m0 + (sr >> 4) * WROWS + i * 32 + rh * 16 + (sr & 15); };
+    auto pass_row = [&](int sr) { return m0 + (sr >> 4) * WROWS + i * 16 + (sr & 15); };
     if (vt_tile) drain_vt(SR, pass_row);
     else drain(SR, pass_row);
     __syncthreads();
