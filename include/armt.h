@@ -131,6 +131,48 @@ armt_status armt_forward_diagonal_batched(const armt_config *cfg, const armt_lay
                                           void *hidden_out, float *A_out, float *z_out,
                                           void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* ---- training: forward with a tape, and the backward pass (the paper's appendix on implementation notes states that
+ * a backward pass of the diagonal schedule exists; it computes the gradient of the forward of Section 2.1, Eq. 2-6).
+ *
+ * armt_forward_train is armt_forward_diagonal (diagonal != 0) or armt_forward_sequential (diagonal == 0) for one
+ * sequence, and in addition records in `tape`, per (segment, layer) cell, the cell's input [T][d_model] and the layer's
+ * A, z from before the cell's update (fp32; armt_tape_bytes(cfg, n_tokens) bytes, 256-byte aligned, device memory
+ * owned by the caller; 0 = configuration rejected).  Same results as the inference calls.
+ *
+ * armt_backward consumes the tape: for J = <hidden_out, d_hidden> + <A_out, dA_out> + <z_out, dz_out> it ADDS dJ/dW to
+ * the caller's fp32 gradient buffers (`grads[l]` mirrors `layers[l]`: one device pointer per weight, same shapes; the
+ * caller zeroes them, or keeps accumulating over calls), ADDS the gradient of the memory-token embeddings to d_mem_emb
+ * [n_mem][d_model], and writes (not adds) dx [n_tokens][d_model] (may be NULL), dA_in [L][d_model][Phi] and dz_in
+ * [L][Phi] (both or neither NULL).  All gradients are fp32; d_hidden [n_tokens][d_model] has the activation type;
+ * dA_out, dz_out may both be NULL (= zero).  carry_in != 0 iff the forward call was given A_in, z_in (otherwise the
+ * cells of segment 0 met an empty memory, and dA_in, dz_in are meaningless).  The cells are visited in the reverse of
+ * the diagonal order (diagonal != 0: one group per anti-diagonal, grouped GEMMs as in the forward pass) or of the
+ * sequential order; each step restores the inputs of its cells from the tape, recomputes their forward and runs the
+ * backward kernels, so no activation other than the tape outlives a step.  `layers` must be the weights of the
+ * forward call.  workspace: armt_backward_workspace_bytes(cfg) bytes, 256-byte aligned.
+ * Supported here: n_mem <= 16, head_dim <= 128, and the limits of the forward calls; anything else is rejected with
+ * ARMT_ERR_UNSUPPORTED (the size queries return 0).  Two cells of one layer never run in the same step, so the
+ * accumulation into a layer's gradient buffers has a fixed order and the result is deterministic. */
+typedef struct {
+  float *rms1, *wq, *wk, *wv, *wo;
+  float *rms2, *wgate, *wup, *wdown;
+  float *wm_q, *wm_k, *wm_v, *wm_b;
+} armt_layer_grads;
+size_t armt_tape_bytes(const armt_config *cfg, int64_t n_tokens);
+size_t armt_backward_workspace_bytes(const armt_config *cfg);
+armt_status armt_forward_train(const armt_config *cfg, const armt_layer_weights *layers,
+                               const void *mem_emb, const void *x, int64_t n_tokens,
+                               const float *A_in, const float *z_in,
+                               void *hidden_out, float *A_out, float *z_out,
+                               void *tape, size_t tape_bytes,
+                               void *workspace, size_t workspace_bytes, void *hip_stream, int32_t diagonal);
+armt_status armt_backward(const armt_config *cfg, const armt_layer_weights *layers, int64_t n_tokens,
+                          const void *tape, size_t tape_bytes, int32_t carry_in,
+                          const void *d_hidden, const float *dA_out, const float *dz_out,
+                          const armt_layer_grads *grads /* [host] array of n_layers */,
+                          float *d_mem_emb, float *dx, float *dA_in, float *dz_in,
+                          void *workspace, size_t workspace_bytes, void *hip_stream, int32_t diagonal);
+
 /* Anti-diagonal schedule (Lemma 3.1), host only: for step t of an L-layer model over N segments,
  * *l_lo .. *l_hi (inclusive) are the live layers; layer l runs segment t - l.  Returns the group
  * size, or 0 (and leaves the outputs alone) if t is outside 0 .. L + N - 2 or L, N < 1. */

@@ -37,6 +37,10 @@ class ArmtLayerWeights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in LAYER_FIELDS]
 
 
+class ArmtLayerGrads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in LAYER_FIELDS]
+
+
 def library_path() -> str:
     return os.environ.get("ARMT_HIP_LIBRARY", os.path.join(HERE, "libarmt_hip.so"))
 
@@ -66,6 +70,16 @@ def load_library():
         getattr(lib, name).restype = C.c_int
     lib.armt_workspace_bytes_batched.argtypes = [C.POINTER(ArmtConfig), i32]
     lib.armt_workspace_bytes_batched.restype = sz
+    lib.armt_tape_bytes.argtypes = [C.POINTER(ArmtConfig), i64]
+    lib.armt_tape_bytes.restype = sz
+    lib.armt_backward_workspace_bytes.argtypes = [C.POINTER(ArmtConfig)]
+    lib.armt_backward_workspace_bytes.restype = sz
+    lib.armt_forward_train.argtypes = [C.POINTER(ArmtConfig), C.POINTER(ArmtLayerWeights), vp, vp, i64, vp, vp, vp, vp, vp,
+                                       vp, sz, vp, sz, vp, i32]
+    lib.armt_forward_train.restype = C.c_int
+    lib.armt_backward.argtypes = [C.POINTER(ArmtConfig), C.POINTER(ArmtLayerWeights), i64, vp, sz, i32, vp, vp, vp,
+                                  C.POINTER(ArmtLayerGrads), vp, vp, vp, vp, vp, sz, vp, i32]
+    lib.armt_backward.restype = C.c_int
     lib.armt_diagonal_group.argtypes = [i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
     lib.armt_diagonal_group.restype = i32
     pp = C.POINTER(C.c_void_p)
@@ -185,6 +199,59 @@ class Armt:
                   _ptr(hidden), _ptr(A), _ptr(z), _ptr(self.workspace), self.workspace.numel(), C.c_void_p(stream))
         _check(self.lib, code)
         return hidden, A, z
+
+    # ------------------------------------------------------------ training
+    def forward_train(self, x, diagonal=True, A_in=None, z_in=None):
+        """Forward pass that also records the tape the backward pass needs.  Returns (hidden, A, z, tape)."""
+        torch, s = self.torch, self.shape
+        assert x.is_cuda and x.dtype == self.act_dtype and x.is_contiguous()
+        n_tokens = x.shape[0]
+        nbytes = self.lib.armt_tape_bytes(C.byref(self.cfg), n_tokens)
+        if nbytes == 0:
+            raise ArmtError(6, "configuration or length rejected by armt_tape_bytes")
+        tape = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        hidden = torch.empty((n_tokens, s.d_model), dtype=self.act_dtype, device=self.device)
+        A = torch.empty((s.n_layers, s.d_model, s.phi), dtype=torch.float32, device=self.device)
+        z = torch.empty((s.n_layers, s.phi), dtype=torch.float32, device=self.device)
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        code = self.lib.armt_forward_train(C.byref(self.cfg), self.c_layers, _ptr(self.mem_emb), _ptr(x), n_tokens,
+                                           _ptr(A_in), _ptr(z_in), _ptr(hidden), _ptr(A), _ptr(z), _ptr(tape), nbytes,
+                                           _ptr(self.workspace), self.workspace_bytes, C.c_void_p(stream),
+                                           1 if diagonal else 0)
+        _check(self.lib, code)
+        return hidden, A, z, tape
+
+    def backward(self, tape, n_tokens, d_hidden, dA_out=None, dz_out=None, carry_in=False, diagonal=True,
+                 want_dx=True, grads=None):
+        """Gradients of <hidden, d_hidden> + <A_out, dA_out> + <z_out, dz_out>.  Returns a dict: "layers" (list of
+        dicts of fp32 tensors, accumulated into `grads["layers"]` if given), "mem_emb", "x", "A_in", "z_in"."""
+        torch, s = self.torch, self.shape
+        f32 = dict(dtype=torch.float32, device=self.device)
+        assert d_hidden.is_cuda and d_hidden.dtype == self.act_dtype and d_hidden.is_contiguous()
+        if grads is None:
+            grads = {"layers": [{f: torch.zeros(tuple(lw[f].shape), **f32) for f in LAYER_FIELDS} for lw in self.layers],
+                     "mem_emb": torch.zeros(tuple(self.mem_emb.shape), **f32)}
+        c_grads = (ArmtLayerGrads * s.n_layers)()
+        for l, g in enumerate(grads["layers"]):
+            for f in LAYER_FIELDS:
+                setattr(c_grads[l], f, g[f].data_ptr())
+        dx = torch.empty((n_tokens, s.d_model), **f32) if want_dx else None
+        dA_in = torch.empty((s.n_layers, s.d_model, s.phi), **f32) if carry_in else None
+        dz_in = torch.empty((s.n_layers, s.phi), **f32) if carry_in else None
+        need = self.lib.armt_backward_workspace_bytes(C.byref(self.cfg))
+        if need == 0:
+            raise ArmtError(6, "configuration rejected by armt_backward_workspace_bytes")
+        if getattr(self, "bwd_workspace", None) is None or self.bwd_workspace.numel() < need:
+            self.bwd_workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        code = self.lib.armt_backward(C.byref(self.cfg), self.c_layers, n_tokens, _ptr(tape), tape.numel(),
+                                      1 if carry_in else 0, _ptr(d_hidden), _ptr(dA_out), _ptr(dz_out), c_grads,
+                                      _ptr(grads["mem_emb"]), _ptr(dx), _ptr(dA_in), _ptr(dz_in),
+                                      _ptr(self.bwd_workspace), self.bwd_workspace.numel(), C.c_void_p(stream),
+                                      1 if diagonal else 0)
+        _check(self.lib, code)
+        grads.update({"x": dx, "A_in": dA_in, "z_in": dz_in})
+        return grads
 
 
 # ---------------------------------------------------------------- single steps (tests, micro-benchmarks)

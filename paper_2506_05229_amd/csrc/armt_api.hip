@@ -12,6 +12,7 @@
 
 #include "attention_generic.h"
 #include "attention_mfma.h"
+#include "backward_kernels.h"
 #include "common.h"
 #include "gemm_generic.h"
 #include "gemm_mfma.h"
@@ -137,6 +138,8 @@ struct Ctx {
   bool fused_rope;           // bf16 MFMA path: rotary embedding applied by the QKV GEMM epilogue
   bool fused_vt;             // ... which also writes V transposed
   int ssq_parts;             // partial sums of squares per row written by the GEMMs that produce a normalised row
+  float* tape = nullptr;     // training forward: per-cell records of what the backward pass cannot recompute
+  size_t rec_floats = 0;     // floats per record
   template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
   const GemmGroup* table(int kind) const { return tables + (size_t)kind * D.L; }
 };
@@ -374,6 +377,17 @@ armt_status run_group(const Ctx& c, int lo, int hi, int read_hi, int empty_layer
                               c.at<float>(c.o.Coef));
 }
 
+// Training forward: record the inputs of the cells of layers [lo, hi] (cell l belongs to segment t - l).
+armt_status save_tape(const Ctx& c, int lo, int hi, int t) {
+  if (!c.tape) return ARMT_OK;
+  const Dims& D = c.D;
+  const size_t nx = (size_t)D.T * D.d, nA = (size_t)D.d * D.Phi, nz = D.Phi;
+  tape_kernel<<<dim3(128, hi - lo + 1), 256, 0, c.st>>>(c.tape, c.rec_floats, c.at<float>(c.o.X), nx, c.aux, nullptr, nullptr, lo, t,
+                                                      D.Lr, nx, nA, nz, 1);
+  HIP_TRY(hipGetLastError());
+  return ARMT_OK;
+}
+
 template <typename T>
 armt_status forward_typed(Ctx& c, const void* mem_emb, const void* x, int64_t N, bool carry_in, void* hidden_out,
                           bool diagonal) {
@@ -412,7 +426,10 @@ armt_status forward_typed(Ctx& c, const void* mem_emb, const void* x, int64_t N,
     for (int64_t s = 0; s < N; ++s) {
       ARMT_TRY(ingest(s));
       const bool empty = (s == 0 && !carry_in);
-      for (int l = 0; l < L; ++l) ARMT_TRY(run_group<T>(c, l, l, empty ? l - 1 : l, empty ? l : -1));
+      for (int l = 0; l < L; ++l) {
+        ARMT_TRY(save_tape(c, l, l, (int)s + l));
+        ARMT_TRY(run_group<T>(c, l, l, empty ? l - 1 : l, empty ? l : -1));
+      }
       ARMT_TRY(emit(s));
     }
   } else {
@@ -423,6 +440,7 @@ armt_status forward_typed(Ctx& c, const void* mem_emb, const void* x, int64_t N,
       if (t < N) ARMT_TRY(ingest(t));
       // only the cell of segment 0 (layer t, while t < L) can meet an empty memory
       const bool top_empty = (!carry_in && t < L);
+      ARMT_TRY(save_tape(c, lo, hi, (int)t));
       ARMT_TRY(run_group<T>(c, lo, hi, top_empty ? hi - 1 : hi, top_empty ? hi : -1));
       if (hi == L - 1) ARMT_TRY(emit(t - (L - 1)));
     }
@@ -432,8 +450,11 @@ armt_status forward_typed(Ctx& c, const void* mem_emb, const void* x, int64_t N,
 
 armt_status forward_impl(const armt_config* cfg, const armt_layer_weights* layers, const void* mem_emb, const void* x,
                          int32_t batch, int64_t n_tokens, const float* A_in, const float* z_in, void* hidden_out, float* A_out,
-                         float* z_out, void* workspace, size_t workspace_bytes, void* hip_stream, bool diagonal) {
+                         float* z_out, void* workspace, size_t workspace_bytes, void* hip_stream, bool diagonal,
+                         float* tape = nullptr, size_t rec_floats = 0) {
   Ctx c;
+  c.tape = tape;
+  c.rec_floats = rec_floats;
   ARMT_TRY(check_config(cfg, &c.D));
   const Dims& D = c.D;
   if (batch < 1 || (int64_t)batch * D.L > 32768) return ARMT_ERR_SHAPE;      // cells of a step index a launch grid
@@ -837,3 +858,5 @@ const char* armt_status_str(armt_status s) {
 const char* armt_last_hip_error(void) { return g_hip_error.c_str(); }
 
 }  // extern "C"
+
+#include "backward_host.h"

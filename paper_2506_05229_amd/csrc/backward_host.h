@@ -1,0 +1,608 @@
+// Host side of the ARMT backward pass (included at the end of armt_api.hip: it uses that file's Ctx-less helpers,
+// the grouped GEMM dispatcher and the forward's step functions).
+//
+// The training forward (armt_forward_train) is the inference forward plus a tape: per (segment, layer) cell the cell
+// input and the layer's memory state from before the cell's update.  The backward pass (armt_backward) walks the cells
+// in the reverse of the forward order (anti-diagonals t = L + N - 2 .. 0, or segment by segment, layer by layer): for
+// the cells of a step it restores their inputs from the tape, recomputes the forward of these cells keeping every
+// intermediate, and runs the backward kernels.  The gradient of the residual stream travels through slots exactly
+// like the activations of the forward pass, in the opposite direction: the input gradient of cell l + 1 is the
+// output gradient of cell l of the next (earlier) step; the gradients of A and z of a layer travel from segment to
+// segment in place.
+#pragma once
+
+namespace {
+
+inline int round64(int v) { return (v + 63) / 64 * 64; }
+
+enum TKind {
+  // forward recomputation
+  TK_MQ = 0, TK_READ, TK_QKV, TK_O, TK_GU, TK_DOWN, TK_MKV,
+  // gradients of activations: dY W
+  TK_DYM, TK_DU, TK_DN2, TK_DATT, TK_DN1, TK_DF, TK_DXQ,
+  // gradients of weights (and of A): dY^T X, accumulated in fp32
+  TK_WD, TK_WG, TK_WU, TK_WO, TK_WQ, TK_WK, TK_WV, TK_DA, TK_WMQ, TK_WMK, TK_WMV,
+  TK_COUNT
+};
+
+struct TrainLayout {
+  size_t Xin, X1, Xb, N1, N2, RStd1, RStd2, QKV, Vt, Att, Hres, GU, Uff, Yf, Yb, Qm, Fphi, RDen, KVm, Fm, Coef, Rope;
+  size_t Aw, zw, A16w, ATr;
+  size_t DX, DYb, DU, DN, DH, DHb, DAtt, DQKV, LSE, Dv, DNum, DF, DDen, DQr, DKV, DV, Part, DB, DZF, DA, DZ;
+  size_t TA, TB, TmA, TmB;
+  size_t WdT, WguT, WoT, WqkvT, WmqT, WmkvT;
+  size_t Ptrs, Tables, Aux, total;
+  int Tp, mp, dmP, Kmkv, nblk;
+  size_t ta_rows, tb_rows;
+};
+
+TrainLayout carve_train(const Dims& D) {
+  TrainLayout o;
+  size_t p = 0;
+  auto take = [&](size_t bytes) { size_t at = p; p = align_up(p + bytes); return at; };
+  const size_t L = D.L, T = D.T, d = D.d, e = D.esz, F = D.F, Hd = (size_t)D.H * D.dh;
+  o.Tp = round64(D.T); o.mp = round64(D.m); o.dmP = round64(D.dm); o.Kmkv = round64(D.dm + D.d);
+  o.nblk = (D.d + UB_ROWS - 1) / UB_ROWS;
+  o.Xin = take(L * T * d * 4);
+  o.X1 = take(L * T * d * 4);
+  o.Xb = take(D.bf16 ? L * T * d * 2 : 0);
+  o.N1 = take(L * T * d * e);
+  o.N2 = take(L * T * d * e);
+  o.RStd1 = take(L * T * 4);
+  o.RStd2 = take(L * T * 4);
+  o.QKV = take(L * T * D.Nqkv * e);
+  o.Vt = take(D.bf16 ? attention_vt_bytes(D.L, D.T, D.Hkv, D.dh) : 0);
+  o.Att = take(L * T * Hd * e);
+  o.Hres = take(L * T * d * 4);
+  o.GU = take(L * T * 2 * F * e);
+  o.Uff = take(L * T * F * e);
+  o.Yf = take(L * T * d * 4);
+  o.Yb = take(D.bf16 ? L * T * d * 2 : 0);
+  o.Qm = take(L * T * D.dm * 4);
+  o.Fphi = take(L * T * D.Phi * e);
+  o.RDen = take(L * T * 4);
+  o.KVm = take(L * D.m * (size_t)(D.dm + D.d) * 4);
+  o.Fm = take(L * D.m * (size_t)D.Phi * 4);
+  o.Coef = take(L * D.m * 4 * 4);
+  o.Rope = take(T * (D.dh / 2) * 2 * 4);
+  o.Aw = take(L * d * D.Phi * 4);
+  o.zw = take(L * (size_t)D.Phi * 4);
+  o.A16w = take(D.bf16 ? L * d * D.Phi * 2 : 0);
+  o.ATr = take(L * d * D.Phi * e);
+  o.DX = take((L + 1) * T * d * 4);
+  o.DYb = take(L * T * d * e);
+  o.DU = take(L * T * F * e);
+  o.DN = take(L * T * d * e);
+  o.DH = take(L * T * d * 4);
+  o.DHb = take(L * T * d * e);
+  o.DAtt = take(L * T * Hd * e);
+  o.DQKV = take(L * T * D.Nqkv * e);
+  o.LSE = take(L * D.H * T * 4);
+  o.Dv = take(L * D.H * T * 4);
+  o.DNum = take(L * T * d * e);
+  o.DF = take(L * T * D.Phi * 4);
+  o.DDen = take(L * T * 4);
+  o.DQr = take(L * T * o.dmP * e);
+  o.DKV = take(L * D.m * (size_t)o.Kmkv * e);
+  o.DV = take(L * D.m * d * 4);
+  o.Part = take(L * o.nblk * D.m * (size_t)(D.Phi + 2) * 4);
+  o.DB = take(L * D.m * 4);
+  o.DZF = take(L * D.m * 4);
+  o.DA = take(L * d * D.Phi * 4);
+  o.DZ = take(L * (size_t)D.Phi * 4);
+  o.ta_rows = std::max(std::max((size_t)2 * F, (size_t)D.Nqkv), std::max(d, (size_t)D.dm));
+  o.tb_rows = std::max(std::max(F, d), std::max(Hd, (size_t)D.Phi));
+  o.TA = take(L * o.ta_rows * o.Tp * e);
+  o.TB = take(L * o.tb_rows * o.Tp * e);
+  o.TmA = take(L * (size_t)(D.dm + D.d) * o.mp * e);
+  o.TmB = take(L * d * o.mp * e);
+  o.WdT = take(L * F * d * e);
+  o.WguT = take(L * d * 2 * F * e);
+  o.WoT = take(L * Hd * d * e);
+  o.WqkvT = take(L * d * D.Nqkv * e);
+  o.WmqT = take(L * d * o.dmP * e);
+  o.WmkvT = take(L * d * o.Kmkv * e);
+  o.Ptrs = take(3 * L * sizeof(float*));
+  o.Tables = take((size_t)TK_COUNT * L * sizeof(GemmGroup));
+  o.Aux = take(L * sizeof(LayerAux));
+  o.total = p;
+  return o;
+}
+
+size_t tape_record_floats(const Dims& D) {
+  const size_t n = (size_t)D.T * D.d + (size_t)D.d * D.Phi + D.Phi;
+  return (n + 63) / 64 * 64;
+}
+
+armt_status check_backward_config(const armt_config* cfg, Dims* D) {
+  ARMT_TRY(check_config(cfg, D));
+  // the delta-rule backward keeps the partial feature gradients of all memory tokens in registers,
+  // the attention backward two head-dimension columns per lane
+  if (D->m > UB_M || D->dh > 128) return ARMT_ERR_UNSUPPORTED;
+  if (((size_t)D->m * D->Phi + (size_t)D->m * (D->Phi + 2)) * 4 > 64000) return ARMT_ERR_UNSUPPORTED;
+  return ARMT_OK;
+}
+
+struct BCtx {
+  Dims D;
+  TrainLayout o;
+  char* ws;
+  hipStream_t st;
+  const GemmGroup* tables;
+  const LayerAux* aux;
+  float* const* dg1; float* const* dg2; float* const* dwb;     // device tables of per-layer gradient pointers
+  GemmShape shape[TK_COUNT];
+  template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
+  const GemmGroup* table(int kind) const { return tables + (size_t)kind * D.L; }
+};
+
+void fill_train_shapes(BCtx& c) {
+  const Dims& D = c.D;
+  const TrainLayout& o = c.o;
+  const int Hd = D.H * D.dh, Hkd = D.Hkv * D.dh;
+  auto set = [&](int k, int M, int N, int K, int lda, int ldc, int epi, int n0 = -1, int n1 = 0) {
+    GemmShape s;
+    s.M = M; s.N = N; s.K = K; s.lda = lda; s.ldc = ldc; s.ldc2 = 0; s.ldr = ldc; s.n0 = n0 < 0 ? N : n0; s.n1 = n1; s.epi = epi;
+    s.tag = -1; s.dbg = 0;
+    c.shape[k] = s;
+  };
+  set(TK_MQ, D.T, D.dm, D.d, D.d, D.dm, EPI_STORE_F32);
+  set(TK_READ, D.T, D.d, D.Phi, D.Phi, D.d, EPI_RESID_F32);
+  set(TK_QKV, D.T, D.Nqkv, D.d, D.d, D.Nqkv, EPI_STORE_ACT, Hd, Hkd);
+  set(TK_O, D.T, D.d, Hd, Hd, D.d, EPI_RESID_F32);
+  set(TK_GU, D.T, 2 * D.F, D.d, D.d, 2 * D.F, EPI_STORE_ACT, D.F, D.F);
+  set(TK_DOWN, D.T, D.d, D.F, D.F, D.d, EPI_RESID_F32);
+  if (D.bf16) c.shape[TK_DOWN].ldc2 = D.d;
+  set(TK_MKV, D.m, D.dm + D.d, D.d, D.d, D.dm + D.d, EPI_STORE_F32, D.dm, D.d);
+  set(TK_DYM, D.m, D.d, o.Kmkv, o.Kmkv, D.d, EPI_RESID_F32);
+  set(TK_DU, D.T, D.F, D.d, D.d, D.F, EPI_STORE_ACT);
+  set(TK_DN2, D.T, D.d, 2 * D.F, 2 * D.F, D.d, EPI_STORE_ACT);
+  set(TK_DATT, D.T, Hd, D.d, D.d, Hd, EPI_STORE_ACT);
+  set(TK_DN1, D.T, D.d, D.Nqkv, D.Nqkv, D.d, EPI_STORE_ACT);
+  set(TK_DF, D.T, D.Phi, D.d, D.d, D.Phi, EPI_STORE_F32);
+  set(TK_DXQ, D.T, D.d, o.dmP, o.dmP, D.d, EPI_RESID_F32);
+  set(TK_WD, D.d, D.F, o.Tp, o.Tp, D.F, EPI_RESID_F32);
+  set(TK_WG, D.F, D.d, o.Tp, o.Tp, D.d, EPI_RESID_F32);
+  set(TK_WU, D.F, D.d, o.Tp, o.Tp, D.d, EPI_RESID_F32);
+  set(TK_WO, D.d, Hd, o.Tp, o.Tp, Hd, EPI_RESID_F32);
+  set(TK_WQ, Hd, D.d, o.Tp, o.Tp, D.d, EPI_RESID_F32);
+  set(TK_WK, Hkd, D.d, o.Tp, o.Tp, D.d, EPI_RESID_F32);
+  set(TK_WV, Hkd, D.d, o.Tp, o.Tp, D.d, EPI_RESID_F32);
+  set(TK_DA, D.d, D.Phi, o.Tp, o.Tp, D.Phi, EPI_RESID_F32);
+  set(TK_WMQ, D.dm, D.d, o.Tp, o.Tp, D.d, EPI_RESID_F32);
+  set(TK_WMK, D.dm, D.d, o.mp, o.mp, D.d, EPI_RESID_F32);
+  set(TK_WMV, D.d, D.d, o.mp, o.mp, D.d, EPI_RESID_F32);
+}
+
+armt_status upload_train_tables(BCtx& c, const armt_layer_weights* W, const armt_layer_grads* G) {
+  const Dims& D = c.D;
+  const TrainLayout& o = c.o;
+  const size_t L = D.L, T = D.T, d = D.d, e = D.esz, F = D.F, Hd = (size_t)D.H * D.dh, Hkd = (size_t)D.Hkv * D.dh;
+  std::vector<GemmGroup> tab((size_t)TK_COUNT * L);
+  std::vector<LayerAux> aux(L);
+  std::vector<float*> ptrs(3 * L);
+  memset(tab.data(), 0, tab.size() * sizeof(GemmGroup));
+  char* ws = c.ws;
+  for (size_t l = 0; l < L; ++l) {
+    const armt_layer_weights& w = W[l];
+    const armt_layer_grads& gw = G[l];
+    auto E = [&](int k) -> GemmGroup* { return &tab[(size_t)k * L + l]; };
+    char* X1 = ws + o.X1 + l * T * d * 4;
+    char* Xin = ws + o.Xin + l * T * d * 4;
+    char* Xop = D.bf16 ? ws + o.Xb + l * T * d * 2 : Xin;           // activation-typed cell input (before the read)
+    char* Yop = D.bf16 ? ws + o.Yb + l * T * d * 2 : ws + o.Yf + l * T * d * 4;
+    char* DXl = ws + o.DX + l * T * d * 4;
+    char* DXup = ws + o.DX + (l + 1) * T * d * 4;
+    char* TA = ws + o.TA + l * o.ta_rows * o.Tp * e;
+    char* TB = ws + o.TB + l * o.tb_rows * o.Tp * e;
+    char* TmA = ws + o.TmA + l * (size_t)(D.dm + D.d) * o.mp * e;
+    char* TmB = ws + o.TmB + l * d * o.mp * e;
+    GemmGroup* g;
+    g = E(TK_MQ); g->A = Xop; g->B0 = w.wm_q; g->C = ws + o.Qm + l * T * D.dm * 4;
+    g = E(TK_READ); g->A = ws + o.Fphi + l * T * D.Phi * e;
+    g->B0 = D.bf16 ? ws + o.A16w + l * d * D.Phi * 2 : ws + o.Aw + l * d * D.Phi * 4;
+    g->C = X1; g->R = (const float*)X1; g->rowscale = (const float*)(ws + o.RDen + l * T * 4);
+    g = E(TK_QKV); g->A = ws + o.N1 + l * T * d * e; g->B0 = w.wq; g->B1 = w.wk; g->B2 = w.wv;
+    g->C = ws + o.QKV + l * T * D.Nqkv * e;
+    g = E(TK_O); g->A = ws + o.Att + l * T * Hd * e; g->B0 = w.wo; g->C = ws + o.Hres + l * T * d * 4; g->R = (const float*)X1;
+    g = E(TK_GU); g->A = ws + o.N2 + l * T * d * e; g->B0 = w.wgate; g->B1 = w.wup; g->C = ws + o.GU + l * T * 2 * F * e;
+    g = E(TK_DOWN); g->A = ws + o.Uff + l * T * F * e; g->B0 = w.wdown; g->C = ws + o.Yf + l * T * d * 4;
+    g->C2 = D.bf16 ? ws + o.Yb + l * T * d * 2 : nullptr; g->R = (const float*)(ws + o.Hres + l * T * d * 4);
+    g = E(TK_MKV); g->A = Yop + (size_t)D.S * d * e; g->B0 = w.wm_k; g->B1 = w.wm_v;
+    g->C = ws + o.KVm + l * D.m * (size_t)(D.dm + D.d) * 4;
+
+    g = E(TK_DYM); g->A = ws + o.DKV + l * D.m * (size_t)o.Kmkv * e; g->B0 = ws + o.WmkvT + l * d * o.Kmkv * e;
+    g->C = DXup + (size_t)D.S * d * 4; g->R = (const float*)g->C;
+    g = E(TK_DU); g->A = ws + o.DYb + l * T * d * e; g->B0 = ws + o.WdT + l * F * d * e; g->C = ws + o.DU + l * T * F * e;
+    g = E(TK_DN2); g->A = ws + o.GU + l * T * 2 * F * e; g->B0 = ws + o.WguT + l * d * 2 * F * e; g->C = ws + o.DN + l * T * d * e;
+    g = E(TK_DATT); g->A = ws + o.DHb + l * T * d * e; g->B0 = ws + o.WoT + l * Hd * d * e; g->C = ws + o.DAtt + l * T * Hd * e;
+    g = E(TK_DN1); g->A = ws + o.DQKV + l * T * D.Nqkv * e; g->B0 = ws + o.WqkvT + l * d * D.Nqkv * e;
+    g->C = ws + o.DN + l * T * d * e;
+    g = E(TK_DF); g->A = ws + o.DNum + l * T * d * e; g->B0 = ws + o.ATr + l * d * D.Phi * e; g->C = ws + o.DF + l * T * D.Phi * 4;
+    g = E(TK_DXQ); g->A = ws + o.DQr + l * T * o.dmP * e; g->B0 = ws + o.WmqT + l * d * o.dmP * e; g->C = DXl; g->R = (const float*)DXl;
+
+    auto wgrad = [&](int k, char* A, char* B, float* C) { GemmGroup* q = E(k); q->A = A; q->B0 = B; q->C = C; q->R = C; };
+    wgrad(TK_WD, TA, TB, gw.wdown);
+    wgrad(TK_WG, TA, TB, gw.wgate);
+    wgrad(TK_WU, TA + F * o.Tp * e, TB, gw.wup);
+    wgrad(TK_WO, TA, TB, gw.wo);
+    wgrad(TK_WQ, TA, TB, gw.wq);
+    wgrad(TK_WK, TA + Hd * o.Tp * e, TB, gw.wk);
+    wgrad(TK_WV, TA + (Hd + Hkd) * o.Tp * e, TB, gw.wv);
+    wgrad(TK_DA, TA, TB, (float*)(ws + o.DA + l * d * D.Phi * 4));
+    wgrad(TK_WMQ, TA, TB, gw.wm_q);
+    wgrad(TK_WMK, TmA, TmB, gw.wm_k);
+    wgrad(TK_WMV, TmA + (size_t)D.dm * o.mp * e, TmB, gw.wm_v);
+
+    LayerAux& a = aux[l];
+    a.rms1 = w.rms1; a.rms2 = w.rms2; a.wm_b = w.wm_b;
+    a.A = (float*)(ws + o.Aw + l * d * D.Phi * 4); a.z = (float*)(ws + o.zw + l * D.Phi * 4);
+    a.A16 = D.bf16 ? (bf16*)(ws + o.A16w + l * d * D.Phi * 2) : nullptr;
+    ptrs[l] = gw.rms1; ptrs[L + l] = gw.rms2; ptrs[2 * L + l] = gw.wm_b;
+  }
+  HIP_TRY(hipMemcpyAsync(ws + o.Tables, tab.data(), tab.size() * sizeof(GemmGroup), hipMemcpyHostToDevice, c.st));
+  HIP_TRY(hipMemcpyAsync(ws + o.Aux, aux.data(), aux.size() * sizeof(LayerAux), hipMemcpyHostToDevice, c.st));
+  HIP_TRY(hipMemcpyAsync(ws + o.Ptrs, ptrs.data(), ptrs.size() * sizeof(float*), hipMemcpyHostToDevice, c.st));
+  HIP_TRY(hipStreamSynchronize(c.st));
+  c.tables = c.at<GemmGroup>(o.Tables);
+  c.aux = c.at<LayerAux>(o.Aux);
+  c.dg1 = c.at<float*>(o.Ptrs); c.dg2 = c.dg1 + L; c.dwb = c.dg1 + 2 * L;
+  return ARMT_OK;
+}
+
+template <typename Tin, typename Tout>
+armt_status transpose(hipStream_t st, const Tin* src, size_t src_cell, int lds, Tout* dst, size_t dst_cell, int ldd, int R, int C,
+                      int g) {
+  if (g <= 0 || R <= 0 || C <= 0) return ARMT_OK;
+  transpose_kernel<Tin, Tout><<<dim3((C + 31) / 32, (R + 31) / 32, g), dim3(32, 8), 0, st>>>(src, src_cell, lds, dst, dst_cell, ldd,
+                                                                                          R, C);
+  HIP_TRY(hipGetLastError());
+  return ARMT_OK;
+}
+
+inline unsigned ew_blocks(size_t n) { return (unsigned)std::max<size_t>(1, std::min<size_t>((n + 255) / 256, 65535)); }
+
+// Transposed copies of the weights, once per call: they are the B operands of the activation-gradient GEMMs.
+template <typename T>
+armt_status transpose_weights(BCtx& c, const armt_layer_weights* W) {
+  const Dims& D = c.D;
+  const TrainLayout& o = c.o;
+  const size_t d = D.d, F = D.F, Hd = (size_t)D.H * D.dh, Hkd = (size_t)D.Hkv * D.dh;
+  const size_t nq = (size_t)D.L * d * o.dmP, nk = (size_t)D.L * d * o.Kmkv;
+  fill_f32_kernel<<<ew_blocks(nq), 256, 0, c.st>>>(c.at<float>(o.WmqT), nq * D.esz / 4, 0.f);   // K padding must read as zero
+  fill_f32_kernel<<<ew_blocks(nk), 256, 0, c.st>>>(c.at<float>(o.WmkvT), nk * D.esz / 4, 0.f);
+  HIP_TRY(hipGetLastError());
+  for (int l = 0; l < D.L; ++l) {
+    const armt_layer_weights& w = W[l];
+    T* WdT = c.at<T>(o.WdT) + l * F * d;
+    T* WguT = c.at<T>(o.WguT) + l * d * 2 * F;
+    T* WoT = c.at<T>(o.WoT) + l * Hd * d;
+    T* WqkvT = c.at<T>(o.WqkvT) + l * d * D.Nqkv;
+    T* WmqT = c.at<T>(o.WmqT) + l * d * o.dmP;
+    T* WmkvT = c.at<T>(o.WmkvT) + l * d * o.Kmkv;
+    ARMT_TRY((transpose<T, T>(c.st, (const T*)w.wdown, 0, D.F, WdT, 0, D.d, D.d, D.F, 1)));
+    ARMT_TRY((transpose<T, T>(c.st, (const T*)w.wgate, 0, D.d, WguT, 0, 2 * D.F, D.F, D.d, 1)));
+    ARMT_TRY((transpose<T, T>(c.st, (const T*)w.wup, 0, D.d, WguT + F, 0, 2 * D.F, D.F, D.d, 1)));
+    ARMT_TRY((transpose<T, T>(c.st, (const T*)w.wo, 0, (int)Hd, WoT, 0, D.d, D.d, (int)Hd, 1)));
+    ARMT_TRY((transpose<T, T>(c.st, (const T*)w.wq, 0, D.d, WqkvT, 0, D.Nqkv, (int)Hd, D.d, 1)));
+    ARMT_TRY((transpose<T, T>(c.st, (const T*)w.wk, 0, D.d, WqkvT + Hd, 0, D.Nqkv, (int)Hkd, D.d, 1)));
+    ARMT_TRY((transpose<T, T>(c.st, (const T*)w.wv, 0, D.d, WqkvT + Hd + Hkd, 0, D.Nqkv, (int)Hkd, D.d, 1)));
+    ARMT_TRY((transpose<T, T>(c.st, (const T*)w.wm_q, 0, D.d, WmqT, 0, o.dmP, D.dm, D.d, 1)));
+    ARMT_TRY((transpose<T, T>(c.st, (const T*)w.wm_k, 0, D.d, WmkvT, 0, o.Kmkv, D.dm, D.d, 1)));
+    ARMT_TRY((transpose<T, T>(c.st, (const T*)w.wm_v, 0, D.d, WmkvT + D.dm, 0, o.Kmkv, D.d, D.d, 1)));
+  }
+  return ARMT_OK;
+}
+
+template <typename T>
+armt_status bgemm(const BCtx& c, int kind, int first, int g) {
+  return gemm<T>(c.st, c.table(kind), first, g, c.shape[kind]);
+}
+
+// Forward of the cells [lo, lo + g) from their restored inputs, every intermediate kept.  The first gr cells read
+// their memory; cells [e0, e1) meet an empty one.
+template <typename T>
+armt_status recompute_group(const BCtx& c, int lo, int g, int gr, int e0, int e1) {
+  const Dims& D = c.D;
+  const TrainLayout& o = c.o;
+  const size_t cell = (size_t)D.T * D.d;
+  float* X1 = c.at<float>(o.X1);
+  copy_f32_kernel<<<ew_blocks(g * cell), 256, 0, c.st>>>(X1 + lo * cell, c.at<float>(o.Xin) + lo * cell, g * cell);
+  if (D.bf16) {
+    f32_to_bf16_kernel<<<ew_blocks(g * cell), 256, 0, c.st>>>(c.at<bf16>(o.Xb) + lo * cell, c.at<float>(o.Xin) + lo * cell, g * cell);
+    const size_t nA = (size_t)D.d * D.Phi;
+    f32_to_bf16_kernel<<<ew_blocks(g * nA), 256, 0, c.st>>>(c.at<bf16>(o.A16w) + lo * nA, c.at<float>(o.Aw) + lo * nA, g * nA);
+  }
+  HIP_TRY(hipGetLastError());
+  ARMT_TRY(step_assoc_read<T>(c.st, c.table(TK_MQ), c.shape[TK_MQ], c.table(TK_READ), c.shape[TK_READ], c.aux, lo, gr, D.T,
+                              D.dm, D.nu, D.assoc_eps, c.at<float>(o.Qm), c.at<T>(o.Fphi), c.at<float>(o.RDen)));
+  rmsnorm_train_kernel<T><<<dim3(D.T, g), 256, 0, c.st>>>(X1, cell, c.aux, lo, 0, D.T, D.d, D.rms_eps, c.at<T>(o.N1),
+                                                         c.at<float>(o.RStd1));
+  HIP_TRY(hipGetLastError());
+  ARMT_TRY(bgemm<T>(c, TK_QKV, lo, g));
+  ARMT_TRY(step_attention<T>(c.st, c.at<T>(o.QKV), c.at<T>(o.Att), c.at<bf16>(o.Vt), c.at<float>(o.Rope), lo, g, D.T, D.H, D.Hkv,
+                             D.dh, false, false));
+  ARMT_TRY(bgemm<T>(c, TK_O, lo, g));
+  rmsnorm_train_kernel<T><<<dim3(D.T, g), 256, 0, c.st>>>(c.at<float>(o.Hres), cell, c.aux, lo, 1, D.T, D.d, D.rms_eps,
+                                                         c.at<T>(o.N2), c.at<float>(o.RStd2));
+  HIP_TRY(hipGetLastError());
+  ARMT_TRY(bgemm<T>(c, TK_GU, lo, g));
+  const size_t rows = (size_t)g * D.T;
+  swiglu_kernel<T><<<ew_blocks(rows * D.F), 256, 0, c.st>>>(c.at<T>(o.GU) + (size_t)lo * D.T * 2 * D.F,
+                                                            c.at<T>(o.Uff) + (size_t)lo * D.T * D.F, rows, D.F);
+  HIP_TRY(hipGetLastError());
+  ARMT_TRY(bgemm<T>(c, TK_DOWN, lo, g));
+  ARMT_TRY(bgemm<T>(c, TK_MKV, lo, g));
+  const T* Yop = D.bf16 ? (const T*)c.at<bf16>(o.Yb) : (const T*)c.at<float>(o.Yf);
+  memupd_prep_kernel<T><<<dim3(D.m, g), 128, (D.dm + 17) * 4, c.st>>>(c.at<float>(o.KVm), Yop + (size_t)D.S * D.d, cell, c.aux, lo,
+                                                                     e0, e1, D.m, D.d, D.dm, D.nu, D.assoc_eps,
+                                                                     c.at<float>(o.Fm), c.at<float>(o.Coef));
+  HIP_TRY(hipGetLastError());
+  return ARMT_OK;
+}
+
+// Backward kernels of the cells [lo, lo + g); the first gr of them have a read to differentiate.
+template <typename T>
+armt_status backward_group(const BCtx& c, int lo, int g, int gr) {
+  const Dims& D = c.D;
+  const TrainLayout& o = c.o;
+  hipStream_t st = c.st;
+  const size_t cell = (size_t)D.T * D.d, Hd = (size_t)D.H * D.dh;
+  const int Tp = o.Tp, Phi = D.Phi;
+  const size_t ta_cell = o.ta_rows * Tp, tb_cell = o.tb_rows * Tp;
+  T* TA = c.at<T>(o.TA) + lo * ta_cell;
+  T* TB = c.at<T>(o.TB) + lo * tb_cell;
+  float* DX = c.at<float>(o.DX);
+  const T* Yop = D.bf16 ? (const T*)c.at<bf16>(o.Yb) : (const T*)c.at<float>(o.Yf);
+  const T* Xop = D.bf16 ? (const T*)c.at<bf16>(o.Xb) : (const T*)c.at<float>(o.Xin);
+
+  // ---- memory update (Eq. 3-5)
+  {
+    const dim3 grid(o.nblk, g);
+    const size_t lds = ((size_t)D.m * Phi + (size_t)D.m * (Phi + 2)) * 4;
+#define ARMT_UB(NPL)                                                                                                      \
+  case NPL:                                                                                                              \
+    update_bwd_rows_kernel<NPL><<<grid, 256, lds, st>>>(c.at<float>(o.KVm), c.at<float>(o.Fm), c.at<float>(o.Coef),      \
+                                                        c.at<float>(o.Aw), c.at<float>(o.DA), c.at<float>(o.DV),         \
+                                                        c.at<float>(o.Part), lo, D.m, D.d, D.dm, Phi);                   \
+    break;
+    switch ((Phi + 63) / 64) { ARMT_UB(1) ARMT_UB(2) ARMT_UB(3) ARMT_UB(4) ARMT_UB(5) ARMT_UB(6) ARMT_UB(7) ARMT_UB(8) }
+#undef ARMT_UB
+    HIP_TRY(hipGetLastError());
+    update_bwd_tokens_kernel<T><<<dim3(D.m, g), 128, (D.dm + Phi + 17) * 4, st>>>(
+        c.at<float>(o.KVm), c.at<float>(o.Fm), c.at<float>(o.Coef), c.at<float>(o.Part), o.nblk, c.at<float>(o.DV),
+        c.at<float>(o.zw), c.at<float>(o.DZ), lo, D.m, D.d, D.dm, D.nu, D.assoc_eps, c.at<T>(o.DKV), o.Kmkv, c.at<float>(o.DB),
+        c.at<float>(o.DZF));
+    HIP_TRY(hipGetLastError());
+    update_bwd_z_kernel<<<dim3((Phi + 255) / 256, g), 256, 0, st>>>(c.at<float>(o.Fm), c.at<float>(o.DZF), c.at<float>(o.DZ), lo,
+                                                                  D.m, Phi);
+    HIP_TRY(hipGetLastError());
+    ARMT_TRY(bgemm<T>(c, TK_DYM, lo, g));
+    beta_bwd_kernel<T><<<dim3((D.d + 255) / 256, g), 256, 0, st>>>(c.at<float>(o.DB), Yop + (size_t)D.S * D.d, cell, c.aux,
+                                                                 DX + cell + (size_t)D.S * D.d, cell, c.dwb, lo, D.m, D.d);
+    HIP_TRY(hipGetLastError());
+    const size_t tma = (size_t)(D.dm + D.d) * o.mp, tmb = (size_t)D.d * o.mp;
+    ARMT_TRY((transpose<T, T>(st, c.at<T>(o.DKV) + (size_t)lo * D.m * o.Kmkv, (size_t)D.m * o.Kmkv, o.Kmkv,
+                              c.at<T>(o.TmA) + lo * tma, tma, o.mp, D.m, D.dm + D.d, g)));
+    ARMT_TRY((transpose<T, T>(st, Yop + lo * cell + (size_t)D.S * D.d, cell, D.d, c.at<T>(o.TmB) + lo * tmb, tmb, o.mp, D.m, D.d, g)));
+    ARMT_TRY(bgemm<T>(c, TK_WMK, lo, g));
+    ARMT_TRY(bgemm<T>(c, TK_WMV, lo, g));
+  }
+  // ---- feed-forward half of the block
+  T* DYb = c.at<T>(o.DYb) + lo * cell;
+  convert_kernel<float, T><<<ew_blocks(g * cell), 256, 0, st>>>(DX + (lo + 1) * cell, DYb, g * cell);
+  HIP_TRY(hipGetLastError());
+  ARMT_TRY(bgemm<T>(c, TK_DU, lo, g));
+  ARMT_TRY((transpose<T, T>(st, DYb, cell, D.d, TA, ta_cell, Tp, D.T, D.d, g)));
+  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.Uff) + (size_t)lo * D.T * D.F, (size_t)D.T * D.F, D.F, TB, tb_cell, Tp, D.T, D.F, g)));
+  ARMT_TRY(bgemm<T>(c, TK_WD, lo, g));
+  T* GU = c.at<T>(o.GU) + (size_t)lo * D.T * 2 * D.F;
+  swiglu_bwd_kernel<T><<<ew_blocks((size_t)g * D.T * D.F), 256, 0, st>>>(GU, c.at<T>(o.DU) + (size_t)lo * D.T * D.F, (size_t)g * D.T,
+                                                                        D.F);
+  HIP_TRY(hipGetLastError());
+  ARMT_TRY(bgemm<T>(c, TK_DN2, lo, g));
+  ARMT_TRY((transpose<T, T>(st, GU, (size_t)D.T * 2 * D.F, 2 * D.F, TA, ta_cell, Tp, D.T, 2 * D.F, g)));
+  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.N2) + lo * cell, cell, D.d, TB, tb_cell, Tp, D.T, D.d, g)));
+  ARMT_TRY(bgemm<T>(c, TK_WG, lo, g));
+  ARMT_TRY(bgemm<T>(c, TK_WU, lo, g));
+  gain_grad_kernel<T><<<dim3((D.d + 255) / 256, g), 256, 0, st>>>(c.at<T>(o.DN), c.at<float>(o.Hres), cell, c.at<float>(o.RStd2),
+                                                                c.dg2, lo, D.T, D.d);
+  rmsnorm_bwd_kernel<T><<<dim3(D.T, g), 256, 0, st>>>(c.at<T>(o.DN), c.at<float>(o.Hres), cell, c.aux, lo, 1, c.at<float>(o.RStd2),
+                                                     DX + cell, cell, c.at<float>(o.DH), cell, c.at<T>(o.DHb), D.T, D.d);
+  HIP_TRY(hipGetLastError());
+  // ---- attention half
+  ARMT_TRY(bgemm<T>(c, TK_DATT, lo, g));
+  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.DHb) + lo * cell, cell, D.d, TA, ta_cell, Tp, D.T, D.d, g)));
+  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.Att) + lo * D.T * Hd, D.T * Hd, (int)Hd, TB, tb_cell, Tp, D.T, (int)Hd, g)));
+  ARMT_TRY(bgemm<T>(c, TK_WO, lo, g));
+  const float scale = 1.0f / sqrtf((float)D.dh);
+  attention_bwd_q_kernel<T><<<dim3(D.T, D.H, g), 64, (2 * D.dh + D.T) * 4, st>>>(c.at<T>(o.QKV), c.at<T>(o.Att), c.at<T>(o.DAtt),
+                                                                               c.at<T>(o.DQKV), c.at<float>(o.LSE),
+                                                                               c.at<float>(o.Dv), lo, D.T, D.H, D.Hkv, D.dh, scale);
+  attention_bwd_kv_kernel<T><<<dim3(D.T, D.Hkv, g), 64, (2 * D.dh + 128) * 4, st>>>(c.at<T>(o.QKV), c.at<T>(o.DAtt), c.at<T>(o.DQKV),
+                                                                                  c.at<float>(o.LSE), c.at<float>(o.Dv), lo, D.T,
+                                                                                  D.H, D.Hkv, D.dh, scale);
+  rope_bwd_kernel<T><<<dim3(D.T, g), 256, 0, st>>>(c.at<T>(o.DQKV), c.at<float>(o.Rope), lo, D.T, D.H + D.Hkv, D.dh, D.Nqkv);
+  HIP_TRY(hipGetLastError());
+  ARMT_TRY(bgemm<T>(c, TK_DN1, lo, g));
+  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.DQKV) + (size_t)lo * D.T * D.Nqkv, (size_t)D.T * D.Nqkv, D.Nqkv, TA, ta_cell, Tp, D.T,
+                            D.Nqkv, g)));
+  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.N1) + lo * cell, cell, D.d, TB, tb_cell, Tp, D.T, D.d, g)));
+  ARMT_TRY(bgemm<T>(c, TK_WQ, lo, g));
+  ARMT_TRY(bgemm<T>(c, TK_WK, lo, g));
+  ARMT_TRY(bgemm<T>(c, TK_WV, lo, g));
+  gain_grad_kernel<T><<<dim3((D.d + 255) / 256, g), 256, 0, st>>>(c.at<T>(o.DN), c.at<float>(o.X1), cell, c.at<float>(o.RStd1),
+                                                                c.dg1, lo, D.T, D.d);
+  rmsnorm_bwd_kernel<T><<<dim3(D.T, g), 256, 0, st>>>(c.at<T>(o.DN), c.at<float>(o.X1), cell, c.aux, lo, 0, c.at<float>(o.RStd1),
+                                                     c.at<float>(o.DH), cell, DX, cell, (T*)nullptr, D.T, D.d);
+  HIP_TRY(hipGetLastError());
+  // ---- associative read (Eq. 6)
+  if (gr > 0) {
+    read_bwd_rows_kernel<T><<<dim3(D.T, gr), 256, 0, st>>>(DX, cell, c.at<float>(o.X1), cell, c.at<float>(o.Xin), cell,
+                                                          c.at<float>(o.RDen), lo, D.T, D.d, c.at<T>(o.DNum), c.at<float>(o.DDen));
+    HIP_TRY(hipGetLastError());
+    const size_t nA = (size_t)D.d * Phi;
+    ARMT_TRY((transpose<float, T>(st, c.at<float>(o.Aw) + lo * nA, nA, Phi, c.at<T>(o.ATr) + lo * nA, nA, D.d, D.d, Phi, gr)));
+    ARMT_TRY(bgemm<T>(c, TK_DF, lo, gr));
+    read_bwd_dpfp_kernel<T><<<dim3(D.T, gr), 128, (D.dm + Phi) * 4, st>>>(c.at<float>(o.Qm), c.at<float>(o.DF), c.at<float>(o.DDen),
+                                                                         c.aux, lo, D.T, D.dm, D.nu, c.at<T>(o.DQr), o.dmP);
+    read_bwd_dz_kernel<T><<<dim3((Phi + 255) / 256, gr), 256, 0, st>>>(c.at<T>(o.Fphi), c.at<float>(o.DDen), c.at<float>(o.DZ), lo,
+                                                                      D.T, Phi);
+    HIP_TRY(hipGetLastError());
+    ARMT_TRY((transpose<T, T>(st, c.at<T>(o.DNum) + lo * cell, cell, D.d, TA, ta_cell, Tp, D.T, D.d, gr)));
+    ARMT_TRY((transpose<T, T>(st, c.at<T>(o.Fphi) + (size_t)lo * D.T * Phi, (size_t)D.T * Phi, Phi, TB, tb_cell, Tp, D.T, Phi, gr)));
+    ARMT_TRY(bgemm<T>(c, TK_DA, lo, gr));
+    ARMT_TRY(bgemm<T>(c, TK_DXQ, lo, gr));
+    ARMT_TRY((transpose<T, T>(st, c.at<T>(o.DQr) + (size_t)lo * D.T * o.dmP, (size_t)D.T * o.dmP, o.dmP, TA, ta_cell, Tp, D.T, D.dm,
+                              gr)));
+    ARMT_TRY((transpose<T, T>(st, Xop + lo * cell, cell, D.d, TB, tb_cell, Tp, D.T, D.d, gr)));
+    ARMT_TRY(bgemm<T>(c, TK_WMQ, lo, gr));
+  }
+  return ARMT_OK;
+}
+
+template <typename T>
+armt_status backward_typed(BCtx& c, const armt_layer_weights* W, int64_t N, float* tape, size_t rec_floats, bool carry_in,
+                           const void* d_hidden, float* d_mem_emb, float* dx, bool diagonal) {
+  const Dims& D = c.D;
+  const TrainLayout& o = c.o;
+  const int L = D.L;
+  const size_t cell = (size_t)D.T * D.d, nA = (size_t)D.d * D.Phi;
+  {
+    const int n = D.T * (D.dh / 2);
+    rope_table_kernel<<<(n + 255) / 256, 256, 0, c.st>>>(c.at<float>(o.Rope), D.T, D.dh / 2, (double)D.rope_theta);
+    // zero what is only ever written in part: the reduction padding of the transposed operands, the K padding of
+    // dq and [dk | dv], and the gradient slots
+    auto zero = [&](size_t off, size_t bytes) {
+      fill_f32_kernel<<<ew_blocks(bytes / 4), 256, 0, c.st>>>(c.at<float>(off), bytes / 4, 0.f);
+    };
+    zero(o.TA, (size_t)L * o.ta_rows * o.Tp * D.esz);
+    zero(o.TB, (size_t)L * o.tb_rows * o.Tp * D.esz);
+    zero(o.TmA, (size_t)L * (D.dm + D.d) * o.mp * D.esz);
+    zero(o.TmB, (size_t)L * D.d * o.mp * D.esz);
+    zero(o.DQr, (size_t)L * D.T * o.dmP * D.esz);
+    zero(o.DKV, (size_t)L * D.m * o.Kmkv * D.esz);
+    zero(o.DX, (size_t)(L + 1) * cell * 4);
+    if (D.bf16) zero(o.Vt, attention_vt_bytes(D.L, D.T, D.Hkv, D.dh));
+    HIP_TRY(hipGetLastError());
+  }
+  ARMT_TRY(transpose_weights<T>(c, W));
+
+  auto step = [&](int lo, int hi, int t) -> armt_status {
+    const int g = hi - lo + 1;
+    // the cell of segment 0 met an empty memory unless a state was carried in
+    const bool top_empty = !carry_in && (t - hi) == 0;
+    const int gr = top_empty ? g - 1 : g;
+    tape_kernel<<<dim3(128, g), 256, 0, c.st>>>(tape, rec_floats, c.at<float>(o.Xin), cell, c.aux, c.at<float>(o.Aw),
+                                               c.at<float>(o.zw), lo, t, L, cell, nA, (size_t)D.Phi, 0);
+    if (hi == L - 1) {
+      const int64_t s = t - (L - 1);
+      load_dhidden_kernel<T><<<D.T, 256, 0, c.st>>>((const T*)d_hidden + (size_t)s * D.S * D.d, D.S, D.d,
+                                                   c.at<float>(o.DX) + (size_t)L * cell);
+    }
+    HIP_TRY(hipGetLastError());
+    ARMT_TRY(recompute_group<T>(c, lo, g, gr, top_empty ? hi : -1, top_empty ? hi + 1 : -1));
+    ARMT_TRY(backward_group<T>(c, lo, g, gr));
+    if (lo == 0) {
+      store_dx_kernel<<<D.T, 256, 0, c.st>>>(c.at<float>(o.DX), D.S, D.d, dx ? dx + (size_t)t * D.S * D.d : nullptr, d_mem_emb);
+      HIP_TRY(hipGetLastError());
+    }
+    return ARMT_OK;
+  };
+  if (diagonal) {
+    for (int64_t t = L + N - 2; t >= 0; --t) {
+      int32_t lo, hi;
+      armt_diagonal_group(L, (int32_t)N, (int32_t)t, &lo, &hi);
+      ARMT_TRY(step(lo, hi, (int)t));
+    }
+  } else {
+    for (int64_t s = N - 1; s >= 0; --s)
+      for (int l = L - 1; l >= 0; --l) ARMT_TRY(step(l, l, (int)s + l));
+  }
+  return ARMT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t armt_tape_bytes(const armt_config* cfg, int64_t n_tokens) {
+  Dims D;
+  if (check_backward_config(cfg, &D) != ARMT_OK || n_tokens <= 0 || n_tokens % D.S != 0) return 0;
+  return (size_t)(n_tokens / D.S) * D.L * tape_record_floats(D) * 4;
+}
+
+size_t armt_backward_workspace_bytes(const armt_config* cfg) {
+  Dims D;
+  if (check_backward_config(cfg, &D) != ARMT_OK) return 0;
+  return carve_train(D).total;
+}
+
+armt_status armt_forward_train(const armt_config* cfg, const armt_layer_weights* layers, const void* mem_emb, const void* x,
+                               int64_t n_tokens, const float* A_in, const float* z_in, void* hidden_out, float* A_out,
+                               float* z_out, void* tape, size_t tape_bytes, void* workspace, size_t workspace_bytes,
+                               void* hip_stream, int32_t diagonal) {
+  Dims D;
+  ARMT_TRY(check_backward_config(cfg, &D));
+  if (!tape) return ARMT_ERR_NULL;
+  if (n_tokens <= 0 || n_tokens % D.S != 0) return ARMT_ERR_SHAPE;
+  if (((uintptr_t)tape % kAlign) != 0 || tape_bytes < armt_tape_bytes(cfg, n_tokens)) return ARMT_ERR_WORKSPACE;
+  return forward_impl(cfg, layers, mem_emb, x, 1, n_tokens, A_in, z_in, hidden_out, A_out, z_out, workspace, workspace_bytes,
+                      hip_stream, diagonal != 0, (float*)tape, tape_record_floats(D));
+}
+
+armt_status armt_backward(const armt_config* cfg, const armt_layer_weights* layers, int64_t n_tokens, const void* tape,
+                          size_t tape_bytes, int32_t carry_in, const void* d_hidden, const float* dA_out, const float* dz_out,
+                          const armt_layer_grads* grads, float* d_mem_emb, float* dx, float* dA_in, float* dz_in,
+                          void* workspace, size_t workspace_bytes, void* hip_stream, int32_t diagonal) {
+  BCtx c;
+  ARMT_TRY(check_backward_config(cfg, &c.D));
+  const Dims& D = c.D;
+  if (!layers || !tape || !d_hidden || !grads || !d_mem_emb) return ARMT_ERR_NULL;
+  for (int l = 0; l < D.L; ++l) {
+    const armt_layer_weights& w = layers[l];
+    const armt_layer_grads& g = grads[l];
+    if (!w.rms1 || !w.wq || !w.wk || !w.wv || !w.wo || !w.rms2 || !w.wgate || !w.wup || !w.wdown || !w.wm_q || !w.wm_k ||
+        !w.wm_v || !w.wm_b)
+      return ARMT_ERR_NULL;
+    if (!g.rms1 || !g.wq || !g.wk || !g.wv || !g.wo || !g.rms2 || !g.wgate || !g.wup || !g.wdown || !g.wm_q || !g.wm_k ||
+        !g.wm_v || !g.wm_b)
+      return ARMT_ERR_NULL;
+  }
+  if (n_tokens <= 0 || n_tokens % D.S != 0) return ARMT_ERR_SHAPE;
+  const int64_t N = n_tokens / D.S;
+  if (N + D.L > (int64_t)1 << 30) return ARMT_ERR_SHAPE;
+  if ((dA_out == nullptr) != (dz_out == nullptr) || (dA_in == nullptr) != (dz_in == nullptr)) return ARMT_ERR_NULL;
+  if (((uintptr_t)tape % kAlign) != 0 || tape_bytes < armt_tape_bytes(cfg, n_tokens)) return ARMT_ERR_WORKSPACE;
+  c.o = carve_train(D);
+  if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < c.o.total) return ARMT_ERR_WORKSPACE;
+  c.ws = (char*)workspace;
+  c.st = (hipStream_t)hip_stream;
+  fill_train_shapes(c);
+  ARMT_TRY(upload_train_tables(c, layers, grads));
+  const size_t nA = (size_t)D.L * D.d * D.Phi, nz = (size_t)D.L * D.Phi;
+  if (dA_out) {
+    copy_f32_kernel<<<1024, 256, 0, c.st>>>(c.at<float>(c.o.DA), dA_out, nA);
+    copy_f32_kernel<<<16, 256, 0, c.st>>>(c.at<float>(c.o.DZ), dz_out, nz);
+  } else {
+    fill_f32_kernel<<<1024, 256, 0, c.st>>>(c.at<float>(c.o.DA), nA, 0.f);
+    fill_f32_kernel<<<16, 256, 0, c.st>>>(c.at<float>(c.o.DZ), nz, 0.f);
+  }
+  HIP_TRY(hipGetLastError());
+  armt_status rc;
+  if (D.bf16)
+    rc = backward_typed<bf16>(c, layers, N, (float*)const_cast<void*>(tape), tape_record_floats(D), carry_in != 0, d_hidden,
+                              d_mem_emb, dx, diagonal != 0);
+  else
+    rc = backward_typed<float>(c, layers, N, (float*)const_cast<void*>(tape), tape_record_floats(D), carry_in != 0, d_hidden,
+                               d_mem_emb, dx, diagonal != 0);
+  if (rc != ARMT_OK) return rc;
+  if (dA_in) {
+    copy_f32_kernel<<<1024, 256, 0, c.st>>>(dA_in, c.at<float>(c.o.DA), nA);
+    copy_f32_kernel<<<16, 256, 0, c.st>>>(dz_in, c.at<float>(c.o.DZ), nz);
+    HIP_TRY(hipGetLastError());
+  }
+  return ARMT_OK;
+}
+
+}  // extern "C"

@@ -205,6 +205,59 @@ def test_batched_workspace_and_argument_errors(lib):
     assert lib.armt_forward_sequential_batched(*args(3, n1)) == 4
 
 
+def test_training_entry_argument_errors(lib):
+    """Tape / workspace sizes and the argument checks of armt_forward_train and armt_backward; nothing is launched."""
+    import paper_2506_05229_amd as P
+    shape = S.get_shape("tiny")
+    cfg = _cfg(shape)
+    L, fake = shape.n_layers, 0x1000
+    T, d, phi = shape.seg_len + shape.n_mem, shape.d_model, shape.phi
+    rec = (T * d + d * phi + phi + 63) // 64 * 64
+    tape_bytes = lib.armt_tape_bytes(C.byref(cfg), shape.n_tokens)
+    assert tape_bytes == shape.n_segments * L * rec * 4
+    assert lib.armt_tape_bytes(C.byref(cfg), shape.n_tokens + 1) == 0 and lib.armt_tape_bytes(C.byref(cfg), 0) == 0
+    ws_bytes = lib.armt_backward_workspace_bytes(C.byref(cfg))
+    assert ws_bytes > 0 and ws_bytes % 256 == 0
+    big_m = _cfg(shape.replace(n_mem=24))                  # more memory tokens than the delta-rule backward holds
+    assert lib.armt_tape_bytes(C.byref(big_m), shape.n_tokens) == 0 and lib.armt_backward_workspace_bytes(C.byref(big_m)) == 0
+    layers = (P.ArmtLayerWeights * L)()
+    grads = (P.ArmtLayerGrads * L)()
+    for l in range(L):
+        for f, _ in P.ArmtLayerWeights._fields_:
+            setattr(layers[l], f, fake)
+            setattr(grads[l], f, fake)
+    fwd_ws = lib.armt_workspace_bytes(C.byref(cfg))
+
+    def train(**kw):
+        a = dict(cfg=C.byref(cfg), tape=0x10000, tb=tape_bytes, n=shape.n_tokens, ws=0x20000, wsb=fwd_ws)
+        a.update(kw)
+        return lib.armt_forward_train(a["cfg"], layers, fake, fake, a["n"], None, None, fake, fake, fake, a["tape"], a["tb"],
+                                      a["ws"], a["wsb"], None, 1)
+
+    assert train(tape=None) == 1 and train(tb=tape_bytes - 1) == 4 and train(tape=0x10001) == 4
+    assert train(n=shape.n_tokens + 3) == 2 and train(ws=None) == 4 and train(cfg=C.byref(big_m)) == 6
+
+    def back(**kw):
+        a = dict(cfg=C.byref(cfg), layers=layers, n=shape.n_tokens, tape=0x10000, tb=tape_bytes, dh=fake, dA=None, dz=None,
+                 grads=grads, dmem=fake, dx=None, dAi=None, dzi=None, ws=0x20000, wsb=ws_bytes)
+        a.update(kw)
+        return lib.armt_backward(a["cfg"], a["layers"], a["n"], a["tape"], a["tb"], 0, a["dh"], a["dA"], a["dz"], a["grads"],
+                                 a["dmem"], a["dx"], a["dAi"], a["dzi"], a["ws"], a["wsb"], None, 1)
+
+    assert back(cfg=None) == 1 and back(layers=None) == 1 and back(tape=None) == 1 and back(dh=None) == 1
+    assert back(grads=None) == 1 and back(dmem=None) == 1
+    assert back(dA=fake) == 1 and back(dAi=fake) == 1            # one of a pair without the other
+    assert back(n=0) == 2 and back(n=shape.n_tokens - 1) == 2
+    assert back(tb=tape_bytes - 1) == 4 and back(ws=None) == 4 and back(wsb=ws_bytes - 1) == 4 and back(ws=0x20001) == 4
+    assert back(cfg=C.byref(big_m)) == 6
+    missing = (P.ArmtLayerGrads * L)()
+    for l in range(L):
+        for f, _ in P.ArmtLayerGrads._fields_:
+            setattr(missing[l], f, fake)
+    missing[0].wm_q = None
+    assert back(grads=missing) == 1
+
+
 def test_microbench_needs_a_gpu_and_says_so(capsys):
     import torch
     if torch.cuda.is_available():

@@ -1,0 +1,136 @@
+"""Parity of the HIP backward pass (through the C ABI) against the backward oracle (float64 autograd of the
+restated forward).  Every gradient tensor is compared by relative Frobenius error.
+fp32 configurations: <= 2e-4.
+bf16 configurations: <= 3e-2 for the decoder block's weights, the embeddings and W_V, W_beta of the memory (every
+gradient GEMM takes bf16 operands and accumulates in fp32; the error grows by about 0.5 % per layer the gradient
+crosses); <= 1e-1 for W_Q and W_K of the memory and for the carried-in state: these gradients are linear in the
+memory matrix A and in its gradient, which the bf16 forward itself only reproduces to a few per cent (the forward
+tolerance on A and z is 5e-2), and they pass through the rank-one cancellation d(num / den)."""
+import numpy as np
+import pytest
+
+import armt_synth as S
+from gpu_util import make_problem, rel_fro
+from oracle import armt_oracle_grad as G
+
+pytestmark = pytest.mark.gpu
+
+F32_REL = 2e-4
+BF16_REL = 3e-2
+BF16_REL_MEM = 1e-1
+
+
+def upstream(shape, seed, with_state):
+    rng = np.random.default_rng(seed + 1000)
+    Gh = rng.standard_normal((shape.n_tokens, shape.d_model)).astype(np.float32)
+    if shape.dtype == "bf16":
+        Gh = S.round_to_bf16(Gh)
+    if not with_state:
+        return Gh, None, None
+    GA = (rng.standard_normal((shape.n_layers, shape.d_model, shape.phi)) * 0.1).astype(np.float32)
+    Gz = (rng.standard_normal((shape.n_layers, shape.phi)) * 0.1).astype(np.float32)
+    return Gh, GA, Gz
+
+
+def carried(shape, seed):
+    rng = np.random.default_rng(seed + 2000)
+    A = (rng.standard_normal((shape.n_layers, shape.d_model, shape.phi)) * 0.05).astype(np.float32)
+    z = rng.uniform(0.5, 1.5, (shape.n_layers, shape.phi)).astype(np.float32)
+    return A, z
+
+
+def run_hip_grad(shape, layers, mem_emb, x, Gs, state, diagonal):
+    import torch
+    import paper_2506_05229_amd as P
+    model = P.Armt(shape, layers, mem_emb)
+    xd = model.embed(x)
+    dev = lambda a: None if a is None else torch.as_tensor(a, dtype=torch.float32).cuda().contiguous()
+    A_in, z_in = (dev(state[0]), dev(state[1])) if state else (None, None)
+    hidden, A, z, tape = model.forward_train(xd, diagonal=diagonal, A_in=A_in, z_in=z_in)
+    ref = model.forward(xd, diagonal=diagonal, A_in=A_in, z_in=z_in)
+    for a, b in zip((hidden, A, z), ref):
+        assert torch.equal(a, b)                     # the tape does not change the forward result
+    g = model.backward(tape, x.shape[0], model.embed(Gs[0]), dev(Gs[1]), dev(Gs[2]), carry_in=state is not None,
+                       diagonal=diagonal)
+    torch.cuda.synchronize()
+    np_ = lambda t: None if t is None else t.float().cpu().numpy()
+    return {"layers": [{k: np_(v) for k, v in lw.items()} for lw in g["layers"]], "mem_emb": np_(g["mem_emb"]),
+            "x": np_(g["x"]), "A_in": np_(g["A_in"]), "z_in": np_(g["z_in"]), "hidden": np_(hidden), "A": np_(A), "z": np_(z)}
+
+
+def compare(got, want, tol, what, tol_mem=None):
+    """tol_mem: tolerance of the tensors whose gradient passes through the associative read or update."""
+    errs = {}
+    def one(name, a, b, t):
+        assert np.isfinite(a).all(), (what, name)
+        e = rel_fro(a, b)
+        key = name.split()[-1]
+        errs[key] = max(errs.get(key, 0.0), e)
+        return [] if e <= t else [(name, e, t)]
+    bad = []
+    tm = tol if tol_mem is None else tol_mem
+    for l, (gl, wl) in enumerate(zip(got["layers"], want["layers"])):
+        for k in G.WEIGHT_KEYS:
+            bad += one(f"layer {l} {k}", gl[k].reshape(wl[k].shape), wl[k], tm if k in ("wm_q", "wm_k") else tol)
+    bad += one("mem_emb", got["mem_emb"], want["mem_emb"], tol)
+    bad += one("x", got["x"], want["x"], tol)
+    if want["A_in"] is not None:
+        bad += one("A_in", got["A_in"], want["A_in"], tm)
+        bad += one("z_in", got["z_in"], want["z_in"], tm)
+    fwd = " ".join(f"{k}={rel_fro(got[k], want[k]):.2e}" for k in ("hidden", "A", "z"))
+    print(f"{what}: forward {fwd}; gradients " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
+    assert not bad, (what, bad)
+
+
+@pytest.mark.parametrize("diagonal", [False, True])
+@pytest.mark.parametrize("case", ["plain", "carry_and_state_grads", "ragged"])
+def test_f32_backward_matches_oracle(case, diagonal):
+    base = S.get_shape("tiny")
+    if case == "ragged":
+        shape = base.replace(n_layers=3, d_model=120, n_heads=6, n_kv_heads=3, head_dim=20, d_ff=200,
+                             seg_len=37, n_mem=5, d_mem=12, n_tokens=37 * 4, dpfp_nu=2)
+    else:
+        shape = base.replace(n_tokens=5 * 64)
+    layers, mem_emb, x = make_problem(shape, seed=3, std=0.02, gain_std=0.1, v_scale=64.0)
+    state = carried(shape, 3) if case == "carry_and_state_grads" else None
+    Gs = upstream(shape, 3, with_state=(case != "plain"))
+    want = G.armt_grad(shape, layers, mem_emb, x, *Gs, A_in=state[0] if state else None, z_in=state[1] if state else None)
+    got = run_hip_grad(shape, layers, mem_emb, x, Gs, state, diagonal)
+    compare(got, want, F32_REL, f"f32 {case} diag={diagonal}")
+
+
+SMALL_BF16 = dict(n_layers=3, d_model=256, n_heads=4, n_kv_heads=2, head_dim=64, d_ff=512, seg_len=144,
+                  n_mem=16, d_mem=32, n_tokens=144 * 4, dtype="bf16")
+
+
+@pytest.mark.parametrize("diagonal", [False, True])
+def test_small_bf16_backward_matches_oracle(diagonal):
+    shape = S.get_shape("tiny").replace(**SMALL_BF16)
+    layers, mem_emb, x = make_problem(shape, seed=11, std=0.02, gain_std=0.1, v_scale=16.0)
+    Gs = upstream(shape, 11, with_state=True)
+    want = G.armt_grad(shape, layers, mem_emb, x, *Gs)
+    got = run_hip_grad(shape, layers, mem_emb, x, Gs, None, diagonal)
+    compare(got, want, BF16_REL, f"bf16 diag={diagonal}", tol_mem=BF16_REL_MEM)
+
+
+def test_backward_orders_agree_bitwise():
+    shape = S.get_shape("tiny").replace(n_tokens=5 * 64)
+    layers, mem_emb, x = make_problem(shape, seed=5, std=0.02, gain_std=0.1, v_scale=64.0)
+    Gs = upstream(shape, 5, with_state=True)
+    a = run_hip_grad(shape, layers, mem_emb, x, Gs, None, False)
+    b = run_hip_grad(shape, layers, mem_emb, x, Gs, None, True)
+    for la, lb in zip(a["layers"], b["layers"]):
+        for k in G.WEIGHT_KEYS:
+            assert np.array_equal(la[k], lb[k]), k
+    assert np.array_equal(a["x"], b["x"]) and np.array_equal(a["mem_emb"], b["mem_emb"])
+
+
+def test_1b_width_bf16_backward_matches_oracle():
+    """Two layers of the 1B shape (d_model 2048, 32/8 heads of 64, d_ff 8192, segment 1024 + 16 memory tokens,
+    d_mem 64) over three segments, diagonal order: the tile configurations and launch shapes of the full model."""
+    shape = S.get_shape("1b_8k").replace(n_layers=2, n_tokens=3 * 1024)
+    layers, mem_emb, x = make_problem(shape, seed=2, std=0.02)
+    Gs = upstream(shape, 2, with_state=True)
+    want = G.armt_grad(shape, layers, mem_emb, x, *Gs)
+    got = run_hip_grad(shape, layers, mem_emb, x, Gs, None, True)
+    compare(got, want, BF16_REL, "1B width, 2 layers, 3 segments", tol_mem=BF16_REL_MEM)
