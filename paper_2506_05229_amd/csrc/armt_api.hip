@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "attention_generic.h"
+#include "attention_bwd_mfma.h"
 #include "attention_mfma.h"
 #include "backward_kernels.h"
 #include "common.h"

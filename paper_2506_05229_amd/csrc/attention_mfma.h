@@ -40,12 +40,13 @@ __global__ __launch_bounds__(256) void v_transpose_kernel(const bf16* __restrict
   }
 }
 
-// QKV: [L][T][(H + 2 Hkv) dh] with q, k already rotated; Vt as above; Out: [L][T][H dh].
+// QKV: [L][T][(H + 2 Hkv) dh] with q, k already rotated; Vt as above; Out: [L][T][H dh]; lse2: optional, see the end.
 // grid: (ceil(T / 32), Hkv, g), block: GROUP * 64 with GROUP = H / Hkv.
 template <int DH>
 __global__ __launch_bounds__(512) void attention_mfma_kernel(const bf16* __restrict__ QKV, const bf16* __restrict__ Vt,
                                                              bf16* __restrict__ Out, int first, int Trows, int Tp,
-                                                             int H, int Hkv, float scale_log2e) {
+                                                             int H, int Hkv, float scale_log2e,
+                                                             float* __restrict__ lse2) {
   // a K tile is DH / 64 sub-tiles [64 keys][64 dims] with 128-byte rows
   constexpr int K_BYTES = AT_KT * DH * 2;
   constexpr int V_BYTES = DH * AT_KT * 2;          // V^T tile: [DH dims][64 keys], 128-byte rows
@@ -193,6 +194,8 @@ __global__ __launch_bounds__(512) void attention_mfma_kernel(const bf16* __restr
   lsum += __shfl_xor(lsum, 32, kWave);
   const float inv = 1.0f / lsum;
   const int qi = q0 + qcol;
+  // log2 of the row's sum of exponentials, [cells][H][T]: what the backward pass needs to rebuild P
+  if (lse2 && qi < Trows && half == 0) lse2[((size_t)l * H + head) * Trows + qi] = fmaf(m, scale_log2e, __builtin_amdgcn_logf(lsum));
   if (qi < Trows) {
     bf16* dst = Out + ((size_t)l * Trows + qi) * (H * DH) + head * DH;
 #pragma unroll
@@ -215,7 +218,7 @@ inline size_t attention_vt_bytes(int g, int Trows, int Hkv, int dh) {
 }
 
 inline hipError_t launch_attention_mfma(const bf16* QKV, bf16* Vt, bf16* Out, int first, int g, int Trows, int H,
-                                        int Hkv, int dh, bool vt_ready, hipStream_t st) {
+                                        int Hkv, int dh, bool vt_ready, hipStream_t st, float* lse2 = nullptr) {
   const int Tp = attention_tp(Trows), group = H / Hkv;
   hipError_t e = hipSuccess;
   if (!vt_ready) {      // V^T not yet written by the producer of QKV
@@ -226,9 +229,9 @@ inline hipError_t launch_attention_mfma(const bf16* QKV, bf16* Vt, bf16* Out, in
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)dh);
   const dim3 grid((Trows + AT_QT - 1) / AT_QT, Hkv, g);
   if (dh == 64)
-    attention_mfma_kernel<64><<<grid, group * 64, 2 * (64 * 64 * 2 * 2), st>>>(QKV, Vt, Out, first, Trows, Tp, H, Hkv, scale_log2e);
+    attention_mfma_kernel<64><<<grid, group * 64, 2 * (64 * 64 * 2 * 2), st>>>(QKV, Vt, Out, first, Trows, Tp, H, Hkv, scale_log2e, lse2);
   else
-    attention_mfma_kernel<128><<<grid, group * 64, 2 * (64 * 128 * 2 * 2), st>>>(QKV, Vt, Out, first, Trows, Tp, H, Hkv, scale_log2e);
+    attention_mfma_kernel<128><<<grid, group * 64, 2 * (64 * 128 * 2 * 2), st>>>(QKV, Vt, Out, first, Trows, Tp, H, Hkv, scale_log2e, lse2);
   return hipGetLastError();
 }
 

@@ -28,7 +28,7 @@ enum TKind {
 struct TrainLayout {
   size_t Xin, X1, Xb, N1, N2, RStd1, RStd2, QKV, Vt, Att, Hres, GU, Uff, Yf, Yb, Qm, Fphi, RDen, KVm, Fm, Coef, Rope;
   size_t Aw, zw, A16w, ATr;
-  size_t DX, DYb, DU, DN, DH, DHb, DAtt, DQKV, LSE, Dv, DNum, DF, DDen, DQr, DKV, DV, Part, DB, DZF, DA, DZ;
+  size_t DX, DYb, DU, DN, DH, DHb, DAtt, DQKV, LSE, Dv, AttS, DNum, DF, DDen, DQr, DKV, DV, Part, DB, DZF, DA, DZ;
   size_t TA, TB, TmA, TmB;
   size_t WdT, WguT, WoT, WqkvT, WmqT, WmkvT;
   size_t Ptrs, Tables, Aux, total;
@@ -79,6 +79,7 @@ TrainLayout carve_train(const Dims& D) {
   o.DQKV = take(L * T * D.Nqkv * e);
   o.LSE = take(L * D.H * T * 4);
   o.Dv = take(L * D.H * T * 4);
+  o.AttS = take(D.bf16 ? attention_bwd_scratch_bytes(D.L, D.T, D.H, D.Hkv, D.dh) : 0);
   o.DNum = take(L * T * d * e);
   o.DF = take(L * T * D.Phi * 4);
   o.DDen = take(L * T * 4);
@@ -294,6 +295,12 @@ armt_status transpose_weights(BCtx& c, const armt_layer_weights* W) {
   return ARMT_OK;
 }
 
+// bf16 with head_dim 64 or 128 (what check_config admits for bf16): attention forward and backward on the matrix cores
+template <typename T>
+bool mfma_attention_bwd(const Dims& D) {
+  return std::is_same<T, bf16>::value && !debug_generic() && (D.dh == 64 || D.dh == 128) && D.H / D.Hkv <= 8;
+}
+
 template <typename T>
 armt_status bgemm(const BCtx& c, int kind, int first, int g) {
   return gemm<T>(c.st, c.table(kind), first, g, c.shape[kind]);
@@ -320,8 +327,15 @@ armt_status recompute_group(const BCtx& c, int lo, int g, int gr, int e0, int e1
                                                          c.at<float>(o.RStd1));
   HIP_TRY(hipGetLastError());
   ARMT_TRY(bgemm<T>(c, TK_QKV, lo, g));
-  ARMT_TRY(step_attention<T>(c.st, c.at<T>(o.QKV), c.at<T>(o.Att), c.at<bf16>(o.Vt), c.at<float>(o.Rope), lo, g, D.T, D.H, D.Hkv,
-                             D.dh, false, false));
+  if (mfma_attention_bwd<T>(D)) {      // the matrix-core forward kernel also leaves the log-sum-exp of every row
+    rope_kernel<T><<<dim3(D.T, g), 256, 0, c.st>>>(c.at<T>(o.QKV), c.at<float>(o.Rope), lo, D.T, D.H + D.Hkv, D.dh, D.Nqkv);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(launch_attention_mfma(c.at<bf16>(o.QKV), c.at<bf16>(o.Vt), c.at<bf16>(o.Att), lo, g, D.T, D.H, D.Hkv, D.dh, false, c.st,
+                                  c.at<float>(o.LSE)));
+  } else {
+    ARMT_TRY(step_attention<T>(c.st, c.at<T>(o.QKV), c.at<T>(o.Att), c.at<bf16>(o.Vt), c.at<float>(o.Rope), lo, g, D.T, D.H, D.Hkv,
+                               D.dh, false, false));
+  }
   ARMT_TRY(bgemm<T>(c, TK_O, lo, g));
   rmsnorm_train_kernel<T><<<dim3(D.T, g), 256, 0, c.st>>>(c.at<float>(o.Hres), cell, c.aux, lo, 1, D.T, D.d, D.rms_eps,
                                                          c.at<T>(o.N2), c.at<float>(o.RStd2));
@@ -416,12 +430,17 @@ armt_status backward_group(const BCtx& c, int lo, int g, int gr) {
   ARMT_TRY((transpose<T, T>(st, c.at<T>(o.Att) + lo * D.T * Hd, D.T * Hd, (int)Hd, TB, tb_cell, Tp, D.T, (int)Hd, g)));
   ARMT_TRY(bgemm<T>(c, TK_WO, lo, g));
   const float scale = 1.0f / sqrtf((float)D.dh);
-  attention_bwd_q_kernel<T><<<dim3(D.T, D.H, g), 64, (2 * D.dh + D.T) * 4, st>>>(c.at<T>(o.QKV), c.at<T>(o.Att), c.at<T>(o.DAtt),
-                                                                               c.at<T>(o.DQKV), c.at<float>(o.LSE),
-                                                                               c.at<float>(o.Dv), lo, D.T, D.H, D.Hkv, D.dh, scale);
-  attention_bwd_kv_kernel<T><<<dim3(D.T, D.Hkv, g), 64, (2 * D.dh + 128) * 4, st>>>(c.at<T>(o.QKV), c.at<T>(o.DAtt), c.at<T>(o.DQKV),
-                                                                                  c.at<float>(o.LSE), c.at<float>(o.Dv), lo, D.T,
-                                                                                  D.H, D.Hkv, D.dh, scale);
+  if (mfma_attention_bwd<T>(D)) {
+    HIP_TRY(launch_attention_bwd_mfma(c.at<bf16>(o.QKV), c.at<bf16>(o.Att), c.at<bf16>(o.DAtt), c.at<float>(o.LSE), c.at<float>(o.Dv),
+                                      c.at<bf16>(o.AttS), c.at<bf16>(o.DQKV), lo, g, D.L, D.T, D.H, D.Hkv, D.dh, st));
+  } else {
+    attention_bwd_q_kernel<T><<<dim3(D.T, D.H, g), 64, (2 * D.dh + D.T) * 4, st>>>(c.at<T>(o.QKV), c.at<T>(o.Att), c.at<T>(o.DAtt),
+                                                                                 c.at<T>(o.DQKV), c.at<float>(o.LSE),
+                                                                                 c.at<float>(o.Dv), lo, D.T, D.H, D.Hkv, D.dh, scale);
+    attention_bwd_kv_kernel<T><<<dim3(D.T, D.Hkv, g), 64, (2 * D.dh + 128) * 4, st>>>(c.at<T>(o.QKV), c.at<T>(o.DAtt), c.at<T>(o.DQKV),
+                                                                                    c.at<float>(o.LSE), c.at<float>(o.Dv), lo, D.T,
+                                                                                    D.H, D.Hkv, D.dh, scale);
+  }
   rope_bwd_kernel<T><<<dim3(D.T, g), 256, 0, st>>>(c.at<T>(o.DQKV), c.at<float>(o.Rope), lo, D.T, D.H + D.Hkv, D.dh, D.Nqkv);
   HIP_TRY(hipGetLastError());
   ARMT_TRY(bgemm<T>(c, TK_DN1, lo, g));
