@@ -8,8 +8,8 @@
 //   dq kernel:  a lane owns a query.  S^T = K Q^T and dP^T = V dO^T (keys along the rows), dS^T in registers,
 //               dQ^T += K^T dS^T.  K, V and K^T tiles of a KV head are shared in LDS by the waves of its query heads.
 //   dkv kernel: a lane owns a key.  S = Q K^T and dP = dO V^T (queries along the rows), P and dS in registers,
-//               dV^T += dO^T P, dK^T += Q^T dS.  Each wave takes one query head of the KV group and streams that head's
-//               Q, dO rows and Q^T, dO^T columns straight from global memory; the waves' sums are added through LDS.
+//               dV^T += dO^T P, dK^T += Q^T dS.  A wave keeps its 32 keys for the whole kernel and adds up all query
+//               heads of the KV group; the waves of a workgroup share the Q, dO, Q^T, dO^T tiles of the current head in LDS.
 // Operands with the sequence index contiguous (K^T, Q^T, dO^T) come from head_transpose_kernel.
 #pragma once
 
@@ -196,27 +196,32 @@ __global__ __launch_bounds__(512) void attention_bwd_dq_kernel(const bf16* __res
 }
 
 // dK, dV.  Qt, dOt: [cells][H][dh][Tp] (sequence index contiguous, zero padded); dQKV: k and v columns written here.
-// grid: (ceil(T / 32), Hkv, g), block: GROUP * 64; LDS: 2 * DH * 32 floats.
+// One workgroup = one KV head of one cell x 128 keys; wave w owns keys [32 w, 32 w + 32) of them (K, V rows in registers
+// as B operands) for the whole kernel and adds the contributions of all query heads of the KV group, one after the
+// other, in its registers: no reduction between waves or workgroups.  The four waves share the tiles of the current
+// (query head, 64 query rows): Q and dO rows, Q^T and dO^T columns, the rows' log-sum-exp and D, double buffered in LDS.
+// grid: (ceil(T / 128), Hkv, g), block: 256; LDS: 2 stages of 4 tiles + 512 bytes.
 template <int DH>
-__global__ __launch_bounds__(512) void attention_bwd_dkv_kernel(const bf16* __restrict__ QKV, const bf16* __restrict__ Qt,
+__global__ __launch_bounds__(256) void attention_bwd_dkv_kernel(const bf16* __restrict__ QKV, const bf16* __restrict__ Qt,
                                                                 const bf16* __restrict__ dO, const bf16* __restrict__ dOt,
                                                                 const float* __restrict__ LSE2, const float* __restrict__ Dv,
                                                                 bf16* __restrict__ dQKV, int first, int Trows, int Tp, int H,
                                                                 int Hkv, float scale) {
+  constexpr int Q_BYTES = 64 * DH * 2;             // one tile: 64 x DH or DH x 64 bf16
+  constexpr int STAGE = 4 * Q_BYTES + 512;         // Q, dO, Q^T, dO^T, then lse[64], D[64]
+  constexpr int Q_SLABS = Q_BYTES / 1024;
   constexpr int KS = DH / 16, OT = DH / 32;
-  extern __shared__ __align__(16) unsigned char smem[];
-  float* red = (float*)smem;                       // [2 * OT * 16][64]
+  extern __shared__ __align__(16) unsigned char smem[];   // [2][STAGE]
 
-  const int kt = blockIdx.x, kvh = blockIdx.y, l = first + blockIdx.z;
+  const int kb = blockIdx.x, kvh = blockIdx.y, l = first + blockIdx.z;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int nw = blockDim.x >> 6, group = H / Hkv;
-  const int head = kvh * group + wave;
+  const int group = H / Hkv;
   const int ldq = (H + 2 * Hkv) * DH, ldo = H * DH;
-  const int k0 = kt * 32;
-  const int kcol = lane & 31, half = lane >> 5;
+  const int k0 = kb * 128 + wave * 32;
+  const int half = lane >> 5;
   const float scale_log2e = scale * 1.4426950408889634f;
-  const int ki = k0 + kcol;
+  const int ki = k0 + (lane & 31);
 
   const bf16* cell = QKV + (size_t)l * Trows * ldq;
   const bf16* gcell = dO + (size_t)l * Trows * ldo;
@@ -231,75 +236,107 @@ __global__ __launch_bounds__(512) void attention_bwd_dkv_kernel(const bf16* __re
       vf[ks] = *(const bf16x8*)(vp + ks * 16);
     }
   }
-  const bf16* qt_base = Qt + (size_t)(l * H + head) * DH * Tp;
-  const bf16* gt_base = dOt + (size_t)(l * H + head) * DH * Tp;
-  const float* lse = LSE2 + ((size_t)l * H + head) * Trows;
-  const float* dvec = Dv + ((size_t)l * H + head) * Trows;
 
+  const int qt_first = 2 * kb;                     // first 64-row query tile that can see these keys
+  const int nq = Tp / 64 - qt_first;               // query tiles per head
+  const int iters = group * nq;
+  const int R = lane >> 3, pc = lane & 7;
+  auto issue_tile = [&](int it, int buf) {
+    typedef const __attribute__((address_space(1))) void* gptr_t;
+    typedef __attribute__((address_space(3))) void* lptr_t;
+    const int head = kvh * group + it / nq, q0 = (qt_first + it % nq) * 64;
+    unsigned char* base = smem + buf * STAGE;
+    const char* qrows = (const char*)(cell + head * DH);
+    const char* grows = (const char*)(gcell + head * DH);
+    const char* qcols = (const char*)(Qt + (size_t)(l * H + head) * DH * Tp);
+    const char* gcols = (const char*)(dOt + (size_t)(l * H + head) * DH * Tp);
+    for (int sl = wave; sl < 4 * Q_SLABS; sl += 4) {
+      const int which = sl / Q_SLABS, s2 = sl - which * Q_SLABS;
+      const char* src;
+      if (which < 2) {           // rows of Q / dO: DH / 64 sub-tiles [64 rows][64 dims]
+        const int sub = s2 >> 3, row = (s2 & 7) * 8 + R;
+        const int q = min(q0 + row, Trows - 1);
+        src = (which == 0 ? qrows + (size_t)q * ldq * 2 : grows + (size_t)q * ldo * 2) + (sub * 64 + ((pc ^ mf_swz(row)) << 3)) * 2;
+      } else {                   // columns: [DH dims][64 rows of the sequence]
+        const int row = s2 * 8 + R;
+        src = (which == 2 ? qcols : gcols) + ((size_t)row * Tp + q0 + ((pc ^ mf_swz(row)) << 3)) * 2;
+      }
+      __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(base + sl * 1024), 16, 0, 0);
+    }
+    if (threadIdx.x < 128) {
+      const int j = threadIdx.x & 63, q = min(q0 + j, Trows - 1);
+      const float* srcf = (threadIdx.x < 64 ? LSE2 : Dv) + ((size_t)l * H + head) * Trows;
+      ((float*)(base + 4 * Q_BYTES))[threadIdx.x] = srcf[q];
+    }
+  };
+
+  const int fl = mf_swz(lane & 31);
   f32x16 dk[OT], dv[OT];
 #pragma unroll
   for (int t = 0; t < OT; ++t)
 #pragma unroll
     for (int r = 0; r < 16; ++r) dk[t][r] = dv[t][r] = 0.f;
 
-  const int nqt = (Trows + 31) / 32;
-  for (int qt = kt; qt < nqt; ++qt) {
-    const int q0 = qt * 32;
-    const int arow = min(q0 + (lane & 31), Trows - 1);
-    const bf16* qp = cell + (size_t)arow * ldq + head * DH + half * 8;
-    const bf16* gp = gcell + (size_t)arow * ldo + head * DH + half * 8;
-    f32x16 s, dp;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(qp + ks * 16), kf[ks], s, 0, 0, 0);
-      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(gp + ks * 16), vf[ks], dp, 0, 0, 0);
-    }
-    bf16x8 pf[2], dsf[2];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int q = q0 + 8 * (r >> 2) + 4 * half + (r & 3);
-      const int qc = min(q, Trows - 1);
-      const bool live = q < Trows && ki <= q;
-      const float p = live ? __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2e, -lse[qc])) : 0.f;
-      pf[r >> 3][r & 7] = (bf16)p;
-      dsf[r >> 3][r & 7] = (bf16)(p * (dp[r] - dvec[qc]) * scale);
-    }
-    // dV^T[dim][key] += dO^T[dim][query] P[query][key],  dK^T[dim][key] += Q^T[dim][query] dS[query][key];
-    // k-step ss covers queries q0 + 16 ss + {4 half + 0..3, 8 + 4 half + 0..3}
-#pragma unroll
-    for (int t = 0; t < OT; ++t) {
-      const size_t roff = (size_t)(t * 32 + (lane & 31)) * Tp + q0 + 4 * half;
-#pragma unroll
-      for (int ss = 0; ss < 2; ++ss) {
-        const bf16x4 glo = *(const bf16x4*)(gt_base + roff + 16 * ss), ghi = *(const bf16x4*)(gt_base + roff + 16 * ss + 8);
-        const bf16x4 qlo = *(const bf16x4*)(qt_base + roff + 16 * ss), qhi = *(const bf16x4*)(qt_base + roff + 16 * ss + 8);
-        bf16x8 ga, qa;
-        ga[0] = glo[0]; ga[1] = glo[1]; ga[2] = glo[2]; ga[3] = glo[3]; ga[4] = ghi[0]; ga[5] = ghi[1]; ga[6] = ghi[2]; ga[7] = ghi[3];
-        qa[0] = qlo[0]; qa[1] = qlo[1]; qa[2] = qlo[2]; qa[3] = qlo[3]; qa[4] = qhi[0]; qa[5] = qhi[1]; qa[6] = qhi[2]; qa[7] = qhi[3];
-        dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, pf[ss], dv[t], 0, 0, 0);
-        dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, dsf[ss], dk[t], 0, 0, 0);
-      }
-    }
-  }
+  issue_tile(0, 0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  __syncthreads();
 
-  // add the query heads of the group: the waves add their registers into one LDS image in turn
-  for (int ww = 0; ww < nw; ++ww) {
-    if (wave == ww) {
+  for (int it = 0; it < iters; ++it) {
+    const int cur = it & 1, q0 = (qt_first + it % nq) * 64;
+    if (it + 1 < iters) issue_tile(it + 1, cur ^ 1);
+    const unsigned char* Qs = smem + cur * STAGE;
+    const unsigned char* Gs = Qs + Q_BYTES;
+    const unsigned char* QTs = Qs + 2 * Q_BYTES;
+    const unsigned char* GTs = Qs + 3 * Q_BYTES;
+    const float* sL = (const float*)(Qs + 4 * Q_BYTES);
+    const float* sD = sL + 64;
+    if (k0 <= q0 + 63 && k0 < Trows) {             // wave-uniform: some query of the tile can see some key of this wave
 #pragma unroll
-      for (int t = 0; t < OT; ++t)
+      for (int jj = 0; jj < 2; ++jj) {
+        if (q0 + jj * 32 + 31 < k0) continue;      // this half of the tile lies before the keys
+        f32x16 s, dp;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
+        const int roff = (jj * 32 + (lane & 31)) * MF_ROW_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const int off = roff + (ks >> 2) * (64 * MF_ROW_BYTES) + (((2 * (ks & 3) + half) ^ fl) << 4);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(Qs + off), kf[ks], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(Gs + off), vf[ks], dp, 0, 0, 0);
+        }
+        bf16x8 pf[2], dsf[2];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float* a = red + ((t * 16 + r) * 64 + lane);
-          float* b = red + ((OT * 16 + t * 16 + r) * 64 + lane);
-          *a = (ww ? *a : 0.f) + dk[t][r];
-          *b = (ww ? *b : 0.f) + dv[t][r];
+          const int j = jj * 32 + 8 * (r >> 2) + 4 * half + (r & 3), q = q0 + j;
+          const bool live = q < Trows && ki <= q;
+          const float p = live ? __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2e, -sL[j])) : 0.f;
+          pf[r >> 3][r & 7] = (bf16)p;
+          dsf[r >> 3][r & 7] = (bf16)(p * (dp[r] - sD[j]) * scale);
         }
+        // dV^T[dim][key] += dO^T[dim][query] P[query][key],  dK^T[dim][key] += Q^T[dim][query] dS[query][key]
+#pragma unroll
+        for (int t = 0; t < OT; ++t) {
+          const int toff = (t * 32 + (lane & 31)) * MF_ROW_BYTES + 8 * half;
+#pragma unroll
+          for (int ss = 0; ss < 2; ++ss) {
+            const int ch = jj * 4 + 2 * ss;
+            const int o0 = toff + ((ch ^ fl) << 4), o1 = toff + (((ch + 1) ^ fl) << 4);
+            const bf16x4 glo = *(const bf16x4*)(GTs + o0), ghi = *(const bf16x4*)(GTs + o1);
+            const bf16x4 qlo = *(const bf16x4*)(QTs + o0), qhi = *(const bf16x4*)(QTs + o1);
+            bf16x8 ga, qa;
+            ga[0] = glo[0]; ga[1] = glo[1]; ga[2] = glo[2]; ga[3] = glo[3]; ga[4] = ghi[0]; ga[5] = ghi[1]; ga[6] = ghi[2]; ga[7] = ghi[3];
+            qa[0] = qlo[0]; qa[1] = qlo[1]; qa[2] = qlo[2]; qa[3] = qlo[3]; qa[4] = qhi[0]; qa[5] = qhi[1]; qa[6] = qhi[2]; qa[7] = qhi[3];
+            dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, pf[ss], dv[t], 0, 0, 0);
+            dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, dsf[ss], dk[t], 0, 0, 0);
+          }
+        }
+      }
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
   }
-  if (wave == 0 && ki < Trows) {
+
+  if (ki < Trows) {
     bf16* dkp = dQKV + ((size_t)l * Trows + ki) * ldq + (H + kvh) * DH;
     bf16* dvp = dQKV + ((size_t)l * Trows + ki) * ldq + (H + Hkv + kvh) * DH;
 #pragma unroll
@@ -309,8 +346,8 @@ __global__ __launch_bounds__(512) void attention_bwd_dkv_kernel(const bf16* __re
         bf16x4 a, b;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          a[e] = (bf16)red[(t * 16 + 4 * rg + e) * 64 + lane];
-          b[e] = (bf16)red[(OT * 16 + t * 16 + 4 * rg + e) * 64 + lane];
+          a[e] = (bf16)dk[t][4 * rg + e];
+          b[e] = (bf16)dv[t][4 * rg + e];
         }
         *(bf16x4*)(dkp + t * 32 + 8 * rg + 4 * half) = a;
         *(bf16x4*)(dvp + t * 32 + 8 * rg + 4 * half) = b;
@@ -339,20 +376,23 @@ inline hipError_t launch_attention_bwd_mfma(const bf16* QKV, const bf16* O, cons
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const float scale = 1.0f / sqrtf((float)dh);
-  const dim3 grid((Trows + 31) / 32, Hkv, g);
+  const dim3 grid((Trows + 31) / 32, Hkv, g), gkv((Trows + 127) / 128, Hkv, g);
   if (dh == 64) {
     attention_bwd_dq_kernel<64><<<grid, group * 64, 2 * 3 * (64 * 64 * 2), st>>>(QKV, Kt, dO, LSE2, Dv, dQKV, first, Trows, Tp, H, Hkv,
                                                                               scale);
-    attention_bwd_dkv_kernel<64><<<grid, group * 64, 2 * 64 * 32 * 4, st>>>(QKV, Qt, dO, Gt, LSE2, Dv, dQKV, first, Trows, Tp, H, Hkv,
-                                                                          scale);
+    attention_bwd_dkv_kernel<64><<<gkv, 256, 2 * (4 * 64 * 64 * 2 + 512), st>>>(QKV, Qt, dO, Gt, LSE2, Dv, dQKV, first, Trows, Tp, H, Hkv,
+                                                                              scale);
   } else {
     hipError_t a = hipFuncSetAttribute((const void*)attention_bwd_dq_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        2 * 3 * (64 * 128 * 2));
     if (a != hipSuccess) return a;
     attention_bwd_dq_kernel<128><<<grid, group * 64, 2 * 3 * (64 * 128 * 2), st>>>(QKV, Kt, dO, LSE2, Dv, dQKV, first, Trows, Tp, H,
                                                                                 Hkv, scale);
-    attention_bwd_dkv_kernel<128><<<grid, group * 64, 2 * 128 * 32 * 4, st>>>(QKV, Qt, dO, Gt, LSE2, Dv, dQKV, first, Trows, Tp, H, Hkv,
-                                                                            scale);
+    a = hipFuncSetAttribute((const void*)attention_bwd_dkv_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            2 * (4 * 64 * 128 * 2 + 512));
+    if (a != hipSuccess) return a;
+    attention_bwd_dkv_kernel<128><<<gkv, 256, 2 * (4 * 64 * 128 * 2 + 512), st>>>(QKV, Qt, dO, Gt, LSE2, Dv, dQKV, first, Trows, Tp, H,
+                                                                                Hkv, scale);
   }
   return hipGetLastError();
 }

@@ -29,7 +29,7 @@ struct TrainLayout {
   size_t Xin, X1, Xb, N1, N2, RStd1, RStd2, QKV, Vt, Att, Hres, GU, Uff, Yf, Yb, Qm, Fphi, RDen, KVm, Fm, Coef, Rope;
   size_t Aw, zw, A16w, ATr;
   size_t DX, DYb, DU, DN, DH, DHb, DAtt, DQKV, LSE, Dv, AttS, DNum, DF, DDen, DQr, DKV, DV, Part, DB, DZF, DA, DZ;
-  size_t TA, TB, TmA, TmB;
+  size_t TA, TB, TmA, TmB, CPart;
   size_t WdT, WguT, WoT, WqkvT, WmqT, WmkvT;
   size_t Ptrs, Tables, Aux, total;
   int Tp, mp, dmP, Kmkv, nblk;
@@ -97,6 +97,7 @@ TrainLayout carve_train(const Dims& D) {
   o.TB = take(L * o.tb_rows * o.Tp * e);
   o.TmA = take(L * (size_t)(D.dm + D.d) * o.mp * e);
   o.TmB = take(L * d * o.mp * e);
+  o.CPart = take(L * CS_CHUNKS * std::max(d, (size_t)D.Phi) * 4);
   o.WdT = take(L * F * d * e);
   o.WguT = take(L * d * 2 * F * e);
   o.WoT = take(L * Hd * d * e);
@@ -306,6 +307,18 @@ armt_status bgemm(const BCtx& c, int kind, int first, int g) {
   return gemm<T>(c.st, c.table(kind), first, g, c.shape[kind]);
 }
 
+// dst[cell][col] += sum over the T rows of w[row] a[row, col] (b ? b[row, col] : 1), rows added in a fixed order.
+template <typename T>
+armt_status colsum(const BCtx& c, const T* a, const float* b, size_t b_cell, const float* w, float* const* dst_tab, float* dst_base,
+                   int first, int g, int C) {
+  if (g <= 0) return ARMT_OK;
+  float* part = c.at<float>(c.o.CPart);
+  colsum_partial_kernel<T><<<dim3((C + 255) / 256, g, CS_CHUNKS), 256, 0, c.st>>>(a, b, b_cell, w, part, first, c.D.T, C);
+  colsum_finish_kernel<<<dim3((C + 255) / 256, g), 256, 0, c.st>>>(part, CS_CHUNKS, dst_tab, dst_base, first, C);
+  HIP_TRY(hipGetLastError());
+  return ARMT_OK;
+}
+
 // Forward of the cells [lo, lo + g) from their restored inputs, every intermediate kept.  The first gr cells read
 // their memory; cells [e0, e1) meet an empty one.
 template <typename T>
@@ -419,8 +432,7 @@ armt_status backward_group(const BCtx& c, int lo, int g, int gr) {
   ARMT_TRY((transpose<T, T>(st, c.at<T>(o.N2) + lo * cell, cell, D.d, TB, tb_cell, Tp, D.T, D.d, g)));
   ARMT_TRY(bgemm<T>(c, TK_WG, lo, g));
   ARMT_TRY(bgemm<T>(c, TK_WU, lo, g));
-  gain_grad_kernel<T><<<dim3((D.d + 255) / 256, g), 256, 0, st>>>(c.at<T>(o.DN), c.at<float>(o.Hres), cell, c.at<float>(o.RStd2),
-                                                                c.dg2, lo, D.T, D.d);
+  ARMT_TRY(colsum<T>(c, c.at<T>(o.DN), c.at<float>(o.Hres), cell, c.at<float>(o.RStd2), c.dg2, nullptr, lo, g, D.d));   // d gain 2
   rmsnorm_bwd_kernel<T><<<dim3(D.T, g), 256, 0, st>>>(c.at<T>(o.DN), c.at<float>(o.Hres), cell, c.aux, lo, 1, c.at<float>(o.RStd2),
                                                      DX + cell, cell, c.at<float>(o.DH), cell, c.at<T>(o.DHb), D.T, D.d);
   HIP_TRY(hipGetLastError());
@@ -450,8 +462,7 @@ armt_status backward_group(const BCtx& c, int lo, int g, int gr) {
   ARMT_TRY(bgemm<T>(c, TK_WQ, lo, g));
   ARMT_TRY(bgemm<T>(c, TK_WK, lo, g));
   ARMT_TRY(bgemm<T>(c, TK_WV, lo, g));
-  gain_grad_kernel<T><<<dim3((D.d + 255) / 256, g), 256, 0, st>>>(c.at<T>(o.DN), c.at<float>(o.X1), cell, c.at<float>(o.RStd1),
-                                                                c.dg1, lo, D.T, D.d);
+  ARMT_TRY(colsum<T>(c, c.at<T>(o.DN), c.at<float>(o.X1), cell, c.at<float>(o.RStd1), c.dg1, nullptr, lo, g, D.d));     // d gain 1
   rmsnorm_bwd_kernel<T><<<dim3(D.T, g), 256, 0, st>>>(c.at<T>(o.DN), c.at<float>(o.X1), cell, c.aux, lo, 0, c.at<float>(o.RStd1),
                                                      c.at<float>(o.DH), cell, DX, cell, (T*)nullptr, D.T, D.d);
   HIP_TRY(hipGetLastError());
@@ -465,9 +476,9 @@ armt_status backward_group(const BCtx& c, int lo, int g, int gr) {
     ARMT_TRY(bgemm<T>(c, TK_DF, lo, gr));
     read_bwd_dpfp_kernel<T><<<dim3(D.T, gr), 128, (D.dm + Phi) * 4, st>>>(c.at<float>(o.Qm), c.at<float>(o.DF), c.at<float>(o.DDen),
                                                                          c.aux, lo, D.T, D.dm, D.nu, c.at<T>(o.DQr), o.dmP);
-    read_bwd_dz_kernel<T><<<dim3((Phi + 255) / 256, gr), 256, 0, st>>>(c.at<T>(o.Fphi), c.at<float>(o.DDen), c.at<float>(o.DZ), lo,
-                                                                      D.T, Phi);
     HIP_TRY(hipGetLastError());
+    // dz += sum_i dden_i f_i over the rows of the cell
+    ARMT_TRY(colsum<T>(c, c.at<T>(o.Fphi), nullptr, 0, c.at<float>(o.DDen), nullptr, c.at<float>(o.DZ), lo, gr, Phi));
     ARMT_TRY((transpose<T, T>(st, c.at<T>(o.DNum) + lo * cell, cell, D.d, TA, ta_cell, Tp, D.T, D.d, gr)));
     ARMT_TRY((transpose<T, T>(st, c.at<T>(o.Fphi) + (size_t)lo * D.T * Phi, (size_t)D.T * Phi, Phi, TB, tb_cell, Tp, D.T, Phi, gr)));
     ARMT_TRY(bgemm<T>(c, TK_DA, lo, gr));

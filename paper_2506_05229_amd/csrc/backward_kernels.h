@@ -85,20 +85,42 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
   }
 }
 
-// Gradient of a norm gain: dgain[c] += sum_i dn[i, c] x[i, c] rstd[i].  One thread per column, rows in order
-// (deterministic).  dgain: per-layer pointer table entry.  grid: (ceil(d / 256), g), block: 256.
+// Column sums over the T rows of a cell, in two deterministic stages.  Stage 1: the rows are cut into gridDim.z
+// chunks; a thread owns a column and adds its chunk's rows in order:
+//   part[cell][chunk][c] = sum_{i in chunk} w[i] a[i, c] (b ? b[i, c] : 1).
+// Stage 2 (colsum_finish_kernel) adds the chunks in order into the destination.
+// a: [cells][T][C] activation type; b: fp32 with its own cell stride (or null); w: [cells][T].
+// grid: (ceil(C / 256), g, chunks), block: 256.
+constexpr int CS_CHUNKS = 16;
 template <typename T>
-__global__ __launch_bounds__(256) void gain_grad_kernel(const T* __restrict__ dN, const float* __restrict__ X, size_t x_cell,
-                                                        const float* __restrict__ rstd_all, float* const* __restrict__ dgain,
-                                                        int first, int Trows, int d) {
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict__ a, const float* __restrict__ b, size_t b_cell,
+                                                             const float* __restrict__ w, float* __restrict__ part, int first,
+                                                             int Trows, int C) {
   const int l = first + blockIdx.y, c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= d) return;
-  const T* dn = dN + (size_t)l * Trows * d;
-  const float* x = X + (size_t)l * x_cell;
-  const float* rstd = rstd_all + (size_t)l * Trows;
+  if (c >= C) return;
+  const int per = (Trows + gridDim.z - 1) / gridDim.z;
+  const int i0 = blockIdx.z * per, i1 = min(Trows, i0 + per);
+  const T* ap = a + (size_t)l * Trows * C;
+  const float* bp = b ? b + (size_t)l * b_cell : nullptr;
+  const float* wp = w + (size_t)l * Trows;
   float s = 0.f;
-  for (int i = 0; i < Trows; ++i) s = fmaf(to_f32(dn[(size_t)i * d + c]) * x[(size_t)i * d + c], rstd[i], s);
-  dgain[l][c] += s;
+  for (int i = i0; i < i1; ++i) {
+    const float v = to_f32(ap[(size_t)i * C + c]) * (bp ? bp[(size_t)i * C + c] : 1.f);
+    s = fmaf(v, wp[i], s);
+  }
+  part[((size_t)l * gridDim.z + blockIdx.z) * C + c] = s;
+}
+
+// dst[c] += sum_chunks part[cell][chunk][c]; dst = dst_tab[cell] if a pointer table is given, else dst_base + cell * C.
+// grid: (ceil(C / 256), g), block: 256.
+__global__ __launch_bounds__(256) void colsum_finish_kernel(const float* __restrict__ part, int chunks, float* const* __restrict__ dst_tab,
+                                                            float* __restrict__ dst_base, int first, int C) {
+  const int l = first + blockIdx.y, c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  float s = 0.f;
+  for (int k = 0; k < chunks; ++k) s += part[((size_t)l * chunks + k) * C + c];
+  float* dst = dst_tab ? dst_tab[l] : dst_base + (size_t)l * C;
+  dst[c] += s;
 }
 
 // u = silu(gate) * up from the stored [gate | up] rows.  GU: [cells][T][2F]; U: [cells][T][F].
@@ -336,17 +358,6 @@ __global__ __launch_bounds__(128) void read_bwd_dpfp_kernel(const float* __restr
   for (int c = threadIdx.x; c < Phi; c += blockDim.x) df[c] = fmaf(dden, z[c], DF[r * Phi + c]);
   __syncthreads();
   for (int c = threadIdx.x; c < dm; c += blockDim.x) DQ[r * ldq + c] = from_f32<T>(dpfp_dk(k, df, dm, nu, c));
-}
-
-// dz[c] += sum_i dden_i f_i[c] over the T rows of the cell.  grid: (ceil(Phi / 256), g), block: 256.
-template <typename T>
-__global__ __launch_bounds__(256) void read_bwd_dz_kernel(const T* __restrict__ Fphi, const float* __restrict__ DDen,
-                                                          float* __restrict__ DZ, int first, int Trows, int Phi) {
-  const int l = first + blockIdx.y, c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= Phi) return;
-  float s = 0.f;
-  for (int i = 0; i < Trows; ++i) s = fmaf(DDen[(size_t)l * Trows + i], to_f32(Fphi[((size_t)l * Trows + i) * Phi + c]), s);
-  DZ[(size_t)l * Phi + c] += s;
 }
 
 // ------------------------------------------------------------------------------------------------
