@@ -41,6 +41,11 @@ def cpu_baseline(shape, layers, mem_emb, x, n_seg):
             "sample": f"first {n_seg} segments ({n_tok} tokens) of the same workload, float64 numpy, {dt:.1f} s"}
 
 
+def C_byref(x):
+    import ctypes
+    return ctypes.byref(x)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -54,6 +59,8 @@ def main():
     ap.add_argument("--no-lm-head", action="store_true",
                     help="skip the extra timing of the token-level ends (embedding gather, final norm + head)")
     ap.add_argument("--cpu-segments", type=int, default=4)
+    ap.add_argument("--no-train", action="store_true",
+                    help="skip the training leg (forward with tape + backward pass; reported under `training`, not in `value`)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of known size (the memory-state carry-in copy), so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled against it")
@@ -174,6 +181,37 @@ def main():
             "tokens_per_s_ids_to_last_segment_logits": n_tok / ((wall_ms + ms_embed + ms_last) / 1e3),
             "tokens_per_s_ids_to_all_logits_extrapolated": n_tok / ((wall_ms + ms_embed + ms_all) / 1e3)}
         del lg_last, lg_big, te
+    if not args.no_train and B == 1 and P.load_library().armt_backward_workspace_bytes(C_byref(model.cfg)) > 0:
+        # Training leg (outside `value`): forward that records the tape, then the backward pass in reverse diagonal
+        # order, for an upstream gradient on every hidden state; one warm-up, one timed pass of each.
+        gh = torch.randn(shape.n_tokens, shape.d_model, device="cuda",
+                         generator=torch.Generator(device="cuda").manual_seed(1)).to(model.act_dtype)
+        grads, t_f, t_b, t_bs = None, 0.0, 0.0, None
+        for rep in range(2):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            _, _, _, tape = model.forward_train(xd, diagonal=True)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            grads = model.backward(tape, shape.n_tokens, gh, diagonal=True, want_dx=False, grads=grads)
+            torch.cuda.synchronize()
+            t_f, t_b = t1 - t0, time.perf_counter() - t1
+        if not args.no_sequential:
+            t0 = time.perf_counter()
+            model.backward(tape, shape.n_tokens, gh, diagonal=False, want_dx=False, grads=grads)
+            torch.cuda.synchronize()
+            t_bs = time.perf_counter() - t0
+        res["training"] = {
+            "forward_with_tape_ms": t_f * 1e3, "backward_ms": t_b * 1e3,
+            "tokens_per_s_forward_backward": n_tok / (t_f + t_b),
+            "backward_over_forward": t_b / (wall_ms / 1e3),
+            "mfma_fraction_forward_backward": 4.0 * total_flops / (t_f + t_b) / 1e12 / MFMA_PEAK_TFLOPS,
+            "flops_counted": "forward + recomputed forward + 2 x forward for the gradients = 4 x algorithmic forward FLOPs",
+            "sequential_backward_ms": None if t_bs is None else t_bs * 1e3,
+            "backward_speedup_vs_sequential": None if t_bs is None else t_bs / t_b,
+            "tape_gb": tape.numel() / 1e9, "backward_workspace_gb": model.bwd_workspace.numel() / 1e9}
+        del tape, grads, gh
+        model.bwd_workspace = None
     if args.calibrate_copy:
         # copy_f32_kernel moves the whole memory state A_in -> A_out: n_layers * d_model * Phi floats read and written
         A_src, z_src = out[1].clone(), out[2].clone()

@@ -263,11 +263,10 @@ __global__ __launch_bounds__(256) void attention_bwd_dkv_kernel(const bf16* __re
       }
       __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(base + sl * 1024), 16, 0, 0);
     }
-    if (threadIdx.x < 128) {
-      const int j = threadIdx.x & 63, q = min(q0 + j, Trows - 1);
-      const float* srcf = (threadIdx.x < 64 ? LSE2 : Dv) + ((size_t)l * H + head) * Trows;
-      ((float*)(base + 4 * Q_BYTES))[threadIdx.x] = srcf[q];
-    }
+    if (wave < 2) {              // lse (wave 0) and D (wave 1) of the 64 rows, also as direct loads: a load through
+      const float* srcf = (wave == 0 ? LSE2 : Dv) + ((size_t)l * H + head) * Trows + min(q0 + lane, Trows - 1);   // registers
+      __builtin_amdgcn_global_load_lds((gptr_t)srcf, (lptr_t)(base + 4 * Q_BYTES + wave * 256), 4, 0, 0);         // would make the
+    }                            // wave wait for the whole prefetch before it starts on the current tile
   };
 
   const int fl = mf_swz(lane & 31);
