@@ -196,13 +196,14 @@ __global__ __launch_bounds__(512) void attention_bwd_dq_kernel(const bf16* __res
 }
 
 // dK, dV.  Qt, dOt: [cells][H][dh][Tp] (sequence index contiguous, zero padded); dQKV: k and v columns written here.
-// One workgroup = one KV head of one cell x 128 keys; wave w owns keys [32 w, 32 w + 32) of them (K, V rows in registers
+// One workgroup = one KV head of one cell x 256 keys; wave w (of 8) owns keys [32 w, 32 w + 32) of them (K, V rows in registers
 // as B operands) for the whole kernel and adds the contributions of all query heads of the KV group, one after the
-// other, in its registers: no reduction between waves or workgroups.  The four waves share the tiles of the current
+// other, in its registers: no reduction between waves or workgroups.  The eight waves share the tiles of the current
 // (query head, 64 query rows): Q and dO rows, Q^T and dO^T columns, the rows' log-sum-exp and D, double buffered in LDS.
-// grid: (ceil(T / 128), Hkv, g), block: 256; LDS: 2 stages of 4 tiles + 512 bytes.
+// grid: (ceil(T / 256), Hkv, g), block: 512; LDS: 2 stages of 4 tiles + 512 bytes.
+constexpr int DKV_WAVES = 8;
 template <int DH>
-__global__ __launch_bounds__(256) void attention_bwd_dkv_kernel(const bf16* __restrict__ QKV, const bf16* __restrict__ Qt,
+__global__ __launch_bounds__(512) void attention_bwd_dkv_kernel(const bf16* __restrict__ QKV, const bf16* __restrict__ Qt,
                                                                 const bf16* __restrict__ dO, const bf16* __restrict__ dOt,
                                                                 const float* __restrict__ LSE2, const float* __restrict__ Dv,
                                                                 bf16* __restrict__ dQKV, int first, int Trows, int Tp, int H,
@@ -218,7 +219,7 @@ __global__ __launch_bounds__(256) void attention_bwd_dkv_kernel(const bf16* __re
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int group = H / Hkv;
   const int ldq = (H + 2 * Hkv) * DH, ldo = H * DH;
-  const int k0 = kb * 128 + wave * 32;
+  const int k0 = kb * (32 * DKV_WAVES) + wave * 32;
   const int half = lane >> 5;
   const float scale_log2e = scale * 1.4426950408889634f;
   const int ki = k0 + (lane & 31);
@@ -237,7 +238,7 @@ __global__ __launch_bounds__(256) void attention_bwd_dkv_kernel(const bf16* __re
     }
   }
 
-  const int qt_first = 2 * kb;                     // first 64-row query tile that can see these keys
+  const int qt_first = kb * (DKV_WAVES / 2);       // first 64-row query tile that can see these keys
   const int nq = Tp / 64 - qt_first;               // query tiles per head
   const int iters = group * nq;
   const int R = lane >> 3, pc = lane & 7;
@@ -250,7 +251,7 @@ __global__ __launch_bounds__(256) void attention_bwd_dkv_kernel(const bf16* __re
     const char* grows = (const char*)(gcell + head * DH);
     const char* qcols = (const char*)(Qt + (size_t)(l * H + head) * DH * Tp);
     const char* gcols = (const char*)(dOt + (size_t)(l * H + head) * DH * Tp);
-    for (int sl = wave; sl < 4 * Q_SLABS; sl += 4) {
+    for (int sl = wave; sl < 4 * Q_SLABS; sl += DKV_WAVES) {
       const int which = sl / Q_SLABS, s2 = sl - which * Q_SLABS;
       const char* src;
       if (which < 2) {           // rows of Q / dO: DH / 64 sub-tiles [64 rows][64 dims]
@@ -375,11 +376,11 @@ inline hipError_t launch_attention_bwd_mfma(const bf16* QKV, const bf16* O, cons
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const float scale = 1.0f / sqrtf((float)dh);
-  const dim3 grid((Trows + 31) / 32, Hkv, g), gkv((Trows + 127) / 128, Hkv, g);
+  const dim3 grid((Trows + 31) / 32, Hkv, g), gkv((Trows + 32 * DKV_WAVES - 1) / (32 * DKV_WAVES), Hkv, g);
   if (dh == 64) {
     attention_bwd_dq_kernel<64><<<grid, group * 64, 2 * 3 * (64 * 64 * 2), st>>>(QKV, Kt, dO, LSE2, Dv, dQKV, first, Trows, Tp, H, Hkv,
                                                                               scale);
-    attention_bwd_dkv_kernel<64><<<gkv, 256, 2 * (4 * 64 * 64 * 2 + 512), st>>>(QKV, Qt, dO, Gt, LSE2, Dv, dQKV, first, Trows, Tp, H, Hkv,
+    attention_bwd_dkv_kernel<64><<<gkv, 64 * DKV_WAVES, 2 * (4 * 64 * 64 * 2 + 512), st>>>(QKV, Qt, dO, Gt, LSE2, Dv, dQKV, first, Trows, Tp, H, Hkv,
                                                                               scale);
   } else {
     hipError_t a = hipFuncSetAttribute((const void*)attention_bwd_dq_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -390,7 +391,7 @@ inline hipError_t launch_attention_bwd_mfma(const bf16* QKV, const bf16* O, cons
     a = hipFuncSetAttribute((const void*)attention_bwd_dkv_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             2 * (4 * 64 * 128 * 2 + 512));
     if (a != hipSuccess) return a;
-    attention_bwd_dkv_kernel<128><<<gkv, 256, 2 * (4 * 64 * 128 * 2 + 512), st>>>(QKV, Qt, dO, Gt, LSE2, Dv, dQKV, first, Trows, Tp, H,
+    attention_bwd_dkv_kernel<128><<<gkv, 64 * DKV_WAVES, 2 * (4 * 64 * 128 * 2 + 512), st>>>(QKV, Qt, dO, Gt, LSE2, Dv, dQKV, first, Trows, Tp, H,
                                                                                 Hkv, scale);
   }
   return hipGetLastError();

@@ -153,7 +153,7 @@ void fill_train_shapes(BCtx& c) {
   set(TK_QKV, D.T, D.Nqkv, D.d, D.d, D.Nqkv, EPI_STORE_ACT, Hd, Hkd);
   set(TK_O, D.T, D.d, Hd, Hd, D.d, EPI_RESID_F32);
   set(TK_GU, D.T, 2 * D.F, D.d, D.d, 2 * D.F, EPI_STORE_ACT, D.F, D.F);
-  set(TK_DOWN, D.T, D.d, D.F, D.F, D.d, EPI_RESID_F32);
+  set(TK_DOWN, D.m, D.d, D.F, D.F, D.d, EPI_RESID_F32);      // only the memory rows of the block's output are needed again
   if (D.bf16) c.shape[TK_DOWN].ldc2 = D.d;
   set(TK_MKV, D.m, D.dm + D.d, D.d, D.d, D.dm + D.d, EPI_STORE_F32, D.dm, D.d);
   set(TK_DYM, D.m, D.d, o.Kmkv, o.Kmkv, D.d, EPI_RESID_F32);
@@ -208,8 +208,9 @@ armt_status upload_train_tables(BCtx& c, const armt_layer_weights* W, const armt
     g->C = ws + o.QKV + l * T * D.Nqkv * e;
     g = E(TK_O); g->A = ws + o.Att + l * T * Hd * e; g->B0 = w.wo; g->C = ws + o.Hres + l * T * d * 4; g->R = (const float*)X1;
     g = E(TK_GU); g->A = ws + o.N2 + l * T * d * e; g->B0 = w.wgate; g->B1 = w.wup; g->C = ws + o.GU + l * T * 2 * F * e;
-    g = E(TK_DOWN); g->A = ws + o.Uff + l * T * F * e; g->B0 = w.wdown; g->C = ws + o.Yf + l * T * d * 4;
-    g->C2 = D.bf16 ? ws + o.Yb + l * T * d * 2 : nullptr; g->R = (const float*)(ws + o.Hres + l * T * d * 4);
+    const size_t mrow = (size_t)D.S;      // first memory row
+    g = E(TK_DOWN); g->A = ws + o.Uff + (l * T + mrow) * F * e; g->B0 = w.wdown; g->C = ws + o.Yf + (l * T + mrow) * d * 4;
+    g->C2 = D.bf16 ? ws + o.Yb + (l * T + mrow) * d * 2 : nullptr; g->R = (const float*)(ws + o.Hres + (l * T + mrow) * d * 4);
     g = E(TK_MKV); g->A = Yop + (size_t)D.S * d * e; g->B0 = w.wm_k; g->B1 = w.wm_v;
     g->C = ws + o.KVm + l * D.m * (size_t)(D.dm + D.d) * 4;
 
@@ -256,6 +257,14 @@ template <typename Tin, typename Tout>
 armt_status transpose(hipStream_t st, const Tin* src, size_t src_cell, int lds, Tout* dst, size_t dst_cell, int ldd, int R, int C,
                       int g) {
   if (g <= 0 || R <= 0 || C <= 0) return ARMT_OK;
+  if constexpr (std::is_same<Tin, bf16>::value && std::is_same<Tout, bf16>::value) {
+    if (C % 8 == 0 && lds % 8 == 0 && ldd % 8 == 0 && src_cell % 8 == 0 && dst_cell % 8 == 0 && ((uintptr_t)src % 16) == 0 &&
+        ((uintptr_t)dst % 16) == 0) {
+      transpose_bf16_kernel<<<dim3((C + 63) / 64, (R + 63) / 64, g), 256, 0, st>>>(src, src_cell, lds, dst, dst_cell, ldd, R, C);
+      HIP_TRY(hipGetLastError());
+      return ARMT_OK;
+    }
+  }
   transpose_kernel<Tin, Tout><<<dim3((C + 31) / 32, (R + 31) / 32, g), dim3(32, 8), 0, st>>>(src, src_cell, lds, dst, dst_cell, ldd,
                                                                                           R, C);
   HIP_TRY(hipGetLastError());

@@ -31,6 +31,40 @@ __global__ __launch_bounds__(256) void transpose_kernel(const Tin* __restrict__ 
   }
 }
 
+// The same for bf16 -> bf16 with 16-byte accesses on both sides: 64 x 64 tiles through LDS (row stride 66 keeps the
+// column reads of the second phase on distinct banks).  Needs C, lds, ldd multiples of 8 and 16-byte aligned bases;
+// rows [R, ldd) of a tile are written as zeros, which is what the padding columns of dst must hold anyway.
+// grid: (ceil(C / 64), ceil(R / 64), g), block: 256.
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16* __restrict__ src, size_t src_cell, int lds,
+                                                             bf16* __restrict__ dst, size_t dst_cell, int ldd, int R, int C) {
+  __shared__ unsigned int tile[64 * 33];
+  const bf16* s = src + (size_t)blockIdx.z * src_cell;
+  bf16* o = dst + (size_t)blockIdx.z * dst_cell;
+  const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int idx = threadIdx.x + 256 * k, r = idx >> 3, ch = idx & 7;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (r0 + r < R && c0 + 8 * ch < C) v = *(const uint4*)(s + (size_t)(r0 + r) * lds + c0 + 8 * ch);
+    unsigned int* t = tile + r * 33 + 4 * ch;
+    t[0] = v.x; t[1] = v.y; t[2] = v.z; t[3] = v.w;
+  }
+  __syncthreads();
+  const unsigned short* th = (const unsigned short*)tile;
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int idx = threadIdx.x + 256 * k, c = idx >> 3, rch = idx & 7;
+    if (c0 + c >= C || r0 + 8 * rch + 7 >= ldd) continue;
+    unsigned int w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const unsigned int lo = th[(8 * rch + 2 * e) * 66 + c], hi = th[(8 * rch + 2 * e + 1) * 66 + c];
+      w[e] = lo | (hi << 16);
+    }
+    *(uint4*)(o + (size_t)(c0 + c) * ldd + r0 + 8 * rch) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
 template <typename Tin, typename Tout>
 __global__ void convert_kernel(const Tin* __restrict__ src, Tout* __restrict__ dst, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
