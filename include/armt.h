@@ -150,7 +150,7 @@ armt_status armt_forward_diagonal_batched(const armt_config *cfg, const armt_lay
  * sequential order; each step restores the inputs of its cells from the tape, recomputes their forward and runs the
  * backward kernels, so no activation other than the tape outlives a step.  `layers` must be the weights of the
  * forward call.  workspace: armt_backward_workspace_bytes(cfg) bytes, 256-byte aligned.
- * Supported here: n_mem <= 16, head_dim <= 128, and the limits of the forward calls; anything else is rejected with
+ * Supported here: head_dim <= 128, one sequence per call, and the limits of the forward calls; anything else is rejected with
  * ARMT_ERR_UNSUPPORTED (the size queries return 0).  Two cells of one layer never run in the same step, so the
  * accumulation into a layer's gradient buffers has a fixed order and the result is deterministic. */
 typedef struct {

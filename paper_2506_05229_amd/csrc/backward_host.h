@@ -118,10 +118,8 @@ size_t tape_record_floats(const Dims& D) {
 
 armt_status check_backward_config(const armt_config* cfg, Dims* D) {
   ARMT_TRY(check_config(cfg, D));
-  // the delta-rule backward keeps the partial feature gradients of all memory tokens in registers,
-  // the attention backward two head-dimension columns per lane
-  if (D->m > UB_M || D->dh > 128) return ARMT_ERR_UNSUPPORTED;
-  if (((size_t)D->m * D->Phi + (size_t)D->m * (D->Phi + 2)) * 4 > 64000) return ARMT_ERR_UNSUPPORTED;
+  // the attention backward kernels hold two head-dimension columns per lane
+  if (D->dh > 128) return ARMT_ERR_UNSUPPORTED;
   return ARMT_OK;
 }
 
@@ -395,7 +393,7 @@ armt_status backward_group(const BCtx& c, int lo, int g, int gr) {
   // ---- memory update (Eq. 3-5)
   {
     const dim3 grid(o.nblk, g);
-    const size_t lds = ((size_t)D.m * Phi + (size_t)D.m * (Phi + 2)) * 4;
+    const size_t lds = (size_t)UB_M * (2 * Phi + 2) * 4;
 #define ARMT_UB(NPL)                                                                                                      \
   case NPL:                                                                                                              \
     update_bwd_rows_kernel<NPL><<<grid, 256, lds, st>>>(c.at<float>(o.KVm), c.at<float>(o.Fm), c.at<float>(o.Coef),      \

@@ -404,7 +404,9 @@ __global__ __launch_bounds__(128) void read_bwd_dpfp_kernel(const float* __restr
 //        dden_i += beta_i v_bar_i[r] P_i[r] / den_i,   df_i[:] += beta_i (v_i[r] - v_bar_i[r]) G_old[r,:] + w_i[r] A[r,:]
 // Part[cells][blocks][m][Phi + 2] holds the partial df_i, dbeta_i, dden_i of every block.
 // Coef as written by memupd_prep_kernel ({beta, gamma, 1/den (0 = memory empty), z.f}).
-// grid: (ceil(d / UB_ROWS), g), block: 256; n_mem <= UB_M; Phi <= 64 * NPL; LDS: m * Phi + m * (Phi + 2) floats.
+// The memory tokens are taken in chunks of UB_M (their partial feature gradients live in registers); a wave re-reads
+// its rows of A and G for every chunk and writes G once at the end.
+// grid: (ceil(d / UB_ROWS), g), block: 256; Phi <= 64 * NPL; LDS: UB_M * (2 Phi + 2) floats.
 constexpr int UB_ROWS = 32, UB_M = 16;
 template <int NPL>
 __global__ __launch_bounds__(256) void update_bwd_rows_kernel(const float* __restrict__ KV, const float* __restrict__ Fm,
@@ -412,89 +414,108 @@ __global__ __launch_bounds__(256) void update_bwd_rows_kernel(const float* __res
                                                               const float* __restrict__ Aold, float* __restrict__ DA,
                                                               float* __restrict__ DV, float* __restrict__ Part, int first,
                                                               int m, int d, int dm, int Phi) {
+  constexpr int RPW = UB_ROWS / 4;             // rows per wave
   extern __shared__ float sm[];
-  float* F = sm;                               // [m][Phi]
-  float* acc = sm + (size_t)m * Phi;           // [m][Phi + 2]
+  float* F = sm;                               // [UB_M][Phi]: the f_i of the current chunk of memory tokens
+  float* acc = sm + (size_t)UB_M * Phi;        // [UB_M][Phi + 2]
   const int l = first + blockIdx.y, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const float* Fl = Fm + (size_t)l * m * Phi;
   const float* cf = Coef + (size_t)l * m * 4;
   const float* A = Aold + (size_t)l * d * Phi;
   float* G = DA + (size_t)l * d * Phi;
   const float* V = KV + (size_t)l * m * (dm + d) + dm;
-  for (int c = threadIdx.x; c < m * Phi; c += blockDim.x) F[c] = Fl[c];
-  __syncthreads();
-  float dfp[UB_M][NPL], db[UB_M], dd[UB_M];
-#pragma unroll
-  for (int i = 0; i < UB_M; ++i) {
-    db[i] = dd[i] = 0.f;
-#pragma unroll
-    for (int k = 0; k < NPL; ++k) dfp[i][k] = 0.f;
-  }
   const int r0 = blockIdx.x * UB_ROWS, r1 = min(d, r0 + UB_ROWS);
-  for (int r = r0 + w; r < r1; r += 4) {
-    float a[NPL], g[NPL], upd[NPL];
+  const int stride = Phi + 2;
+  float* out = Part + ((size_t)l * gridDim.x + blockIdx.x) * m * stride;
+  float upd[RPW][NPL];                         // sum_i w_i[r] f_i of this wave's rows, over all chunks
 #pragma unroll
-    for (int k = 0; k < NPL; ++k) {
-      const int c = lane + 64 * k;
-      a[k] = c < Phi ? A[(size_t)r * Phi + c] : 0.f;
-      g[k] = c < Phi ? G[(size_t)r * Phi + c] : 0.f;
-      upd[k] = 0.f;
-    }
+  for (int q = 0; q < RPW; ++q)
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) upd[q][k] = 0.f;
+
+  for (int i0 = 0; i0 < m; i0 += UB_M) {       // memory tokens in chunks of UB_M; G is only written after the last one
+    const int n = min(UB_M, m - i0);
+    __syncthreads();                           // the previous chunk's F and acc are no longer read
+    for (int c = threadIdx.x; c < n * Phi; c += blockDim.x) F[c] = Fl[(size_t)i0 * Phi + c];
+    __syncthreads();
+    float dfp[UB_M][NPL], db[UB_M], dd[UB_M];
 #pragma unroll
     for (int i = 0; i < UB_M; ++i) {
-      if (i >= m) continue;      // uniform; `continue` keeps the loop unrollable (dfp[][] must stay in registers)
-      float pa = 0.f, pg = 0.f;
+      db[i] = dd[i] = 0.f;
+#pragma unroll
+      for (int k = 0; k < NPL; ++k) dfp[i][k] = 0.f;
+    }
+#pragma unroll
+    for (int q = 0; q < RPW; ++q) {
+      const int r = r0 + w + 4 * q;
+      if (r >= r1) continue;                   // wave-uniform
+      float a[NPL], g[NPL];
 #pragma unroll
       for (int k = 0; k < NPL; ++k) {
         const int c = lane + 64 * k;
-        const float f = c < Phi ? F[i * Phi + c] : 0.f;
-        pa = fmaf(a[k], f, pa);
-        pg = fmaf(g[k], f, pg);
+        a[k] = c < Phi ? A[(size_t)r * Phi + c] : 0.f;
+        g[k] = c < Phi ? G[(size_t)r * Phi + c] : 0.f;
       }
-      pa = wave_sum(pa);
-      pg = wave_sum(pg);
-      const float beta = cf[i * 4 + 0], rden = cf[i * 4 + 2];
-      const float vbar = pa * rden, e = V[(size_t)i * (dm + d) + r] - vbar;
-      const float wi = -beta * pg * rden;
-      if (lane == 0) DV[((size_t)l * m + i) * d + r] = beta * pg;
-      db[i] = fmaf(e, pg, db[i]);
-      dd[i] = fmaf(beta * vbar * rden, pg, dd[i]);
-#pragma unroll
-      for (int k = 0; k < NPL; ++k) {
-        const int c = lane + 64 * k;
-        const float f = c < Phi ? F[i * Phi + c] : 0.f;
-        dfp[i][k] = fmaf(beta * e, g[k], fmaf(wi, a[k], dfp[i][k]));
-        upd[k] = fmaf(wi, f, upd[k]);
-      }
-    }
-#pragma unroll
-    for (int k = 0; k < NPL; ++k) {
-      const int c = lane + 64 * k;
-      if (c < Phi) G[(size_t)r * Phi + c] = g[k] + upd[k];
-    }
-  }
-  // the four waves' partial sums -> one partial per block (the waves add into one LDS image in turn)
-  const int stride = Phi + 2;
-  for (int ww = 0; ww < 4; ++ww) {
-    if (w == ww) {
 #pragma unroll
       for (int i = 0; i < UB_M; ++i) {
-        if (i >= m) continue;
+        if (i >= n) continue;                  // uniform; `continue` keeps the loop unrollable (dfp[][] stays in registers)
+        float pa = 0.f, pg = 0.f;
 #pragma unroll
         for (int k = 0; k < NPL; ++k) {
           const int c = lane + 64 * k;
-          if (c < Phi) acc[(size_t)i * stride + c] = (ww ? acc[(size_t)i * stride + c] : 0.f) + dfp[i][k];
+          const float f = c < Phi ? F[i * Phi + c] : 0.f;
+          pa = fmaf(a[k], f, pa);
+          pg = fmaf(g[k], f, pg);
         }
-        if (lane == 0) {
-          acc[(size_t)i * stride + Phi] = (ww ? acc[(size_t)i * stride + Phi] : 0.f) + db[i];
-          acc[(size_t)i * stride + Phi + 1] = (ww ? acc[(size_t)i * stride + Phi + 1] : 0.f) + dd[i];
+        pa = wave_sum(pa);
+        pg = wave_sum(pg);
+        const int it = i0 + i;
+        const float beta = cf[it * 4 + 0], rden = cf[it * 4 + 2];
+        const float vbar = pa * rden, e = V[(size_t)it * (dm + d) + r] - vbar;
+        const float wi = -beta * pg * rden;
+        if (lane == 0) DV[((size_t)l * m + it) * d + r] = beta * pg;
+        db[i] = fmaf(e, pg, db[i]);
+        dd[i] = fmaf(beta * vbar * rden, pg, dd[i]);
+#pragma unroll
+        for (int k = 0; k < NPL; ++k) {
+          const int c = lane + 64 * k;
+          const float f = c < Phi ? F[i * Phi + c] : 0.f;
+          dfp[i][k] = fmaf(beta * e, g[k], fmaf(wi, a[k], dfp[i][k]));
+          upd[q][k] = fmaf(wi, f, upd[q][k]);
         }
       }
     }
-    __syncthreads();
+    // the four waves' partial sums -> one partial per block (the waves add into one LDS image in turn)
+    for (int ww = 0; ww < 4; ++ww) {
+      if (w == ww) {
+#pragma unroll
+        for (int i = 0; i < UB_M; ++i) {
+          if (i >= n) continue;
+#pragma unroll
+          for (int k = 0; k < NPL; ++k) {
+            const int c = lane + 64 * k;
+            if (c < Phi) acc[(size_t)i * stride + c] = (ww ? acc[(size_t)i * stride + c] : 0.f) + dfp[i][k];
+          }
+          if (lane == 0) {
+            acc[(size_t)i * stride + Phi] = (ww ? acc[(size_t)i * stride + Phi] : 0.f) + db[i];
+            acc[(size_t)i * stride + Phi + 1] = (ww ? acc[(size_t)i * stride + Phi + 1] : 0.f) + dd[i];
+          }
+        }
+      }
+      __syncthreads();
+    }
+    for (int c = threadIdx.x; c < n * stride; c += blockDim.x) out[(size_t)i0 * stride + c] = acc[c];
   }
-  float* out = Part + ((size_t)l * gridDim.x + blockIdx.x) * m * stride;
-  for (int c = threadIdx.x; c < m * stride; c += blockDim.x) out[c] = acc[c];
+#pragma unroll
+  for (int q = 0; q < RPW; ++q) {
+    const int r = r0 + w + 4 * q;
+    if (r >= r1) continue;
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) {
+      const int c = lane + 64 * k;
+      if (c < Phi) G[(size_t)r * Phi + c] += upd[q][k];
+    }
+  }
 }
 
 // Part 2, one block per memory token i: sums the partials, adds the terms that come through z and gamma, pushes

@@ -218,7 +218,7 @@ def test_training_entry_argument_errors(lib):
     assert lib.armt_tape_bytes(C.byref(cfg), shape.n_tokens + 1) == 0 and lib.armt_tape_bytes(C.byref(cfg), 0) == 0
     ws_bytes = lib.armt_backward_workspace_bytes(C.byref(cfg))
     assert ws_bytes > 0 and ws_bytes % 256 == 0
-    big_m = _cfg(shape.replace(n_mem=24))                  # more memory tokens than the delta-rule backward holds
+    big_m = _cfg(shape.replace(d_model=256, n_heads=1, n_kv_heads=1, head_dim=256))   # heads wider than the attention backward holds
     assert lib.armt_tape_bytes(C.byref(big_m), shape.n_tokens) == 0 and lib.armt_backward_workspace_bytes(C.byref(big_m)) == 0
     layers = (P.ArmtLayerWeights * L)()
     grads = (P.ArmtLayerGrads * L)()

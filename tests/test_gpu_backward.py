@@ -134,6 +134,23 @@ def test_small_bf16_backward_matches_oracle(heads, diagonal):
     compare(got, want, BF16_REL, f"bf16 {heads} diag={diagonal}", tol_mem=BF16_REL_MEM)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_many_memory_tokens_backward_matches_oracle(dtype):
+    """n_mem above the 16 tokens the delta-rule backward holds at once: several chunks, the last one ragged (fp32)."""
+    if dtype == "f32":
+        shape = S.get_shape("tiny").replace(n_mem=40, n_tokens=4 * 64)
+    else:
+        shape = S.get_shape("tiny").replace(**dict(SMALL_BF16, n_mem=48, n_tokens=144 * 3))
+    shape, layers, mem_emb, x = well_conditioned(shape, seed=4)
+    Gs = upstream(shape, 4, with_state=True)
+    want = G.armt_grad(shape, layers, mem_emb, x, *Gs)
+    got = run_hip_grad(shape, layers, mem_emb, x, Gs, None, True)
+    if dtype == "f32":
+        compare(got, want, F32_REL, "f32 n_mem 40")
+    else:
+        compare(got, want, BF16_REL, "bf16 n_mem 48", tol_mem=BF16_REL_MEM)
+
+
 def test_backward_orders_agree_bitwise():
     shape = S.get_shape("tiny").replace(n_tokens=5 * 64)
     layers, mem_emb, x = make_problem(shape, seed=5, std=0.02, gain_std=0.1, v_scale=64.0)
