@@ -28,7 +28,7 @@ enum TKind {
 struct TrainLayout {
   size_t Xin, X1, Xb, N1, N2, RStd1, RStd2, QKV, Vt, Att, Hres, GU, Uff, Yf, Yb, Qm, Fphi, RDen, KVm, Fm, Coef, Rope;
   size_t Aw, zw, A16w, ATr;
-  size_t DX, DYb, DU, DN, DH, DHb, DAtt, DQKV, LSE, Dv, AttS, DNum, DF, DDen, DQr, DKV, DV, Part, DB, DZF, DA, DZ;
+  size_t DX, DYb, DU, DN, DH, DHb, DAtt, DQKV, LSE, Dv, AttS, DNum, DF, DDen, DQr, DKV, DV, Part, DB, DZF, DA, DZ, Upd;
   size_t TA, TB, TmA, TmB, CPart;
   size_t WdT, WguT, WoT, WqkvT, WmqT, WmkvT;
   size_t Ptrs, Tables, Aux, total;
@@ -91,6 +91,7 @@ TrainLayout carve_train(const Dims& D) {
   o.DZF = take(L * D.m * 4);
   o.DA = take(L * d * D.Phi * 4);
   o.DZ = take(L * (size_t)D.Phi * 4);
+  o.Upd = take(D.m > UB_M ? L * d * D.Phi * 4 : 0);
   o.ta_rows = std::max(std::max((size_t)2 * F, (size_t)D.Nqkv), std::max(d, (size_t)D.dm));
   o.tb_rows = std::max(std::max(F, d), std::max(Hd, (size_t)D.Phi));
   o.TA = take(L * o.ta_rows * o.Tp * e);
@@ -397,7 +398,7 @@ armt_status backward_group(const BCtx& c, int lo, int g, int gr) {
 #define ARMT_UB(NPL)                                                                                                      \
   case NPL:                                                                                                              \
     update_bwd_rows_kernel<NPL><<<grid, 256, lds, st>>>(c.at<float>(o.KVm), c.at<float>(o.Fm), c.at<float>(o.Coef),      \
-                                                        c.at<float>(o.Aw), c.at<float>(o.DA), c.at<float>(o.DV),         \
+                                                        c.at<float>(o.Aw), c.at<float>(o.DA), c.at<float>(o.Upd), c.at<float>(o.DV), \
                                                         c.at<float>(o.Part), lo, D.m, D.d, D.dm, Phi);                   \
     break;
     switch ((Phi + 63) / 64) { ARMT_UB(1) ARMT_UB(2) ARMT_UB(3) ARMT_UB(4) ARMT_UB(5) ARMT_UB(6) ARMT_UB(7) ARMT_UB(8) }

@@ -405,16 +405,15 @@ __global__ __launch_bounds__(128) void read_bwd_dpfp_kernel(const float* __restr
 // Part[cells][blocks][m][Phi + 2] holds the partial df_i, dbeta_i, dden_i of every block.
 // Coef as written by memupd_prep_kernel ({beta, gamma, 1/den (0 = memory empty), z.f}).
 // The memory tokens are taken in chunks of UB_M (their partial feature gradients live in registers); a wave re-reads
-// its rows of A and G for every chunk and writes G once at the end.
+// its rows of A and G for every chunk, carries the running update of G between chunks in Upd and writes G with the last.
 // grid: (ceil(d / UB_ROWS), g), block: 256; Phi <= 64 * NPL; LDS: UB_M * (2 Phi + 2) floats.
 constexpr int UB_ROWS = 32, UB_M = 16;
 template <int NPL>
 __global__ __launch_bounds__(256) void update_bwd_rows_kernel(const float* __restrict__ KV, const float* __restrict__ Fm,
                                                               const float* __restrict__ Coef,
                                                               const float* __restrict__ Aold, float* __restrict__ DA,
-                                                              float* __restrict__ DV, float* __restrict__ Part, int first,
-                                                              int m, int d, int dm, int Phi) {
-  constexpr int RPW = UB_ROWS / 4;             // rows per wave
+                                                              float* __restrict__ Upd, float* __restrict__ DV,
+                                                              float* __restrict__ Part, int first, int m, int d, int dm, int Phi) {
   extern __shared__ float sm[];
   float* F = sm;                               // [UB_M][Phi]: the f_i of the current chunk of memory tokens
   float* acc = sm + (size_t)UB_M * Phi;        // [UB_M][Phi + 2]
@@ -423,17 +422,13 @@ __global__ __launch_bounds__(256) void update_bwd_rows_kernel(const float* __res
   const float* cf = Coef + (size_t)l * m * 4;
   const float* A = Aold + (size_t)l * d * Phi;
   float* G = DA + (size_t)l * d * Phi;
+  float* U = Upd + (size_t)l * d * Phi;        // sum_i w_i[r] f_i over the chunks so far (used only if m > UB_M)
   const float* V = KV + (size_t)l * m * (dm + d) + dm;
   const int r0 = blockIdx.x * UB_ROWS, r1 = min(d, r0 + UB_ROWS);
   const int stride = Phi + 2;
   float* out = Part + ((size_t)l * gridDim.x + blockIdx.x) * m * stride;
-  float upd[RPW][NPL];                         // sum_i w_i[r] f_i of this wave's rows, over all chunks
-#pragma unroll
-  for (int q = 0; q < RPW; ++q)
-#pragma unroll
-    for (int k = 0; k < NPL; ++k) upd[q][k] = 0.f;
 
-  for (int i0 = 0; i0 < m; i0 += UB_M) {       // memory tokens in chunks of UB_M; G is only written after the last one
+  for (int i0 = 0; i0 < m; i0 += UB_M) {       // memory tokens in chunks of UB_M; every chunk needs the ORIGINAL G
     const int n = min(UB_M, m - i0);
     __syncthreads();                           // the previous chunk's F and acc are no longer read
     for (int c = threadIdx.x; c < n * Phi; c += blockDim.x) F[c] = Fl[(size_t)i0 * Phi + c];
@@ -445,16 +440,14 @@ __global__ __launch_bounds__(256) void update_bwd_rows_kernel(const float* __res
 #pragma unroll
       for (int k = 0; k < NPL; ++k) dfp[i][k] = 0.f;
     }
-#pragma unroll
-    for (int q = 0; q < RPW; ++q) {
-      const int r = r0 + w + 4 * q;
-      if (r >= r1) continue;                   // wave-uniform
-      float a[NPL], g[NPL];
+    for (int r = r0 + w; r < r1; r += 4) {
+      float a[NPL], g[NPL], upd[NPL];
 #pragma unroll
       for (int k = 0; k < NPL; ++k) {
         const int c = lane + 64 * k;
         a[k] = c < Phi ? A[(size_t)r * Phi + c] : 0.f;
         g[k] = c < Phi ? G[(size_t)r * Phi + c] : 0.f;
+        upd[k] = (i0 > 0 && c < Phi) ? U[(size_t)r * Phi + c] : 0.f;
       }
 #pragma unroll
       for (int i = 0; i < UB_M; ++i) {
@@ -481,7 +474,16 @@ __global__ __launch_bounds__(256) void update_bwd_rows_kernel(const float* __res
           const int c = lane + 64 * k;
           const float f = c < Phi ? F[i * Phi + c] : 0.f;
           dfp[i][k] = fmaf(beta * e, g[k], fmaf(wi, a[k], dfp[i][k]));
-          upd[q][k] = fmaf(wi, f, upd[q][k]);
+          upd[k] = fmaf(wi, f, upd[k]);
+        }
+      }
+      const bool last = i0 + UB_M >= m;
+#pragma unroll
+      for (int k = 0; k < NPL; ++k) {
+        const int c = lane + 64 * k;
+        if (c < Phi) {
+          if (last) G[(size_t)r * Phi + c] = g[k] + upd[k];      // rows are private to a wave: nobody reads this G again
+          else U[(size_t)r * Phi + c] = upd[k];
         }
       }
     }
@@ -505,16 +507,6 @@ __global__ __launch_bounds__(256) void update_bwd_rows_kernel(const float* __res
       __syncthreads();
     }
     for (int c = threadIdx.x; c < n * stride; c += blockDim.x) out[(size_t)i0 * stride + c] = acc[c];
-  }
-#pragma unroll
-  for (int q = 0; q < RPW; ++q) {
-    const int r = r0 + w + 4 * q;
-    if (r >= r1) continue;
-#pragma unroll
-    for (int k = 0; k < NPL; ++k) {
-      const int c = lane + 64 * k;
-      if (c < Phi) G[(size_t)r * Phi + c] += upd[q][k];
-    }
   }
 }
 
