@@ -152,6 +152,7 @@ void fill_shapes(Ctx& c) {
     s.M = M; s.N = N; s.K = K; s.lda = lda; s.ldc = ldc; s.ldc2 = ldc2; s.ldr = ldr; s.n0 = n0; s.n1 = n1; s.epi = epi;
     s.tag = k;
     s.dbg = g_gemm_dbg;
+    s.ldb = K;
     c.shape[k] = s;
   };
   set(K_MQ, D.T, D.dm, D.d, D.d, D.dm, 0, 0, D.dm, 0, EPI_STORE_F32);
@@ -566,7 +567,7 @@ armt_status lm_head_typed(const Dims& D, const HeadLayout& h, const void* hidden
   HIP_TRY(hipStreamSynchronize(st));
   GemmShape s;
   s.M = (int)kHeadRows; s.N = vocab; s.K = D.d; s.lda = D.d; s.ldc = vocab; s.ldc2 = 0; s.ldr = 0; s.n0 = vocab; s.n1 = 0;
-  s.epi = EPI_STORE_F32; s.tag = -1; s.dbg = g_gemm_dbg;
+  s.epi = EPI_STORE_F32; s.tag = -1; s.dbg = g_gemm_dbg; s.ldb = s.K;
   const GemmGroup* table = (const GemmGroup*)(ws + h.table);
   for (int64_t g0 = 0; g0 < h.groups; g0 += 256)          // at most 256 groups per launch
     ARMT_TRY(gemm<T>(st, table, (int)g0, (int)std::min<int64_t>(256, h.groups - g0), s));
@@ -651,6 +652,7 @@ armt_status armt_grouped_gemm(int32_t dtype, int32_t g, int32_t M, int32_t N, in
   s.M = M; s.N = N; s.K = K; s.lda = K; s.ldc = N; s.ldc2 = 0; s.ldr = 0; s.n0 = N; s.n1 = 0; s.epi = EPI_STORE_ACT;
   s.tag = -1;
   s.dbg = g_gemm_dbg;
+  s.ldb = K;
   if (dtype == ARMT_BF16) return gemm_entry<bf16>(g, s, (const GemmGroup*)workspace, st);
   return gemm_entry<float>(g, s, (const GemmGroup*)workspace, st);
 }

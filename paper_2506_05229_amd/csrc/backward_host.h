@@ -15,6 +15,12 @@ namespace {
 
 inline int round64(int v) { return (v + 63) / 64 * 64; }
 
+// Weight gradients are accumulated over a window of WG_WIN consecutive steps: the transposed operands of a step go into
+// slot (step % WG_WIN) of buffers whose rows hold WG_WIN slots side by side, and one GEMM per kind with the reduction
+// dimension WG_WIN x T then adds the window to the fp32 gradient.  The fp32 read-modify-write of a layer's 60.8 M
+// weight gradients (486 MB at the 1B shape) is as expensive as the product of one segment; this divides it by WG_WIN.
+constexpr int WG_WIN = 4;
+
 enum TKind {
   // forward recomputation
   TK_MQ = 0, TK_READ, TK_QKV, TK_O, TK_GU, TK_DOWN, TK_MKV,
@@ -29,7 +35,8 @@ struct TrainLayout {
   size_t Xin, X1, Xb, N1, N2, RStd1, RStd2, QKV, Vt, Att, Hres, GU, Uff, Yf, Yb, Qm, Fphi, RDen, KVm, Fm, Coef, Rope;
   size_t Aw, zw, A16w, ATr;
   size_t DX, DYb, DU, DN, DH, DHb, DAtt, DQKV, LSE, Dv, AttS, DNum, DF, DDen, DQr, DKV, DV, Part, DB, DZF, DA, DZ, Upd;
-  size_t TA, TB, TmA, TmB, CPart;
+  size_t TA, TB, TmA, TmB, CPart, WinA, WinB;
+  size_t wa_rows, wb_rows, aDY, aDGU, aDH, aDQKV, aDQR, bU, bN2, bATT, bN1, bX;   // rows of a layer's window operands
   size_t WdT, WguT, WoT, WqkvT, WmqT, WmkvT;
   size_t Ptrs, Tables, Aux, total;
   int Tp, mp, dmP, Kmkv, nblk;
@@ -92,12 +99,18 @@ TrainLayout carve_train(const Dims& D) {
   o.DA = take(L * d * D.Phi * 4);
   o.DZ = take(L * (size_t)D.Phi * 4);
   o.Upd = take(D.m > UB_M ? L * d * D.Phi * 4 : 0);
-  o.ta_rows = std::max(std::max((size_t)2 * F, (size_t)D.Nqkv), std::max(d, (size_t)D.dm));
-  o.tb_rows = std::max(std::max(F, d), std::max(Hd, (size_t)D.Phi));
+  o.ta_rows = d;                                   // dnum^T and phi^T of the read: operands of dA += dnum^T phi (every step)
+  o.tb_rows = (size_t)D.Phi;
   o.TA = take(L * o.ta_rows * o.Tp * e);
   o.TB = take(L * o.tb_rows * o.Tp * e);
-  o.TmA = take(L * (size_t)(D.dm + D.d) * o.mp * e);
-  o.TmB = take(L * d * o.mp * e);
+  o.TmA = take(L * (size_t)(D.dm + D.d) * WG_WIN * o.mp * e);
+  o.TmB = take(L * d * WG_WIN * o.mp * e);
+  o.aDY = 0; o.aDGU = d; o.aDH = d + 2 * F; o.aDQKV = 2 * d + 2 * F; o.aDQR = 2 * d + 2 * F + D.Nqkv;
+  o.wa_rows = o.aDQR + D.dm;
+  o.bU = 0; o.bN2 = F; o.bATT = F + d; o.bN1 = F + d + Hd; o.bX = F + 2 * d + Hd;
+  o.wb_rows = o.bX + d;
+  o.WinA = take(L * o.wa_rows * WG_WIN * o.Tp * e);
+  o.WinB = take(L * o.wb_rows * WG_WIN * o.Tp * e);
   o.CPart = take(L * CS_CHUNKS * std::max(d, (size_t)D.Phi) * 4);
   o.WdT = take(L * F * d * e);
   o.WguT = take(L * d * 2 * F * e);
@@ -141,10 +154,10 @@ void fill_train_shapes(BCtx& c) {
   const Dims& D = c.D;
   const TrainLayout& o = c.o;
   const int Hd = D.H * D.dh, Hkd = D.Hkv * D.dh;
-  auto set = [&](int k, int M, int N, int K, int lda, int ldc, int epi, int n0 = -1, int n1 = 0) {
+  auto set = [&](int k, int M, int N, int K, int lda, int ldc, int epi, int n0 = -1, int n1 = 0, int ldb = 0) {
     GemmShape s;
     s.M = M; s.N = N; s.K = K; s.lda = lda; s.ldc = ldc; s.ldc2 = 0; s.ldr = ldc; s.n0 = n0 < 0 ? N : n0; s.n1 = n1; s.epi = epi;
-    s.tag = -1; s.dbg = 0;
+    s.tag = -1; s.dbg = 0; s.ldb = ldb ? ldb : K;
     c.shape[k] = s;
   };
   set(TK_MQ, D.T, D.dm, D.d, D.d, D.dm, EPI_STORE_F32);
@@ -162,17 +175,19 @@ void fill_train_shapes(BCtx& c) {
   set(TK_DN1, D.T, D.d, D.Nqkv, D.Nqkv, D.d, EPI_STORE_ACT);
   set(TK_DF, D.T, D.Phi, D.d, D.d, D.Phi, EPI_STORE_F32);
   set(TK_DXQ, D.T, D.d, o.dmP, o.dmP, D.d, EPI_RESID_F32);
-  set(TK_WD, D.d, D.F, o.Tp, o.Tp, D.F, EPI_RESID_F32);
-  set(TK_WG, D.F, D.d, o.Tp, o.Tp, D.d, EPI_RESID_F32);
-  set(TK_WU, D.F, D.d, o.Tp, o.Tp, D.d, EPI_RESID_F32);
-  set(TK_WO, D.d, Hd, o.Tp, o.Tp, Hd, EPI_RESID_F32);
-  set(TK_WQ, Hd, D.d, o.Tp, o.Tp, D.d, EPI_RESID_F32);
-  set(TK_WK, Hkd, D.d, o.Tp, o.Tp, D.d, EPI_RESID_F32);
-  set(TK_WV, Hkd, D.d, o.Tp, o.Tp, D.d, EPI_RESID_F32);
+  // weight gradients: K = slots of the window actually filled (set at launch), lda = ldb = a whole window row
+  const int Kw = WG_WIN * o.Tp, Km = WG_WIN * o.mp;
+  set(TK_WD, D.d, D.F, Kw, Kw, D.F, EPI_RESID_F32, -1, 0, Kw);
+  set(TK_WG, D.F, D.d, Kw, Kw, D.d, EPI_RESID_F32, -1, 0, Kw);
+  set(TK_WU, D.F, D.d, Kw, Kw, D.d, EPI_RESID_F32, -1, 0, Kw);
+  set(TK_WO, D.d, Hd, Kw, Kw, Hd, EPI_RESID_F32, -1, 0, Kw);
+  set(TK_WQ, Hd, D.d, Kw, Kw, D.d, EPI_RESID_F32, -1, 0, Kw);
+  set(TK_WK, Hkd, D.d, Kw, Kw, D.d, EPI_RESID_F32, -1, 0, Kw);
+  set(TK_WV, Hkd, D.d, Kw, Kw, D.d, EPI_RESID_F32, -1, 0, Kw);
   set(TK_DA, D.d, D.Phi, o.Tp, o.Tp, D.Phi, EPI_RESID_F32);
-  set(TK_WMQ, D.dm, D.d, o.Tp, o.Tp, D.d, EPI_RESID_F32);
-  set(TK_WMK, D.dm, D.d, o.mp, o.mp, D.d, EPI_RESID_F32);
-  set(TK_WMV, D.d, D.d, o.mp, o.mp, D.d, EPI_RESID_F32);
+  set(TK_WMQ, D.dm, D.d, Kw, Kw, D.d, EPI_RESID_F32, -1, 0, Kw);
+  set(TK_WMK, D.dm, D.d, Km, Km, D.d, EPI_RESID_F32, -1, 0, Km);
+  set(TK_WMV, D.d, D.d, Km, Km, D.d, EPI_RESID_F32, -1, 0, Km);
 }
 
 armt_status upload_train_tables(BCtx& c, const armt_layer_weights* W, const armt_layer_grads* G) {
@@ -196,8 +211,11 @@ armt_status upload_train_tables(BCtx& c, const armt_layer_weights* W, const armt
     char* DXup = ws + o.DX + (l + 1) * T * d * 4;
     char* TA = ws + o.TA + l * o.ta_rows * o.Tp * e;
     char* TB = ws + o.TB + l * o.tb_rows * o.Tp * e;
-    char* TmA = ws + o.TmA + l * (size_t)(D.dm + D.d) * o.mp * e;
-    char* TmB = ws + o.TmB + l * d * o.mp * e;
+    char* TmA = ws + o.TmA + l * (size_t)(D.dm + D.d) * WG_WIN * o.mp * e;
+    char* TmB = ws + o.TmB + l * d * WG_WIN * o.mp * e;
+    const size_t rowb = (size_t)WG_WIN * o.Tp * e;      // bytes of one window row
+    char* WA = ws + o.WinA + l * o.wa_rows * rowb;
+    char* WB = ws + o.WinB + l * o.wb_rows * rowb;
     GemmGroup* g;
     g = E(TK_MQ); g->A = Xop; g->B0 = w.wm_q; g->C = ws + o.Qm + l * T * D.dm * 4;
     g = E(TK_READ); g->A = ws + o.Fphi + l * T * D.Phi * e;
@@ -224,17 +242,17 @@ armt_status upload_train_tables(BCtx& c, const armt_layer_weights* W, const armt
     g = E(TK_DXQ); g->A = ws + o.DQr + l * T * o.dmP * e; g->B0 = ws + o.WmqT + l * d * o.dmP * e; g->C = DXl; g->R = (const float*)DXl;
 
     auto wgrad = [&](int k, char* A, char* B, float* C) { GemmGroup* q = E(k); q->A = A; q->B0 = B; q->C = C; q->R = C; };
-    wgrad(TK_WD, TA, TB, gw.wdown);
-    wgrad(TK_WG, TA, TB, gw.wgate);
-    wgrad(TK_WU, TA + F * o.Tp * e, TB, gw.wup);
-    wgrad(TK_WO, TA, TB, gw.wo);
-    wgrad(TK_WQ, TA, TB, gw.wq);
-    wgrad(TK_WK, TA + Hd * o.Tp * e, TB, gw.wk);
-    wgrad(TK_WV, TA + (Hd + Hkd) * o.Tp * e, TB, gw.wv);
+    wgrad(TK_WD, WA + o.aDY * rowb, WB + o.bU * rowb, gw.wdown);
+    wgrad(TK_WG, WA + o.aDGU * rowb, WB + o.bN2 * rowb, gw.wgate);
+    wgrad(TK_WU, WA + (o.aDGU + F) * rowb, WB + o.bN2 * rowb, gw.wup);
+    wgrad(TK_WO, WA + o.aDH * rowb, WB + o.bATT * rowb, gw.wo);
+    wgrad(TK_WQ, WA + o.aDQKV * rowb, WB + o.bN1 * rowb, gw.wq);
+    wgrad(TK_WK, WA + (o.aDQKV + Hd) * rowb, WB + o.bN1 * rowb, gw.wk);
+    wgrad(TK_WV, WA + (o.aDQKV + Hd + Hkd) * rowb, WB + o.bN1 * rowb, gw.wv);
     wgrad(TK_DA, TA, TB, (float*)(ws + o.DA + l * d * D.Phi * 4));
-    wgrad(TK_WMQ, TA, TB, gw.wm_q);
+    wgrad(TK_WMQ, WA + o.aDQR * rowb, WB + o.bX * rowb, gw.wm_q);
     wgrad(TK_WMK, TmA, TmB, gw.wm_k);
-    wgrad(TK_WMV, TmA + (size_t)D.dm * o.mp * e, TmB, gw.wm_v);
+    wgrad(TK_WMV, TmA + (size_t)D.dm * WG_WIN * o.mp * e, TmB, gw.wm_v);
 
     LayerAux& a = aux[l];
     a.rms1 = w.rms1; a.rms2 = w.rms2; a.wm_b = w.wm_b;
@@ -378,7 +396,7 @@ armt_status recompute_group(const BCtx& c, int lo, int g, int gr, int e0, int e1
 
 // Backward kernels of the cells [lo, lo + g); the first gr of them have a read to differentiate.
 template <typename T>
-armt_status backward_group(const BCtx& c, int lo, int g, int gr) {
+armt_status backward_group(const BCtx& c, int lo, int g, int gr, int slot) {
   const Dims& D = c.D;
   const TrainLayout& o = c.o;
   hipStream_t st = c.st;
@@ -387,6 +405,13 @@ armt_status backward_group(const BCtx& c, int lo, int g, int gr) {
   const size_t ta_cell = o.ta_rows * Tp, tb_cell = o.tb_rows * Tp;
   T* TA = c.at<T>(o.TA) + lo * ta_cell;
   T* TB = c.at<T>(o.TB) + lo * tb_cell;
+  // window operands of the weight gradients: this step's columns of a layer's rows
+  const int Kw = WG_WIN * Tp, Km = WG_WIN * o.mp;
+  const size_t wa_cell = o.wa_rows * Kw, wb_cell = o.wb_rows * Kw;
+  T* WA = c.at<T>(o.WinA) + lo * wa_cell + (size_t)slot * Tp;
+  T* WB = c.at<T>(o.WinB) + lo * wb_cell + (size_t)slot * Tp;
+  auto arow = [&](size_t r) { return WA + r * Kw; };
+  auto brow = [&](size_t r) { return WB + r * Kw; };
   float* DX = c.at<float>(o.DX);
   const T* Yop = D.bf16 ? (const T*)c.at<bf16>(o.Yb) : (const T*)c.at<float>(o.Yf);
   const T* Xop = D.bf16 ? (const T*)c.at<bf16>(o.Xb) : (const T*)c.at<float>(o.Xin);
@@ -416,39 +441,34 @@ armt_status backward_group(const BCtx& c, int lo, int g, int gr) {
     beta_bwd_kernel<T><<<dim3((D.d + 255) / 256, g), 256, 0, st>>>(c.at<float>(o.DB), Yop + (size_t)D.S * D.d, cell, c.aux,
                                                                  DX + cell + (size_t)D.S * D.d, cell, c.dwb, lo, D.m, D.d);
     HIP_TRY(hipGetLastError());
-    const size_t tma = (size_t)(D.dm + D.d) * o.mp, tmb = (size_t)D.d * o.mp;
+    const size_t tma = (size_t)(D.dm + D.d) * Km, tmb = (size_t)D.d * Km;
     ARMT_TRY((transpose<T, T>(st, c.at<T>(o.DKV) + (size_t)lo * D.m * o.Kmkv, (size_t)D.m * o.Kmkv, o.Kmkv,
-                              c.at<T>(o.TmA) + lo * tma, tma, o.mp, D.m, D.dm + D.d, g)));
-    ARMT_TRY((transpose<T, T>(st, Yop + lo * cell + (size_t)D.S * D.d, cell, D.d, c.at<T>(o.TmB) + lo * tmb, tmb, o.mp, D.m, D.d, g)));
-    ARMT_TRY(bgemm<T>(c, TK_WMK, lo, g));
-    ARMT_TRY(bgemm<T>(c, TK_WMV, lo, g));
+                              c.at<T>(o.TmA) + lo * tma + (size_t)slot * o.mp, tma, Km, D.m, D.dm + D.d, g)));
+    ARMT_TRY((transpose<T, T>(st, Yop + lo * cell + (size_t)D.S * D.d, cell, D.d, c.at<T>(o.TmB) + lo * tmb + (size_t)slot * o.mp, tmb,
+                              Km, D.m, D.d, g)));
   }
   // ---- feed-forward half of the block
   T* DYb = c.at<T>(o.DYb) + lo * cell;
   convert_kernel<float, T><<<ew_blocks(g * cell), 256, 0, st>>>(DX + (lo + 1) * cell, DYb, g * cell);
   HIP_TRY(hipGetLastError());
   ARMT_TRY(bgemm<T>(c, TK_DU, lo, g));
-  ARMT_TRY((transpose<T, T>(st, DYb, cell, D.d, TA, ta_cell, Tp, D.T, D.d, g)));
-  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.Uff) + (size_t)lo * D.T * D.F, (size_t)D.T * D.F, D.F, TB, tb_cell, Tp, D.T, D.F, g)));
-  ARMT_TRY(bgemm<T>(c, TK_WD, lo, g));
+  ARMT_TRY((transpose<T, T>(st, DYb, cell, D.d, arow(o.aDY), wa_cell, Kw, D.T, D.d, g)));
+  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.Uff) + (size_t)lo * D.T * D.F, (size_t)D.T * D.F, D.F, brow(o.bU), wb_cell, Kw, D.T, D.F, g)));
   T* GU = c.at<T>(o.GU) + (size_t)lo * D.T * 2 * D.F;
   swiglu_bwd_kernel<T><<<ew_blocks((size_t)g * D.T * D.F), 256, 0, st>>>(GU, c.at<T>(o.DU) + (size_t)lo * D.T * D.F, (size_t)g * D.T,
                                                                         D.F);
   HIP_TRY(hipGetLastError());
   ARMT_TRY(bgemm<T>(c, TK_DN2, lo, g));
-  ARMT_TRY((transpose<T, T>(st, GU, (size_t)D.T * 2 * D.F, 2 * D.F, TA, ta_cell, Tp, D.T, 2 * D.F, g)));
-  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.N2) + lo * cell, cell, D.d, TB, tb_cell, Tp, D.T, D.d, g)));
-  ARMT_TRY(bgemm<T>(c, TK_WG, lo, g));
-  ARMT_TRY(bgemm<T>(c, TK_WU, lo, g));
+  ARMT_TRY((transpose<T, T>(st, GU, (size_t)D.T * 2 * D.F, 2 * D.F, arow(o.aDGU), wa_cell, Kw, D.T, 2 * D.F, g)));
+  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.N2) + lo * cell, cell, D.d, brow(o.bN2), wb_cell, Kw, D.T, D.d, g)));
   ARMT_TRY(colsum<T>(c, c.at<T>(o.DN), c.at<float>(o.Hres), cell, c.at<float>(o.RStd2), c.dg2, nullptr, lo, g, D.d));   // d gain 2
   rmsnorm_bwd_kernel<T><<<dim3(D.T, g), 256, 0, st>>>(c.at<T>(o.DN), c.at<float>(o.Hres), cell, c.aux, lo, 1, c.at<float>(o.RStd2),
                                                      DX + cell, cell, c.at<float>(o.DH), cell, c.at<T>(o.DHb), D.T, D.d);
   HIP_TRY(hipGetLastError());
   // ---- attention half
   ARMT_TRY(bgemm<T>(c, TK_DATT, lo, g));
-  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.DHb) + lo * cell, cell, D.d, TA, ta_cell, Tp, D.T, D.d, g)));
-  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.Att) + lo * D.T * Hd, D.T * Hd, (int)Hd, TB, tb_cell, Tp, D.T, (int)Hd, g)));
-  ARMT_TRY(bgemm<T>(c, TK_WO, lo, g));
+  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.DHb) + lo * cell, cell, D.d, arow(o.aDH), wa_cell, Kw, D.T, D.d, g)));
+  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.Att) + lo * D.T * Hd, D.T * Hd, (int)Hd, brow(o.bATT), wb_cell, Kw, D.T, (int)Hd, g)));
   const float scale = 1.0f / sqrtf((float)D.dh);
   if (mfma_attention_bwd<T>(D)) {
     HIP_TRY(launch_attention_bwd_mfma(c.at<bf16>(o.QKV), c.at<bf16>(o.Att), c.at<bf16>(o.DAtt), c.at<float>(o.LSE), c.at<float>(o.Dv),
@@ -464,12 +484,9 @@ armt_status backward_group(const BCtx& c, int lo, int g, int gr) {
   rope_bwd_kernel<T><<<dim3(D.T, g), 256, 0, st>>>(c.at<T>(o.DQKV), c.at<float>(o.Rope), lo, D.T, D.H + D.Hkv, D.dh, D.Nqkv);
   HIP_TRY(hipGetLastError());
   ARMT_TRY(bgemm<T>(c, TK_DN1, lo, g));
-  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.DQKV) + (size_t)lo * D.T * D.Nqkv, (size_t)D.T * D.Nqkv, D.Nqkv, TA, ta_cell, Tp, D.T,
-                            D.Nqkv, g)));
-  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.N1) + lo * cell, cell, D.d, TB, tb_cell, Tp, D.T, D.d, g)));
-  ARMT_TRY(bgemm<T>(c, TK_WQ, lo, g));
-  ARMT_TRY(bgemm<T>(c, TK_WK, lo, g));
-  ARMT_TRY(bgemm<T>(c, TK_WV, lo, g));
+  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.DQKV) + (size_t)lo * D.T * D.Nqkv, (size_t)D.T * D.Nqkv, D.Nqkv, arow(o.aDQKV), wa_cell, Kw,
+                            D.T, D.Nqkv, g)));
+  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.N1) + lo * cell, cell, D.d, brow(o.bN1), wb_cell, Kw, D.T, D.d, g)));
   ARMT_TRY(colsum<T>(c, c.at<T>(o.DN), c.at<float>(o.X1), cell, c.at<float>(o.RStd1), c.dg1, nullptr, lo, g, D.d));     // d gain 1
   rmsnorm_bwd_kernel<T><<<dim3(D.T, g), 256, 0, st>>>(c.at<T>(o.DN), c.at<float>(o.X1), cell, c.aux, lo, 0, c.at<float>(o.RStd1),
                                                      c.at<float>(o.DH), cell, DX, cell, (T*)nullptr, D.T, D.d);
@@ -491,10 +508,9 @@ armt_status backward_group(const BCtx& c, int lo, int g, int gr) {
     ARMT_TRY((transpose<T, T>(st, c.at<T>(o.Fphi) + (size_t)lo * D.T * Phi, (size_t)D.T * Phi, Phi, TB, tb_cell, Tp, D.T, Phi, gr)));
     ARMT_TRY(bgemm<T>(c, TK_DA, lo, gr));
     ARMT_TRY(bgemm<T>(c, TK_DXQ, lo, gr));
-    ARMT_TRY((transpose<T, T>(st, c.at<T>(o.DQr) + (size_t)lo * D.T * o.dmP, (size_t)D.T * o.dmP, o.dmP, TA, ta_cell, Tp, D.T, D.dm,
-                              gr)));
-    ARMT_TRY((transpose<T, T>(st, Xop + lo * cell, cell, D.d, TB, tb_cell, Tp, D.T, D.d, gr)));
-    ARMT_TRY(bgemm<T>(c, TK_WMQ, lo, gr));
+    ARMT_TRY((transpose<T, T>(st, c.at<T>(o.DQr) + (size_t)lo * D.T * o.dmP, (size_t)D.T * o.dmP, o.dmP, arow(o.aDQR), wa_cell, Kw, D.T,
+                              D.dm, gr)));
+    ARMT_TRY((transpose<T, T>(st, Xop + lo * cell, cell, D.d, brow(o.bX), wb_cell, Kw, D.T, D.d, gr)));
   }
   return ARMT_OK;
 }
@@ -516,8 +532,10 @@ armt_status backward_typed(BCtx& c, const armt_layer_weights* W, int64_t N, floa
     };
     zero(o.TA, (size_t)L * o.ta_rows * o.Tp * D.esz);
     zero(o.TB, (size_t)L * o.tb_rows * o.Tp * D.esz);
-    zero(o.TmA, (size_t)L * (D.dm + D.d) * o.mp * D.esz);
-    zero(o.TmB, (size_t)L * D.d * o.mp * D.esz);
+    zero(o.TmA, (size_t)L * (D.dm + D.d) * WG_WIN * o.mp * D.esz);
+    zero(o.TmB, (size_t)L * D.d * WG_WIN * o.mp * D.esz);
+    zero(o.WinA, (size_t)L * o.wa_rows * WG_WIN * o.Tp * D.esz);
+    zero(o.WinB, (size_t)L * o.wb_rows * WG_WIN * o.Tp * D.esz);
     zero(o.DQr, (size_t)L * D.T * o.dmP * D.esz);
     zero(o.DKV, (size_t)L * D.m * o.Kmkv * D.esz);
     zero(o.DX, (size_t)(L + 1) * cell * 4);
@@ -525,6 +543,43 @@ armt_status backward_typed(BCtx& c, const armt_layer_weights* W, int64_t N, floa
     HIP_TRY(hipGetLastError());
   }
   ARMT_TRY(transpose_weights<T>(c, W));
+
+  // window of steps whose weight-gradient operands are waiting in the slot buffers
+  const int win = diagonal ? WG_WIN : 1;       // cell-by-cell order: a step has one layer, nothing to gain from waiting
+  struct Slot { int lo, hi, no_read; };        // live layers of the step; the layer whose cell had no read (-1: none)
+  Slot slots[WG_WIN];
+  int n_slots = 0;
+  auto clear_slot = [&](int l, int p, bool read_only) {
+    // zero slot p of layer l on the A side (then the stale B side of that slot adds nothing)
+    const size_t e = D.esz, rowb = (size_t)WG_WIN * o.Tp * e, colb = (size_t)o.Tp * e;
+    char* WA = c.ws + o.WinA + (size_t)l * o.wa_rows * rowb + (size_t)p * colb;
+    const size_t r0 = read_only ? o.aDQR : 0, nr = read_only ? (size_t)D.dm : o.wa_rows;
+    zero_columns_kernel<<<dim3((unsigned)nr), 256, 0, c.st>>>(WA + r0 * rowb, rowb, colb);
+    if (!read_only) {
+      const size_t mrow = (size_t)WG_WIN * o.mp * e, mcol = (size_t)o.mp * e;
+      zero_columns_kernel<<<dim3((unsigned)(D.dm + D.d)), 256, 0, c.st>>>(c.ws + o.TmA + (size_t)l * (D.dm + D.d) * mrow + (size_t)p * mcol,
+                                                                         mrow, mcol);
+    }
+  };
+  auto flush = [&]() -> armt_status {
+    if (n_slots == 0) return ARMT_OK;
+    int LO = slots[0].lo, HI = slots[0].hi;
+    for (int p = 1; p < n_slots; ++p) { LO = std::min(LO, slots[p].lo); HI = std::max(HI, slots[p].hi); }
+    for (int p = 0; p < n_slots; ++p) {
+      for (int l = LO; l <= HI; ++l)
+        if (l < slots[p].lo || l > slots[p].hi) clear_slot(l, p, false);
+      if (slots[p].no_read >= 0) clear_slot(slots[p].no_read, p, true);
+    }
+    HIP_TRY(hipGetLastError());
+    const int kinds[] = {TK_WD, TK_WG, TK_WU, TK_WO, TK_WQ, TK_WK, TK_WV, TK_WMQ, TK_WMK, TK_WMV};
+    for (int k : kinds) {
+      GemmShape s = c.shape[k];
+      s.K = n_slots * ((k == TK_WMK || k == TK_WMV) ? o.mp : o.Tp);
+      ARMT_TRY(gemm<T>(c.st, c.table(k), LO, HI - LO + 1, s));
+    }
+    n_slots = 0;
+    return ARMT_OK;
+  };
 
   auto step = [&](int lo, int hi, int t) -> armt_status {
     const int g = hi - lo + 1;
@@ -540,7 +595,9 @@ armt_status backward_typed(BCtx& c, const armt_layer_weights* W, int64_t N, floa
     }
     HIP_TRY(hipGetLastError());
     ARMT_TRY(recompute_group<T>(c, lo, g, gr, top_empty ? hi : -1, top_empty ? hi + 1 : -1));
-    ARMT_TRY(backward_group<T>(c, lo, g, gr));
+    ARMT_TRY(backward_group<T>(c, lo, g, gr, n_slots));
+    slots[n_slots++] = Slot{lo, hi, top_empty ? hi : -1};
+    if (n_slots == win) ARMT_TRY(flush());
     if (lo == 0) {
       store_dx_kernel<<<D.T, 256, 0, c.st>>>(c.at<float>(o.DX), D.S, D.d, dx ? dx + (size_t)t * D.S * D.d : nullptr, d_mem_emb);
       HIP_TRY(hipGetLastError());
@@ -557,7 +614,7 @@ armt_status backward_typed(BCtx& c, const armt_layer_weights* W, int64_t N, floa
     for (int64_t s = N - 1; s >= 0; --s)
       for (int l = L - 1; l >= 0; --l) ARMT_TRY(step(l, l, (int)s + l));
   }
-  return ARMT_OK;
+  return flush();
 }
 
 }  // namespace

@@ -65,6 +65,12 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16* __restr
   }
 }
 
+// Zero `col_bytes` bytes (a multiple of 4) at the start of each of gridDim.x rows that are `row_bytes` apart.
+__global__ __launch_bounds__(256) void zero_columns_kernel(char* __restrict__ base, size_t row_bytes, size_t col_bytes) {
+  unsigned int* p = (unsigned int*)(base + (size_t)blockIdx.x * row_bytes);
+  for (size_t i = threadIdx.x; i < col_bytes / 4; i += blockDim.x) p[i] = 0u;
+}
+
 template <typename Tin, typename Tout>
 __global__ void convert_kernel(const Tin* __restrict__ src, Tout* __restrict__ dst, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)

@@ -86,6 +86,7 @@ struct GemmShape {
   int epi;              // GemmEpilogue
   int tag;              // which GEMM of the step this is (profiling only)
   int dbg;              // diagnosis only: bit 0 freezes the k offset of B, bit 1 that of A (wrong results)
+  int ldb;              // row stride of the weight blocks in elements (>= K); the weights of the model are dense: ldb = K
 };
 
 }  // namespace armt

@@ -11,10 +11,10 @@ constexpr int GG_BM = 64, GG_BN = 64, GG_BK = 16;
 
 template <typename T>
 __device__ __forceinline__ const T* weight_row(const GemmGroup& g, const GemmShape& s, int n) {
-  if (n < s.n0) return (const T*)g.B0 + (size_t)n * s.K;
+  if (n < s.n0) return (const T*)g.B0 + (size_t)n * s.ldb;
   n -= s.n0;
-  if (n < s.n1) return (const T*)g.B1 + (size_t)n * s.K;
-  return (const T*)g.B2 + (size_t)(n - s.n1) * s.K;
+  if (n < s.n1) return (const T*)g.B1 + (size_t)n * s.ldb;
+  return (const T*)g.B2 + (size_t)(n - s.n1) * s.ldb;
 }
 
 // grid: (ceil(N / 64), ceil(M / 64), g); block: 256 threads, each owns a 4 x 4 patch of the tile.
@@ -38,8 +38,8 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const GemmGroup* __re
   const T* urow = nullptr;
   if (n0 + lr < s.N) {
     if (swiglu) {
-      brow = (const T*)g.B0 + (size_t)(n0 + lr) * s.K;
-      urow = (const T*)g.B1 + (size_t)(n0 + lr) * s.K;
+      brow = (const T*)g.B0 + (size_t)(n0 + lr) * s.ldb;
+      urow = (const T*)g.B1 + (size_t)(n0 + lr) * s.ldb;
     } else {
       brow = weight_row<T>(g, s, n0 + lr);
     }

@@ -90,7 +90,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       // both for output columns n0 + (block / 2) * 32 ...
       const int blk = row >> 5;
       const int n = min(n0 + (blk >> 1) * 32 + (row & 31), s.N - 1);
-      return (const bf16*)((blk & 1) ? g.B1 : g.B0) + (size_t)n * s.K;
+      return (const bf16*)((blk & 1) ? g.B1 : g.B0) + (size_t)n * s.ldb;
     }
     return weight_row<bf16>(g, s, min(n0 + row, s.N - 1));
   };
@@ -134,14 +134,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   } else {
     const int chunk = (dpc ^ mf_swz((wave & 1) * 8 + dR)) << 4;
     a_off0 = (unsigned)dR * (unsigned)s.lda * 2u + chunk;
-    b_off0 = (unsigned)dR * (unsigned)s.K * 2u + chunk;
+    b_off0 = (unsigned)dR * (unsigned)s.ldb * 2u + chunk;
   }
   // scalar source of the first row of slab `slab` (REG only)
   auto a_base = [&](int slab) -> const char* { return (const char*)g.A + (size_t)(m0 + 8 * slab) * s.lda * 2; };
   auto b_base = [&](int slab) -> const char* {
     if (EPI == EPI_SWIGLU) {   // tile rows 32 * blk ..: blk even from the gate, odd from the up weight, columns n0 + 32 * (blk / 2) ..
       const int n = n0 + (slab >> 3) * 32 + (slab & 3) * 8;
-      return (const char*)(((slab >> 2) & 1) ? g.B1 : g.B0) + (size_t)n * s.K * 2;
+      return (const char*)(((slab >> 2) & 1) ? g.B1 : g.B0) + (size_t)n * s.ldb * 2;
     }
     return (const char*)weight_row<bf16>(g, s, n0 + 8 * slab);
   };

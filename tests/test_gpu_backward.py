@@ -151,16 +151,21 @@ def test_many_memory_tokens_backward_matches_oracle(dtype):
         compare(got, want, BF16_REL, "bf16 n_mem 48", tol_mem=BF16_REL_MEM)
 
 
-def test_backward_orders_agree_bitwise():
-    shape = S.get_shape("tiny").replace(n_tokens=5 * 64)
+def test_backward_orders_agree():
+    """Reverse diagonal and reverse sequential order: the same cells and the same per-cell arithmetic, so everything that
+    flows from cell to cell (dx, d_mem_emb, the gradient of the state) is bit-identical; a layer's weight gradient is a
+    sum over its segments that the diagonal order adds four segments at a time, so it agrees to fp32 rounding."""
+    shape = S.get_shape("tiny").replace(n_tokens=6 * 64)
     layers, mem_emb, x = make_problem(shape, seed=5, std=0.02, gain_std=0.1, v_scale=64.0)
     Gs = upstream(shape, 5, with_state=True)
-    a = run_hip_grad(shape, layers, mem_emb, x, Gs, None, False)
-    b = run_hip_grad(shape, layers, mem_emb, x, Gs, None, True)
+    state = carried(shape, 5)
+    a = run_hip_grad(shape, layers, mem_emb, x, Gs, state, False)
+    b = run_hip_grad(shape, layers, mem_emb, x, Gs, state, True)
     for la, lb in zip(a["layers"], b["layers"]):
         for k in G.WEIGHT_KEYS:
-            assert np.array_equal(la[k], lb[k]), k
-    assert np.array_equal(a["x"], b["x"]) and np.array_equal(a["mem_emb"], b["mem_emb"])
+            assert rel_fro(la[k], lb[k]) <= 2e-6, k
+    for k in ("x", "mem_emb", "A_in", "z_in"):
+        assert np.array_equal(a[k], b[k]), k
 
 
 def test_1b_width_bf16_backward_matches_oracle():
