@@ -177,3 +177,37 @@ def test_1b_width_bf16_backward_matches_oracle():
     want = G.armt_grad(shape, layers, mem_emb, x, *Gs)
     got = run_hip_grad(shape, layers, mem_emb, x, Gs, None, True)
     compare(got, want, BF16_REL, "1B width, 2 layers, 3 segments", tol_mem=BF16_REL_MEM)
+
+
+def test_full_1b_model_backward_properties():
+    """The whole 1B model (16 layers) over 8 segments, in the launch configuration bench.py times; the oracle cannot
+    differentiate this size in minutes, so properties that hold at any size: (i) an upstream gradient on segment 2 only
+    leaves the embeddings of segments 3.. without gradient, exactly (dependency rule of Section 3.1); (ii) reverse
+    diagonal and reverse sequential order agree (bit for bit on what flows between cells, to fp32 rounding on the
+    weight gradients, which the diagonal order adds four segments at a time); (iii) everything is finite and non-zero."""
+    import torch
+    import paper_2506_05229_amd as P
+    shape = S.get_shape("1b_8k")
+    layers, mem_emb = S.make_weights(shape, seed=0)
+    x = S.make_embeddings(shape, seed=0)
+    model = P.Armt(shape, layers, mem_emb)
+    xd = model.embed(x)
+    Sg = shape.seg_len
+    Gh = torch.zeros(shape.n_tokens, shape.d_model, device="cuda", dtype=model.act_dtype)
+    Gh[2 * Sg:3 * Sg] = torch.randn(Sg, shape.d_model, device="cuda", generator=torch.Generator(device="cuda").manual_seed(3)).to(
+        model.act_dtype)
+    _, _, _, tape = model.forward_train(xd, diagonal=True)
+    gd = model.backward(tape, shape.n_tokens, Gh, diagonal=True)
+    gs = model.backward(tape, shape.n_tokens, Gh, diagonal=False)
+    torch.cuda.synchronize()
+    assert not gd["x"][3 * Sg:].any().item()                       # (i)
+    assert gd["x"][:3 * Sg].abs().max().item() > 0
+    assert torch.equal(gd["x"], gs["x"]) and torch.equal(gd["mem_emb"], gs["mem_emb"])      # (ii)
+    worst = 0.0
+    for ld, ls in zip(gd["layers"], gs["layers"]):
+        for k in G.WEIGHT_KEYS:
+            a, b = ld[k].double(), ls[k].double()
+            assert torch.isfinite(a).all().item() and a.abs().max().item() > 0, k                 # (iii)
+            worst = max(worst, ((a - b).norm() / b.norm()).item())
+    print(f"full 1B model: worst relative difference between the two orders {worst:.2e}", flush=True)
+    assert worst <= 1e-5
