@@ -306,12 +306,17 @@ __global__ __launch_bounds__(512) void attention_bwd_dkv_kernel(const bf16* __re
         }
         bf16x8 pf[2], dsf[2];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int j = jj * 32 + 8 * (r >> 2) + 4 * half + (r & 3), q = q0 + j;
-          const bool live = q < Trows && ki <= q;
-          const float p = live ? __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2e, -sL[j])) : 0.f;
-          pf[r >> 3][r & 7] = (bf16)p;
-          dsf[r >> 3][r & 7] = (bf16)(p * (dp[r] - sD[j]) * scale);
+        for (int rg = 0; rg < 4; ++rg) {         // registers 4 rg .. 4 rg + 3 hold four consecutive query rows
+          const int j4 = jj * 32 + 8 * rg + 4 * half;
+          const f32x4 l4 = *(const f32x4*)(sL + j4), d4 = *(const f32x4*)(sD + j4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int r = 4 * rg + e, q = q0 + j4 + e;
+            const bool live = q < Trows && ki <= q;
+            const float p = live ? __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2e, -l4[e])) : 0.f;
+            pf[r >> 3][r & 7] = (bf16)p;
+            dsf[r >> 3][r & 7] = (bf16)(p * (dp[r] - d4[e]) * scale);
+          }
         }
         // dV^T[dim][key] += dO^T[dim][query] P[query][key],  dK^T[dim][key] += Q^T[dim][query] dS[query][key]
 #pragma unroll
