@@ -180,6 +180,19 @@ def main():
             "lm_head_rows_timed": rows_big, "lm_head_ms": ms_big, "lm_head_tflops": fl(rows_big) / ms_big / 1e9,
             "tokens_per_s_ids_to_last_segment_logits": n_tok / ((wall_ms + ms_embed + ms_last) / 1e3),
             "tokens_per_s_ids_to_all_logits_extrapolated": n_tok / ((wall_ms + ms_embed + ms_all) / 1e3)}
+        if not args.no_train:
+            # backward of the head on the same 16 segments: d_hidden, d_gain, d_W_lm from an upstream gradient of the logits
+            dl = torch.randn(lg_big.shape, device="cuda", generator=torch.Generator(device="cuda").manual_seed(2))
+            grads = None
+            def head_bwd():
+                nonlocal grads
+                out_b = te.logits_backward(hid[:rows_big], dl, grads=grads)
+                grads = (out_b[1], out_b[2])
+            ms_bwd = ev(head_bwd, reps=2)
+            res["token_ends"]["lm_head_backward_ms"] = ms_bwd
+            res["token_ends"]["lm_head_backward_tflops"] = 2.0 * fl(rows_big) / ms_bwd / 1e9
+            del dl, grads
+            te.bws = None
         del lg_last, lg_big, te
     if not args.no_train and B == 1 and P.load_library().armt_backward_workspace_bytes(C_byref(model.cfg)) > 0:
         # Training leg (outside `value`): forward that records the tape, then the backward pass in reverse diagonal

@@ -173,6 +173,22 @@ armt_status armt_backward(const armt_config *cfg, const armt_layer_weights *laye
                           float *d_mem_emb, float *dx, float *dA_in, float *dz_in,
                           void *workspace, size_t workspace_bytes, void *hip_stream, int32_t diagonal);
 
+/* Backward of the token-level ends (Algorithm 1 ends in logits; a training step differentiates a loss on them).
+ * armt_lm_head_backward: for logits = rmsnorm(hidden; final_gain, rms_eps) W_lm^T and an upstream gradient d_logits
+ * [n_rows][vocab] fp32, WRITES d_hidden [n_rows][d_model] fp32 and ADDS to d_final_gain [d_model] and d_w_lm
+ * [vocab][d_model] (fp32; the caller zeroes them or keeps accumulating).  hidden, final_gain, w_lm as in armt_lm_head.
+ * The rows are taken 8192 at a time (the weight gradient is read and written once per pass).  workspace:
+ * armt_lm_head_backward_workspace_bytes(cfg, n_rows, vocab) bytes, 256-byte aligned (0 = rejected).
+ * armt_embed_tokens_backward: d_emb_table[ids[i]][:] += dx[i][:] (fp32, [vocab][d_model]); ids outside the vocabulary
+ * are clamped as in the forward gather; rows that share an id are added with atomics in an unspecified order. */
+size_t armt_lm_head_backward_workspace_bytes(const armt_config *cfg, int64_t n_rows, int32_t vocab);
+armt_status armt_lm_head_backward(const armt_config *cfg, const void *hidden, int64_t n_rows, const void *final_gain,
+                                  const void *w_lm, int32_t vocab, const float *d_logits,
+                                  float *d_hidden, float *d_final_gain, float *d_w_lm,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+armt_status armt_embed_tokens_backward(const armt_config *cfg, const float *dx, const int32_t *ids /* device */,
+                                       int64_t n_tokens, int32_t vocab, float *d_emb_table, void *hip_stream);
+
 /* Anti-diagonal schedule (Lemma 3.1), host only: for step t of an L-layer model over N segments,
  * *l_lo .. *l_hi (inclusive) are the live layers; layer l runs segment t - l.  Returns the group
  * size, or 0 (and leaves the outputs alone) if t is outside 0 .. L + N - 2 or L, N < 1. */

@@ -20,6 +20,9 @@ Parity status (tests/test_oracle_grad.py):
                             equals the decoder block's library gradient; linearity in (G_h, G_A, G_z);
                             zero gradient of earlier hidden states with respect to later segments
 
+  lm_head_grad              finite differences of the numpy lm_head; library rms_norm + linear differentiated by the library
+  embed_tokens_grad         a table of ones-hot rows (each row's gradient counts its occurrences); pure-python loop
+
 Readings taken here: the same as in the forward oracle; in addition the decision "memory
 empty -> skip the read and use v_bar = 0" is a constant of the run (not differentiated), and
 the gradient with respect to A_in, z_in is reported only when a state was carried in.
@@ -144,3 +147,21 @@ def armt_grad(cfg, layers, mem_emb, x, G_h, G_A=None, G_z=None, A_in=None, z_in=
     return {"layers": [{k: g(w[k]) for k in WEIGHT_KEYS} for w in W], "mem_emb": g(me), "x": g(xx),
             "A_in": None if Ai is None else g(Ai), "z_in": None if zi is None else g(zi),
             "hidden": hidden.detach().numpy(), "A": A.detach().numpy(), "z": z.detach().numpy(), "J": float(J.detach())}
+
+
+# --------------------------------------------------------------------------- token-level ends (Algorithm 1)
+def lm_head_grad(hidden, final_gain, w_lm, eps, G_logits):
+    """Gradient of <logits, G_logits>, logits = rmsnorm(hidden, final_gain) W_lm^T, with respect to hidden, final_gain
+    and W_lm (autograd of the definition).  Returns (d_hidden, d_final_gain, d_w_lm)."""
+    h, g, w = _leaf(hidden), _leaf(final_gain), _leaf(w_lm)
+    logits = rmsnorm(h, g, eps) @ w.T
+    (logits * torch.as_tensor(np.asarray(G_logits, dtype=np.float64))).sum().backward()
+    return h.grad.numpy().copy(), g.grad.numpy().copy(), w.grad.numpy().copy()
+
+
+def embed_tokens_grad(ids, dx, vocab):
+    """Backward of the gather x[i] = table[ids[i]]: every row of dx is added to the table row it was read from."""
+    out = np.zeros((vocab, np.asarray(dx).shape[1]))
+    np.add.at(out, np.asarray(ids), np.asarray(dx, dtype=np.float64))
+    return out
+

@@ -97,6 +97,12 @@ def load_library():
     lib.armt_lm_head_workspace_bytes.restype = sz
     lib.armt_lm_head.argtypes = [C.POINTER(ArmtConfig), vp, i64, vp, vp, i32, vp, vp, sz, vp]
     lib.armt_lm_head.restype = C.c_int
+    lib.armt_lm_head_backward_workspace_bytes.argtypes = [C.POINTER(ArmtConfig), i64, i32]
+    lib.armt_lm_head_backward_workspace_bytes.restype = sz
+    lib.armt_lm_head_backward.argtypes = [C.POINTER(ArmtConfig), vp, i64, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.armt_lm_head_backward.restype = C.c_int
+    lib.armt_embed_tokens_backward.argtypes = [C.POINTER(ArmtConfig), vp, vp, i64, i32, vp, vp]
+    lib.armt_embed_tokens_backward.restype = C.c_int
     lib.armt_set_gemm_tile_config.argtypes = [i32]
     lib.armt_set_gemm_tile_config.restype = i32
     lib.armt_profile_begin.argtypes = [i32, i32]
@@ -380,3 +386,33 @@ class TokenEnds:
                                                _ptr(self.w_lm), V, _ptr(out), _ptr(self.ws), self.ws.numel(),
                                                _stream(torch)))
         return out
+
+    def logits_backward(self, hidden, d_logits, grads=None):
+        """Gradients of <logits, d_logits>: returns (d_hidden [n, d_model] fp32, d_final_gain [d_model], d_w_lm [vocab, d_model]);
+        the last two are accumulated into `grads = (d_final_gain, d_w_lm)` if given."""
+        torch = self.torch
+        n, V = hidden.shape[0], int(self.w_lm.shape[0])
+        assert d_logits.dtype == torch.float32 and d_logits.is_contiguous() and tuple(d_logits.shape) == (n, V)
+        need = self.lib.armt_lm_head_backward_workspace_bytes(C.byref(self.cfg), n, V)
+        if need == 0:
+            raise ArmtError(2, "configuration or sizes rejected by armt_lm_head_backward_workspace_bytes")
+        if getattr(self, "bws", None) is None or self.bws.numel() < need:
+            self.bws = torch.empty(need, dtype=torch.uint8, device=hidden.device)
+        f32 = dict(dtype=torch.float32, device=hidden.device)
+        d_hidden = torch.empty((n, self.shape.d_model), **f32)
+        d_gain, d_w = grads if grads is not None else (torch.zeros(self.shape.d_model, **f32), torch.zeros((V, self.shape.d_model), **f32))
+        _check(self.lib, self.lib.armt_lm_head_backward(C.byref(self.cfg), _ptr(hidden), n, _ptr(self.final_gain), _ptr(self.w_lm), V,
+                                                        _ptr(d_logits), _ptr(d_hidden), _ptr(d_gain), _ptr(d_w), _ptr(self.bws),
+                                                        self.bws.numel(), _stream(torch)))
+        return d_hidden, d_gain, d_w
+
+    def embed_backward(self, ids, dx, d_table=None):
+        """d_table[ids[i]] += dx[i] (fp32 [vocab, d_model]; allocated as zeros if not given)."""
+        torch = self.torch
+        assert dx.dtype == torch.float32 and dx.is_contiguous()
+        if d_table is None:
+            d_table = torch.zeros((self.vocab, self.shape.d_model), dtype=torch.float32, device=dx.device)
+        _check(self.lib, self.lib.armt_embed_tokens_backward(C.byref(self.cfg), _ptr(dx), _ptr(ids), ids.numel(), self.vocab,
+                                                             _ptr(d_table), _stream(torch)))
+        return d_table
+

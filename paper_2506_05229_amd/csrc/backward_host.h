@@ -701,3 +701,122 @@ armt_status armt_backward(const armt_config* cfg, const armt_layer_weights* laye
 }
 
 }  // extern "C"
+
+// ---- backward of the token-level ends (final RMSNorm + head, embedding gather)
+namespace {
+
+constexpr int64_t kHeadBwdRows = 8192;     // rows per pass: the head's weight gradient (V x d fp32) is read and written once per pass
+struct HeadBwdLayout { size_t WT, Nn, rstd, DLb, U, DLT, NT, CPart, table, total; int Vp, Rp; int64_t ch; };
+HeadBwdLayout head_bwd_layout(const Dims& D, int64_t n_rows, int vocab) {
+  HeadBwdLayout h;
+  h.ch = std::min<int64_t>(n_rows, kHeadBwdRows);
+  h.Vp = round64(vocab);
+  h.Rp = round64((int)h.ch);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t at = off; off += (bytes + kAlign - 1) / kAlign * kAlign; return at; };
+  h.WT = take((size_t)D.d * h.Vp * D.esz);
+  h.Nn = take((size_t)h.ch * D.d * D.esz);
+  h.rstd = take((size_t)h.ch * 4);
+  h.DLb = take((size_t)h.ch * h.Vp * D.esz);
+  h.U = take((size_t)h.ch * D.d * 4);
+  h.DLT = take((size_t)h.Vp * h.Rp * D.esz);
+  h.NT = take((size_t)D.d * h.Rp * D.esz);
+  h.CPart = take((size_t)CS_CHUNKS * D.d * 4);
+  h.table = take(2 * sizeof(GemmGroup));
+  h.total = off;
+  return h;
+}
+
+template <typename T>
+armt_status lm_head_backward_typed(const Dims& D, const HeadBwdLayout& h, const void* hidden, int64_t n_rows, const void* gain,
+                                   const void* w_lm, int32_t vocab, const float* d_logits, float* d_hidden, float* d_gain,
+                                   float* d_w, char* ws, hipStream_t st) {
+  T* WT = (T*)(ws + h.WT);
+  T* Nn = (T*)(ws + h.Nn);
+  float* rstd = (float*)(ws + h.rstd);
+  T* DLb = (T*)(ws + h.DLb);
+  float* U = (float*)(ws + h.U);
+  T* DLT = (T*)(ws + h.DLT);
+  T* NT = (T*)(ws + h.NT);
+  float* part = (float*)(ws + h.CPart);
+  auto zero = [&](void* p, size_t bytes) { fill_f32_kernel<<<ew_blocks(bytes / 4), 256, 0, st>>>((float*)p, bytes / 4, 0.f); };
+  zero(WT, (size_t)D.d * h.Vp * D.esz);                    // the padding of the vocabulary dimension must read as zero
+  HIP_TRY(hipGetLastError());
+  ARMT_TRY((transpose<T, T>(st, (const T*)w_lm, 0, D.d, WT, 0, h.Vp, vocab, D.d, 1)));
+  std::vector<GemmGroup> tab(2);
+  memset(tab.data(), 0, tab.size() * sizeof(GemmGroup));
+  tab[0].A = DLb; tab[0].B0 = WT; tab[0].C = U;                               // u = dL W
+  tab[1].A = DLT; tab[1].B0 = NT; tab[1].C = d_w; tab[1].R = d_w;             // dW += dL^T n
+  HIP_TRY(hipMemcpyAsync(ws + h.table, tab.data(), tab.size() * sizeof(GemmGroup), hipMemcpyHostToDevice, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  const GemmGroup* table = (const GemmGroup*)(ws + h.table);
+  GemmShape su, sw;
+  su.M = 0; su.N = D.d; su.K = h.Vp; su.lda = h.Vp; su.ldb = h.Vp; su.ldc = D.d; su.ldc2 = 0; su.ldr = 0; su.n0 = D.d; su.n1 = 0;
+  su.epi = EPI_STORE_F32; su.tag = -1; su.dbg = 0;
+  sw.M = vocab; sw.N = D.d; sw.K = 0; sw.lda = h.Rp; sw.ldb = h.Rp; sw.ldc = D.d; sw.ldc2 = 0; sw.ldr = D.d; sw.n0 = D.d; sw.n1 = 0;
+  sw.epi = EPI_RESID_F32; sw.tag = -1; sw.dbg = 0;
+  int64_t last_r = -1;
+  for (int64_t r0 = 0; r0 < n_rows; r0 += h.ch) {
+    const int r = (int)std::min<int64_t>(h.ch, n_rows - r0);
+    const T* hs = (const T*)hidden + (size_t)r0 * D.d;
+    if (r != last_r) {      // columns past this pass's rows must be zero in both transposed operands
+      zero(DLT, (size_t)h.Vp * h.Rp * D.esz);
+      zero(NT, (size_t)D.d * h.Rp * D.esz);
+      last_r = r;
+    }
+    final_norm_train_kernel<T><<<r, 256, 0, st>>>(hs, (const T*)gain, D.d, D.rms_eps, Nn, rstd);
+    pad_convert_rows_kernel<T><<<r, 256, 0, st>>>(d_logits + (size_t)r0 * vocab, vocab, DLb, h.Vp);
+    HIP_TRY(hipGetLastError());
+    su.M = r;
+    ARMT_TRY(gemm<T>(st, table, 0, 1, su));
+    final_norm_bwd_kernel<T><<<r, 256, 0, st>>>(U, hs, (const T*)gain, rstd, D.d, d_hidden + (size_t)r0 * D.d);
+    colsum_partial_kernel<T><<<dim3((D.d + 255) / 256, 1, CS_CHUNKS), 256, 0, st>>>(hs, U, 0, rstd, part, 0, r, D.d);
+    colsum_finish_kernel<<<dim3((D.d + 255) / 256, 1), 256, 0, st>>>(part, CS_CHUNKS, nullptr, d_gain, 0, D.d);
+    HIP_TRY(hipGetLastError());
+    ARMT_TRY((transpose<T, T>(st, DLb, 0, h.Vp, DLT, 0, h.Rp, r, h.Vp, 1)));
+    ARMT_TRY((transpose<T, T>(st, Nn, 0, D.d, NT, 0, h.Rp, r, D.d, 1)));
+    sw.K = round64(r);
+    ARMT_TRY(gemm<T>(st, table, 1, 1, sw));
+  }
+  return ARMT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t armt_lm_head_backward_workspace_bytes(const armt_config* cfg, int64_t n_rows, int32_t vocab) {
+  Dims D;
+  if (check_config(cfg, &D) != ARMT_OK || n_rows < 1 || vocab < 1) return 0;
+  return head_bwd_layout(D, n_rows, vocab).total;
+}
+
+armt_status armt_lm_head_backward(const armt_config* cfg, const void* hidden, int64_t n_rows, const void* final_gain,
+                                  const void* w_lm, int32_t vocab, const float* d_logits, float* d_hidden, float* d_final_gain,
+                                  float* d_w_lm, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Dims D;
+  ARMT_TRY(check_config(cfg, &D));
+  if (!hidden || !final_gain || !w_lm || !d_logits || !d_hidden || !d_final_gain || !d_w_lm) return ARMT_ERR_NULL;
+  if (n_rows < 1 || n_rows > 0x7fffffff || vocab < 1) return ARMT_ERR_SHAPE;
+  const HeadBwdLayout h = head_bwd_layout(D, n_rows, vocab);
+  if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < h.total) return ARMT_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (D.bf16)
+    return lm_head_backward_typed<bf16>(D, h, hidden, n_rows, final_gain, w_lm, vocab, d_logits, d_hidden, d_final_gain, d_w_lm,
+                                        (char*)workspace, st);
+  return lm_head_backward_typed<float>(D, h, hidden, n_rows, final_gain, w_lm, vocab, d_logits, d_hidden, d_final_gain, d_w_lm,
+                                       (char*)workspace, st);
+}
+
+armt_status armt_embed_tokens_backward(const armt_config* cfg, const float* dx, const int32_t* ids, int64_t n_tokens, int32_t vocab,
+                                       float* d_emb_table, void* hip_stream) {
+  Dims D;
+  ARMT_TRY(check_config(cfg, &D));
+  if (!dx || !ids || !d_emb_table) return ARMT_ERR_NULL;
+  if (vocab < 1 || n_tokens < 1 || n_tokens > 0x7fffffff) return ARMT_ERR_SHAPE;
+  embed_bwd_kernel<<<(unsigned)n_tokens, 256, 0, (hipStream_t)hip_stream>>>(dx, ids, vocab, D.d, d_emb_table);
+  HIP_TRY(hipGetLastError());
+  return ARMT_OK;
+}
+
+}  // extern "C"

@@ -258,6 +258,29 @@ def test_training_entry_argument_errors(lib):
     assert back(grads=missing) == 1
 
 
+def test_token_end_backward_argument_errors(lib):
+    shape = S.get_shape("tiny")
+    cfg = _cfg(shape)
+    fake, V, n = 0x1000, 301, 72
+    need = lib.armt_lm_head_backward_workspace_bytes(C.byref(cfg), n, V)
+    assert need > 0 and need % 256 == 0
+    assert lib.armt_lm_head_backward_workspace_bytes(C.byref(cfg), 0, V) == 0
+    assert lib.armt_lm_head_backward_workspace_bytes(C.byref(cfg), n, 0) == 0
+
+    def head(**kw):
+        a = dict(cfg=C.byref(cfg), h=fake, n=n, g=fake, w=fake, V=V, dl=fake, dh=fake, dg=fake, dw=fake, ws=0x10000, wsb=need)
+        a.update(kw)
+        return lib.armt_lm_head_backward(a["cfg"], a["h"], a["n"], a["g"], a["w"], a["V"], a["dl"], a["dh"], a["dg"], a["dw"],
+                                         a["ws"], a["wsb"], None)
+
+    assert head(cfg=None) == 1 and head(h=None) == 1 and head(dl=None) == 1 and head(dh=None) == 1 and head(dw=None) == 1
+    assert head(n=0) == 2 and head(V=0) == 2
+    assert head(ws=None) == 4 and head(wsb=need - 1) == 4 and head(ws=0x10001) == 4
+    emb = lambda **kw: lib.armt_embed_tokens_backward(C.byref(cfg), kw.get("dx", fake), kw.get("ids", fake), kw.get("n", 8),
+                                                      kw.get("V", V), kw.get("dt", fake), None)
+    assert emb(dx=None) == 1 and emb(ids=None) == 1 and emb(dt=None) == 1 and emb(n=0) == 2 and emb(V=0) == 2
+
+
 def test_microbench_needs_a_gpu_and_says_so(capsys):
     import torch
     if torch.cuda.is_available():

@@ -88,3 +88,49 @@ def test_lm_head_full_vocabulary_sampled():
     want = O.lm_head(h[r], gf, W[c], shape.rms_eps)
     assert rel_fro(sub, want) <= 2e-2, rel_fro(sub, want)
     assert np.isfinite(got.sum().item())
+
+
+# ------------------------------------------------------------------ backward of the token-level ends
+@pytest.mark.parametrize("name,vocab,rows,tol", [
+    ("tiny", 301, 72, 2e-5),          # fp32: ragged vocabulary (reduction padded to 320), one pass
+    ("tiny", 64, 9000, 2e-5),         # fp32: two passes of rows (8192 + 808)
+    ("1b_8k", 1000, 1040, 2e-2),      # bf16: vocabulary padded to 1024, rows not a multiple of the tile
+    ("1b_8k", 2048, 8200, 2e-2),      # bf16: a full pass and a short one
+])
+def test_lm_head_backward_matches_oracle(name, vocab, rows, tol):
+    """Relative Frobenius error of d_hidden, d_final_gain, d_W_lm against the autograd oracle; bf16: the upstream
+    gradient, the normalised rows and the weight are bf16 operands of the two gradient GEMMs."""
+    from oracle import armt_oracle_grad as OG
+    shape = S.get_shape(name)
+    ids, E, gf, W, te = _ends(shape, vocab, 4, shape.seg_len)
+    rng = np.random.default_rng(6)
+    h = (rng.standard_normal((rows, shape.d_model)) * 2.0).astype(np.float32)
+    Gl = rng.standard_normal((rows, vocab)).astype(np.float32)
+    if shape.dtype == "bf16":
+        h = S.round_to_bf16(h)
+    want = OG.lm_head_grad(h, gf, W, shape.rms_eps, Gl)
+    hd = torch.from_numpy(h).cuda().to(te.dt)
+    got = te.logits_backward(hd, torch.from_numpy(Gl).cuda())
+    torch.cuda.synchronize()
+    errs = [rel_fro(a.cpu().numpy(), b) for a, b in zip(got, want)]
+    print(f"{name} vocab {vocab} rows {rows}: d_hidden {errs[0]:.2e} d_gain {errs[1]:.2e} d_W {errs[2]:.2e}", flush=True)
+    assert max(errs) <= tol
+    # accumulation: a second call adds to the weight and gain gradients and rewrites d_hidden
+    got2 = te.logits_backward(hd, torch.from_numpy(Gl).cuda(), grads=(got[1], got[2]))
+    torch.cuda.synchronize()
+    assert rel_fro(got2[2].cpu().numpy(), 2.0 * want[2]) <= tol and rel_fro(got2[0].cpu().numpy(), want[0]) <= tol
+
+
+def test_embedding_backward_matches_oracle():
+    from oracle import armt_oracle_grad as OG
+    shape = S.get_shape("tiny")
+    ids, E, gf, W, te = _ends(shape, 50, 7, 4 * shape.seg_len)       # 256 tokens over 50 ids: every id repeats
+    dx = np.random.default_rng(7).standard_normal((ids.size, shape.d_model)).astype(np.float32)
+    got = te.embed_backward(torch.from_numpy(ids).cuda(), torch.from_numpy(dx).cuda())
+    torch.cuda.synchronize()
+    want = OG.embed_tokens_grad(ids, dx, 50)
+    assert np.abs(got.cpu().numpy() - want).max() <= 1e-5 * np.abs(want).max()      # atomics: order of the additions varies
+    unique = np.arange(40, dtype=np.int32)[::-1].copy()                             # no repeats: a permuted copy, exact
+    got = te.embed_backward(torch.from_numpy(unique).cuda(), torch.from_numpy(dx[:40].copy()).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy().astype(np.float64), OG.embed_tokens_grad(unique, dx[:40], 50))

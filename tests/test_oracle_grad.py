@@ -183,3 +183,40 @@ def test_gradient_respects_causality_over_segments():
     for l in range(cfg.n_layers):
         for k in G.WEIGHT_KEYS:
             assert np.allclose(full["layers"][l][k], one["layers"][l][k], rtol=1e-10, atol=1e-13), k
+
+
+# ------------------------------------------------------------------ token-level ends
+def test_lm_head_gradient_matches_finite_differences_and_library():
+    rng = np.random.default_rng(8)
+    n, d, V, eps = 5, 8, 11, 1e-5
+    h, g, w = rng.standard_normal((n, d)), 1.0 + 0.2 * rng.standard_normal(d), rng.standard_normal((V, d)) * 0.5
+    Gl = rng.standard_normal((n, V))
+    dh, dg, dw = G.lm_head_grad(h, g, w, eps, Gl)
+    J = lambda: float((O.lm_head(h, g, w, eps) * Gl).sum())
+    step = 1e-6
+    for arr, grad in ((h, dh), (g, dg), (w, dw)):
+        for idx in _fd_entries(arr, rng, 6):
+            keep = arr[idx]
+            arr[idx] = keep + step
+            jp = J()
+            arr[idx] = keep - step
+            jm = J()
+            arr[idx] = keep
+            assert abs((jp - jm) / (2 * step) - grad[idx]) <= 1e-6 * max(1.0, abs(grad[idx]))
+    ht, gt, wt = (torch.tensor(a, requires_grad=True) for a in (h, g, w))
+    (F.linear(F.rms_norm(ht, (d,), gt, eps), wt) * torch.tensor(Gl)).sum().backward()
+    for a, b in ((dh, ht.grad), (dg, gt.grad), (dw, wt.grad)):
+        assert np.allclose(a, b.numpy(), rtol=1e-10, atol=1e-12)
+
+
+def test_embedding_gradient_adds_rows_per_occurrence():
+    ids = np.array([3, 0, 3, 3, 1], dtype=np.int32)
+    dx = np.arange(10, dtype=np.float64).reshape(5, 2) + 1.0
+    got = G.embed_tokens_grad(ids, dx, vocab=5)
+    want = np.zeros((5, 2))
+    for i, t in enumerate(ids):
+        for c in range(2):
+            want[t, c] += dx[i, c]
+    assert np.array_equal(got, want) and not got[2].any() and not got[4].any()
+    assert np.array_equal(G.embed_tokens_grad(ids, np.ones((5, 2)), 5)[:, 0], np.array([1.0, 1.0, 0.0, 3.0, 0.0]))
+
