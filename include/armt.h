@@ -150,7 +150,7 @@ armt_status armt_forward_diagonal_batched(const armt_config *cfg, const armt_lay
  * sequential order; each step restores the inputs of its cells from the tape, recomputes their forward and runs the
  * backward kernels, so no activation other than the tape outlives a step.  `layers` must be the weights of the
  * forward call.  workspace: armt_backward_workspace_bytes(cfg) bytes, 256-byte aligned.
- * Supported here: head_dim <= 128, one sequence per call, and the limits of the forward calls; anything else is rejected with
+ * Supported here: head_dim <= 128 and the limits of the forward calls; anything else is rejected with
  * ARMT_ERR_UNSUPPORTED (the size queries return 0).  Two cells of one layer never run in the same step, so the
  * accumulation into a layer's gradient buffers has a fixed order and the result is deterministic. */
 typedef struct {
@@ -172,6 +172,26 @@ armt_status armt_backward(const armt_config *cfg, const armt_layer_weights *laye
                           const armt_layer_grads *grads /* [host] array of n_layers */,
                           float *d_mem_emb, float *dx, float *dA_in, float *dz_in,
                           void *workspace, size_t workspace_bytes, void *hip_stream, int32_t diagonal);
+
+/* The training calls for a batch of B sequences of equal length (x, hidden_out, d_hidden, dx: [B][n_tokens][d_model];
+ * A_in, A_out, dA_out, dA_in: [B][n_layers][d_model][Phi]; z likewise): the cells of a step are those of the batched
+ * forward calls; the B cells of a layer put their operands side by side in the reduction dimension of the layer's
+ * weight-gradient GEMMs, so the gradients of the shared weights (and of mem_emb) are the sums over the sequences, added in
+ * a fixed order.  The calls above are the case B = 1.  B * n_layers must not exceed 32768. */
+size_t armt_tape_bytes_batched(const armt_config *cfg, int32_t batch, int64_t n_tokens);
+size_t armt_backward_workspace_bytes_batched(const armt_config *cfg, int32_t batch);
+armt_status armt_forward_train_batched(const armt_config *cfg, const armt_layer_weights *layers,
+                                       const void *mem_emb, const void *x, int32_t batch, int64_t n_tokens,
+                                       const float *A_in, const float *z_in,
+                                       void *hidden_out, float *A_out, float *z_out,
+                                       void *tape, size_t tape_bytes,
+                                       void *workspace, size_t workspace_bytes, void *hip_stream, int32_t diagonal);
+armt_status armt_backward_batched(const armt_config *cfg, const armt_layer_weights *layers, int32_t batch, int64_t n_tokens,
+                                  const void *tape, size_t tape_bytes, int32_t carry_in,
+                                  const void *d_hidden, const float *dA_out, const float *dz_out,
+                                  const armt_layer_grads *grads /* [host] array of n_layers */,
+                                  float *d_mem_emb, float *dx, float *dA_in, float *dz_in,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream, int32_t diagonal);
 
 /* Backward of the token-level ends (Algorithm 1 ends in logits; a training step differentiates a loss on them).
  * armt_lm_head_backward: for logits = rmsnorm(hidden; final_gain, rms_eps) W_lm^T and an upstream gradient d_logits

@@ -80,6 +80,16 @@ def load_library():
     lib.armt_backward.argtypes = [C.POINTER(ArmtConfig), C.POINTER(ArmtLayerWeights), i64, vp, sz, i32, vp, vp, vp,
                                   C.POINTER(ArmtLayerGrads), vp, vp, vp, vp, vp, sz, vp, i32]
     lib.armt_backward.restype = C.c_int
+    lib.armt_tape_bytes_batched.argtypes = [C.POINTER(ArmtConfig), i32, i64]
+    lib.armt_tape_bytes_batched.restype = sz
+    lib.armt_backward_workspace_bytes_batched.argtypes = [C.POINTER(ArmtConfig), i32]
+    lib.armt_backward_workspace_bytes_batched.restype = sz
+    lib.armt_forward_train_batched.argtypes = [C.POINTER(ArmtConfig), C.POINTER(ArmtLayerWeights), vp, vp, i32, i64, vp, vp, vp, vp,
+                                               vp, vp, sz, vp, sz, vp, i32]
+    lib.armt_forward_train_batched.restype = C.c_int
+    lib.armt_backward_batched.argtypes = [C.POINTER(ArmtConfig), C.POINTER(ArmtLayerWeights), i32, i64, vp, sz, i32, vp, vp, vp,
+                                          C.POINTER(ArmtLayerGrads), vp, vp, vp, vp, vp, sz, vp, i32]
+    lib.armt_backward_batched.restype = C.c_int
     lib.armt_diagonal_group.argtypes = [i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
     lib.armt_diagonal_group.restype = i32
     pp = C.POINTER(C.c_void_p)
@@ -208,32 +218,42 @@ class Armt:
 
     # ------------------------------------------------------------ training
     def forward_train(self, x, diagonal=True, A_in=None, z_in=None):
-        """Forward pass that also records the tape the backward pass needs.  Returns (hidden, A, z, tape)."""
+        """Forward pass that also records the tape the backward pass needs.  x: [n_tokens, d] or, for a batch of
+        sequences, [B, n_tokens, d] (then hidden is [B, n_tokens, d], A [B, L, d, Phi], z [B, L, Phi]).
+        Returns (hidden, A, z, tape)."""
         torch, s = self.torch, self.shape
-        assert x.is_cuda and x.dtype == self.act_dtype and x.is_contiguous()
-        n_tokens = x.shape[0]
-        nbytes = self.lib.armt_tape_bytes(C.byref(self.cfg), n_tokens)
+        assert x.is_cuda and x.dtype == self.act_dtype and x.is_contiguous() and x.dim() in (2, 3)
+        B = x.shape[0] if x.dim() == 3 else 1
+        lead = (B,) if x.dim() == 3 else ()
+        n_tokens = x.shape[-2]
+        nbytes = self.lib.armt_tape_bytes_batched(C.byref(self.cfg), B, n_tokens)
         if nbytes == 0:
-            raise ArmtError(6, "configuration or length rejected by armt_tape_bytes")
+            raise ArmtError(6, "configuration, batch or length rejected by armt_tape_bytes_batched")
+        need = self.lib.armt_workspace_bytes_batched(C.byref(self.cfg), B)
+        if self.workspace.numel() < need:
+            self.workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
         tape = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
-        hidden = torch.empty((n_tokens, s.d_model), dtype=self.act_dtype, device=self.device)
-        A = torch.empty((s.n_layers, s.d_model, s.phi), dtype=torch.float32, device=self.device)
-        z = torch.empty((s.n_layers, s.phi), dtype=torch.float32, device=self.device)
+        hidden = torch.empty(lead + (n_tokens, s.d_model), dtype=self.act_dtype, device=self.device)
+        A = torch.empty(lead + (s.n_layers, s.d_model, s.phi), dtype=torch.float32, device=self.device)
+        z = torch.empty(lead + (s.n_layers, s.phi), dtype=torch.float32, device=self.device)
         stream = torch.cuda.current_stream(self.device).cuda_stream
-        code = self.lib.armt_forward_train(C.byref(self.cfg), self.c_layers, _ptr(self.mem_emb), _ptr(x), n_tokens,
-                                           _ptr(A_in), _ptr(z_in), _ptr(hidden), _ptr(A), _ptr(z), _ptr(tape), nbytes,
-                                           _ptr(self.workspace), self.workspace_bytes, C.c_void_p(stream),
-                                           1 if diagonal else 0)
+        code = self.lib.armt_forward_train_batched(C.byref(self.cfg), self.c_layers, _ptr(self.mem_emb), _ptr(x), B, n_tokens,
+                                                   _ptr(A_in), _ptr(z_in), _ptr(hidden), _ptr(A), _ptr(z), _ptr(tape), nbytes,
+                                                   _ptr(self.workspace), self.workspace.numel(), C.c_void_p(stream),
+                                                   1 if diagonal else 0)
         _check(self.lib, code)
         return hidden, A, z, tape
 
     def backward(self, tape, n_tokens, d_hidden, dA_out=None, dz_out=None, carry_in=False, diagonal=True,
                  want_dx=True, grads=None):
-        """Gradients of <hidden, d_hidden> + <A_out, dA_out> + <z_out, dz_out>.  Returns a dict: "layers" (list of
-        dicts of fp32 tensors, accumulated into `grads["layers"]` if given), "mem_emb", "x", "A_in", "z_in"."""
+        """Gradients of <hidden, d_hidden> + <A_out, dA_out> + <z_out, dz_out>; d_hidden [n_tokens, d] or [B, n_tokens, d]
+        as in forward_train.  Returns a dict: "layers" (list of dicts of fp32 tensors, accumulated into `grads["layers"]`
+        if given; summed over the sequences of a batch), "mem_emb", "x", "A_in", "z_in" (per sequence)."""
         torch, s = self.torch, self.shape
         f32 = dict(dtype=torch.float32, device=self.device)
-        assert d_hidden.is_cuda and d_hidden.dtype == self.act_dtype and d_hidden.is_contiguous()
+        assert d_hidden.is_cuda and d_hidden.dtype == self.act_dtype and d_hidden.is_contiguous() and d_hidden.dim() in (2, 3)
+        B = d_hidden.shape[0] if d_hidden.dim() == 3 else 1
+        lead = (B,) if d_hidden.dim() == 3 else ()
         if grads is None:
             grads = {"layers": [{f: torch.zeros(tuple(lw[f].shape), **f32) for f in LAYER_FIELDS} for lw in self.layers],
                      "mem_emb": torch.zeros(tuple(self.mem_emb.shape), **f32)}
@@ -241,20 +261,20 @@ class Armt:
         for l, g in enumerate(grads["layers"]):
             for f in LAYER_FIELDS:
                 setattr(c_grads[l], f, g[f].data_ptr())
-        dx = torch.empty((n_tokens, s.d_model), **f32) if want_dx else None
-        dA_in = torch.empty((s.n_layers, s.d_model, s.phi), **f32) if carry_in else None
-        dz_in = torch.empty((s.n_layers, s.phi), **f32) if carry_in else None
-        need = self.lib.armt_backward_workspace_bytes(C.byref(self.cfg))
+        dx = torch.empty(lead + (n_tokens, s.d_model), **f32) if want_dx else None
+        dA_in = torch.empty(lead + (s.n_layers, s.d_model, s.phi), **f32) if carry_in else None
+        dz_in = torch.empty(lead + (s.n_layers, s.phi), **f32) if carry_in else None
+        need = self.lib.armt_backward_workspace_bytes_batched(C.byref(self.cfg), B)
         if need == 0:
-            raise ArmtError(6, "configuration rejected by armt_backward_workspace_bytes")
+            raise ArmtError(6, "configuration or batch rejected by armt_backward_workspace_bytes_batched")
         if getattr(self, "bwd_workspace", None) is None or self.bwd_workspace.numel() < need:
             self.bwd_workspace = torch.empty(need, dtype=torch.uint8, device=self.device)
         stream = torch.cuda.current_stream(self.device).cuda_stream
-        code = self.lib.armt_backward(C.byref(self.cfg), self.c_layers, n_tokens, _ptr(tape), tape.numel(),
-                                      1 if carry_in else 0, _ptr(d_hidden), _ptr(dA_out), _ptr(dz_out), c_grads,
-                                      _ptr(grads["mem_emb"]), _ptr(dx), _ptr(dA_in), _ptr(dz_in),
-                                      _ptr(self.bwd_workspace), self.bwd_workspace.numel(), C.c_void_p(stream),
-                                      1 if diagonal else 0)
+        code = self.lib.armt_backward_batched(C.byref(self.cfg), self.c_layers, B, n_tokens, _ptr(tape), tape.numel(),
+                                              1 if carry_in else 0, _ptr(d_hidden), _ptr(dA_out), _ptr(dz_out), c_grads,
+                                              _ptr(grads["mem_emb"]), _ptr(dx), _ptr(dA_in), _ptr(dz_in),
+                                              _ptr(self.bwd_workspace), self.bwd_workspace.numel(), C.c_void_p(stream),
+                                              1 if diagonal else 0)
         _check(self.lib, code)
         grads.update({"x": dx, "A_in": dA_in, "z_in": dz_in})
         return grads

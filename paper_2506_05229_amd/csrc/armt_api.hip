@@ -384,8 +384,8 @@ armt_status save_tape(const Ctx& c, int lo, int hi, int t) {
   if (!c.tape) return ARMT_OK;
   const Dims& D = c.D;
   const size_t nx = (size_t)D.T * D.d, nA = (size_t)D.d * D.Phi, nz = D.Phi;
-  tape_kernel<<<dim3(128, hi - lo + 1), 256, 0, c.st>>>(c.tape, c.rec_floats, c.at<float>(c.o.X), nx, c.aux, nullptr, nullptr, lo, t,
-                                                      D.Lr, nx, nA, nz, 1);
+  tape_kernel<<<dim3(128, (hi - lo + 1) * D.B), 256, 0, c.st>>>(c.tape, c.rec_floats, c.at<float>(c.o.X), nx, c.aux, nullptr, nullptr,
+                                                              lo * D.B, t, D.L, D.B, nx, nA, nz, 1);
   HIP_TRY(hipGetLastError());
   return ARMT_OK;
 }

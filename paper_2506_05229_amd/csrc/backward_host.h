@@ -39,7 +39,7 @@ struct TrainLayout {
   size_t wa_rows, wb_rows, aDY, aDGU, aDH, aDQKV, aDQR, bU, bN2, bATT, bN1, bX;   // rows of a layer's window operands
   size_t WdT, WguT, WoT, WqkvT, WmqT, WmkvT;
   size_t Ptrs, Tables, Aux, total;
-  int Tp, mp, dmP, Kmkv, nblk;
+  int Tp, mp, dmP, Kmkv, nblk, Kw, Km;     // Kw, Km: columns of a window row (WG_WIN slots x batch x Tp or mp)
   size_t ta_rows, tb_rows;
 };
 
@@ -47,9 +47,11 @@ TrainLayout carve_train(const Dims& D) {
   TrainLayout o;
   size_t p = 0;
   auto take = [&](size_t bytes) { size_t at = p; p = align_up(p + bytes); return at; };
-  const size_t L = D.L, T = D.T, d = D.d, e = D.esz, F = D.F, Hd = (size_t)D.H * D.dh;
+  // L = cells of a step (layers x batch): everything per cell; Lr = layers: weights, their gradients' window operands
+  const size_t L = D.L, Lr = D.Lr, B = D.B, T = D.T, d = D.d, e = D.esz, F = D.F, Hd = (size_t)D.H * D.dh;
   o.Tp = round64(D.T); o.mp = round64(D.m); o.dmP = round64(D.dm); o.Kmkv = round64(D.dm + D.d);
   o.nblk = (D.d + UB_ROWS - 1) / UB_ROWS;
+  o.Kw = WG_WIN * (int)B * o.Tp; o.Km = WG_WIN * (int)B * o.mp;
   o.Xin = take(L * T * d * 4);
   o.X1 = take(L * T * d * 4);
   o.Xb = take(D.bf16 ? L * T * d * 2 : 0);
@@ -76,7 +78,7 @@ TrainLayout carve_train(const Dims& D) {
   o.zw = take(L * (size_t)D.Phi * 4);
   o.A16w = take(D.bf16 ? L * d * D.Phi * 2 : 0);
   o.ATr = take(L * d * D.Phi * e);
-  o.DX = take((L + 1) * T * d * 4);
+  o.DX = take((L + B) * T * d * 4);
   o.DYb = take(L * T * d * e);
   o.DU = take(L * T * F * e);
   o.DN = take(L * T * d * e);
@@ -103,21 +105,21 @@ TrainLayout carve_train(const Dims& D) {
   o.tb_rows = (size_t)D.Phi;
   o.TA = take(L * o.ta_rows * o.Tp * e);
   o.TB = take(L * o.tb_rows * o.Tp * e);
-  o.TmA = take(L * (size_t)(D.dm + D.d) * WG_WIN * o.mp * e);
-  o.TmB = take(L * d * WG_WIN * o.mp * e);
+  o.TmA = take(Lr * (size_t)(D.dm + D.d) * o.Km * e);
+  o.TmB = take(Lr * d * o.Km * e);
   o.aDY = 0; o.aDGU = d; o.aDH = d + 2 * F; o.aDQKV = 2 * d + 2 * F; o.aDQR = 2 * d + 2 * F + D.Nqkv;
   o.wa_rows = o.aDQR + D.dm;
   o.bU = 0; o.bN2 = F; o.bATT = F + d; o.bN1 = F + d + Hd; o.bX = F + 2 * d + Hd;
   o.wb_rows = o.bX + d;
-  o.WinA = take(L * o.wa_rows * WG_WIN * o.Tp * e);
-  o.WinB = take(L * o.wb_rows * WG_WIN * o.Tp * e);
+  o.WinA = take(Lr * o.wa_rows * o.Kw * e);
+  o.WinB = take(Lr * o.wb_rows * o.Kw * e);
   o.CPart = take(L * CS_CHUNKS * std::max(d, (size_t)D.Phi) * 4);
-  o.WdT = take(L * F * d * e);
-  o.WguT = take(L * d * 2 * F * e);
-  o.WoT = take(L * Hd * d * e);
-  o.WqkvT = take(L * d * D.Nqkv * e);
-  o.WmqT = take(L * d * o.dmP * e);
-  o.WmkvT = take(L * d * o.Kmkv * e);
+  o.WdT = take(Lr * F * d * e);
+  o.WguT = take(Lr * d * 2 * F * e);
+  o.WoT = take(Lr * Hd * d * e);
+  o.WqkvT = take(Lr * d * D.Nqkv * e);
+  o.WmqT = take(Lr * d * o.dmP * e);
+  o.WmkvT = take(Lr * d * o.Kmkv * e);
   o.Ptrs = take(3 * L * sizeof(float*));
   o.Tables = take((size_t)TK_COUNT * L * sizeof(GemmGroup));
   o.Aux = take(L * sizeof(LayerAux));
@@ -176,7 +178,7 @@ void fill_train_shapes(BCtx& c) {
   set(TK_DF, D.T, D.Phi, D.d, D.d, D.Phi, EPI_STORE_F32);
   set(TK_DXQ, D.T, D.d, o.dmP, o.dmP, D.d, EPI_RESID_F32);
   // weight gradients: K = slots of the window actually filled (set at launch), lda = ldb = a whole window row
-  const int Kw = WG_WIN * o.Tp, Km = WG_WIN * o.mp;
+  const int Kw = o.Kw, Km = o.Km;
   set(TK_WD, D.d, D.F, Kw, Kw, D.F, EPI_RESID_F32, -1, 0, Kw);
   set(TK_WG, D.F, D.d, Kw, Kw, D.d, EPI_RESID_F32, -1, 0, Kw);
   set(TK_WU, D.F, D.d, Kw, Kw, D.d, EPI_RESID_F32, -1, 0, Kw);
@@ -199,23 +201,25 @@ armt_status upload_train_tables(BCtx& c, const armt_layer_weights* W, const armt
   std::vector<float*> ptrs(3 * L);
   memset(tab.data(), 0, tab.size() * sizeof(GemmGroup));
   char* ws = c.ws;
-  for (size_t l = 0; l < L; ++l) {
-    const armt_layer_weights& w = W[l];
-    const armt_layer_grads& gw = G[l];
+  const size_t B = D.B;
+  for (size_t l = 0; l < L; ++l) {                 // l = cell: layer lr = l / B of sequence l % B
+    const size_t lr = l / B;
+    const armt_layer_weights& w = W[lr];
+    const armt_layer_grads& gw = G[lr];
     auto E = [&](int k) -> GemmGroup* { return &tab[(size_t)k * L + l]; };
     char* X1 = ws + o.X1 + l * T * d * 4;
     char* Xin = ws + o.Xin + l * T * d * 4;
     char* Xop = D.bf16 ? ws + o.Xb + l * T * d * 2 : Xin;           // activation-typed cell input (before the read)
     char* Yop = D.bf16 ? ws + o.Yb + l * T * d * 2 : ws + o.Yf + l * T * d * 4;
     char* DXl = ws + o.DX + l * T * d * 4;
-    char* DXup = ws + o.DX + (l + 1) * T * d * 4;
+    char* DXup = ws + o.DX + (l + B) * T * d * 4;       // output gradient of cell l: the slot of the cell one layer up
     char* TA = ws + o.TA + l * o.ta_rows * o.Tp * e;
     char* TB = ws + o.TB + l * o.tb_rows * o.Tp * e;
-    char* TmA = ws + o.TmA + l * (size_t)(D.dm + D.d) * WG_WIN * o.mp * e;
-    char* TmB = ws + o.TmB + l * d * WG_WIN * o.mp * e;
-    const size_t rowb = (size_t)WG_WIN * o.Tp * e;      // bytes of one window row
-    char* WA = ws + o.WinA + l * o.wa_rows * rowb;
-    char* WB = ws + o.WinB + l * o.wb_rows * rowb;
+    char* TmA = ws + o.TmA + lr * (size_t)(D.dm + D.d) * o.Km * e;
+    char* TmB = ws + o.TmB + lr * d * o.Km * e;
+    const size_t rowb = (size_t)o.Kw * e;               // bytes of one window row
+    char* WA = ws + o.WinA + lr * o.wa_rows * rowb;
+    char* WB = ws + o.WinB + lr * o.wb_rows * rowb;
     GemmGroup* g;
     g = E(TK_MQ); g->A = Xop; g->B0 = w.wm_q; g->C = ws + o.Qm + l * T * D.dm * 4;
     g = E(TK_READ); g->A = ws + o.Fphi + l * T * D.Phi * e;
@@ -231,17 +235,21 @@ armt_status upload_train_tables(BCtx& c, const armt_layer_weights* W, const armt
     g = E(TK_MKV); g->A = Yop + (size_t)D.S * d * e; g->B0 = w.wm_k; g->B1 = w.wm_v;
     g->C = ws + o.KVm + l * D.m * (size_t)(D.dm + D.d) * 4;
 
-    g = E(TK_DYM); g->A = ws + o.DKV + l * D.m * (size_t)o.Kmkv * e; g->B0 = ws + o.WmkvT + l * d * o.Kmkv * e;
+    g = E(TK_DYM); g->A = ws + o.DKV + l * D.m * (size_t)o.Kmkv * e; g->B0 = ws + o.WmkvT + lr * d * o.Kmkv * e;
     g->C = DXup + (size_t)D.S * d * 4; g->R = (const float*)g->C;
-    g = E(TK_DU); g->A = ws + o.DYb + l * T * d * e; g->B0 = ws + o.WdT + l * F * d * e; g->C = ws + o.DU + l * T * F * e;
-    g = E(TK_DN2); g->A = ws + o.GU + l * T * 2 * F * e; g->B0 = ws + o.WguT + l * d * 2 * F * e; g->C = ws + o.DN + l * T * d * e;
-    g = E(TK_DATT); g->A = ws + o.DHb + l * T * d * e; g->B0 = ws + o.WoT + l * Hd * d * e; g->C = ws + o.DAtt + l * T * Hd * e;
-    g = E(TK_DN1); g->A = ws + o.DQKV + l * T * D.Nqkv * e; g->B0 = ws + o.WqkvT + l * d * D.Nqkv * e;
+    g = E(TK_DU); g->A = ws + o.DYb + l * T * d * e; g->B0 = ws + o.WdT + lr * F * d * e; g->C = ws + o.DU + l * T * F * e;
+    g = E(TK_DN2); g->A = ws + o.GU + l * T * 2 * F * e; g->B0 = ws + o.WguT + lr * d * 2 * F * e; g->C = ws + o.DN + l * T * d * e;
+    g = E(TK_DATT); g->A = ws + o.DHb + l * T * d * e; g->B0 = ws + o.WoT + lr * Hd * d * e; g->C = ws + o.DAtt + l * T * Hd * e;
+    g = E(TK_DN1); g->A = ws + o.DQKV + l * T * D.Nqkv * e; g->B0 = ws + o.WqkvT + lr * d * D.Nqkv * e;
     g->C = ws + o.DN + l * T * d * e;
     g = E(TK_DF); g->A = ws + o.DNum + l * T * d * e; g->B0 = ws + o.ATr + l * d * D.Phi * e; g->C = ws + o.DF + l * T * D.Phi * 4;
-    g = E(TK_DXQ); g->A = ws + o.DQr + l * T * o.dmP * e; g->B0 = ws + o.WmqT + l * d * o.dmP * e; g->C = DXl; g->R = (const float*)DXl;
+    g = E(TK_DXQ); g->A = ws + o.DQr + l * T * o.dmP * e; g->B0 = ws + o.WmqT + lr * d * o.dmP * e; g->C = DXl; g->R = (const float*)DXl;
 
-    auto wgrad = [&](int k, char* A, char* B, float* C) { GemmGroup* q = E(k); q->A = A; q->B0 = B; q->C = C; q->R = C; };
+    // weight gradients: one entry per LAYER (index lr), written when its first cell comes by; dA: one per cell
+    auto wgrad = [&](int k, char* A, char* Bp, float* C) {
+      if (k != TK_DA && l % B != 0) return;
+      GemmGroup* q = &tab[(size_t)k * L + (k == TK_DA ? l : lr)]; q->A = A; q->B0 = Bp; q->C = C; q->R = C;
+    };
     wgrad(TK_WD, WA + o.aDY * rowb, WB + o.bU * rowb, gw.wdown);
     wgrad(TK_WG, WA + o.aDGU * rowb, WB + o.bN2 * rowb, gw.wgate);
     wgrad(TK_WU, WA + (o.aDGU + F) * rowb, WB + o.bN2 * rowb, gw.wup);
@@ -252,7 +260,7 @@ armt_status upload_train_tables(BCtx& c, const armt_layer_weights* W, const armt
     wgrad(TK_DA, TA, TB, (float*)(ws + o.DA + l * d * D.Phi * 4));
     wgrad(TK_WMQ, WA + o.aDQR * rowb, WB + o.bX * rowb, gw.wm_q);
     wgrad(TK_WMK, TmA, TmB, gw.wm_k);
-    wgrad(TK_WMV, TmA + (size_t)D.dm * WG_WIN * o.mp * e, TmB, gw.wm_v);
+    wgrad(TK_WMV, TmA + (size_t)D.dm * o.Km * e, TmB, gw.wm_v);
 
     LayerAux& a = aux[l];
     a.rms1 = w.rms1; a.rms2 = w.rms2; a.wm_b = w.wm_b;
@@ -296,11 +304,11 @@ armt_status transpose_weights(BCtx& c, const armt_layer_weights* W) {
   const Dims& D = c.D;
   const TrainLayout& o = c.o;
   const size_t d = D.d, F = D.F, Hd = (size_t)D.H * D.dh, Hkd = (size_t)D.Hkv * D.dh;
-  const size_t nq = (size_t)D.L * d * o.dmP, nk = (size_t)D.L * d * o.Kmkv;
+  const size_t nq = (size_t)D.Lr * d * o.dmP, nk = (size_t)D.Lr * d * o.Kmkv;
   fill_f32_kernel<<<ew_blocks(nq), 256, 0, c.st>>>(c.at<float>(o.WmqT), nq * D.esz / 4, 0.f);   // K padding must read as zero
   fill_f32_kernel<<<ew_blocks(nk), 256, 0, c.st>>>(c.at<float>(o.WmkvT), nk * D.esz / 4, 0.f);
   HIP_TRY(hipGetLastError());
-  for (int l = 0; l < D.L; ++l) {
+  for (int l = 0; l < D.Lr; ++l) {
     const armt_layer_weights& w = W[l];
     T* WdT = c.at<T>(o.WdT) + l * F * d;
     T* WguT = c.at<T>(o.WguT) + l * d * 2 * F;
@@ -340,7 +348,9 @@ armt_status colsum(const BCtx& c, const T* a, const float* b, size_t b_cell, con
   if (g <= 0) return ARMT_OK;
   float* part = c.at<float>(c.o.CPart);
   colsum_partial_kernel<T><<<dim3((C + 255) / 256, g, CS_CHUNKS), 256, 0, c.st>>>(a, b, b_cell, w, part, first, c.D.T, C);
-  colsum_finish_kernel<<<dim3((C + 255) / 256, g), 256, 0, c.st>>>(part, CS_CHUNKS, dst_tab, dst_base, first, C);
+  // a per-layer destination (pointer table) takes the B cells of the layer in one thread, in order
+  const int nb = dst_tab ? c.D.B : 1;
+  colsum_finish_kernel<<<dim3((C + 255) / 256, g / nb), 256, 0, c.st>>>(part, CS_CHUNKS, dst_tab, dst_base, first, C, nb);
   HIP_TRY(hipGetLastError());
   return ARMT_OK;
 }
@@ -405,13 +415,21 @@ armt_status backward_group(const BCtx& c, int lo, int g, int gr, int slot) {
   const size_t ta_cell = o.ta_rows * Tp, tb_cell = o.tb_rows * Tp;
   T* TA = c.at<T>(o.TA) + lo * ta_cell;
   T* TB = c.at<T>(o.TB) + lo * tb_cell;
-  // window operands of the weight gradients: this step's columns of a layer's rows
-  const int Kw = WG_WIN * Tp, Km = WG_WIN * o.mp;
+  // window operands of the weight gradients: this step's columns of a layer's rows; the B cells of a layer side by side
+  const int B = D.B, lo_r = lo / B;
+  const int Kw = o.Kw, Km = o.Km;
   const size_t wa_cell = o.wa_rows * Kw, wb_cell = o.wb_rows * Kw;
-  T* WA = c.at<T>(o.WinA) + lo * wa_cell + (size_t)slot * Tp;
-  T* WB = c.at<T>(o.WinB) + lo * wb_cell + (size_t)slot * Tp;
+  T* WA = c.at<T>(o.WinA) + lo_r * wa_cell + (size_t)slot * B * Tp;
+  T* WB = c.at<T>(o.WinB) + lo_r * wb_cell + (size_t)slot * B * Tp;
   auto arow = [&](size_t r) { return WA + r * Kw; };
   auto brow = [&](size_t r) { return WB + r * Kw; };
+  // transposes of n cells (from cell `lo` on) into window rows: sequence b of every layer goes to columns b * colstep
+  auto wtr = [&](const T* src, size_t src_cell, int lds, T* dst, size_t dst_cell, int colstep, int ldd, int R, int C, int n) -> armt_status {
+    for (int b = 0; b < B; ++b)
+      ARMT_TRY((transpose<T, T>(st, src + (size_t)b * src_cell, (size_t)B * src_cell, lds, dst + (size_t)b * colstep, dst_cell, ldd, R, C,
+                                n / B)));
+    return ARMT_OK;
+  };
   float* DX = c.at<float>(o.DX);
   const T* Yop = D.bf16 ? (const T*)c.at<bf16>(o.Yb) : (const T*)c.at<float>(o.Yf);
   const T* Xop = D.bf16 ? (const T*)c.at<bf16>(o.Xb) : (const T*)c.at<float>(o.Xin);
@@ -439,36 +457,38 @@ armt_status backward_group(const BCtx& c, int lo, int g, int gr, int slot) {
     HIP_TRY(hipGetLastError());
     ARMT_TRY(bgemm<T>(c, TK_DYM, lo, g));
     beta_bwd_kernel<T><<<dim3((D.d + 255) / 256, g), 256, 0, st>>>(c.at<float>(o.DB), Yop + (size_t)D.S * D.d, cell, c.aux,
-                                                                 DX + cell + (size_t)D.S * D.d, cell, c.dwb, lo, D.m, D.d);
+                                                                 DX + B * cell + (size_t)D.S * D.d, cell, c.at<float>(o.CPart), lo,
+                                                                 D.m, D.d);
+    colsum_finish_kernel<<<dim3((D.d + 255) / 256, g / B), 256, 0, st>>>(c.at<float>(o.CPart), 1, c.dwb, nullptr, lo, D.d, B);
     HIP_TRY(hipGetLastError());
     const size_t tma = (size_t)(D.dm + D.d) * Km, tmb = (size_t)D.d * Km;
-    ARMT_TRY((transpose<T, T>(st, c.at<T>(o.DKV) + (size_t)lo * D.m * o.Kmkv, (size_t)D.m * o.Kmkv, o.Kmkv,
-                              c.at<T>(o.TmA) + lo * tma + (size_t)slot * o.mp, tma, Km, D.m, D.dm + D.d, g)));
-    ARMT_TRY((transpose<T, T>(st, Yop + lo * cell + (size_t)D.S * D.d, cell, D.d, c.at<T>(o.TmB) + lo * tmb + (size_t)slot * o.mp, tmb,
-                              Km, D.m, D.d, g)));
+    ARMT_TRY(wtr(c.at<T>(o.DKV) + (size_t)lo * D.m * o.Kmkv, (size_t)D.m * o.Kmkv, o.Kmkv,
+                 c.at<T>(o.TmA) + lo_r * tma + (size_t)slot * B * o.mp, tma, o.mp, Km, D.m, D.dm + D.d, g));
+    ARMT_TRY(wtr(Yop + lo * cell + (size_t)D.S * D.d, cell, D.d, c.at<T>(o.TmB) + lo_r * tmb + (size_t)slot * B * o.mp, tmb, o.mp, Km,
+                 D.m, D.d, g));
   }
   // ---- feed-forward half of the block
   T* DYb = c.at<T>(o.DYb) + lo * cell;
-  convert_kernel<float, T><<<ew_blocks(g * cell), 256, 0, st>>>(DX + (lo + 1) * cell, DYb, g * cell);
+  convert_kernel<float, T><<<ew_blocks(g * cell), 256, 0, st>>>(DX + (lo + B) * cell, DYb, g * cell);
   HIP_TRY(hipGetLastError());
   ARMT_TRY(bgemm<T>(c, TK_DU, lo, g));
-  ARMT_TRY((transpose<T, T>(st, DYb, cell, D.d, arow(o.aDY), wa_cell, Kw, D.T, D.d, g)));
-  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.Uff) + (size_t)lo * D.T * D.F, (size_t)D.T * D.F, D.F, brow(o.bU), wb_cell, Kw, D.T, D.F, g)));
+  ARMT_TRY(wtr(DYb, cell, D.d, arow(o.aDY), wa_cell, Tp, Kw, D.T, D.d, g));
+  ARMT_TRY(wtr(c.at<T>(o.Uff) + (size_t)lo * D.T * D.F, (size_t)D.T * D.F, D.F, brow(o.bU), wb_cell, Tp, Kw, D.T, D.F, g));
   T* GU = c.at<T>(o.GU) + (size_t)lo * D.T * 2 * D.F;
   swiglu_bwd_kernel<T><<<ew_blocks((size_t)g * D.T * D.F), 256, 0, st>>>(GU, c.at<T>(o.DU) + (size_t)lo * D.T * D.F, (size_t)g * D.T,
                                                                         D.F);
   HIP_TRY(hipGetLastError());
   ARMT_TRY(bgemm<T>(c, TK_DN2, lo, g));
-  ARMT_TRY((transpose<T, T>(st, GU, (size_t)D.T * 2 * D.F, 2 * D.F, arow(o.aDGU), wa_cell, Kw, D.T, 2 * D.F, g)));
-  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.N2) + lo * cell, cell, D.d, brow(o.bN2), wb_cell, Kw, D.T, D.d, g)));
+  ARMT_TRY(wtr(GU, (size_t)D.T * 2 * D.F, 2 * D.F, arow(o.aDGU), wa_cell, Tp, Kw, D.T, 2 * D.F, g));
+  ARMT_TRY(wtr(c.at<T>(o.N2) + lo * cell, cell, D.d, brow(o.bN2), wb_cell, Tp, Kw, D.T, D.d, g));
   ARMT_TRY(colsum<T>(c, c.at<T>(o.DN), c.at<float>(o.Hres), cell, c.at<float>(o.RStd2), c.dg2, nullptr, lo, g, D.d));   // d gain 2
   rmsnorm_bwd_kernel<T><<<dim3(D.T, g), 256, 0, st>>>(c.at<T>(o.DN), c.at<float>(o.Hres), cell, c.aux, lo, 1, c.at<float>(o.RStd2),
-                                                     DX + cell, cell, c.at<float>(o.DH), cell, c.at<T>(o.DHb), D.T, D.d);
+                                                     DX + B * cell, cell, c.at<float>(o.DH), cell, c.at<T>(o.DHb), D.T, D.d);
   HIP_TRY(hipGetLastError());
   // ---- attention half
   ARMT_TRY(bgemm<T>(c, TK_DATT, lo, g));
-  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.DHb) + lo * cell, cell, D.d, arow(o.aDH), wa_cell, Kw, D.T, D.d, g)));
-  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.Att) + lo * D.T * Hd, D.T * Hd, (int)Hd, brow(o.bATT), wb_cell, Kw, D.T, (int)Hd, g)));
+  ARMT_TRY(wtr(c.at<T>(o.DHb) + lo * cell, cell, D.d, arow(o.aDH), wa_cell, Tp, Kw, D.T, D.d, g));
+  ARMT_TRY(wtr(c.at<T>(o.Att) + lo * D.T * Hd, D.T * Hd, (int)Hd, brow(o.bATT), wb_cell, Tp, Kw, D.T, (int)Hd, g));
   const float scale = 1.0f / sqrtf((float)D.dh);
   if (mfma_attention_bwd<T>(D)) {
     HIP_TRY(launch_attention_bwd_mfma(c.at<bf16>(o.QKV), c.at<bf16>(o.Att), c.at<bf16>(o.DAtt), c.at<float>(o.LSE), c.at<float>(o.Dv),
@@ -484,9 +504,8 @@ armt_status backward_group(const BCtx& c, int lo, int g, int gr, int slot) {
   rope_bwd_kernel<T><<<dim3(D.T, g), 256, 0, st>>>(c.at<T>(o.DQKV), c.at<float>(o.Rope), lo, D.T, D.H + D.Hkv, D.dh, D.Nqkv);
   HIP_TRY(hipGetLastError());
   ARMT_TRY(bgemm<T>(c, TK_DN1, lo, g));
-  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.DQKV) + (size_t)lo * D.T * D.Nqkv, (size_t)D.T * D.Nqkv, D.Nqkv, arow(o.aDQKV), wa_cell, Kw,
-                            D.T, D.Nqkv, g)));
-  ARMT_TRY((transpose<T, T>(st, c.at<T>(o.N1) + lo * cell, cell, D.d, brow(o.bN1), wb_cell, Kw, D.T, D.d, g)));
+  ARMT_TRY(wtr(c.at<T>(o.DQKV) + (size_t)lo * D.T * D.Nqkv, (size_t)D.T * D.Nqkv, D.Nqkv, arow(o.aDQKV), wa_cell, Tp, Kw, D.T, D.Nqkv, g));
+  ARMT_TRY(wtr(c.at<T>(o.N1) + lo * cell, cell, D.d, brow(o.bN1), wb_cell, Tp, Kw, D.T, D.d, g));
   ARMT_TRY(colsum<T>(c, c.at<T>(o.DN), c.at<float>(o.X1), cell, c.at<float>(o.RStd1), c.dg1, nullptr, lo, g, D.d));     // d gain 1
   rmsnorm_bwd_kernel<T><<<dim3(D.T, g), 256, 0, st>>>(c.at<T>(o.DN), c.at<float>(o.X1), cell, c.aux, lo, 0, c.at<float>(o.RStd1),
                                                      c.at<float>(o.DH), cell, DX, cell, (T*)nullptr, D.T, D.d);
@@ -508,9 +527,8 @@ armt_status backward_group(const BCtx& c, int lo, int g, int gr, int slot) {
     ARMT_TRY((transpose<T, T>(st, c.at<T>(o.Fphi) + (size_t)lo * D.T * Phi, (size_t)D.T * Phi, Phi, TB, tb_cell, Tp, D.T, Phi, gr)));
     ARMT_TRY(bgemm<T>(c, TK_DA, lo, gr));
     ARMT_TRY(bgemm<T>(c, TK_DXQ, lo, gr));
-    ARMT_TRY((transpose<T, T>(st, c.at<T>(o.DQr) + (size_t)lo * D.T * o.dmP, (size_t)D.T * o.dmP, o.dmP, arow(o.aDQR), wa_cell, Kw, D.T,
-                              D.dm, gr)));
-    ARMT_TRY((transpose<T, T>(st, Xop + lo * cell, cell, D.d, brow(o.bX), wb_cell, Kw, D.T, D.d, gr)));
+    ARMT_TRY(wtr(c.at<T>(o.DQr) + (size_t)lo * D.T * o.dmP, (size_t)D.T * o.dmP, o.dmP, arow(o.aDQR), wa_cell, Tp, Kw, D.T, D.dm, gr));
+    ARMT_TRY(wtr(Xop + lo * cell, cell, D.d, brow(o.bX), wb_cell, Tp, Kw, D.T, D.d, gr));
   }
   return ARMT_OK;
 }
@@ -520,8 +538,9 @@ armt_status backward_typed(BCtx& c, const armt_layer_weights* W, int64_t N, floa
                            const void* d_hidden, float* d_mem_emb, float* dx, bool diagonal) {
   const Dims& D = c.D;
   const TrainLayout& o = c.o;
-  const int L = D.L;
+  const int L = D.L, Lr = D.Lr, B = D.B;           // cells of a full step, layers, sequences
   const size_t cell = (size_t)D.T * D.d, nA = (size_t)D.d * D.Phi;
+  const size_t seq = (size_t)N * D.S * D.d;        // elements of one sequence of d_hidden / dx
   {
     const int n = D.T * (D.dh / 2);
     rope_table_kernel<<<(n + 255) / 256, 256, 0, c.st>>>(c.at<float>(o.Rope), D.T, D.dh / 2, (double)D.rope_theta);
@@ -532,13 +551,13 @@ armt_status backward_typed(BCtx& c, const armt_layer_weights* W, int64_t N, floa
     };
     zero(o.TA, (size_t)L * o.ta_rows * o.Tp * D.esz);
     zero(o.TB, (size_t)L * o.tb_rows * o.Tp * D.esz);
-    zero(o.TmA, (size_t)L * (D.dm + D.d) * WG_WIN * o.mp * D.esz);
-    zero(o.TmB, (size_t)L * D.d * WG_WIN * o.mp * D.esz);
-    zero(o.WinA, (size_t)L * o.wa_rows * WG_WIN * o.Tp * D.esz);
-    zero(o.WinB, (size_t)L * o.wb_rows * WG_WIN * o.Tp * D.esz);
+    zero(o.TmA, (size_t)Lr * (D.dm + D.d) * o.Km * D.esz);
+    zero(o.TmB, (size_t)Lr * D.d * o.Km * D.esz);
+    zero(o.WinA, (size_t)Lr * o.wa_rows * o.Kw * D.esz);
+    zero(o.WinB, (size_t)Lr * o.wb_rows * o.Kw * D.esz);
     zero(o.DQr, (size_t)L * D.T * o.dmP * D.esz);
     zero(o.DKV, (size_t)L * D.m * o.Kmkv * D.esz);
-    zero(o.DX, (size_t)(L + 1) * cell * 4);
+    zero(o.DX, (size_t)(L + B) * cell * 4);
     if (D.bf16) zero(o.Vt, attention_vt_bytes(D.L, D.T, D.Hkv, D.dh));
     HIP_TRY(hipGetLastError());
   }
@@ -551,12 +570,12 @@ armt_status backward_typed(BCtx& c, const armt_layer_weights* W, int64_t N, floa
   int n_slots = 0;
   auto clear_slot = [&](int l, int p, bool read_only) {
     // zero slot p of layer l on the A side (then the stale B side of that slot adds nothing)
-    const size_t e = D.esz, rowb = (size_t)WG_WIN * o.Tp * e, colb = (size_t)o.Tp * e;
+    const size_t e = D.esz, rowb = (size_t)o.Kw * e, colb = (size_t)B * o.Tp * e;
     char* WA = c.ws + o.WinA + (size_t)l * o.wa_rows * rowb + (size_t)p * colb;
     const size_t r0 = read_only ? o.aDQR : 0, nr = read_only ? (size_t)D.dm : o.wa_rows;
     zero_columns_kernel<<<dim3((unsigned)nr), 256, 0, c.st>>>(WA + r0 * rowb, rowb, colb);
     if (!read_only) {
-      const size_t mrow = (size_t)WG_WIN * o.mp * e, mcol = (size_t)o.mp * e;
+      const size_t mrow = (size_t)o.Km * e, mcol = (size_t)B * o.mp * e;
       zero_columns_kernel<<<dim3((unsigned)(D.dm + D.d)), 256, 0, c.st>>>(c.ws + o.TmA + (size_t)l * (D.dm + D.d) * mrow + (size_t)p * mcol,
                                                                          mrow, mcol);
     }
@@ -574,45 +593,48 @@ armt_status backward_typed(BCtx& c, const armt_layer_weights* W, int64_t N, floa
     const int kinds[] = {TK_WD, TK_WG, TK_WU, TK_WO, TK_WQ, TK_WK, TK_WV, TK_WMQ, TK_WMK, TK_WMV};
     for (int k : kinds) {
       GemmShape s = c.shape[k];
-      s.K = n_slots * ((k == TK_WMK || k == TK_WMV) ? o.mp : o.Tp);
+      s.K = n_slots * B * ((k == TK_WMK || k == TK_WMV) ? o.mp : o.Tp);
       ARMT_TRY(gemm<T>(c.st, c.table(k), LO, HI - LO + 1, s));
     }
     n_slots = 0;
     return ARMT_OK;
   };
 
-  auto step = [&](int lo, int hi, int t) -> armt_status {
-    const int g = hi - lo + 1;
-    // the cell of segment 0 met an empty memory unless a state was carried in
+  auto step = [&](int lo, int hi, int t) -> armt_status {       // layers lo .. hi, each on segment t - layer
+    const int gc = (hi - lo + 1) * B, loc = lo * B;              // the cells of these layers: layer * B + sequence
+    // the cells of segment 0 met an empty memory unless a state was carried in
     const bool top_empty = !carry_in && (t - hi) == 0;
-    const int gr = top_empty ? g - 1 : g;
-    tape_kernel<<<dim3(128, g), 256, 0, c.st>>>(tape, rec_floats, c.at<float>(o.Xin), cell, c.aux, c.at<float>(o.Aw),
-                                               c.at<float>(o.zw), lo, t, L, cell, nA, (size_t)D.Phi, 0);
-    if (hi == L - 1) {
-      const int64_t s = t - (L - 1);
-      load_dhidden_kernel<T><<<D.T, 256, 0, c.st>>>((const T*)d_hidden + (size_t)s * D.S * D.d, D.S, D.d,
-                                                   c.at<float>(o.DX) + (size_t)L * cell);
+    const int grc = top_empty ? gc - B : gc;
+    tape_kernel<<<dim3(128, gc), 256, 0, c.st>>>(tape, rec_floats, c.at<float>(o.Xin), cell, c.aux, c.at<float>(o.Aw),
+                                                c.at<float>(o.zw), loc, t, L, B, cell, nA, (size_t)D.Phi, 0);
+    if (hi == Lr - 1) {
+      const int64_t s = t - (Lr - 1);
+      for (int b = 0; b < B; ++b)
+        load_dhidden_kernel<T><<<D.T, 256, 0, c.st>>>((const T*)d_hidden + b * seq + (size_t)s * D.S * D.d, D.S, D.d,
+                                                     c.at<float>(o.DX) + (size_t)(L + b) * cell);
     }
     HIP_TRY(hipGetLastError());
-    ARMT_TRY(recompute_group<T>(c, lo, g, gr, top_empty ? hi : -1, top_empty ? hi + 1 : -1));
-    ARMT_TRY(backward_group<T>(c, lo, g, gr, n_slots));
+    ARMT_TRY(recompute_group<T>(c, loc, gc, grc, top_empty ? hi * B : -1, top_empty ? (hi + 1) * B : -1));
+    ARMT_TRY(backward_group<T>(c, loc, gc, grc, n_slots));
     slots[n_slots++] = Slot{lo, hi, top_empty ? hi : -1};
     if (n_slots == win) ARMT_TRY(flush());
     if (lo == 0) {
-      store_dx_kernel<<<D.T, 256, 0, c.st>>>(c.at<float>(o.DX), D.S, D.d, dx ? dx + (size_t)t * D.S * D.d : nullptr, d_mem_emb);
+      for (int b = 0; b < B; ++b)
+        store_dx_kernel<<<D.T, 256, 0, c.st>>>(c.at<float>(o.DX) + (size_t)b * cell, D.S, D.d,
+                                               dx ? dx + b * seq + (size_t)t * D.S * D.d : nullptr, d_mem_emb);
       HIP_TRY(hipGetLastError());
     }
     return ARMT_OK;
   };
   if (diagonal) {
-    for (int64_t t = L + N - 2; t >= 0; --t) {
+    for (int64_t t = Lr + N - 2; t >= 0; --t) {
       int32_t lo, hi;
-      armt_diagonal_group(L, (int32_t)N, (int32_t)t, &lo, &hi);
+      armt_diagonal_group(Lr, (int32_t)N, (int32_t)t, &lo, &hi);
       ARMT_TRY(step(lo, hi, (int)t));
     }
   } else {
     for (int64_t s = N - 1; s >= 0; --s)
-      for (int l = L - 1; l >= 0; --l) ARMT_TRY(step(l, l, (int)s + l));
+      for (int l = Lr - 1; l >= 0; --l) ARMT_TRY(step(l, l, (int)s + l));
   }
   return flush();
 }
@@ -621,40 +643,52 @@ armt_status backward_typed(BCtx& c, const armt_layer_weights* W, int64_t N, floa
 
 extern "C" {
 
-size_t armt_tape_bytes(const armt_config* cfg, int64_t n_tokens) {
+size_t armt_tape_bytes_batched(const armt_config* cfg, int32_t batch, int64_t n_tokens) {
   Dims D;
   if (check_backward_config(cfg, &D) != ARMT_OK || n_tokens <= 0 || n_tokens % D.S != 0) return 0;
-  return (size_t)(n_tokens / D.S) * D.L * tape_record_floats(D) * 4;
+  if (batch < 1 || (int64_t)batch * D.L > 32768) return 0;
+  return (size_t)(n_tokens / D.S) * D.L * batch * tape_record_floats(D) * 4;
 }
+size_t armt_tape_bytes(const armt_config* cfg, int64_t n_tokens) { return armt_tape_bytes_batched(cfg, 1, n_tokens); }
 
-size_t armt_backward_workspace_bytes(const armt_config* cfg) {
+size_t armt_backward_workspace_bytes_batched(const armt_config* cfg, int32_t batch) {
   Dims D;
-  if (check_backward_config(cfg, &D) != ARMT_OK) return 0;
+  if (check_backward_config(cfg, &D) != ARMT_OK || batch < 1 || (int64_t)batch * D.L > 32768) return 0;
+  D.B = batch;
+  D.L = D.Lr * batch;
   return carve_train(D).total;
 }
+size_t armt_backward_workspace_bytes(const armt_config* cfg) { return armt_backward_workspace_bytes_batched(cfg, 1); }
 
+armt_status armt_forward_train_batched(const armt_config* cfg, const armt_layer_weights* layers, const void* mem_emb,
+                                       const void* x, int32_t batch, int64_t n_tokens, const float* A_in, const float* z_in,
+                                       void* hidden_out, float* A_out, float* z_out, void* tape, size_t tape_bytes,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream, int32_t diagonal) {
+  Dims D;
+  ARMT_TRY(check_backward_config(cfg, &D));
+  if (!tape) return ARMT_ERR_NULL;
+  if (n_tokens <= 0 || n_tokens % D.S != 0 || batch < 1 || (int64_t)batch * D.L > 32768) return ARMT_ERR_SHAPE;
+  if (((uintptr_t)tape % kAlign) != 0 || tape_bytes < armt_tape_bytes_batched(cfg, batch, n_tokens)) return ARMT_ERR_WORKSPACE;
+  return forward_impl(cfg, layers, mem_emb, x, batch, n_tokens, A_in, z_in, hidden_out, A_out, z_out, workspace, workspace_bytes,
+                      hip_stream, diagonal != 0, (float*)tape, tape_record_floats(D));
+}
 armt_status armt_forward_train(const armt_config* cfg, const armt_layer_weights* layers, const void* mem_emb, const void* x,
                                int64_t n_tokens, const float* A_in, const float* z_in, void* hidden_out, float* A_out,
                                float* z_out, void* tape, size_t tape_bytes, void* workspace, size_t workspace_bytes,
                                void* hip_stream, int32_t diagonal) {
-  Dims D;
-  ARMT_TRY(check_backward_config(cfg, &D));
-  if (!tape) return ARMT_ERR_NULL;
-  if (n_tokens <= 0 || n_tokens % D.S != 0) return ARMT_ERR_SHAPE;
-  if (((uintptr_t)tape % kAlign) != 0 || tape_bytes < armt_tape_bytes(cfg, n_tokens)) return ARMT_ERR_WORKSPACE;
-  return forward_impl(cfg, layers, mem_emb, x, 1, n_tokens, A_in, z_in, hidden_out, A_out, z_out, workspace, workspace_bytes,
-                      hip_stream, diagonal != 0, (float*)tape, tape_record_floats(D));
+  return armt_forward_train_batched(cfg, layers, mem_emb, x, 1, n_tokens, A_in, z_in, hidden_out, A_out, z_out, tape, tape_bytes,
+                                    workspace, workspace_bytes, hip_stream, diagonal);
 }
 
-armt_status armt_backward(const armt_config* cfg, const armt_layer_weights* layers, int64_t n_tokens, const void* tape,
-                          size_t tape_bytes, int32_t carry_in, const void* d_hidden, const float* dA_out, const float* dz_out,
-                          const armt_layer_grads* grads, float* d_mem_emb, float* dx, float* dA_in, float* dz_in,
-                          void* workspace, size_t workspace_bytes, void* hip_stream, int32_t diagonal) {
+armt_status armt_backward_batched(const armt_config* cfg, const armt_layer_weights* layers, int32_t batch, int64_t n_tokens,
+                                  const void* tape, size_t tape_bytes, int32_t carry_in, const void* d_hidden, const float* dA_out,
+                                  const float* dz_out, const armt_layer_grads* grads, float* d_mem_emb, float* dx, float* dA_in,
+                                  float* dz_in, void* workspace, size_t workspace_bytes, void* hip_stream, int32_t diagonal) {
   BCtx c;
   ARMT_TRY(check_backward_config(cfg, &c.D));
   const Dims& D = c.D;
   if (!layers || !tape || !d_hidden || !grads || !d_mem_emb) return ARMT_ERR_NULL;
-  for (int l = 0; l < D.L; ++l) {
+  for (int l = 0; l < D.Lr; ++l) {
     const armt_layer_weights& w = layers[l];
     const armt_layer_grads& g = grads[l];
     if (!w.rms1 || !w.wq || !w.wk || !w.wv || !w.wo || !w.rms2 || !w.wgate || !w.wup || !w.wdown || !w.wm_q || !w.wm_k ||
@@ -664,24 +698,27 @@ armt_status armt_backward(const armt_config* cfg, const armt_layer_weights* laye
         !g.wm_v || !g.wm_b)
       return ARMT_ERR_NULL;
   }
-  if (n_tokens <= 0 || n_tokens % D.S != 0) return ARMT_ERR_SHAPE;
+  if (n_tokens <= 0 || n_tokens % D.S != 0 || batch < 1 || (int64_t)batch * D.Lr > 32768) return ARMT_ERR_SHAPE;
   const int64_t N = n_tokens / D.S;
-  if (N + D.L > (int64_t)1 << 30) return ARMT_ERR_SHAPE;
+  if (N + D.Lr > (int64_t)1 << 30) return ARMT_ERR_SHAPE;
   if ((dA_out == nullptr) != (dz_out == nullptr) || (dA_in == nullptr) != (dz_in == nullptr)) return ARMT_ERR_NULL;
-  if (((uintptr_t)tape % kAlign) != 0 || tape_bytes < armt_tape_bytes(cfg, n_tokens)) return ARMT_ERR_WORKSPACE;
+  if (((uintptr_t)tape % kAlign) != 0 || tape_bytes < armt_tape_bytes_batched(cfg, batch, n_tokens)) return ARMT_ERR_WORKSPACE;
+  c.D.B = batch;
+  c.D.L = D.Lr * batch;                    // from here on L counts the cells of a full step
   c.o = carve_train(D);
   if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < c.o.total) return ARMT_ERR_WORKSPACE;
   c.ws = (char*)workspace;
   c.st = (hipStream_t)hip_stream;
   fill_train_shapes(c);
   ARMT_TRY(upload_train_tables(c, layers, grads));
-  const size_t nA = (size_t)D.L * D.d * D.Phi, nz = (size_t)D.L * D.Phi;
+  // the caller's state gradients are [batch][layers][...]; the cells of a step are ordered layer-major
+  const size_t nA = (size_t)D.d * D.Phi, nz = (size_t)D.Phi;
   if (dA_out) {
-    copy_f32_kernel<<<1024, 256, 0, c.st>>>(c.at<float>(c.o.DA), dA_out, nA);
-    copy_f32_kernel<<<16, 256, 0, c.st>>>(c.at<float>(c.o.DZ), dz_out, nz);
+    state_permute_kernel<<<dim3(64, D.L), 256, 0, c.st>>>(c.at<float>(c.o.DA), dA_out, D.Lr, batch, nA, 1);
+    state_permute_kernel<<<dim3(1, D.L), 256, 0, c.st>>>(c.at<float>(c.o.DZ), dz_out, D.Lr, batch, nz, 1);
   } else {
-    fill_f32_kernel<<<1024, 256, 0, c.st>>>(c.at<float>(c.o.DA), nA, 0.f);
-    fill_f32_kernel<<<16, 256, 0, c.st>>>(c.at<float>(c.o.DZ), nz, 0.f);
+    fill_f32_kernel<<<1024, 256, 0, c.st>>>(c.at<float>(c.o.DA), nA * D.L, 0.f);
+    fill_f32_kernel<<<16, 256, 0, c.st>>>(c.at<float>(c.o.DZ), nz * D.L, 0.f);
   }
   HIP_TRY(hipGetLastError());
   armt_status rc;
@@ -693,11 +730,18 @@ armt_status armt_backward(const armt_config* cfg, const armt_layer_weights* laye
                                d_mem_emb, dx, diagonal != 0);
   if (rc != ARMT_OK) return rc;
   if (dA_in) {
-    copy_f32_kernel<<<1024, 256, 0, c.st>>>(dA_in, c.at<float>(c.o.DA), nA);
-    copy_f32_kernel<<<16, 256, 0, c.st>>>(dz_in, c.at<float>(c.o.DZ), nz);
+    state_permute_kernel<<<dim3(64, D.L), 256, 0, c.st>>>(dA_in, c.at<float>(c.o.DA), D.Lr, batch, nA, 0);
+    state_permute_kernel<<<dim3(1, D.L), 256, 0, c.st>>>(dz_in, c.at<float>(c.o.DZ), D.Lr, batch, nz, 0);
     HIP_TRY(hipGetLastError());
   }
   return ARMT_OK;
+}
+armt_status armt_backward(const armt_config* cfg, const armt_layer_weights* layers, int64_t n_tokens, const void* tape,
+                          size_t tape_bytes, int32_t carry_in, const void* d_hidden, const float* dA_out, const float* dz_out,
+                          const armt_layer_grads* grads, float* d_mem_emb, float* dx, float* dA_in, float* dz_in,
+                          void* workspace, size_t workspace_bytes, void* hip_stream, int32_t diagonal) {
+  return armt_backward_batched(cfg, layers, 1, n_tokens, tape, tape_bytes, carry_in, d_hidden, dA_out, dz_out, grads, d_mem_emb, dx,
+                               dA_in, dz_in, workspace, workspace_bytes, hip_stream, diagonal);
 }
 
 }  // extern "C"
@@ -771,7 +815,7 @@ armt_status lm_head_backward_typed(const Dims& D, const HeadBwdLayout& h, const 
     ARMT_TRY(gemm<T>(st, table, 0, 1, su));
     final_norm_bwd_kernel<T><<<r, 256, 0, st>>>(U, hs, (const T*)gain, rstd, D.d, d_hidden + (size_t)r0 * D.d);
     colsum_partial_kernel<T><<<dim3((D.d + 255) / 256, 1, CS_CHUNKS), 256, 0, st>>>(hs, U, 0, rstd, part, 0, r, D.d);
-    colsum_finish_kernel<<<dim3((D.d + 255) / 256, 1), 256, 0, st>>>(part, CS_CHUNKS, nullptr, d_gain, 0, D.d);
+    colsum_finish_kernel<<<dim3((D.d + 255) / 256, 1), 256, 0, st>>>(part, CS_CHUNKS, nullptr, d_gain, 0, D.d, 1);
     HIP_TRY(hipGetLastError());
     ARMT_TRY((transpose<T, T>(st, DLb, 0, h.Vp, DLT, 0, h.Rp, r, h.Vp, 1)));
     ARMT_TRY((transpose<T, T>(st, Nn, 0, D.d, NT, 0, h.Rp, r, D.d, 1)));

@@ -151,14 +151,16 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict
   part[((size_t)l * gridDim.z + blockIdx.z) * C + c] = s;
 }
 
-// dst[c] += sum_chunks part[cell][chunk][c]; dst = dst_tab[cell] if a pointer table is given, else dst_base + cell * C.
-// grid: (ceil(C / 256), g), block: 256.
+// dst[c] += sum over nb consecutive cells and their chunks of part[cell][chunk][c]; dst = dst_tab[first cell] if a pointer
+// table is given (the nb cells of a batch that share a layer's gradient), else dst_base + cell * C (nb = 1).
+// grid: (ceil(C / 256), cells / nb), block: 256.
 __global__ __launch_bounds__(256) void colsum_finish_kernel(const float* __restrict__ part, int chunks, float* const* __restrict__ dst_tab,
-                                                            float* __restrict__ dst_base, int first, int C) {
-  const int l = first + blockIdx.y, c = blockIdx.x * 256 + threadIdx.x;
+                                                            float* __restrict__ dst_base, int first, int C, int nb) {
+  const int l = first + blockIdx.y * nb, c = blockIdx.x * 256 + threadIdx.x;      // destination of cells l .. l + nb - 1
   if (c >= C) return;
   float s = 0.f;
-  for (int k = 0; k < chunks; ++k) s += part[((size_t)l * chunks + k) * C + c];
+  for (int b = 0; b < nb; ++b)
+    for (int k = 0; k < chunks; ++k) s += part[((size_t)(l + b) * chunks + k) * C + c];
   float* dst = dst_tab ? dst_tab[l] : dst_base + (size_t)l * C;
   dst[c] += s;
 }
@@ -584,13 +586,13 @@ __global__ __launch_bounds__(256) void update_bwd_z_kernel(const float* __restri
   DZ[(size_t)l * Phi + c] += s;
 }
 
-// beta_i = sigmoid(w_b . y_i): the memory rows of the output gradient get db_i w_b, and dw_b += sum_i db_i y_i.
+// beta_i = sigmoid(w_b . y_i): the memory rows of the output gradient get db_i w_b, and part[cell] = sum_i db_i y_i.
 // dY: gradient slots (row 0 of the memory rows of cell l at dY + l * dy_cell); Ym: [cells][m][d] memory rows of the output.
 // grid: (ceil(d / 256), g), block: 256.
 template <typename T>
 __global__ __launch_bounds__(256) void beta_bwd_kernel(const float* __restrict__ DB, const T* __restrict__ Ym, size_t ym_cell,
                                                        const LayerAux* __restrict__ aux, float* __restrict__ dY,
-                                                       size_t dy_cell, float* const* __restrict__ dwb, int first, int m, int d) {
+                                                       size_t dy_cell, float* __restrict__ part, int first, int m, int d) {
   const int l = first + blockIdx.y, c = blockIdx.x * 256 + threadIdx.x;
   if (c >= d) return;
   const float wb = to_f32(((const T*)aux[l].wm_b)[c]);
@@ -600,20 +602,20 @@ __global__ __launch_bounds__(256) void beta_bwd_kernel(const float* __restrict__
     dY[(size_t)l * dy_cell + (size_t)i * d + c] += db * wb;
     s = fmaf(db, to_f32(Ym[(size_t)l * ym_cell + (size_t)i * d + c]), s);
   }
-  dwb[l][c] += s;
+  part[(size_t)l * d + c] = s;       // per cell; colsum_finish_kernel adds the cells of a layer into dw_b
 }
 
 // ------------------------------------------------------------------------------------------------
 // Tape of the training forward: inputs of a cell that the backward pass cannot recompute from its neighbours.
-// Per cell (segment s, layer l), record index s * n_layers + l: the cell input [T][d] fp32, the layer's A [d][Phi] and
+// Per cell (segment s, layer l, sequence b), record index s * n_cells + l * batch + b: the cell input [T][d] fp32, the layer's A [d][Phi] and
 // z [Phi] from BEFORE the cell's update.  save = 1 copies slots / state into the tape, save = 0 copies back.
-// The cell of (virtual) layer l in a launch belongs to segment t - l.  grid: (blocks, g), block: 256.
+// Cell l of a launch belongs to layer l / batch and to segment t - l / batch.  grid: (blocks, g), block: 256.
 __global__ __launch_bounds__(256) void tape_kernel(float* __restrict__ tape, size_t rec_floats, float* __restrict__ X,
                                                    size_t x_cell, const LayerAux* __restrict__ aux, float* __restrict__ Aw,
-                                                   float* __restrict__ zw, int first, int t, int n_layers, size_t nx,
+                                                   float* __restrict__ zw, int first, int t, int n_cells, int batch, size_t nx,
                                                    size_t nA, size_t nz, int save) {
-  const int l = first + blockIdx.y;
-  float* rec = tape + ((size_t)(t - l) * n_layers + l) * rec_floats;
+  const int l = first + blockIdx.y;            // cell = layer * batch + sequence
+  float* rec = tape + ((size_t)(t - l / batch) * n_cells + l) * rec_floats;
   float* x = X + (size_t)l * x_cell;
   float* A = save ? aux[l].A : Aw + (size_t)l * nA;
   float* z = save ? aux[l].z : zw + (size_t)l * nz;
@@ -622,6 +624,17 @@ __global__ __launch_bounds__(256) void tape_kernel(float* __restrict__ tape, siz
     float* p = i < nx ? x + i : (i < nx + nA ? A + (i - nx) : z + (i - nx - nA));
     if (save) rec[i] = *p; else *p = rec[i];
   }
+}
+
+// Memory-state gradients between the caller's order [batch][layers][n] and the cell order [layers][batch][n] of a step.
+// to_cells = 1: cells <- caller; 0: caller <- cells.  grid: (blocks, layers * batch), block: 256.
+__global__ __launch_bounds__(256) void state_permute_kernel(float* __restrict__ dst, const float* __restrict__ src, int n_layers,
+                                                            int batch, size_t n, int to_cells) {
+  const int v = blockIdx.y, l = v / batch, b = v % batch;
+  const size_t cell = (size_t)v * n, user = ((size_t)b * n_layers + l) * n;
+  float* d = dst + (to_cells ? cell : user);
+  const float* s = src + (to_cells ? user : cell);
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) d[i] = s[i];
 }
 
 // Gradient of the top layer's output: token rows from the caller's d_hidden, memory rows zero.

@@ -256,6 +256,19 @@ def test_training_entry_argument_errors(lib):
             setattr(missing[l], f, fake)
     missing[0].wm_q = None
     assert back(grads=missing) == 1
+    # batched variants: sizes scale with the batch, the batch is checked
+    assert lib.armt_tape_bytes_batched(C.byref(cfg), 3, shape.n_tokens) == 3 * tape_bytes
+    assert lib.armt_tape_bytes_batched(C.byref(cfg), 0, shape.n_tokens) == 0
+    wsb3 = lib.armt_backward_workspace_bytes_batched(C.byref(cfg), 3)
+    assert wsb3 > ws_bytes and lib.armt_backward_workspace_bytes_batched(C.byref(cfg), 0) == 0
+    assert lib.armt_backward_workspace_bytes_batched(C.byref(cfg), 40000) == 0
+    bb = lambda batch, tb, wsb: lib.armt_backward_batched(C.byref(cfg), layers, batch, shape.n_tokens, 0x10000, tb, 0, fake, None, None,
+                                                          grads, fake, None, None, None, 0x20000, wsb, None, 1)
+    assert bb(0, 3 * tape_bytes, wsb3) == 2 and bb(3, 3 * tape_bytes - 1, wsb3) == 4 and bb(3, 3 * tape_bytes, wsb3 - 1) == 4
+    ft = lambda batch, tb: lib.armt_forward_train_batched(C.byref(cfg), layers, fake, fake, batch, shape.n_tokens, None, None, fake, fake,
+                                                          fake, 0x10000, tb, 0x20000, lib.armt_workspace_bytes_batched(C.byref(cfg), 3),
+                                                          None, 1)
+    assert ft(0, 3 * tape_bytes) == 2 and ft(3, 3 * tape_bytes - 1) == 4
 
 
 def test_token_end_backward_argument_errors(lib):

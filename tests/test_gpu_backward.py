@@ -211,3 +211,43 @@ def test_full_1b_model_backward_properties():
             worst = max(worst, ((a - b).norm() / b.norm()).item())
     print(f"full 1B model: worst relative difference between the two orders {worst:.2e}", flush=True)
     assert worst <= 1e-5
+
+
+@pytest.mark.parametrize("dtype,diagonal", [("f32", True), ("f32", False), ("bf16", True)])
+def test_batched_backward_matches_oracle(dtype, diagonal):
+    """Three sequences in one call, with gradients into the final state (fp32: also a carried-in state): the gradients of the shared
+    weights and of mem_emb are the sums of the oracle's per-sequence gradients; dx, dA_in, dz_in are per sequence."""
+    import torch
+    import paper_2506_05229_amd as P
+    B = 3
+    if dtype == "f32":
+        shape, tol, tol_mem = S.get_shape("tiny").replace(n_tokens=5 * 64), F32_REL, None
+        layers, mem_emb, _ = make_problem(shape, seed=3, std=0.02, gain_std=0.1, v_scale=64.0)
+    else:
+        shape, layers, mem_emb, _ = well_conditioned(S.get_shape("tiny").replace(**SMALL_BF16), seed=11)
+        tol, tol_mem = BF16_REL, BF16_REL_MEM
+    xs = [S.make_embeddings(shape, seed=20 + b) for b in range(B)]
+    carry = dtype == "f32"       # a random carried-in state drives z.phi through zero on the bf16 shape (the oracle shows it)
+    states = [carried(shape, 30 + b) if carry else (None, None) for b in range(B)]
+    Gss = [upstream(shape, 40 + b, with_state=True) for b in range(B)]
+    wants = [G.armt_grad(shape, layers, mem_emb, xs[b], *Gss[b], A_in=states[b][0], z_in=states[b][1]) for b in range(B)]
+    model = P.Armt(shape, layers, mem_emb)
+    dev = lambda a: torch.as_tensor(np.stack(a), dtype=torch.float32).cuda().contiguous()
+    xd = model.embed(np.stack(xs))
+    A_in, z_in = (dev([s[0] for s in states]), dev([s[1] for s in states])) if carry else (None, None)
+    hidden, A, z, tape = model.forward_train(xd, diagonal=diagonal, A_in=A_in, z_in=z_in)
+    ref = model.forward_batched(xd, diagonal=diagonal, A_in=A_in, z_in=z_in)
+    for a, b in zip((hidden, A, z), ref):
+        assert torch.equal(a, b)
+    g = model.backward(tape, shape.n_tokens, model.embed(np.stack([q[0] for q in Gss])), dev([q[1] for q in Gss]),
+                       dev([q[2] for q in Gss]), carry_in=carry, diagonal=diagonal)
+    torch.cuda.synchronize()
+    np_ = lambda t: None if t is None else t.float().cpu().numpy()
+    got = {"layers": [{k: np_(v) for k, v in lw.items()} for lw in g["layers"]], "mem_emb": np_(g["mem_emb"]),
+           "x": np_(g["x"]), "A_in": np_(g["A_in"]), "z_in": np_(g["z_in"]), "hidden": np_(hidden), "A": np_(A), "z": np_(z)}
+    want = {"layers": [{k: sum(w["layers"][l][k] for w in wants) for k in G.WEIGHT_KEYS} for l in range(shape.n_layers)],
+            "mem_emb": sum(w["mem_emb"] for w in wants)}
+    for k in ("x", "A_in", "z_in", "hidden", "A", "z"):
+        want[k] = None if wants[0][k] is None else np.stack([w[k] for w in wants])
+    compare(got, want, tol, f"batch of {B}, {dtype}, diag={diagonal}", tol_mem=tol_mem)
+
