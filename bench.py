@@ -194,11 +194,10 @@ def main():
             del dl, grads
             te.bws = None
         del lg_last, lg_big, te
-    if not args.no_train and B == 1 and P.load_library().armt_backward_workspace_bytes(C_byref(model.cfg)) > 0:
+    if not args.no_train and P.load_library().armt_backward_workspace_bytes_batched(C_byref(model.cfg), B) > 0:
         # Training leg (outside `value`): forward that records the tape, then the backward pass in reverse diagonal
         # order, for an upstream gradient on every hidden state; one warm-up, one timed pass of each.
-        gh = torch.randn(shape.n_tokens, shape.d_model, device="cuda",
-                         generator=torch.Generator(device="cuda").manual_seed(1)).to(model.act_dtype)
+        gh = torch.randn(tuple(xd.shape), device="cuda", generator=torch.Generator(device="cuda").manual_seed(1)).to(model.act_dtype)
         grads, t_f, t_b, t_bs = None, 0.0, 0.0, None
         for rep in range(2):
             torch.cuda.synchronize()
