@@ -147,7 +147,7 @@ def main():
         res["sequential_tokens_per_s"] = n_tok / (swall / 1e3)
         res["speedup_vs_sequential"] = swall / wall_ms
     if not args.no_lm_head and B == 1:
-        # Token-level ends of Algorithm 1 (not part of `value`, which is the BASELINE metric on hidden states):
+        # Token-level ends of Algorithm 1 (not part of `value`, which is the headline metric on hidden states):
         # embedding gather for the whole sequence, final norm + LLaMA-3-sized head on the last segment and on
         # 16 segments, the latter extrapolated to all rows (the head's cost is linear in the rows).
         ids, E, gf, Wlm = S.make_token_ends(shape, vocab=S.LLAMA3_VOCAB, seed=0)

@@ -26,7 +26,7 @@ def _check_f32(got, want, what):
 
 @pytest.mark.parametrize("diagonal", [False, True])
 def test_tiny_f32_matches_oracle(diagonal):
-    """BASELINE config 1: 4 layers, d=128, 4/2 heads, 8 segments of 64 + 8 memory tokens."""
+    """The tiny configuration: 4 layers, d=128, 4/2 heads, 8 segments of 64 + 8 memory tokens."""
     shape = S.get_shape("tiny")
     prob = make_problem(shape, seed=0)
     _check_f32(run_hip(shape, *prob, diagonal=diagonal), run_oracle(shape, *prob), f"tiny diag={diagonal}")
