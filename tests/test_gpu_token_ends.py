@@ -134,3 +134,53 @@ def test_embedding_backward_matches_oracle():
     got = te.embed_backward(torch.from_numpy(unique).cuda(), torch.from_numpy(dx[:40].copy()).cuda())
     torch.cuda.synchronize()
     assert np.array_equal(got.cpu().numpy().astype(np.float64), OG.embed_tokens_grad(unique, dx[:40], 50))
+
+
+def test_training_step_from_token_ids_matches_autograd():
+    """One whole training step on the tiny configuration, every piece through the C ABI: ids -> embedding gather ->
+    forward with tape -> final norm + head -> (cross-entropy of the next token, formed by the caller) -> head backward ->
+    ARMT backward in reverse diagonal order -> embedding scatter-add.  The oracle differentiates the same chain in float64."""
+    import torch.nn.functional as F
+    import paper_2506_05229_amd as P
+    from oracle import armt_oracle_grad as OG
+    shape = S.get_shape("tiny").replace(n_tokens=3 * 64)
+    vocab = 97
+    layers, mem_emb = S.make_weights(shape, seed=1, gain_std=0.1)
+    ids, E, gf, W = S.make_token_ends(shape, vocab=vocab, seed=1, n_tokens=shape.n_tokens, gain_std=0.1)
+    targets = np.roll(ids, -1).astype(np.int64)
+    # ---- oracle: autograd through gather, sequential forward, head and loss
+    f64 = lambda a: torch.tensor(np.asarray(a, dtype=np.float64), requires_grad=True)
+    Wt = [{k: f64(lw[k]) for k in OG.WEIGHT_KEYS} for lw in layers]
+    met, Et, gft, Wlt = f64(mem_emb), f64(E), f64(gf), f64(W)
+    hid, _, _ = OG.armt_forward_torch(shape, Wt, met, Et[torch.from_numpy(ids.astype(np.int64))])
+    loss = F.cross_entropy(OG.rmsnorm(hid, gft, shape.rms_eps) @ Wlt.T, torch.from_numpy(targets))
+    loss.backward()
+    # ---- library
+    model = P.Armt(shape, layers, mem_emb)
+    te = P.TokenEnds(shape, E, gf, W)
+    ids_d = torch.from_numpy(ids).cuda()
+    x = te.embed(ids_d)
+    hidden, _, _, tape = model.forward_train(x, diagonal=True)
+    logits = te.logits(hidden)
+    p = torch.softmax(logits, dim=-1)                        # the loss is the caller's: mean cross-entropy
+    got_loss = -torch.log(p[torch.arange(shape.n_tokens), torch.from_numpy(targets).cuda()]).mean().item()
+    p[torch.arange(shape.n_tokens), torch.from_numpy(targets).cuda()] -= 1.0
+    d_hidden, d_gain, d_wlm = te.logits_backward(hidden, (p / shape.n_tokens).contiguous())
+    g = model.backward(tape, shape.n_tokens, d_hidden.to(model.act_dtype).contiguous(), diagonal=True)
+    d_table = te.embed_backward(ids_d, g["x"])
+    torch.cuda.synchronize()
+    assert abs(got_loss - loss.item()) <= 1e-5 * abs(loss.item())
+    worst = ("", 0.0)
+    def check(name, a, b):
+        nonlocal worst
+        e = rel_fro(a.cpu().numpy().reshape(b.shape), b.grad.numpy())
+        worst = max(worst, (name, e), key=lambda t: t[1])
+        assert e <= 2e-4, (name, e)
+    check("emb_table", d_table, Et)
+    check("final_gain", d_gain, gft)
+    check("w_lm", d_wlm, Wlt)
+    check("mem_emb", g["mem_emb"], met)
+    for l in range(shape.n_layers):
+        for k in OG.WEIGHT_KEYS:
+            check(f"layer {l} {k}", g["layers"][l][k], Wt[l][k])
+    print(f"training step: loss {got_loss:.6f}; worst relative gradient error {worst[1]:.2e} ({worst[0]})", flush=True)
