@@ -153,11 +153,19 @@ __global__ __launch_bounds__(512) void attention_bwd_dq_kernel(const bf16* __res
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(Ks + off), qf[ks], s, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(Vs + off), gf[ks], dp, 0, 0, 0);
       }
+      if (k0 + jj * 32 + 31 > q0) {              // this half crosses the diagonal: keys after the query contribute nothing
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = k0 + jj * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        const float p = key > qi ? 0.f : __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2e, -lse));
-        dsf[jj][r >> 3][r & 7] = (bf16)(p * (dp[r] - dvec) * scale);
+        for (int r = 0; r < 16; ++r) {
+          const int key = k0 + jj * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+          const float p = key > qi ? 0.f : __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2e, -lse));
+          dsf[jj][r >> 3][r & 7] = (bf16)(p * (dp[r] - dvec) * scale);
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2e, -lse));
+          dsf[jj][r >> 3][r & 7] = (bf16)(p * (dp[r] - dvec) * scale);
+        }
       }
     }
     // dQ^T[dim][query] += K^T[dim][key] dS^T[key][query]
@@ -305,6 +313,8 @@ __global__ __launch_bounds__(512) void attention_bwd_dkv_kernel(const bf16* __re
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(Gs + off), vf[ks], dp, 0, 0, 0);
         }
         bf16x8 pf[2], dsf[2];
+        // all 32 queries of this half exist and lie at or after all 32 keys of the wave: nothing to mask
+        const bool interior = q0 + jj * 32 >= k0 + 31 && q0 + jj * 32 + 31 < Trows;
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {         // registers 4 rg .. 4 rg + 3 hold four consecutive query rows
           const int j4 = jj * 32 + 8 * rg + 4 * half;
@@ -312,7 +322,7 @@ __global__ __launch_bounds__(512) void attention_bwd_dkv_kernel(const bf16* __re
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int r = 4 * rg + e, q = q0 + j4 + e;
-            const bool live = q < Trows && ki <= q;
+            const bool live = interior || (q < Trows && ki <= q);
             const float p = live ? __builtin_amdgcn_exp2f(fmaf(s[r], scale_log2e, -l4[e])) : 0.f;
             pf[r >> 3][r & 7] = (bf16)p;
             dsf[r >> 3][r & 7] = (bf16)(p * (dp[r] - d4[e]) * scale);
