@@ -154,7 +154,7 @@ def test_many_memory_tokens_backward_matches_oracle(dtype):
 def test_backward_orders_agree():
     """Reverse diagonal and reverse sequential order: the same cells and the same per-cell arithmetic, so everything that
     flows from cell to cell (dx, d_mem_emb, the gradient of the state) is bit-identical; a layer's weight gradient is a
-    sum over its segments that the diagonal order adds four segments at a time, so it agrees to fp32 rounding."""
+    sum over its segments that the diagonal order adds eight segments at a time, so it agrees to fp32 rounding."""
     shape = S.get_shape("tiny").replace(n_tokens=6 * 64)
     layers, mem_emb, x = make_problem(shape, seed=5, std=0.02, gain_std=0.1, v_scale=64.0)
     Gs = upstream(shape, 5, with_state=True)
@@ -184,7 +184,7 @@ def test_full_1b_model_backward_properties():
     differentiate this size in minutes, so properties that hold at any size: (i) an upstream gradient on segment 2 only
     leaves the embeddings of segments 3.. without gradient, exactly (dependency rule of Section 3.1); (ii) reverse
     diagonal and reverse sequential order agree (bit for bit on what flows between cells, to fp32 rounding on the
-    weight gradients, which the diagonal order adds four segments at a time); (iii) everything is finite and non-zero."""
+    weight gradients, which the diagonal order adds eight segments at a time); (iii) everything is finite and non-zero."""
     import torch
     import paper_2506_05229_amd as P
     shape = S.get_shape("1b_8k")
