@@ -359,7 +359,7 @@ armt_status colsum(const BCtx& c, const T* a, const float* b, size_t b_cell, con
 // Forward of the cells [lo, lo + g) from their restored inputs, every intermediate kept.  The first gr cells read
 // their memory; cells [e0, e1) meet an empty one.
 template <typename T>
-armt_status recompute_group(const BCtx& c, int lo, int g, int gr, int e0, int e1) {
+armt_status recompute_group(const BCtx& c, int lo, int g, int gr, int e0, int e1, int slot) {
   const Dims& D = c.D;
   const TrainLayout& o = c.o;
   const size_t cell = (size_t)D.T * D.d;
@@ -391,9 +391,19 @@ armt_status recompute_group(const BCtx& c, int lo, int g, int gr, int e0, int e1
                                                          c.at<T>(o.N2), c.at<float>(o.RStd2));
   HIP_TRY(hipGetLastError());
   ARMT_TRY(bgemm<T>(c, TK_GU, lo, g));
-  const size_t rows = (size_t)g * D.T;
-  swiglu_kernel<T><<<ew_blocks(rows * D.F), 256, 0, c.st>>>(c.at<T>(o.GU) + (size_t)lo * D.T * 2 * D.F,
-                                                            c.at<T>(o.Uff) + (size_t)lo * D.T * D.F, rows, D.F);
+  if constexpr (std::is_same<T, bf16>::value) {
+    // u = silu(gate) up, written transposed into the window rows of dW_down's B operand; U itself only on the memory rows
+    const int Kw = o.Kw;
+    const size_t wb_cell = o.wb_rows * Kw;
+    bf16* dstB = c.at<bf16>(o.WinB) + (size_t)(lo / D.B) * wb_cell + (size_t)slot * D.B * o.Tp + o.bU * Kw;
+    swiglu_tiles_kernel<false><<<dim3(D.F / 64, (D.T + 63) / 64, g), 256, 0, c.st>>>(
+        c.at<bf16>(o.GU) + (size_t)lo * D.T * 2 * D.F, c.at<bf16>(o.Uff) + (size_t)lo * D.T * D.F, D.T, D.F, D.S, dstB, wb_cell, Kw, D.B,
+        o.Tp);
+  } else {
+    const size_t rows = (size_t)g * D.T;
+    swiglu_kernel<T><<<ew_blocks(rows * D.F), 256, 0, c.st>>>(c.at<T>(o.GU) + (size_t)lo * D.T * 2 * D.F,
+                                                              c.at<T>(o.Uff) + (size_t)lo * D.T * D.F, rows, D.F);
+  }
   HIP_TRY(hipGetLastError());
   ARMT_TRY(bgemm<T>(c, TK_DOWN, lo, g));
   ARMT_TRY(bgemm<T>(c, TK_MKV, lo, g));
@@ -474,13 +484,20 @@ armt_status backward_group(const BCtx& c, int lo, int g, int gr, int slot) {
   HIP_TRY(hipGetLastError());
   ARMT_TRY(bgemm<T>(c, TK_DU, lo, g));
   ARMT_TRY(wtr(DYb, cell, D.d, arow(o.aDY), wa_cell, Tp, Kw, D.T, D.d, g));
-  ARMT_TRY(wtr(c.at<T>(o.Uff) + (size_t)lo * D.T * D.F, (size_t)D.T * D.F, D.F, brow(o.bU), wb_cell, Tp, Kw, D.T, D.F, g));
+  if (!std::is_same<T, bf16>::value)      // bf16: the recomputation wrote U^T already
+    ARMT_TRY(wtr(c.at<T>(o.Uff) + (size_t)lo * D.T * D.F, (size_t)D.T * D.F, D.F, brow(o.bU), wb_cell, Tp, Kw, D.T, D.F, g));
   T* GU = c.at<T>(o.GU) + (size_t)lo * D.T * 2 * D.F;
-  swiglu_bwd_kernel<T><<<ew_blocks((size_t)g * D.T * D.F), 256, 0, st>>>(GU, c.at<T>(o.DU) + (size_t)lo * D.T * D.F, (size_t)g * D.T,
-                                                                        D.F);
+  if constexpr (std::is_same<T, bf16>::value) {
+    // [gate | up] <- [dgate | dup] in place, and transposed into the window rows of dW_gate, dW_up's A operand
+    swiglu_tiles_kernel<true><<<dim3(D.F / 64, (D.T + 63) / 64, g), 256, 0, st>>>(
+        (bf16*)GU, c.at<bf16>(o.DU) + (size_t)lo * D.T * D.F, D.T, D.F, 0, (bf16*)arow(o.aDGU), wa_cell, Kw, B, Tp);
+  } else {
+    swiglu_bwd_kernel<T><<<ew_blocks((size_t)g * D.T * D.F), 256, 0, st>>>(GU, c.at<T>(o.DU) + (size_t)lo * D.T * D.F, (size_t)g * D.T,
+                                                                          D.F);
+  }
   HIP_TRY(hipGetLastError());
   ARMT_TRY(bgemm<T>(c, TK_DN2, lo, g));
-  ARMT_TRY(wtr(GU, (size_t)D.T * 2 * D.F, 2 * D.F, arow(o.aDGU), wa_cell, Tp, Kw, D.T, 2 * D.F, g));
+  if (!std::is_same<T, bf16>::value) ARMT_TRY(wtr(GU, (size_t)D.T * 2 * D.F, 2 * D.F, arow(o.aDGU), wa_cell, Tp, Kw, D.T, 2 * D.F, g));
   ARMT_TRY(wtr(c.at<T>(o.N2) + lo * cell, cell, D.d, brow(o.bN2), wb_cell, Tp, Kw, D.T, D.d, g));
   ARMT_TRY(colsum<T>(c, c.at<T>(o.DN), c.at<float>(o.Hres), cell, c.at<float>(o.RStd2), c.dg2, nullptr, lo, g, D.d));   // d gain 2
   rmsnorm_bwd_kernel<T><<<dim3(D.T, g), 256, 0, st>>>(c.at<T>(o.DN), c.at<float>(o.Hres), cell, c.aux, lo, 1, c.at<float>(o.RStd2),
@@ -615,7 +632,7 @@ armt_status backward_typed(BCtx& c, const armt_layer_weights* W, int64_t N, floa
                                                      c.at<float>(o.DX) + (size_t)(L + b) * cell);
     }
     HIP_TRY(hipGetLastError());
-    ARMT_TRY(recompute_group<T>(c, loc, gc, grc, top_empty ? hi * B : -1, top_empty ? (hi + 1) * B : -1));
+    ARMT_TRY(recompute_group<T>(c, loc, gc, grc, top_empty ? hi * B : -1, top_empty ? (hi + 1) * B : -1, n_slots));
     ARMT_TRY(backward_group<T>(c, loc, gc, grc, n_slots));
     slots[n_slots++] = Slot{lo, hi, top_empty ? hi : -1};
     if (n_slots == win) ARMT_TRY(flush());

@@ -189,6 +189,76 @@ __global__ void swiglu_bwd_kernel(T* __restrict__ GU, const T* __restrict__ dU, 
   }
 }
 
+// bf16 versions of the two SwiGLU kernels that also leave the transposed copy the weight-gradient GEMMs need, written
+// straight into a layer's window rows (row stride ldd; the cell z of the launch belongs to layer z / batch and puts its
+// T columns at column offset (z % batch) * Tp): 64 x 64 tiles, 16-byte accesses, the transposed half through LDS as in
+// transpose_bf16_kernel (tile rows past T are written as zeros: the padding of the reduction dimension).
+// Forward (BWD = false): u = silu(gate) up; U^T -> dst rows [c]; U itself only for rows >= first_row (the memory rows, all
+//   the recomputed down projection reads).  GU: [cells][T][2F], U: [cells][T][F].
+// Backward (BWD = true): [gate | up] <- [dgate | dup] in place from dU, and the same values transposed -> dst rows [c] (dgate)
+//   and [F + c] (dup).
+// grid: (F / 64, ceil(T / 64), cells), block: 256.  F a multiple of 64.
+template <bool BWD>
+__global__ __launch_bounds__(256) void swiglu_tiles_kernel(bf16* __restrict__ GU, bf16* __restrict__ U /* BWD: dU (read) */,
+                                                           int Trows, int F, int first_row, bf16* __restrict__ dst,
+                                                           size_t dst_layer, int ldd, int batch, int Tp) {
+  __shared__ unsigned int tg[64 * 33], tu[64 * 33];
+  const int z = blockIdx.z, c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+  bf16* gu = GU + (size_t)z * Trows * 2 * F;
+  bf16* uu = U + (size_t)z * Trows * F;
+  bf16* o = dst + (size_t)(z / batch) * dst_layer + (size_t)(z % batch) * Tp;
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int idx = threadIdx.x + 256 * k, r = idx >> 3, ch = idx & 7, row = r0 + r, col = c0 + 8 * ch;
+    bf16x8 a = {0, 0, 0, 0, 0, 0, 0, 0}, b = a;           // what goes to the transposed copy
+    if (row < Trows) {
+      const bf16x8 g = *(const bf16x8*)(gu + (size_t)row * 2 * F + col), up = *(const bf16x8*)(gu + (size_t)row * 2 * F + F + col);
+      if (BWD) {
+        const bf16x8 du = *(const bf16x8*)(uu + (size_t)row * F + col);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float gf = (float)g[e], sg = 1.f / (1.f + expf(-gf)), d = (float)du[e];
+          a[e] = (bf16)(d * (float)up[e] * sg * (1.f + gf * (1.f - sg)));
+          b[e] = (bf16)(d * gf * sg);
+        }
+        *(bf16x8*)(gu + (size_t)row * 2 * F + col) = a;
+        *(bf16x8*)(gu + (size_t)row * 2 * F + F + col) = b;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float gf = (float)g[e];
+          a[e] = (bf16)(gf / (1.f + expf(-gf)) * (float)up[e]);
+        }
+        if (row >= first_row) *(bf16x8*)(uu + (size_t)row * F + col) = a;
+      }
+    }
+    const uint4 av = __builtin_bit_cast(uint4, a), bv = __builtin_bit_cast(uint4, b);
+    unsigned int* t = tg + r * 33 + 4 * ch;
+    t[0] = av.x; t[1] = av.y; t[2] = av.z; t[3] = av.w;
+    if (BWD) {
+      unsigned int* t2 = tu + r * 33 + 4 * ch;
+      t2[0] = bv.x; t2[1] = bv.y; t2[2] = bv.z; t2[3] = bv.w;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int idx = threadIdx.x + 256 * k, c = idx >> 3, rch = idx & 7;
+    if (r0 + 8 * rch + 7 >= Tp) continue;                 // Tp is a multiple of 64: never true for a started tile row block
+#pragma unroll
+    for (int h = 0; h < (BWD ? 2 : 1); ++h) {
+      const unsigned short* th = (const unsigned short*)(h ? tu : tg);
+      unsigned int w[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const unsigned int lo = th[(8 * rch + 2 * e) * 66 + c], hi = th[(8 * rch + 2 * e + 1) * 66 + c];
+        w[e] = lo | (hi << 16);
+      }
+      *(uint4*)(o + (size_t)(h * F + c0 + c) * ldd + r0 + 8 * rch) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+  }
+}
+
 // Backward of the rotary embedding: rotate the gradient of q and k by the opposite angle, in place.
 template <typename T>
 __global__ __launch_bounds__(256) void rope_bwd_kernel(T* __restrict__ dQKV, const float* __restrict__ cs, int first,
