@@ -272,11 +272,18 @@ armt_status armt_lm_head(const armt_config *cfg, const void *hidden, int64_t n_r
                          const void *w_lm, int32_t vocab, float *logits,
                          void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Environment: ARMT_DEBUG_GENERIC=1 (read once per process) makes bf16 configurations run the plain
+ * fp32-FMA GPU kernels of the fp32 path on bf16 operands instead of the MFMA kernels: slow, for telling an
+ * error of a fast kernel from an error of the method.  Nothing ever runs on the host. */
+
 /* Benchmarking knob: force the tile configuration of the bf16 grouped GEMM for all later calls of this
  * process (0: 256x256 tile, 8 waves; 1: 128x128, 4 waves; 2: 64x128, 4 waves; 3: 128x256, 8 waves; 4: 256x256,
  * 16 waves; 5 / 6: as 4 / 1 with the tile copies addressed by scalar base + lane offset where the shape allows;
- * anything else: choose by shape and tile count, the default).  Results do not depend on it beyond rounding order.
- * Returns the previous setting.  Not thread safe. */
+ * anything else below 100: choose by shape and tile count, the default).  config = 100 * switches + tile
+ * configuration (or + 99 for the default choice) additionally turns fusions off, for A/B timing: switch 32 the
+ * strip of memory rows in the last M-tile, 64 the transposed V written by the QKV epilogue, 128 the rotary
+ * embedding in the QKV epilogue (plain kernels run instead).  Results do not depend on any of this beyond
+ * rounding order.  Returns the previous tile configuration.  Not thread safe. */
 int32_t armt_set_gemm_tile_config(int32_t config);
 
 /* Kernel timing for benchmarks: between armt_profile_begin and armt_profile_end every launch of one

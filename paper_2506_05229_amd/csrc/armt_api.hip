@@ -125,7 +125,7 @@ bool debug_generic() {
 
 
 int g_gemm_tile_config = -1;     // armt_set_gemm_tile_config
-int g_gemm_dbg = 0;              // diagnosis variants (tile config / 100)
+int g_gemm_dbg = 0;              // A/B switches of armt_set_gemm_tile_config (config / 100)
 
 struct Ctx {
   Dims D;

@@ -85,7 +85,8 @@ struct GemmShape {
   int n0, n1;           // rows in weight blocks 0 and 1 (block 2 holds N - n0 - n1)
   int epi;              // GemmEpilogue
   int tag;              // which GEMM of the step this is (profiling only)
-  int dbg;              // diagnosis only: bit 0 freezes the k offset of B, bit 1 that of A (wrong results)
+  int dbg;              // A/B switches for benchmarks: bit 5 (32) multiplies the 16 memory rows as a tile of their own
+                        // instead of a strip of the last M-tile (same results up to rounding order)
   int ldb;              // row stride of the weight blocks in elements (>= K); the weights of the model are dense: ldb = K
 };
 

@@ -153,7 +153,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   auto issue_tile = [&](int kt, int buf) {
     typedef const __attribute__((address_space(1))) void* gptr_t;
     typedef __attribute__((address_space(3))) void* lptr_t;
-    const size_t ka = (size_t)((s.dbg & 2) ? 0 : kt) * MF_ROW_BYTES, kb = (size_t)((s.dbg & 1) ? 0 : kt) * MF_ROW_BYTES;
+    const size_t ka = (size_t)kt * MF_ROW_BYTES, kb = ka;
     if (KEEP_PTRS) {
       unsigned char* As = smem + buf * A_BYTES;
       unsigned char* Bs = smem + NS * A_BYTES + buf * B_BYTES;
