@@ -2,7 +2,7 @@
 //
 //   C_g = A_g B_g^T for every group g of the launch; A_g [M, K] activations, B_g [N, K] the
 //   weights of the group's own layer (taken from a pointer table, never stacked), fp32
-//   accumulation in v_mfma_f32_32x32x16_bf16, epilogue fused (residual add, row scale,
+//   accumulation in v_mfma_f32_16x16x32_bf16, epilogue fused (residual add, row scale,
 //   SwiGLU, bf16 copy and sums of squares for the next RMSNorm, rotary embedding and transposed
 //   V for the QKV projection).
 //
@@ -17,7 +17,8 @@
 // group-major tile sequence: with 16 groups every XCD streams the weights of 2 layers through its
 // own L2, and the M-tiles sharing a weight panel run back to back.
 // Template parameters of the kernel: BM x BN tile, WGM x WGN waves, REG (see above), EPI (GemmEpilogue),
-// TAIL (see below), NS (LDS stages).  The launcher picks the configuration from the shape and the
+// TAIL (see below), NS (LDS stages), BK (k-tile: 64, or 32 = 64-byte tile rows, four chunks, REG only: half the bytes
+// per stage, so that twice the stages fit and more copies are in flight at a barrier).  The launcher picks the configuration from the shape and the
 // number of tiles of the launch (mfma_pick_config).
 #pragma once
 
@@ -28,10 +29,14 @@ namespace armt {
 
 constexpr int MF_BK = 64;                 // k-tile (bf16 elements): 128 bytes per tile row
 constexpr int MF_ROW_BYTES = MF_BK * 2;
-constexpr int MF_NUM_CONFIGS = 7;         // tile configurations of launch_gemm_mfma_epi
+constexpr int MF_NUM_CONFIGS = 8;         // tile configurations of launch_gemm_mfma_epi
 
 // swizzle of the 16-byte chunk index inside a 128-byte tile row; depends on row bits 0..3 only
 __device__ __forceinline__ int mf_swz(int row) { return ((row >> 1) & 7) ^ ((row & 1) << 2); }
+// ... and inside a 64-byte tile row (four chunks): rows r, r + 4, r + 8, r + 12 share their LDS banks, so they take
+// different chunks; depends on row bits 2..3 only
+template <int BK>
+__device__ __forceinline__ int mf_swz_bk(int row) { return BK == 64 ? mf_swz(row) : ((row >> 2) & 3); }
 
 template <int N>
 __device__ __forceinline__ void mf_wait_vmcnt() {      // s_waitcnt vmcnt(N) only (N <= 63)
@@ -41,22 +46,25 @@ __device__ __forceinline__ void mf_wait_vmcnt() {      // s_waitcnt vmcnt(N) onl
 // TAIL: the last M-tile of every group also owns the 16 rows that follow it (M = tiles_m * BM + 16).  With
 // T = seg_len + 16 memory rows and seg_len a multiple of BM this removes the nearly empty fifth tile a
 // 1040-row cell would otherwise need: the 16 memory rows ride along as one extra strip of 16x16x32 MFMAs.
-template <int BM, int BN, int WGM, int WGN, bool REG, int EPI, bool TAIL, int NS>
+template <int BM, int BN, int WGM, int WGN, bool REG, int EPI, bool TAIL, int NS, int BK = MF_BK>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGroup* __restrict__ table, int first,
                                                                   GemmShape s, int tiles_m, int tiles_n,
                                                                   int total_tiles) {
   constexpr int NW = WGM * WGN;
   constexpr int WROWS = BM / WGM, WCOLS = BN / WGN;       // wave tile
   constexpr int TM = WROWS / 16, TN = WCOLS / 16;         // 16x16 MFMA tiles per wave
-  constexpr int A_DMA = BM / 8 / NW, B_DMA = BN / 8 / NW; // 8-row (1 KB) slabs each wave copies per k-tile
+  constexpr int ROWB = BK * 2;                            // bytes of a tile row
+  constexpr int RPS = 1024 / ROWB;                        // rows of a 1 KB slab (one copy instruction)
+  constexpr int A_DMA = BM / RPS / NW, B_DMA = BN / RPS / NW;   // slabs each wave copies per k-tile
+  constexpr int TAIL_SLABS = 16 / RPS;                    // slabs of the 16 tail rows, copied by the first waves
   constexpr int A_ROWS = TAIL ? BM + 16 : BM;
-  constexpr int A_BYTES = A_ROWS * MF_ROW_BYTES, B_BYTES = BN * MF_ROW_BYTES;
+  constexpr int A_BYTES = A_ROWS * ROWB, B_BYTES = BN * ROWB;
+  static_assert(BK == 64 || (BK == 32 && REG), "64-byte tile rows are written for the scalar-addressed copies only");
   constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;   // output columns per tile
   static_assert(BM % (WGM * 32) == 0 && BN % (WGN * 32) == 0, "wave tile must be a multiple of 32x32");
   static_assert(EPI != EPI_SWIGLU || WCOLS % 64 == 0, "SwiGLU: a wave owns whole gate/up pairs of 32-row weight blocks");
-  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must divide into 8-row slabs per wave");
+  static_assert(BM % (RPS * NW) == 0 && BN % (RPS * NW) == 0, "tile rows must divide into slabs per wave");
   static_assert(!TAIL || (BN <= NW * 32 && NW >= 2), "the tail strip gives each of the first BN / 32 waves two 16-column tiles");
-  constexpr int TAIL_WAVES = BN / 32;
 
   extern __shared__ __align__(16) unsigned char smem[];   // [NS][A_BYTES], [NS][B_BYTES], then A_ROWS row scales
 
@@ -132,18 +140,21 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
 #pragma unroll
     for (int j = 0; j < (KEEP_PTRS ? B_DMA : 0); ++j) bp[j] = b_src(j);
   } else {
-    const int chunk = (dpc ^ mf_swz((wave & 1) * 8 + dR)) << 4;
-    a_off0 = (unsigned)dR * (unsigned)s.lda * 2u + chunk;
-    b_off0 = (unsigned)dR * (unsigned)s.ldb * 2u + chunk;
+    // lane i fills row i / (ROWB / 16), physical chunk i % (ROWB / 16) of its slab
+    const int rR = BK == 64 ? dR : (lane >> 2), rc = BK == 64 ? dpc : (lane & 3);
+    const int chunk = (rc ^ mf_swz_bk<BK>(BK == 64 ? (wave & 1) * 8 + rR : rR)) << 4;   // BK = 32: the same for every slab
+    a_off0 = (unsigned)rR * (unsigned)s.lda * 2u + chunk;
+    b_off0 = (unsigned)rR * (unsigned)s.ldb * 2u + chunk;
   }
   // scalar source of the first row of slab `slab` (REG only)
-  auto a_base = [&](int slab) -> const char* { return (const char*)g.A + (size_t)(m0 + 8 * slab) * s.lda * 2; };
+  auto a_base = [&](int slab) -> const char* { return (const char*)g.A + (size_t)(m0 + RPS * slab) * s.lda * 2; };
   auto b_base = [&](int slab) -> const char* {
     if (EPI == EPI_SWIGLU) {   // tile rows 32 * blk ..: blk even from the gate, odd from the up weight, columns n0 + 32 * (blk / 2) ..
-      const int n = n0 + (slab >> 3) * 32 + (slab & 3) * 8;
-      return (const char*)(((slab >> 2) & 1) ? g.B1 : g.B0) + (size_t)n * s.ldb * 2;
+      const int row = slab * RPS, blk = row >> 5;
+      const int n = n0 + (blk >> 1) * 32 + (row & 31);
+      return (const char*)((blk & 1) ? g.B1 : g.B0) + (size_t)n * s.ldb * 2;
     }
-    return (const char*)weight_row<bf16>(g, s, n0 + 8 * slab);
+    return (const char*)weight_row<bf16>(g, s, n0 + RPS * slab);
   };
   const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) void*)smem;
   // one copy: 64 lanes x 16 bytes from base + lane offset to LDS address `lds` (M0) onwards; scalar operands only
@@ -153,7 +164,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   auto issue_tile = [&](int kt, int buf) {
     typedef const __attribute__((address_space(1))) void* gptr_t;
     typedef __attribute__((address_space(3))) void* lptr_t;
-    const size_t ka = (size_t)kt * MF_ROW_BYTES, kb = ka;
+    const size_t ka = (size_t)kt * ROWB, kb = ka;
     if (KEEP_PTRS) {
       unsigned char* As = smem + buf * A_BYTES;
       unsigned char* Bs = smem + NS * A_BYTES + buf * B_BYTES;
@@ -169,7 +180,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       const unsigned As = lds0 + buf * A_BYTES, Bs = lds0 + NS * A_BYTES + buf * B_BYTES;
 #pragma unroll
       for (int j = 0; j < A_DMA; ++j) dma(a_base(wave + j * NW) + ka, a_off0, As + (wave + j * NW) * 1024);
-      if (TAIL && tail_blk && wave < 2) dma(a_base(BM / 8 + wave) + ka, a_off0, As + BM * MF_ROW_BYTES + wave * 1024);
+      if (TAIL && tail_blk && wave < TAIL_SLABS) dma(a_base(BM / RPS + wave) + ka, a_off0, As + BM * ROWB + wave * 1024);
 #pragma unroll
       for (int j = 0; j < B_DMA; ++j) dma(b_base(wave + j * NW) + kb, b_off0, Bs + (wave + j * NW) * 1024);
     }
@@ -179,18 +190,19 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   // 1.9 PFLOP/s on the chip against 1.35 for the 32x32x16 form, which draws more power per flop; measured with
   // register-only loops): lane reads tile row (lane % 16) of each 16-row block, 16-byte chunk 4 * ks2 + lane / 16
   // of the 128-byte row; a 16x16 result tile has lane = column lane % 16 and registers = rows 4 * (lane / 16) + r.
-  const int t_sw = mf_swz(lane & 15), t_q = lane >> 4;
-  int koff[2];
+  constexpr int KS2 = BK / 32;                 // MFMA k-steps per k-tile
+  const int t_sw = mf_swz_bk<BK>(lane & 15), t_q = lane >> 4;
+  int koff[KS2];
 #pragma unroll
-  for (int ks2 = 0; ks2 < 2; ++ks2) koff[ks2] = ((4 * ks2 + t_q) ^ t_sw) << 4;
-  const int a_frag = (wm * WROWS + (lane & 15)) * MF_ROW_BYTES;
-  const int b_frag = (wn * WCOLS + (lane & 15)) * MF_ROW_BYTES;
+  for (int ks2 = 0; ks2 < KS2; ++ks2) koff[ks2] = ((4 * ks2 + t_q) ^ t_sw) << 4;
+  const int a_frag = (wm * WROWS + (lane & 15)) * ROWB;
+  const int b_frag = (wn * WCOLS + (lane & 15)) * ROWB;
   // tail strip: the same instruction on the 16 extra rows.  Wave w owns two 16-column
   // tiles whose B rows lie 32 apart, so that for SwiGLU tile 0 is the gate and tile 1 the up projection of the
   // same 16 output columns: B tile rows ((w / 2) * 2 + t) * 32 + (w % 2) * 16 + lane % 16.
-  const int t_a = (BM + (lane & 15)) * MF_ROW_BYTES;
+  const int t_a = (BM + (lane & 15)) * ROWB;
   const int t_brow = ((wave >> 1) * 2) * 32 + (wave & 1) * 16 + (lane & 15);
-  const int t_b = t_brow * MF_ROW_BYTES;
+  const int t_b = t_brow * ROWB;
 
   f32x4 acc[TM][TN];
 #pragma unroll
@@ -204,8 +216,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
     // multiplied (copies complete in issue order, so waiting for tile kt+1 leaves the younger ones outstanding);
     // one barrier per k-tile
     constexpr int CNT = A_DMA + B_DMA;                 // copy instructions per wave and tile (+1 on the tail waves)
-    const bool extra = TAIL && tail_blk && wave < 2;
-    const int nk = s.K / MF_BK;
+    const bool extra = TAIL && tail_blk && wave < TAIL_SLABS;
+    const int nk = s.K / BK;
 #pragma unroll
     for (int p = 0; p < NS - 1; ++p)
       if (p < nk) issue_tile(p, p);
@@ -222,12 +234,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       const unsigned char* As = smem + cur * A_BYTES;
       const unsigned char* Bs = smem + NS * A_BYTES + cur * B_BYTES;
 #pragma unroll
-      for (int ks2 = 0; ks2 < 2; ++ks2) {
+      for (int ks2 = 0; ks2 < KS2; ++ks2) {
         bf16x8 af[TM], bfr[TN];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8*)(As + a_frag + i * 16 * MF_ROW_BYTES + koff[ks2]);
+        for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8*)(As + a_frag + i * 16 * ROWB + koff[ks2]);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8*)(Bs + b_frag + j * 16 * MF_ROW_BYTES + koff[ks2]);
+        for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8*)(Bs + b_frag + j * 16 * ROWB + koff[ks2]);
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -236,12 +248,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       }
       if (TAIL && tail) {
 #pragma unroll
-        for (int ks2 = 0; ks2 < 2; ++ks2) {
+        for (int ks2 = 0; ks2 < KS2; ++ks2) {
           const int ko = koff[ks2];
           const bf16x8 ta = *(const bf16x8*)(As + t_a + ko);
 #pragma unroll
           for (int t = 0; t < 2; ++t) {
-            const bf16x8 tb = *(const bf16x8*)(Bs + t_b + t * 32 * MF_ROW_BYTES + ko);
+            const bf16x8 tb = *(const bf16x8*)(Bs + t_b + t * 32 * ROWB + ko);
             tacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ta, tb, tacc[t], 0, 0, 0);
           }
         }
@@ -417,14 +429,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool REG, int EPI, bool TAIL, int NS>
+template <int BM, int BN, int WGM, int WGN, bool REG, int EPI, bool TAIL, int NS, int BK = MF_BK>
 inline hipError_t launch_mfma_tail(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st) {
   constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
-  constexpr int LDS = NS * ((TAIL ? BM + 16 : BM) + BN) * MF_ROW_BYTES + (BM + 16) * 4;
+  constexpr int LDS = NS * ((TAIL ? BM + 16 : BM) + BN) * BK * 2 + (BM + 16) * 4;
   const int tiles_m = TAIL ? s.M / BM : (s.M + BM - 1) / BM, tiles_n = (s.N + BN_OUT - 1) / BN_OUT;
   const int total = g * tiles_m * tiles_n;
   const int grid = ((total + 7) / 8) * 8;
-  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, REG, EPI, TAIL, NS>;
+  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, REG, EPI, TAIL, NS, BK>;
   static bool attr_set = false;            // raising the dynamic-LDS limit is a per-function, idempotent setting
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -446,13 +458,13 @@ inline bool mfma_regular_shape(const GemmShape& s) {
   return m_ok && s.N % BN_OUT == 0 && w_ok && s.K % MF_BK == 0;
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, bool REG = false, int NS = 2>
+template <int BM, int BN, int WGM, int WGN, int EPI, bool REG = false, int NS = 2, int BK = MF_BK>
 inline hipError_t launch_mfma_cfg(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st) {
   if constexpr (BN <= WGM * WGN * 32) {
     if (s.M > BM && s.M % BM == 16 && !(s.dbg & 32))
-      return launch_mfma_tail<BM, BN, WGM, WGN, REG, EPI, true, NS>(table, first, g, s, st);
+      return launch_mfma_tail<BM, BN, WGM, WGN, REG, EPI, true, NS, BK>(table, first, g, s, st);
   }
-  return launch_mfma_tail<BM, BN, WGM, WGN, REG, EPI, false, NS>(table, first, g, s, st);
+  return launch_mfma_tail<BM, BN, WGM, WGN, REG, EPI, false, NS, BK>(table, first, g, s, st);
 }
 
 // Big tiles move the fewest bytes per flop, but a launch needs about one tile per CU to use the chip: a single
@@ -479,6 +491,9 @@ inline hipError_t launch_gemm_mfma_epi(const GemmGroup* table, int first, int g,
     case 4: return launch_mfma_cfg<256, 256, 4, 4, EPI>(table, first, g, s, st);
     case 5:   // as 4, copies addressed by scalar base + lane offset
       if (mfma_regular_shape<256, 256, EPI>(s)) return launch_mfma_cfg<256, 256, 4, 4, EPI, true>(table, first, g, s, st);
+      return launch_mfma_cfg<256, 256, 4, 4, EPI>(table, first, g, s, st);
+    case 7:   // as 5 with k-tiles of 32 in four stages (three tiles in flight at a barrier instead of one)
+      if (mfma_regular_shape<256, 256, EPI>(s)) return launch_mfma_cfg<256, 256, 4, 4, EPI, true, 4, 32>(table, first, g, s, st);
       return launch_mfma_cfg<256, 256, 4, 4, EPI>(table, first, g, s, st);
     case 6:   // as 1, copies addressed by scalar base + lane offset
       if (mfma_regular_shape<128, 128, EPI>(s)) return launch_mfma_cfg<128, 128, 2, 2, EPI, true>(table, first, g, s, st);
