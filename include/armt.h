@@ -279,7 +279,8 @@ armt_status armt_lm_head(const armt_config *cfg, const void *hidden, int64_t n_r
 /* Benchmarking knob: force the tile configuration of the bf16 grouped GEMM for all later calls of this
  * process (0: 256x256 tile, 8 waves; 1: 128x128, 4 waves; 2: 64x128, 4 waves; 3: 128x256, 8 waves; 4: 256x256,
  * 16 waves; 5 / 6: as 4 / 1 with the tile copies addressed by scalar base + lane offset where the shape allows;
- * 7: as 5 with k-tiles of 32 in four LDS stages instead of 64 in two (measured slower; kept for comparison);
+ * 7: as 5 with k-tiles of 32 in four LDS stages instead of 64 in two; 8: as 5 with a second barrier per k-tile that
+ * frees a tile buffer before the MFMAs of its last k-step (both measured slower than 5; kept for comparison);
  * anything else below 100: choose by shape and tile count, the default).  config = 100 * switches + tile
  * configuration (or + 99 for the default choice) additionally turns fusions off, for A/B timing: switch 32 the
  * strip of memory rows in the last M-tile, 64 the transposed V written by the QKV epilogue, 128 the rotary

@@ -29,7 +29,7 @@ namespace armt {
 
 constexpr int MF_BK = 64;                 // k-tile (bf16 elements): 128 bytes per tile row
 constexpr int MF_ROW_BYTES = MF_BK * 2;
-constexpr int MF_NUM_CONFIGS = 8;         // tile configurations of launch_gemm_mfma_epi
+constexpr int MF_NUM_CONFIGS = 9;         // tile configurations of launch_gemm_mfma_epi
 
 // swizzle of the 16-byte chunk index inside a 128-byte tile row; depends on row bits 0..3 only
 __device__ __forceinline__ int mf_swz(int row) { return ((row >> 1) & 7) ^ ((row & 1) << 2); }
@@ -46,7 +46,7 @@ __device__ __forceinline__ void mf_wait_vmcnt() {      // s_waitcnt vmcnt(N) onl
 // TAIL: the last M-tile of every group also owns the 16 rows that follow it (M = tiles_m * BM + 16).  With
 // T = seg_len + 16 memory rows and seg_len a multiple of BM this removes the nearly empty fifth tile a
 // 1040-row cell would otherwise need: the 16 memory rows ride along as one extra strip of 16x16x32 MFMAs.
-template <int BM, int BN, int WGM, int WGN, bool REG, int EPI, bool TAIL, int NS, int BK = MF_BK>
+template <int BM, int BN, int WGM, int WGN, bool REG, int EPI, bool TAIL, int NS, int BK = MF_BK, bool EARLY = false>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGroup* __restrict__ table, int first,
                                                                   GemmShape s, int tiles_m, int tiles_n,
                                                                   int total_tiles) {
@@ -211,7 +211,73 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
     for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
   f32x4 tacc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 
-  {
+  if constexpr (EARLY) {
+    // main loop with two tile buffers and two barriers per k-tile.  A buffer is free as soon as every wave holds the
+    // fragments of the tile's last k-step in registers, which is before the MFMAs of that k-step run: the first
+    // barrier sits there and the copy of k-tile kt + 2 goes out behind it, half a k-tile of arithmetic earlier than
+    // with one barrier at the end.  The second barrier, after those MFMAs, makes k-tile kt + 1 visible.
+    static_assert(!EARLY || (NS == 2 && KS2 == 2), "written for two buffers and two k-steps per tile");
+    constexpr int CNT = A_DMA + B_DMA;
+    const bool extra = TAIL && tail_blk && wave < TAIL_SLABS;
+    const int nk = s.K / BK;
+    issue_tile(0, 0);
+    if (nk > 1) {
+      issue_tile(1, 1);
+      if (extra) mf_wait_vmcnt<CNT + 1>(); else mf_wait_vmcnt<CNT>();
+    } else {
+      mf_wait_vmcnt<0>();
+    }
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+      const int cur = kt & 1;
+      const unsigned char* As = smem + cur * A_BYTES;
+      const unsigned char* Bs = smem + NS * A_BYTES + cur * B_BYTES;
+      {
+        bf16x8 af[TM], bfr[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8*)(As + a_frag + i * 16 * ROWB + koff[0]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8*)(Bs + b_frag + j * 16 * ROWB + koff[0]);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+      }
+      if (TAIL && tail) {       // the strip of memory rows, both k-steps, while the buffer is still held
+#pragma unroll
+        for (int ks2 = 0; ks2 < KS2; ++ks2) {
+          const int ko = koff[ks2];
+          const bf16x8 ta = *(const bf16x8*)(As + t_a + ko);
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            const bf16x8 tb = *(const bf16x8*)(Bs + t_b + t * 32 * ROWB + ko);
+            tacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ta, tb, tacc[t], 0, 0, 0);
+          }
+        }
+      }
+      bf16x8 af[TM], bfr[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8*)(As + a_frag + i * 16 * ROWB + koff[1]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8*)(Bs + b_frag + j * 16 * ROWB + koff[1]);
+      __syncthreads();          // (waits for the fragment reads) nobody reads buffer cur any more
+      if (kt + 2 < nk) issue_tile(kt + 2, cur);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+      // k-tile kt + 1 (copied into the other buffer half a k-tile ago or more) must have landed; the copy just issued stays in flight
+      if (kt + 2 < nk) {
+        if (extra) mf_wait_vmcnt<CNT + 1>(); else mf_wait_vmcnt<CNT>();
+      } else {
+        mf_wait_vmcnt<0>();
+      }
+      __syncthreads();
+    }
+  } else {
     // main loop: NS tile buffers; the copies of k-tiles kt+1 .. kt+NS-1 are in flight while k-tile kt is
     // multiplied (copies complete in issue order, so waiting for tile kt+1 leaves the younger ones outstanding);
     // one barrier per k-tile
@@ -429,14 +495,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool REG, int EPI, bool TAIL, int NS, int BK = MF_BK>
+template <int BM, int BN, int WGM, int WGN, bool REG, int EPI, bool TAIL, int NS, int BK = MF_BK, bool EARLY = false>
 inline hipError_t launch_mfma_tail(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st) {
   constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   constexpr int LDS = NS * ((TAIL ? BM + 16 : BM) + BN) * BK * 2 + (BM + 16) * 4;
   const int tiles_m = TAIL ? s.M / BM : (s.M + BM - 1) / BM, tiles_n = (s.N + BN_OUT - 1) / BN_OUT;
   const int total = g * tiles_m * tiles_n;
   const int grid = ((total + 7) / 8) * 8;
-  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, REG, EPI, TAIL, NS, BK>;
+  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, REG, EPI, TAIL, NS, BK, EARLY>;
   static bool attr_set = false;            // raising the dynamic-LDS limit is a per-function, idempotent setting
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -458,13 +524,13 @@ inline bool mfma_regular_shape(const GemmShape& s) {
   return m_ok && s.N % BN_OUT == 0 && w_ok && s.K % MF_BK == 0;
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, bool REG = false, int NS = 2, int BK = MF_BK>
+template <int BM, int BN, int WGM, int WGN, int EPI, bool REG = false, int NS = 2, int BK = MF_BK, bool EARLY = false>
 inline hipError_t launch_mfma_cfg(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st) {
   if constexpr (BN <= WGM * WGN * 32) {
     if (s.M > BM && s.M % BM == 16 && !(s.dbg & 32))
-      return launch_mfma_tail<BM, BN, WGM, WGN, REG, EPI, true, NS, BK>(table, first, g, s, st);
+      return launch_mfma_tail<BM, BN, WGM, WGN, REG, EPI, true, NS, BK, EARLY>(table, first, g, s, st);
   }
-  return launch_mfma_tail<BM, BN, WGM, WGN, REG, EPI, false, NS, BK>(table, first, g, s, st);
+  return launch_mfma_tail<BM, BN, WGM, WGN, REG, EPI, false, NS, BK, EARLY>(table, first, g, s, st);
 }
 
 // Big tiles move the fewest bytes per flop, but a launch needs about one tile per CU to use the chip: a single
@@ -494,6 +560,9 @@ inline hipError_t launch_gemm_mfma_epi(const GemmGroup* table, int first, int g,
       return launch_mfma_cfg<256, 256, 4, 4, EPI>(table, first, g, s, st);
     case 7:   // as 5 with k-tiles of 32 in four stages (three tiles in flight at a barrier instead of one)
       if (mfma_regular_shape<256, 256, EPI>(s)) return launch_mfma_cfg<256, 256, 4, 4, EPI, true, 4, 32>(table, first, g, s, st);
+      return launch_mfma_cfg<256, 256, 4, 4, EPI>(table, first, g, s, st);
+    case 8:   // as 5 with the buffer released (and refilled) before the MFMAs of a tile's last k-step
+      if (mfma_regular_shape<256, 256, EPI>(s)) return launch_mfma_cfg<256, 256, 4, 4, EPI, true, 2, 64, true>(table, first, g, s, st);
       return launch_mfma_cfg<256, 256, 4, 4, EPI>(table, first, g, s, st);
     case 6:   // as 1, copies addressed by scalar base + lane offset
       if (mfma_regular_shape<128, 128, EPI>(s)) return launch_mfma_cfg<128, 128, 2, 2, EPI, true>(table, first, g, s, st);
