@@ -92,3 +92,28 @@ def test_small_bf16_matches_oracle(case, diagonal):
     print(f"small bf16 {case} diag={diagonal}: rel hidden={e[0]:.3e} A={e[1]:.3e} z={e[2]:.3e}", flush=True)
     assert np.isfinite(h).all()
     assert e[0] <= BF16_REL and e[1] <= 5e-2 and e[2] <= 5e-2
+
+
+# a cell of 1024 + 16 rows and widths that are multiples of 256: the shapes on which the forced tile configurations take
+# their own code paths (256-row tiles with the strip of memory rows, scalar-addressed copies, fused epilogues)
+TILED_BF16 = dict(n_layers=3, d_model=512, n_heads=8, n_kv_heads=2, head_dim=64, d_ff=1024, seg_len=1024,
+                  n_mem=16, d_mem=32, n_tokens=1024 * 3, dtype="bf16")
+
+
+def test_tile_configurations_give_the_same_bits():
+    """Every tile configuration of the grouped GEMM accumulates a result element in the same order (k ascending, fp32),
+    so forcing one for all GEMMs of a pass must not change a single bit of the outputs."""
+    import paper_2506_05229_amd as P
+    shape = S.get_shape("tiny").replace(**TILED_BF16)
+    prob = make_problem(shape, seed=3, std=0.02, gain_std=0.1, v_scale=16.0)
+    model = P.Armt(shape, prob[0], prob[1])
+    want = run_hip(shape, *prob, diagonal=True, model=model)
+    assert np.isfinite(want[0]).all()
+    for cfg in range(9):
+        old = P.set_gemm_tile_config(cfg)
+        try:
+            got = run_hip(shape, *prob, diagonal=True, model=model)
+        finally:
+            P.set_gemm_tile_config(old)
+        for u, v in zip(got, want):
+            assert np.array_equal(u, v), cfg
