@@ -316,6 +316,15 @@ armt_status step_assoc_update(hipStream_t st, const GemmGroup* t_mkv, const Gemm
       ARMT_DELTA16(8)
     }
 #undef ARMT_DELTA16
+  } else if (m % 16 == 0 && Phi % 64 == 0 && Phi <= 512) {
+    const dim3 grid((d + 4 * DRC_ROWS - 1) / (4 * DRC_ROWS), g);
+#define ARMT_DELTA16C(NPL) \
+  case NPL: delta_rule16c_kernel<NPL><<<grid, 256, 0, st>>>(KVm, Fm, Coef, aux, first, m, d, dm); break;
+    switch (Phi / 64) {
+      ARMT_DELTA16C(1) ARMT_DELTA16C(2) ARMT_DELTA16C(3) ARMT_DELTA16C(4) ARMT_DELTA16C(5) ARMT_DELTA16C(6) ARMT_DELTA16C(7)
+      ARMT_DELTA16C(8)
+    }
+#undef ARMT_DELTA16C
   } else {
     const int rows_per_block = 4 * DR_ROWS;
     const size_t lds = (size_t)std::min(m, DR_CHUNK) * (Phi + 4) * 4;

@@ -365,4 +365,102 @@ __global__ __launch_bounds__(256) void delta_rule16_kernel(const float* __restri
   }
 }
 
+// The same for n_mem = 16 * C (the paper's tables use 128 memory tokens): the tokens are taken 16 at a time as above.
+// All of them see the OLD row (Eq. 4 is written with A_{s-1}), so a wave keeps the running update of its DRC_ROWS rows
+// in registers over the chunks, re-reads the old rows for every chunk (they stay in the L2) and writes each row once
+// at the end.  grid: (ceil(d / (4 * DRC_ROWS)), g), block: 256.
+constexpr int DRC_ROWS = 8;
+template <int NPL>
+__global__ __launch_bounds__(256) void delta_rule16c_kernel(const float* __restrict__ KV, const float* __restrict__ Fm,
+                                                            const float* __restrict__ Coef,
+                                                            const LayerAux* __restrict__ aux, int first, int m, int d,
+                                                            int dm) {
+  constexpr int Phi = 64 * NPL;
+  const int l = first + blockIdx.y;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const float* Fl = Fm + (size_t)l * m * Phi;
+  const float* cf = Coef + (size_t)l * m * 4;
+  float* A = aux[l].A;
+  bf16* A16 = aux[l].A16;
+  const int mi = (lane >> 2) & 15;                 // the token of the chunk whose dot product this lane ends up with
+  const bool b5 = lane & 32, b4 = lane & 16, b3 = lane & 8, b2 = lane & 4;
+  const int r0 = blockIdx.x * (4 * DRC_ROWS) + w;  // this wave's rows: r0 + 4 q
+  const bool zwave = blockIdx.x == 0 && w == 0;    // also updates z += sum_i gamma_i f_i
+  float upd[DRC_ROWS][NPL], zs[NPL];
+#pragma unroll
+  for (int k = 0; k < NPL; ++k) {
+    zs[k] = 0.f;
+#pragma unroll
+    for (int q = 0; q < DRC_ROWS; ++q) upd[q][k] = 0.f;
+  }
+  for (int i0 = 0; i0 < m; i0 += 16) {
+    float f[16][NPL];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+      for (int k = 0; k < NPL; ++k) f[i][k] = Fl[(size_t)(i0 + i) * Phi + lane + 64 * k];
+    const float beta = cf[(i0 + mi) * 4 + 0], rden = cf[(i0 + mi) * 4 + 2];
+    const float* Vmi = KV + ((size_t)l * m + i0 + mi) * (dm + d) + dm;
+#pragma unroll
+    for (int q = 0; q < DRC_ROWS; ++q) {
+      const int r = r0 + 4 * q;
+      if (r >= d) continue;                        // wave-uniform
+      float a[NPL];
+#pragma unroll
+      for (int k = 0; k < NPL; ++k) a[k] = A[(size_t)r * Phi + lane + 64 * k];
+      const float vr = Vmi[r];
+      float p[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        float t = 0.f;
+#pragma unroll
+        for (int k = 0; k < NPL; ++k) t = fmaf(a[k], f[i][k], t);
+        p[i] = t;
+      }
+      float q8[8], q4[4], q2[2];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) q8[j] = (b5 ? p[j + 8] : p[j]) + __shfl_xor(b5 ? p[j] : p[j + 8], 32, kWave);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) q4[j] = (b4 ? q8[j + 4] : q8[j]) + __shfl_xor(b4 ? q8[j] : q8[j + 4], 16, kWave);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) q2[j] = (b3 ? q4[j + 2] : q4[j]) + __shfl_xor(b3 ? q4[j] : q4[j + 2], 8, kWave);
+      float dot = (b2 ? q2[1] : q2[0]) + __shfl_xor(b2 ? q2[0] : q2[1], 4, kWave);
+      dot += __shfl_xor(dot, 2, kWave);
+      dot += __shfl_xor(dot, 1, kWave);
+      const float coef = beta * (vr - dot * rden);      // beta_i (v_i[r] - v_bar_i[r])
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float ci = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, coef), i * 4));
+#pragma unroll
+        for (int k = 0; k < NPL; ++k) upd[q][k] = fmaf(ci, f[i][k], upd[q][k]);
+      }
+    }
+    if (zwave) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float gi = cf[(i0 + i) * 4 + 1];
+#pragma unroll
+        for (int k = 0; k < NPL; ++k) zs[k] = fmaf(gi, f[i][k], zs[k]);
+      }
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < DRC_ROWS; ++q) {
+    const int r = r0 + 4 * q;
+    if (r >= d) continue;
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) {
+      const size_t at = (size_t)r * Phi + lane + 64 * k;
+      const float v = A[at] + upd[q][k];
+      A[at] = v;
+      if (A16) A16[at] = (bf16)v;
+    }
+  }
+  if (zwave) {
+    float* z = aux[l].z;
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) z[lane + 64 * k] += zs[k];
+  }
+}
+
 }  // namespace armt
