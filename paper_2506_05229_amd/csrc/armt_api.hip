@@ -88,21 +88,26 @@ struct Layout {          // byte offsets into the workspace
   size_t X, Xb, Nrm, QKV, Vt, Att, Hres, Uff, Qm, Fphi, RDen, A16, KVm, Fm, Coef, Rope, Ssq, RStd, Tables, Aux, total;
 };
 
+// rows of a cell rounded up to whole tiles of the largest GEMM tile
+inline size_t padded_rows(int T) { return ((size_t)T + 255) / 256 * 256; }
+
 Layout carve(const Dims& D) {
   Layout o;
   size_t p = 0;
   auto take = [&](size_t bytes) { size_t at = p; p = align_up(p + bytes); return at; };
   const size_t L = D.L, T = D.T;
+  // the bf16 GEMM operands end in `pad` rows nobody writes: the grouped GEMM may read whole 256-row tiles of them
+  const size_t pad = D.bf16 ? padded_rows(D.T) - T : 0;
   o.X = take((L + D.B) * T * D.d * 4);                            // residual stream, slot v = input of cell v; output in v + B
-  o.Xb = take(D.bf16 ? (L + D.B) * T * D.d * 2 : 0);              // bf16 copy of the slots (GEMM operand)
-  o.Nrm = take(L * T * D.d * D.esz);
+  o.Xb = take(D.bf16 ? ((L + D.B) * T + pad) * D.d * 2 : 0);      // bf16 copy of the slots (GEMM operand)
+  o.Nrm = take((L * T + pad) * D.d * D.esz);
   o.QKV = take(L * T * D.Nqkv * D.esz);
   o.Vt = take(D.bf16 ? attention_vt_bytes(D.L, D.T, D.Hkv, D.dh) : 0);   // V transposed, for the MFMA attention
-  o.Att = take(L * T * D.d * D.esz);
+  o.Att = take((L * T + pad) * D.d * D.esz);
   o.Hres = take(L * T * D.d * 4);
-  o.Uff = take(L * T * D.F * D.esz);
+  o.Uff = take((L * T + pad) * D.F * D.esz);
   o.Qm = take(L * T * D.dm * 4);
-  o.Fphi = take(L * T * D.Phi * D.esz);
+  o.Fphi = take((L * T + pad) * D.Phi * D.esz);
   o.RDen = take(L * T * 4);
   o.A16 = take(D.bf16 ? L * (size_t)D.d * D.Phi * 2 : 0);
   o.KVm = take(L * D.m * (size_t)(D.dm + D.d) * 4);
@@ -162,6 +167,8 @@ void fill_shapes(Ctx& c) {
   set(K_GU, D.T, D.F, D.d, D.d, D.F, 0, 0, D.F, D.F, EPI_SWIGLU);
   set(K_DOWN, D.T, D.d, D.F, D.F, D.d, D.d, D.d, D.d, 0, EPI_RESID_F32);
   set(K_MKV, D.m, D.dm + D.d, D.d, D.d, D.dm + D.d, 0, 0, D.dm, D.d, EPI_STORE_F32);
+  if (D.bf16)      // A operands of the T-row GEMMs are workspace buffers that end in padding rows (carve)
+    for (int k : {K_MQ, K_READ, K_QKV, K_O, K_GU, K_DOWN}) c.shape[k].a_rows = (int)padded_rows(D.T);
   c.fused_norm = D.bf16 && !debug_generic();
   // rotary embedding as the epilogue of the QKV GEMM: heads must not straddle its output tiles
   c.fused_rope = D.bf16 && !debug_generic() && 128 % D.dh == 0 && !(g_gemm_dbg & 128);

@@ -88,6 +88,8 @@ struct GemmShape {
   int dbg;              // A/B switches for benchmarks: bit 5 (32) multiplies the 16 memory rows as a tile of their own
                         // instead of a strip of the last M-tile (same results up to rounding order)
   int ldb;              // row stride of the weight blocks in elements (>= K); the weights of the model are dense: ldb = K
+  int a_rows = 0;       // rows of A that may be READ in every group (0: M).  Operand buffers that are padded to whole
+                        // tiles let a ragged M take the copies without per-lane clamping; rows >= M are never stored
 };
 
 }  // namespace armt

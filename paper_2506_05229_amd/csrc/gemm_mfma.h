@@ -518,7 +518,7 @@ inline hipError_t launch_mfma_tail(const GemmGroup* table, int first, int g, con
 template <int BM, int BN, int EPI>
 inline bool mfma_regular_shape(const GemmShape& s) {
   constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
-  const bool m_ok = s.M % BM == 0 || (s.M > BM && s.M % BM == 16 && !(s.dbg & 32));
+  const bool m_ok = s.M % BM == 0 || (s.M > BM && s.M % BM == 16 && !(s.dbg & 32)) || s.a_rows >= (s.M + BM - 1) / BM * BM;
   const int e0 = s.n0, e1 = s.n0 + s.n1;      // ends of weight blocks 0 and 1
   const bool w_ok = EPI == EPI_SWIGLU || ((e0 >= s.N || e0 % BN == 0) && (e1 >= s.N || e1 % BN == 0));
   return m_ok && s.N % BN_OUT == 0 && w_ok && s.K % MF_BK == 0;
