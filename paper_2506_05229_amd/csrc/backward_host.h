@@ -53,23 +53,25 @@ TrainLayout carve_train(const Dims& D) {
   o.Tp = round64(D.T); o.mp = round64(D.m); o.dmP = round64(D.dm); o.Kmkv = round64(D.dm + D.d);
   o.nblk = (D.d + UB_ROWS - 1) / UB_ROWS;
   o.Kw = WG_WIN * (int)B * o.Tp; o.Km = WG_WIN * (int)B * o.mp;
+  // bf16 GEMM operands with T rows per cell end in padding rows, so that the grouped GEMM may read whole 256-row tiles
+  const size_t LT = L * T + (D.bf16 ? padded_rows(D.T) - T : 0);
   o.Xin = take(L * T * d * 4);
   o.X1 = take(L * T * d * 4);
-  o.Xb = take(D.bf16 ? L * T * d * 2 : 0);
-  o.N1 = take(L * T * d * e);
-  o.N2 = take(L * T * d * e);
+  o.Xb = take(D.bf16 ? LT * d * 2 : 0);
+  o.N1 = take(LT * d * e);
+  o.N2 = take(LT * d * e);
   o.RStd1 = take(L * T * 4);
   o.RStd2 = take(L * T * 4);
   o.QKV = take(L * T * D.Nqkv * e);
   o.Vt = take(D.bf16 ? attention_vt_bytes(D.L, D.T, D.Hkv, D.dh) : 0);
-  o.Att = take(L * T * Hd * e);
+  o.Att = take(LT * Hd * e);
   o.Hres = take(L * T * d * 4);
-  o.GU = take(L * T * 2 * F * e);
+  o.GU = take(LT * 2 * F * e);
   o.Uff = take(L * T * F * e);
   o.Yf = take(L * T * d * 4);
   o.Yb = take(D.bf16 ? L * T * d * 2 : 0);
   o.Qm = take(L * T * D.dm * 4);
-  o.Fphi = take(L * T * D.Phi * e);
+  o.Fphi = take(LT * D.Phi * e);
   o.RDen = take(L * T * 4);
   o.KVm = take(L * D.m * (size_t)(D.dm + D.d) * 4);
   o.Fm = take(L * D.m * (size_t)D.Phi * 4);
@@ -80,20 +82,20 @@ TrainLayout carve_train(const Dims& D) {
   o.A16w = take(D.bf16 ? L * d * D.Phi * 2 : 0);
   o.ATr = take(L * d * D.Phi * e);
   o.DX = take((L + B) * T * d * 4);
-  o.DYb = take(L * T * d * e);
+  o.DYb = take(LT * d * e);
   o.DU = take(L * T * F * e);
   o.DN = take(L * T * d * e);
   o.DH = take(L * T * d * 4);
-  o.DHb = take(L * T * d * e);
+  o.DHb = take(LT * d * e);
   o.DAtt = take(L * T * Hd * e);
-  o.DQKV = take(L * T * D.Nqkv * e);
+  o.DQKV = take(LT * D.Nqkv * e);
   o.LSE = take(L * D.H * T * 4);
   o.Dv = take(L * D.H * T * 4);
   o.AttS = take(D.bf16 ? attention_bwd_scratch_bytes(D.L, D.T, D.H, D.Hkv, D.dh) : 0);
-  o.DNum = take(L * T * d * e);
+  o.DNum = take(LT * d * e);
   o.DF = take(L * T * D.Phi * 4);
   o.DDen = take(L * T * 4);
-  o.DQr = take(L * T * o.dmP * e);
+  o.DQr = take(LT * o.dmP * e);
   o.DKV = take(L * D.m * (size_t)o.Kmkv * e);
   o.DV = take(L * D.m * d * 4);
   o.Part = take(L * o.nblk * D.m * (size_t)(D.Phi + 2) * 4);
@@ -178,6 +180,9 @@ void fill_train_shapes(BCtx& c) {
   set(TK_DN1, D.T, D.d, D.Nqkv, D.Nqkv, D.d, EPI_STORE_ACT);
   set(TK_DF, D.T, D.Phi, D.d, D.d, D.Phi, EPI_STORE_F32);
   set(TK_DXQ, D.T, D.d, o.dmP, o.dmP, D.d, EPI_RESID_F32);
+  if (D.bf16)      // their A operands end in padding rows (carve_train)
+    for (int k : {TK_MQ, TK_READ, TK_QKV, TK_O, TK_GU, TK_DU, TK_DN2, TK_DATT, TK_DN1, TK_DF, TK_DXQ})
+      c.shape[k].a_rows = (int)padded_rows(D.T);
   // weight gradients: K = slots of the window actually filled (set at launch), lda = ldb = a whole window row
   const int Kw = o.Kw, Km = o.Km;
   set(TK_WD, D.d, D.F, Kw, Kw, D.F, EPI_RESID_F32, -1, 0, Kw);
