@@ -18,6 +18,7 @@ namespace armt {
 
 constexpr int AT_KT = 64;      // keys per tile
 constexpr int AT_QT = 32;      // query rows per wave / workgroup
+constexpr float AT_LAZY = 8.f; // log2 of the largest unnormalised probability the online softmax lets through
 
 // V of every cell transposed: Vt[l][kvh][c][j] = V[l][j][kvh*dh + c], j padded with zeros to Tp.
 // grid: (Tp / 64, Hkv, g), block: 256.
@@ -151,15 +152,20 @@ __global__ __launch_bounds__(512) void attention_mfma_kernel(const bf16* __restr
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[jj][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-    const float m_new = fmaxf(m, mx);
-    const float alpha = __builtin_amdgcn_exp2f((m - m_new) * scale_log2e);
-    m = m_new;
+    // m is the reference maximum of the exponents, not the running maximum: it only moves when some score of the
+    // wave exceeds it by more than 2^AT_LAZY, so that most tiles skip rescaling O and the sum (the result does not
+    // depend on the reference: numerator and denominator carry the same factor; p stays below 2^AT_LAZY)
+    if (__builtin_amdgcn_ballot_w64(mx * scale_log2e > fmaf(m, scale_log2e, AT_LAZY)) != 0) {
+      const float m_new = fmaxf(m, mx);
+      const float alpha = __builtin_amdgcn_exp2f((m - m_new) * scale_log2e);
+      m = m_new;
+      lsum *= alpha;
+#pragma unroll
+      for (int t = 0; t < OT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[t][r] *= alpha;
+    }
     const float mc = m * scale_log2e;
-    lsum *= alpha;
-#pragma unroll
-    for (int t = 0; t < OT; ++t)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[t][r] *= alpha;
     bf16x8 pf[2][2];
 #pragma unroll
     for (int jj = 0; jj < 2; ++jj)
