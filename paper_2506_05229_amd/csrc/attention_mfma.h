@@ -1,8 +1,10 @@
 // Segment attention on the CDNA4 matrix cores (paper Section 4.2): causal softmax(q k^T / sqrt(dh)) v
 // over the T rows of each cell, grouped-query heads, batched over the cells of the group.
 //
-// One workgroup = one KV head of one cell x 32 query rows; wave w handles query head (kv * GROUP + w),
-// so all waves share the K / V tiles in LDS and have the same causal extent.  Per 64-key tile a wave
+// One workgroup = one KV head of one cell x NQ x 32 query rows; wave w handles query head kv * GROUP + w % GROUP and
+// the 32 rows of sub-tile w / GROUP, so all waves share the K / V tiles in LDS.  NQ = 1 for grouped-query heads (all
+// waves have the same causal extent); with one query head per KV head a workgroup of a single wave would leave the CU
+// nearly empty, so NQ = 4 consecutive row tiles share the stream of K / V tiles (a wave skips the tiles past its rows).  Per 64-key tile a wave
 // computes S^T = K Q^T with v_mfma_f32_32x32x16_bf16 (keys along the rows, so a lane holds ONE query
 // column: the running max / sum of the online softmax are per-lane scalars and need a single exchange
 // between the two half-waves), turns it into P^T in registers -- the MFMA result layout is directly the
@@ -42,11 +44,11 @@ __global__ __launch_bounds__(256) void v_transpose_kernel(const bf16* __restrict
 }
 
 // QKV: [L][T][(H + 2 Hkv) dh] with q, k already rotated; Vt as above; Out: [L][T][H dh]; lse2: optional, see the end.
-// grid: (ceil(T / 32), Hkv, g), block: GROUP * 64 with GROUP = H / Hkv.
+// grid: (ceil(T / (32 NQ)), Hkv, g), block: NQ * GROUP * 64 with GROUP = H / Hkv.
 template <int DH>
 __global__ __launch_bounds__(512) void attention_mfma_kernel(const bf16* __restrict__ QKV, const bf16* __restrict__ Vt,
                                                              bf16* __restrict__ Out, int first, int Trows, int Tp,
-                                                             int H, int Hkv, float scale_log2e,
+                                                             int H, int Hkv, int nq, float scale_log2e,
                                                              float* __restrict__ lse2) {
   // a K tile is DH / 64 sub-tiles [64 keys][64 dims] with 128-byte rows
   constexpr int K_BYTES = AT_KT * DH * 2;
@@ -63,9 +65,10 @@ __global__ __launch_bounds__(512) void attention_mfma_kernel(const bf16* __restr
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nw = blockDim.x >> 6, group = H / Hkv;
-  const int head = kvh * group + wave;
+  const int head = kvh * group + wave % group;
   const int ldq = (H + 2 * Hkv) * DH;
-  const int q0 = qt * AT_QT;
+  const int q0 = (qt * nq + wave / group) * AT_QT;  // first row of this wave (may lie past the cell in the last workgroup)
+  const bool live = q0 < Trows;
   const int qcol = lane & 31, half = lane >> 5;
 
   const bf16* cell = QKV + (size_t)l * Trows * ldq;
@@ -111,7 +114,7 @@ __global__ __launch_bounds__(512) void attention_mfma_kernel(const bf16* __restr
     for (int r = 0; r < 16; ++r) o[t][r] = 0.f;
   float m = -INFINITY, lsum = 0.f;
 
-  const int nkt = (min(q0 + AT_QT, Trows) + AT_KT - 1) / AT_KT;
+  const int nkt = (min((qt + 1) * nq * AT_QT, Trows) + AT_KT - 1) / AT_KT;   // key tiles of the workgroup's last rows
   issue_tile(0, 0);
   __builtin_amdgcn_s_waitcnt(0x0F70);
   __syncthreads();
@@ -121,6 +124,7 @@ __global__ __launch_bounds__(512) void attention_mfma_kernel(const bf16* __restr
     if (kt + 1 < nkt) issue_tile(kt + 1, cur ^ 1);
     const unsigned char* Ks = smem + cur * STAGE;
     const unsigned char* Vs = Ks + K_BYTES;
+    if (live && k0 < q0 + AT_QT) {                 // wave-uniform: the tile holds keys this wave's rows may see
 
     // S^T[key][query] for the two 32-key halves of the tile
     f32x16 s[2];
@@ -193,6 +197,7 @@ __global__ __launch_bounds__(512) void attention_mfma_kernel(const bf16* __restr
           o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[jj][ss], o[t], 0, 0, 0);
         }
     }
+    }
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
   }
@@ -233,11 +238,12 @@ inline hipError_t launch_attention_mfma(const bf16* QKV, bf16* Vt, bf16* Out, in
     if (e != hipSuccess) return e;
   }
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)dh);
-  const dim3 grid((Trows + AT_QT - 1) / AT_QT, Hkv, g);
+  const int nq = group == 1 ? 4 : (group == 2 ? 2 : 1);       // row tiles per workgroup: at least 4 waves share the K / V tiles
+  const dim3 grid((Trows + nq * AT_QT - 1) / (nq * AT_QT), Hkv, g);
   if (dh == 64)
-    attention_mfma_kernel<64><<<grid, group * 64, 2 * (64 * 64 * 2 * 2), st>>>(QKV, Vt, Out, first, Trows, Tp, H, Hkv, scale_log2e, lse2);
+    attention_mfma_kernel<64><<<grid, nq * group * 64, 2 * (64 * 64 * 2 * 2), st>>>(QKV, Vt, Out, first, Trows, Tp, H, Hkv, nq, scale_log2e, lse2);
   else
-    attention_mfma_kernel<128><<<grid, group * 64, 2 * (64 * 128 * 2 * 2), st>>>(QKV, Vt, Out, first, Trows, Tp, H, Hkv, scale_log2e, lse2);
+    attention_mfma_kernel<128><<<grid, nq * group * 64, 2 * (64 * 128 * 2 * 2), st>>>(QKV, Vt, Out, first, Trows, Tp, H, Hkv, nq, scale_log2e, lse2);
   return hipGetLastError();
 }
 

@@ -64,6 +64,9 @@ def test_grouped_gemm(dtype, g, M, N, K, tile_cfg):
     ("bf16", dict(n_heads=4, n_kv_heads=2, head_dim=64, d_model=256, d_ff=512, seg_len=144, n_mem=16, d_mem=32)),
     ("bf16", dict(n_heads=8, n_kv_heads=2, head_dim=64, d_model=512, d_ff=512, seg_len=1024, n_mem=16, d_mem=32)),
     ("bf16", dict(n_heads=3, n_kv_heads=1, head_dim=128, d_model=384, d_ff=512, seg_len=200, n_mem=16, d_mem=32)),
+    # one query head per KV head: four row tiles per workgroup, the last workgroup only partly inside the cell
+    ("bf16", dict(n_heads=4, n_kv_heads=4, head_dim=64, d_model=256, d_ff=512, seg_len=200, n_mem=16, d_mem=32)),
+    ("bf16", dict(n_heads=2, n_kv_heads=2, head_dim=128, d_model=256, d_ff=512, seg_len=1024, n_mem=16, d_mem=32)),
 ])
 def test_segment_attention(dtype, kw):
     import paper_2506_05229_amd as P
