@@ -541,7 +541,9 @@ inline int mfma_pick_config(const GemmShape& s, int g, int force_cfg) {
   const int tm = (s.M > 256 && s.M % 256 == 16) ? s.M / 256 : (s.M + 255) / 256;
   const int bn_out = (s.epi == EPI_SWIGLU) ? 128 : 256;
   const long tiles = (long)g * tm * ((s.N + bn_out - 1) / bn_out);
-  return (s.M >= 192 && s.N >= 192 && tiles >= 224) ? 5 : 6;
+  // measured crossover (1040-row cells, N = 768 ... 3072, K = 768 ... 8192): 128x128 tiles win up to 128 tiles of
+  // 256x256 (they still fit the chip in one round of two workgroups per CU), 256x256 tiles from 144 on
+  return (s.M >= 192 && s.N >= 192 && tiles >= 136) ? 5 : 6;
 }
 
 // Tile configuration by problem shape: big square tiles for the block's linears, small tiles for
