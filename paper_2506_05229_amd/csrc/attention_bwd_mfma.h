@@ -55,12 +55,14 @@ __global__ __launch_bounds__(256) void attention_dvec_kernel(const bf16* __restr
 
 // dQ.  QKV: [cells][T][(H + 2 Hkv) dh] (q, k rotated); Kt: [cells][Hkv][dh][Tp]; dO: [cells][T][H dh];
 // LSE2 (log2 domain), Dv: [cells][H][T]; dQKV: gradient rows, q columns written here.
-// grid: (ceil(T / 32), Hkv, g), block: GROUP * 64; LDS: 2 stages of K, V, K^T tiles.
+// As in the forward kernel a workgroup takes NQ consecutive 32-row tiles (NQ > 1 when a KV head has fewer than four
+// query heads): wave w handles query head kv * GROUP + w % GROUP and row tile w / GROUP.
+// grid: (ceil(T / (32 NQ)), Hkv, g), block: NQ * GROUP * 64; LDS: 2 stages of K, V, K^T tiles.
 template <int DH>
 __global__ __launch_bounds__(512) void attention_bwd_dq_kernel(const bf16* __restrict__ QKV, const bf16* __restrict__ Kt,
                                                                const bf16* __restrict__ dO, const float* __restrict__ LSE2,
                                                                const float* __restrict__ Dv, bf16* __restrict__ dQKV,
-                                                               int first, int Trows, int Tp, int H, int Hkv, float scale) {
+                                                               int first, int Trows, int Tp, int H, int Hkv, int nq, float scale) {
   constexpr int K_BYTES = AT_KT * DH * 2;          // K and V tiles: DH / 64 sub-tiles [64 keys][64 dims], 128-byte rows
   constexpr int T_BYTES = DH * AT_KT * 2;          // K^T tile: [DH dims][64 keys]
   constexpr int STAGE = 2 * K_BYTES + T_BYTES;
@@ -74,9 +76,10 @@ __global__ __launch_bounds__(512) void attention_bwd_dq_kernel(const bf16* __res
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nw = blockDim.x >> 6, group = H / Hkv;
-  const int head = kvh * group + wave;
+  const int head = kvh * group + wave % group;
   const int ldq = (H + 2 * Hkv) * DH;
-  const int q0 = qt * AT_QT;
+  const int q0 = (qt * nq + wave / group) * AT_QT;   // may lie past the cell in the last workgroup
+  const bool live = q0 < Trows;
   const int qcol = lane & 31, half = lane >> 5;
   const float scale_log2e = scale * 1.4426950408889634f;
 
@@ -129,7 +132,7 @@ __global__ __launch_bounds__(512) void attention_bwd_dq_kernel(const bf16* __res
     for (int r = 0; r < 16; ++r) o[t][r] = 0.f;
 
   const int qi = q0 + qcol;
-  const int nkt = (min(q0 + AT_QT, Trows) + AT_KT - 1) / AT_KT;
+  const int nkt = (min((qt + 1) * nq * AT_QT, Trows) + AT_KT - 1) / AT_KT;   // key tiles of the workgroup's last rows
   issue_tile(0, 0);
   __builtin_amdgcn_s_waitcnt(0x0F70);
   __syncthreads();
@@ -140,6 +143,7 @@ __global__ __launch_bounds__(512) void attention_bwd_dq_kernel(const bf16* __res
     const unsigned char* Ks = smem + cur * STAGE;
     const unsigned char* Vs = Ks + K_BYTES;
     const unsigned char* Ts = Ks + 2 * K_BYTES;
+    if (live && k0 < q0 + AT_QT) {                 // wave-uniform: the tile holds keys this wave's rows may see
     bf16x8 dsf[2][2];
 #pragma unroll
     for (int jj = 0; jj < 2; ++jj) {
@@ -184,6 +188,7 @@ __global__ __launch_bounds__(512) void attention_bwd_dq_kernel(const bf16* __res
           tf[4] = hi[0]; tf[5] = hi[1]; tf[6] = hi[2]; tf[7] = hi[3];
           o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf, dsf[jj][ss], o[t], 0, 0, 0);
         }
+    }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
@@ -391,18 +396,19 @@ inline hipError_t launch_attention_bwd_mfma(const bf16* QKV, const bf16* O, cons
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const float scale = 1.0f / sqrtf((float)dh);
-  const dim3 grid((Trows + 31) / 32, Hkv, g), gkv((Trows + 32 * DKV_WAVES - 1) / (32 * DKV_WAVES), Hkv, g);
+  const int nq = group == 1 ? 4 : (group == 2 ? 2 : 1);       // row tiles per dQ workgroup, as in the forward kernel
+  const dim3 grid((Trows + 32 * nq - 1) / (32 * nq), Hkv, g), gkv((Trows + 32 * DKV_WAVES - 1) / (32 * DKV_WAVES), Hkv, g);
   if (dh == 64) {
-    attention_bwd_dq_kernel<64><<<grid, group * 64, 2 * 3 * (64 * 64 * 2), st>>>(QKV, Kt, dO, LSE2, Dv, dQKV, first, Trows, Tp, H, Hkv,
-                                                                              scale);
+    attention_bwd_dq_kernel<64><<<grid, nq * group * 64, 2 * 3 * (64 * 64 * 2), st>>>(QKV, Kt, dO, LSE2, Dv, dQKV, first, Trows, Tp, H, Hkv,
+                                                                                   nq, scale);
     attention_bwd_dkv_kernel<64><<<gkv, 64 * DKV_WAVES, 2 * (4 * 64 * 64 * 2 + 512), st>>>(QKV, Qt, dO, Gt, LSE2, Dv, dQKV, first, Trows, Tp, H, Hkv,
                                                                               scale);
   } else {
     hipError_t a = hipFuncSetAttribute((const void*)attention_bwd_dq_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        2 * 3 * (64 * 128 * 2));
     if (a != hipSuccess) return a;
-    attention_bwd_dq_kernel<128><<<grid, group * 64, 2 * 3 * (64 * 128 * 2), st>>>(QKV, Kt, dO, LSE2, Dv, dQKV, first, Trows, Tp, H,
-                                                                                Hkv, scale);
+    attention_bwd_dq_kernel<128><<<grid, nq * group * 64, 2 * 3 * (64 * 128 * 2), st>>>(QKV, Kt, dO, LSE2, Dv, dQKV, first, Trows, Tp, H,
+                                                                                     Hkv, nq, scale);
     a = hipFuncSetAttribute((const void*)attention_bwd_dkv_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             2 * (4 * 64 * 128 * 2 + 512));
     if (a != hipSuccess) return a;

@@ -122,11 +122,13 @@ SMALL_BF16 = dict(n_layers=3, d_model=256, n_heads=4, n_kv_heads=2, head_dim=64,
 
 
 @pytest.mark.parametrize("diagonal", [False, True])
-@pytest.mark.parametrize("heads", ["4x64_kv2", "4x128_kv1", "8x64_kv1"])
+@pytest.mark.parametrize("heads", ["4x64_kv2", "4x128_kv1", "8x64_kv1", "4x64_kv4"])
 def test_small_bf16_backward_matches_oracle(heads, diagonal):
-    """Head layouts of the three attention-backward configurations: head_dim 64 and 128, 2, 4 and 8 query heads per KV head."""
+    """Head layouts of the attention-backward configurations: head_dim 64 and 128; 1, 2, 4 and 8 query heads per KV head
+    (with 1 and 2 a workgroup of the dQ and of the forward kernel takes 4 and 2 row tiles)."""
     kw = {"4x64_kv2": dict(), "4x128_kv1": dict(d_model=512, n_heads=4, n_kv_heads=1, head_dim=128),
-          "8x64_kv1": dict(d_model=512, n_heads=8, n_kv_heads=1, head_dim=64)}[heads]
+          "8x64_kv1": dict(d_model=512, n_heads=8, n_kv_heads=1, head_dim=64),
+          "4x64_kv4": dict(n_heads=4, n_kv_heads=4, seg_len=200, n_tokens=200 * 4)}[heads]
     shape, layers, mem_emb, x = well_conditioned(S.get_shape("tiny").replace(**dict(SMALL_BF16, **kw)), seed=11)
     Gs = upstream(shape, 11, with_state=True)
     want = G.armt_grad(shape, layers, mem_emb, x, *Gs)
