@@ -11,7 +11,9 @@ Values are i.i.d. normal: the paper's pretrained weights and token streams are
 not available, so these stand in for them.
 """
 from .workloads import (ArmtShape, CONFIGS, get_shape, make_weights, make_embeddings,
-                        round_to_bf16, bf16_bits, from_bf16_bits, LAYER_FIELDS, make_token_ends, LLAMA3_VOCAB)
+                        round_to_bf16, bf16_bits, from_bf16_bits, LAYER_FIELDS, make_token_ends, LLAMA3_VOCAB,
+                        describe_workload)
 
 __all__ = ["ArmtShape", "CONFIGS", "get_shape", "make_weights", "make_embeddings",
-           "round_to_bf16", "bf16_bits", "from_bf16_bits", "LAYER_FIELDS", "make_token_ends", "LLAMA3_VOCAB"]
+           "round_to_bf16", "bf16_bits", "from_bf16_bits", "LAYER_FIELDS", "make_token_ends", "LLAMA3_VOCAB",
+           "describe_workload"]

@@ -67,18 +67,24 @@ class ArmtShape:
 
 # At LLaMA widths the plain N(0, 0.02) recipe makes the recurrence of Eq. 4-5 diverge within a few segments
 # (the float64 oracle shows it, it is not a rounding effect): the 16 keys phi(k_i) written together are
-# positively correlated and as large as 1, so gamma_i = 1 - z.phi(k_i) / |phi(k_i)|^2 goes below -1, z turns
-# negative, a denominator z.phi crosses zero and the values read back grow without bound; values of size
-# |W_V y| ~ |y| fed back through every layer then grow from segment to segment as well.  The LLaMA-shaped
-# workloads therefore draw W_K ~ N(0, (0.02 * 2^-10)^2) (then |phi(k)|^2 << assoc_eps: gamma stays in (0, 1] and z
-# positive) and W_V ~ N(0, (0.02 * 2^-3)^2) (a contraction from segment to segment).  Every other weight keeps
-# N(0, 0.02^2); the equations are untouched.  With these the 131072-token run is stable and the memory still
-# changes the hidden states by several per cent.
-_MEM_SCALES = dict(mem_k_scale=2.0 ** -10, mem_v_scale=2.0 ** -3)
+# positively correlated, so gamma_i = 1 - z.phi(k_i) / (|phi(k_i)|^2 + eps) goes below -1 once |phi(k)|^2 is a few times
+# assoc_eps, z turns negative, a denominator z.phi crosses zero and the values read back grow without bound; values of
+# size |W_V y| ~ |y| fed back through every layer then grow from segment to segment as well.  The LLaMA-shaped
+# workloads therefore scale W_K^mem by the LARGEST power of two for which the oracle keeps every z.phi positive and
+# the hidden states stationary over the first segments (`python -m oracle.key_scale_search`; the deeper and wider
+# the model, the larger its memory rows and the smaller that scale), and W_V^mem by 2^-3 (a contraction from segment to
+# segment).  At that key scale |phi(k)|^2 is of the order of assoc_eps: gamma ranges from below 0 to 1 and v_bar is a
+# visible fraction of v, so every term of Eq. 4 takes part.  Every other weight keeps N(0, 0.02^2); the equations
+# are untouched.
+def _mem_scales(k_log2: int, v_log2: int = -3):
+    return dict(mem_k_scale=2.0 ** k_log2, mem_v_scale=2.0 ** v_log2)
+
+
+_MEM_SCALES = _mem_scales(-7)
 _1B = dict(n_layers=16, d_model=2048, n_heads=32, n_kv_heads=8, head_dim=64, d_ff=8192,
            seg_len=1024, n_mem=16, d_mem=64, dtype="bf16", **_MEM_SCALES)
 _3B = dict(n_layers=28, d_model=3072, n_heads=24, n_kv_heads=8, head_dim=128, d_ff=8192,
-           seg_len=1024, n_mem=16, d_mem=64, dtype="bf16", **_MEM_SCALES)
+           seg_len=1024, n_mem=16, d_mem=64, dtype="bf16", **_mem_scales(-8))
 
 # LLaMA-160M (12 layers of width 768, 12 heads without grouping): the small model of the paper's tables
 _160M = dict(n_layers=12, d_model=768, n_heads=12, n_kv_heads=12, head_dim=64, d_ff=3072,
@@ -107,6 +113,19 @@ CONFIGS = {
 
 def get_shape(name: str) -> ArmtShape:
     return CONFIGS[name]
+
+
+def _pow2(v: float) -> str:
+    e = int(round(np.log2(v)))
+    return "1" if e == 0 else (f"2^{e}" if 2.0 ** e == v else f"{v:g}")
+
+
+def describe_workload(shape: ArmtShape, batch: int = 1, seed: int = 0) -> str:
+    """One line that states the whole input recipe of a workload, memory-projection scales included."""
+    return (f"{shape.name}: {shape.n_layers} layers, d_model {shape.d_model}, {shape.n_heads}/{shape.n_kv_heads} heads x "
+            f"{shape.head_dim}, d_ff {shape.d_ff}, segment {shape.seg_len} + {shape.n_mem} memory tokens, d_mem {shape.d_mem}, "
+            f"{shape.n_segments} segments, batch {batch}, weights N(0, 0.02^2) with W_K^mem x {_pow2(shape.mem_k_scale)} and "
+            f"W_V^mem x {_pow2(shape.mem_v_scale)}, N(0,1) embeddings, assoc_eps {shape.assoc_eps:g}, seed {seed}")
 
 
 # per-layer tensors: field -> (rows, cols) as functions of the shape; row-major [out, in]

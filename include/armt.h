@@ -9,11 +9,18 @@
  *
  * Conventions, valid for every call unless stated otherwise:
  *   - every pointer is a DEVICE pointer unless marked [host];
- *   - the caller owns all memory; the library allocates and frees no device memory and
- *     keeps no state between calls; scratch space comes in through `workspace`;
+ *   - the caller owns all memory; the library allocates and frees no device memory;
+ *     scratch space comes in through `workspace`;
+ *   - no call keeps state for a later call.  Excluded from this, and NOT thread safe: the
+ *     process-wide benchmarking and debugging knobs at the end of this header
+ *     (armt_set_gemm_tile_config, armt_profile_begin / armt_profile_end, the environment
+ *     variable ARMT_DEBUG_GENERIC), which change kernel selection or event recording for every
+ *     later call of the process on any stream.  Leave them alone and the calls are re-entrant;
  *   - work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = default
- *     stream) and the call returns without waiting for the GPU, except for one small
- *     host-to-device copy of pointer tables that is complete when the call returns;
+ *     stream) and the call returns without waiting for the GPU or for earlier work on the
+ *     stream: the small host tables a call builds (per-layer operand pointers) travel as kernel
+ *     arguments, not as copies, so nothing synchronises and the host arrays passed in
+ *     (`layers`, `grads`, pointer lists) may be freed as soon as the call returns;
  *   - errors are return codes; argument errors are detected before anything is launched
  *     and leave all outputs untouched;
  *   - matrices are row-major; a weight W is [out_features, in_features] and is applied as
@@ -75,9 +82,11 @@ typedef struct {
   const void *wm_b;                 /* [1, d]                         W_beta (Eq. 3)           */
 } armt_layer_weights;
 
-/* Bytes of scratch space armt_forward_* needs for this configuration (independent of n_tokens
- * and of the execution order); 0 if cfg is invalid.  The workspace must be 256-byte aligned.
- * Its contents need not be initialised and are undefined afterwards. */
+/* Bytes of scratch space armt_forward_* needs for this configuration; 0 if cfg is invalid.  The size depends on
+ * neither n_tokens nor the execution order (one slot of every intermediate per layer: a step of the diagonal order
+ * has at most n_layers live cells, the sequential order uses the same slots one at a time), which is why this query
+ * takes the configuration only.  The workspace must be 256-byte aligned.  Its contents need not be initialised and
+ * are undefined afterwards. */
 size_t armt_workspace_bytes(const armt_config *cfg /* [host] */);
 
 /* Forward pass, cells visited segment by segment, layer by layer (Section 3.1; Fig. 3a):
@@ -110,6 +119,33 @@ armt_status armt_forward_diagonal(const armt_config *cfg, const armt_layer_weigh
                                   const float *A_in, const float *z_in,
                                   void *hidden_out, float *A_out, float *z_out,
                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Choice between the two orders (the paper's appendix notes that one can fall back to the original order at run time
+ * where Diagonal Batching does not pay off; its timing tables have such entries at 4096 - 8192 tokens).
+ * armt_auto_order returns 1 (diagonal) or 0 (sequential) for a configuration and length, -1 if they are invalid.
+ * Rule: diagonal from two segments and two layers on, else sequential.  With one segment (or one layer) every
+ * anti-diagonal holds a single cell and both orders launch the same kernels; from two segments on a diagonal step
+ * runs the kernels of the sequential order on larger launches and was never slower in any measured case, the
+ * 4096-token column of the paper's tables included (table in the design notes).
+ * armt_forward_auto runs the order armt_auto_order picks (arguments and result as armt_forward_sequential) and
+ * reports it in *order_used ([host], may be NULL). */
+int32_t armt_auto_order(const armt_config *cfg, int64_t n_tokens);
+armt_status armt_forward_auto(const armt_config *cfg, const armt_layer_weights *layers,
+                              const void *mem_emb, const void *x, int64_t n_tokens,
+                              const float *A_in, const float *z_in,
+                              void *hidden_out, float *A_out, float *z_out,
+                              void *workspace, size_t workspace_bytes, void *hip_stream, int32_t *order_used);
+
+/* The hybrid of the two orders: Diagonal Batching in which a group of at most split_upto cells (the small groups at
+ * both ends of the schedule) is launched cell by cell instead of as one group.  split_upto = 0 is
+ * armt_forward_diagonal; split_upto >= n_layers launches every cell on its own, in anti-diagonal order.  Same result
+ * bit for bit.  Measured slower than the plain diagonal order for every split_upto >= 1 (a group launch is never
+ * slower than its cells one after the other here); exported so that the comparison can be repeated. */
+armt_status armt_forward_diagonal_split(const armt_config *cfg, const armt_layer_weights *layers,
+                                        const void *mem_emb, const void *x, int64_t n_tokens,
+                                        const float *A_in, const float *z_in,
+                                        void *hidden_out, float *A_out, float *z_out,
+                                        void *workspace, size_t workspace_bytes, void *hip_stream, int32_t split_upto);
 
 /* Batch of B independent sequences of the same length (the paper's batched setting, Section 4.3): step t
  * runs the cells (layer l, segment t - l) of all B sequences as one group of up to B * n_layers cells; the B
@@ -276,22 +312,24 @@ armt_status armt_lm_head(const armt_config *cfg, const void *hidden, int64_t n_r
  * fp32-FMA GPU kernels of the fp32 path on bf16 operands instead of the MFMA kernels: slow, for telling an
  * error of a fast kernel from an error of the method.  Nothing ever runs on the host. */
 
-/* Benchmarking knob: force the tile configuration of the bf16 grouped GEMM for all later calls of this
- * process (0: 256x256 tile, 8 waves; 1: 128x128, 4 waves; 2: 64x128, 4 waves; 3: 128x256, 8 waves; 4: 256x256,
- * 16 waves; 5 / 6: as 4 / 1 with the tile copies addressed by scalar base + lane offset where the shape allows;
- * 7: as 5 with k-tiles of 32 in four LDS stages instead of 64 in two; 8: as 5 with a second barrier per k-tile that
- * frees a tile buffer before the MFMAs of its last k-step (both measured slower than 5; kept for comparison);
- * anything else below 100: choose by shape and tile count, the default).  config = 100 * switches + tile
- * configuration (or + 99 for the default choice) additionally turns fusions off, for A/B timing: switch 32 the
- * strip of memory rows in the last M-tile, 64 the transposed V written by the QKV epilogue, 128 the rotary
- * embedding in the QKV epilogue (plain kernels run instead).  Results do not depend on any of this beyond
- * rounding order.  Returns the previous tile configuration.  Not thread safe. */
+/* ---- process-wide benchmarking and debugging knobs (not part of the re-entrant contract above, not thread safe) ---- */
+
+/* Force the tile configuration of the bf16 grouped GEMM for all later calls of this process (1: 128x128 tile, 4 waves;
+ * 2: 64x128, 4 waves; 5: 256x256, 16 waves; 6: as 1; 5 and 6 address the tile copies by scalar base + lane offset
+ * where the shape allows; anything else below 100: choose by shape and tile count, the default).  config = 100 *
+ * switches + tile configuration (or + 99 for the default choice) additionally turns fusions off, for A/B timing:
+ * switch 16 the feature map of the read in the epilogue of the W_Q projection, 32 the strip of memory rows in the last
+ * M-tile, 64 the transposed V written by the QKV epilogue, 128 the rotary embedding in the QKV epilogue (plain kernels
+ * run instead).  Results do not depend on any of this beyond
+ * rounding order.  Returns the previous tile configuration. */
 int32_t armt_set_gemm_tile_config(int32_t config);
 
 /* Kernel timing for benchmarks: between armt_profile_begin and armt_profile_end every launch of one
- * grouped GEMM of the step (up to max_launches of them) made by this process is bracketed by a pair of
+ * kernel kind of the step (up to max_launches of them) made by this process is bracketed by a pair of
  * HIP events on the launch stream.  gemm_kind: 0 W_Q projection of the read, 1 read A phi, 2 QKV,
- * 3 attention output, 4 gate/up with SwiGLU, 5 down, 6 W_K / W_V projections of the update.
+ * 3 attention output, 4 gate/up with SwiGLU, 5 down, 6 W_K / W_V projections of the update (the grouped GEMMs);
+ * 7 feature map + denominator of the read, 8 feature map + coefficients of the update, 9 the delta rule's pass over A,
+ * 10 segment attention.
  * armt_profile_end waits for the recorded events and returns the summed kernel time in milliseconds,
  * the number of launches timed and the number of groups (cells) they covered; any pointer may be NULL.
  * Not thread safe; the events are created in begin and destroyed in end. */

@@ -150,6 +150,21 @@ def assoc_update(Ym: np.ndarray, A: np.ndarray, z: np.ndarray, empty: bool, w: d
     return A_new, z_new
 
 
+def update_conditioning(Ym: np.ndarray, A: np.ndarray, z: np.ndarray, w: dict, eps: float, nu: int) -> dict:
+    """Diagnostics of one delta-rule update on a non-empty memory (no arithmetic of the method depends on them):
+    smallest z.phi(k), range of gamma (Eq. 4), |v_bar| / |v| (how much of the written value is the correction by what
+    the memory already holds) and the median of |phi(k)|^2 / eps."""
+    f = dpfp(Ym @ w["wm_k"].T, nu)
+    zf = f @ z
+    f2 = np.sum(f * f, axis=-1)
+    gamma = 1.0 - zf / (f2 + eps)
+    v = Ym @ w["wm_v"].T
+    vbar = (f @ A.T) / (zf + eps)[:, None]
+    return dict(min_zf=float(zf.min()), gamma_min=float(gamma.min()), gamma_max=float(gamma.max()),
+                vbar_over_v=float(np.linalg.norm(vbar) / max(np.linalg.norm(v), 1e-300)),
+                f2_over_eps=float(np.median(f2) / eps) if eps > 0 else float("inf"))
+
+
 # --------------------------------------------------------------------------- one (layer, segment) cell
 def armt_cell(U: np.ndarray, A: np.ndarray, z: np.ndarray, empty: bool, w: dict, cfg):
     """Cell (l, s): read from layer l's memory, run the decoder block, update the memory
@@ -184,7 +199,7 @@ def _prepare(cfg, layers, mem_emb, x, A_in, z_in):
 def armt_forward_sequential(cfg, layers, mem_emb, x, A_in=None, z_in=None, stats=None):
     """Sequential ARMT forward: for each segment, for each layer (Section 3.1).
     x [n_tokens, d] token embeddings; returns (hidden [n_tokens, d], A [L, d, Phi], z [L, Phi]).
-    stats, if a list, receives per-cell conditioning figures of the associative read."""
+    stats, if a list, receives per-cell conditioning figures of the associative read and update."""
     x, W, mem_emb, A, z, empty = _prepare(cfg, layers, mem_emb, x, A_in, z_in)
     S = cfg.seg_len
     N = x.shape[0] // S
@@ -199,7 +214,10 @@ def armt_forward_sequential(cfg, layers, mem_emb, x, A_in=None, z_in=None, stats
                                   min_den=float(den.min()), max_den=float(den.max()),
                                   max_abs_read=float(np.abs((f @ A[l].T) / (den + cfg.assoc_eps)[:, None]).max()),
                                   max_abs_A=float(np.abs(A[l]).max()), max_abs_z=float(np.abs(z[l]).max())))
+            was_empty, A_old, z_old = empty[l], A[l], z[l]
             U, A[l], z[l] = armt_cell(U, A[l], z[l], empty[l], W[l], cfg)
+            if stats is not None and not was_empty:      # the update side of the same cell (U is the cell's output here)
+                stats[-1].update(update_conditioning(U[S:], A_old, z_old, W[l], cfg.assoc_eps, cfg.dpfp_nu))
             empty[l] = False
         hidden[s * S:(s + 1) * S] = U[:S]
     return hidden, np.stack(A), np.stack(z)

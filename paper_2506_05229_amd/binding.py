@@ -64,6 +64,12 @@ def load_library():
     for name in ("armt_forward_sequential", "armt_forward_diagonal"):
         getattr(lib, name).argtypes = fwd
         getattr(lib, name).restype = C.c_int
+    lib.armt_forward_auto.argtypes = fwd + [C.POINTER(i32)]
+    lib.armt_forward_auto.restype = C.c_int
+    lib.armt_forward_diagonal_split.argtypes = fwd + [i32]
+    lib.armt_forward_diagonal_split.restype = C.c_int
+    lib.armt_auto_order.argtypes = [C.POINTER(ArmtConfig), i64]
+    lib.armt_auto_order.restype = i32
     fwdb = fwd[:4] + [i32] + fwd[4:]
     for name in ("armt_forward_sequential_batched", "armt_forward_diagonal_batched"):
         getattr(lib, name).argtypes = fwdb
@@ -174,8 +180,10 @@ class Armt:
     def embed(self, x):
         return self.torch.as_tensor(x).to(device=self.device, dtype=self.act_dtype).contiguous()
 
-    def forward(self, x, diagonal=True, A_in=None, z_in=None, out=None):
-        """x: [n_tokens, d] device tensor of the activation type.  Returns (hidden, A, z)."""
+    def forward(self, x, diagonal=True, A_in=None, z_in=None, out=None, split_upto=None):
+        """x: [n_tokens, d] device tensor of the activation type.  Returns (hidden, A, z).
+        diagonal: True / False, or "auto" (armt_forward_auto; the order it took is left in self.order_used).
+        split_upto: if given, armt_forward_diagonal_split with that threshold."""
         torch, s = self.torch, self.shape
         assert x.is_cuda and x.dtype == self.act_dtype and x.is_contiguous()
         n_tokens = x.shape[0]
@@ -185,10 +193,18 @@ class Armt:
             z = torch.empty((s.n_layers, s.phi), dtype=torch.float32, device=self.device)
         else:
             hidden, A, z = out
-        fn = self.lib.armt_forward_diagonal if diagonal else self.lib.armt_forward_sequential
         stream = torch.cuda.current_stream(self.device).cuda_stream
-        code = fn(C.byref(self.cfg), self.c_layers, _ptr(self.mem_emb), _ptr(x), n_tokens, _ptr(A_in), _ptr(z_in),
-                  _ptr(hidden), _ptr(A), _ptr(z), _ptr(self.workspace), self.workspace_bytes, C.c_void_p(stream))
+        args = (C.byref(self.cfg), self.c_layers, _ptr(self.mem_emb), _ptr(x), n_tokens, _ptr(A_in), _ptr(z_in),
+                _ptr(hidden), _ptr(A), _ptr(z), _ptr(self.workspace), self.workspace_bytes, C.c_void_p(stream))
+        if split_upto is not None:
+            code = self.lib.armt_forward_diagonal_split(*args, int(split_upto))
+        elif diagonal == "auto":
+            used = C.c_int32(-1)
+            code = self.lib.armt_forward_auto(*args, C.byref(used))
+            self.order_used = used.value
+        else:
+            fn = self.lib.armt_forward_diagonal if diagonal else self.lib.armt_forward_sequential
+            code = fn(*args)
         _check(self.lib, code)
         return hidden, A, z
 
@@ -296,7 +312,8 @@ def set_gemm_tile_config(config: int) -> int:
     return load_library().armt_set_gemm_tile_config(config)
 
 
-GEMM_KINDS = {"mem_q": 0, "mem_read": 1, "qkv": 2, "attn_out": 3, "gate_up": 4, "down": 5, "mem_kv": 6}
+GEMM_KINDS = {"mem_q": 0, "mem_read": 1, "qkv": 2, "attn_out": 3, "gate_up": 4, "down": 5, "mem_kv": 6,
+              "dpfp_read": 7, "update_prep": 8, "delta_rule": 9, "attention": 10}
 
 
 def profile_begin(kind: str, max_launches: int):

@@ -4,6 +4,7 @@
 // is declared in include/armt.h.
 #include "../../include/armt.h"
 
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
 #include <string>
@@ -83,6 +84,8 @@ armt_status check_config(const armt_config* c, Dims* out) {
 
 // GEMM kinds of one step, in launch order; each has one table entry per layer.
 enum Kind { K_MQ = 0, K_READ, K_QKV, K_O, K_GU, K_DOWN, K_MKV, K_COUNT };
+// further kinds of armt_profile_begin: kernels of the associative memory that are not GEMMs, and the attention kernel
+enum ProfKind { PK_DPFP_READ = K_COUNT, PK_UPD_PREP, PK_DELTA_RULE, PK_ATTENTION, PK_COUNT };
 
 struct Layout {          // byte offsets into the workspace
   size_t X, Xb, Nrm, QKV, Vt, Att, Hres, Uff, Qm, Fphi, RDen, A16, KVm, Fm, Coef, Rope, Ssq, RStd, Tables, Aux, total;
@@ -143,6 +146,7 @@ struct Ctx {
   bool fused_norm;           // bf16 MFMA path: RMSNorm folded into the GEMM epilogues around it
   bool fused_rope;           // bf16 MFMA path: rotary embedding applied by the QKV GEMM epilogue
   bool fused_vt;             // ... which also writes V transposed
+  bool fused_dpfp;           // bf16 MFMA path: feature map and denominator of the read in the epilogue of the W_Q projection
   int ssq_parts;             // partial sums of squares per row written by the GEMMs that produce a normalised row
   float* tape = nullptr;     // training forward: per-cell records of what the backward pass cannot recompute
   size_t rec_floats = 0;     // floats per record
@@ -177,10 +181,40 @@ void fill_shapes(Ctx& c) {
   c.fused_vt = c.fused_rope && ((D.H + D.Hkv) * D.dh) % 256 == 0 && D.T % 8 == 0 && !(g_gemm_dbg & 64);
   if (c.fused_vt) c.shape[K_QKV].ldc2 = attention_tp(D.T);
   if (c.fused_norm) c.shape[K_READ].ldc2 = c.shape[K_O].ldc2 = D.d;
+  // feature map + denominator of the read (Eq. 6) as the epilogue of the W_Q projection: q never goes to memory
+  c.fused_dpfp = D.bf16 && !debug_generic() && D.dm <= 128 && !(g_gemm_dbg & 16);
+  if (c.fused_dpfp) {
+    GemmShape& q = c.shape[K_MQ];
+    q.epi = EPI_DPFP_READ; q.ldc = D.Phi; q.ldr = D.nu; q.fparam = D.assoc_eps;
+  }
   c.ssq_parts = (D.d + 127) / 128;   // the GEMM epilogue writes one partial sum of squares per 128 columns
 }
 
-// Build the per-layer pointer tables on the host and copy them into the workspace.
+// Small host tables (pointer tables of the grouped GEMMs and the like) reach the device as KERNEL ARGUMENTS, 3.5 KB per
+// launch: the runtime copies the arguments when the launch is enqueued, so the host buffer may die right after the call,
+// nothing waits for the stream, and the call can be recorded into a HIP graph (a host-to-device copy from pageable
+// memory would need a synchronisation before the buffer is freed).
+struct ArgChunk { uint32_t w[896]; };
+__global__ __launch_bounds__(256) void arg_upload_kernel(ArgChunk c, uint32_t* __restrict__ dst, int n_words) {
+  for (int i = threadIdx.x; i < n_words; i += 256) dst[i] = c.w[i];
+}
+
+armt_status upload_bytes(hipStream_t st, void* dst, const void* src, size_t bytes) {
+  static_assert(sizeof(ArgChunk) + 16 <= 4096, "kernel arguments are limited to 4 KB");
+  const size_t words = (bytes + 3) / 4;          // destinations are carved in multiples of 256 bytes
+  ArgChunk c;
+  for (size_t w0 = 0; w0 < words; w0 += 896) {
+    const size_t n = std::min<size_t>(896, words - w0);
+    const size_t nb = std::min(bytes - w0 * 4, n * 4);
+    memset(&c, 0, sizeof(c));
+    memcpy(c.w, (const char*)src + w0 * 4, nb);
+    arg_upload_kernel<<<1, 256, 0, st>>>(c, (uint32_t*)dst + w0, (int)n);
+  }
+  HIP_TRY(hipGetLastError());
+  return ARMT_OK;
+}
+
+// Build the per-layer pointer tables on the host and send them into the workspace.
 armt_status upload_tables(Ctx& c, const armt_layer_weights* W, float* A, float* z) {
   const Dims& D = c.D;
   const size_t L = D.L, T = D.T;
@@ -199,6 +233,10 @@ armt_status upload_tables(Ctx& c, const armt_layer_weights* W, float* A, float* 
     GemmGroup* g;
     g = &tab[K_MQ * L + l];
     g->A = Xop + l * slotXop; g->B0 = w.wm_q; g->C = c.ws + c.o.Qm + l * T * D.dm * 4;
+    if (c.fused_dpfp) {
+      g->C = c.ws + c.o.Fphi + l * T * D.Phi * D.esz; g->C2 = c.ws + c.o.RDen + l * T * 4;
+      g->R = z + state * (size_t)D.Phi;
+    }
     g = &tab[K_READ * L + l];
     g->A = c.ws + c.o.Fphi + l * T * D.Phi * D.esz;
     g->B0 = D.bf16 ? (const void*)A16l : (const void*)Al;
@@ -233,10 +271,8 @@ armt_status upload_tables(Ctx& c, const armt_layer_weights* W, float* A, float* 
     a.rms1 = w.rms1; a.rms2 = w.rms2; a.wm_b = w.wm_b;
     a.A = Al; a.z = z + state * (size_t)D.Phi; a.A16 = A16l;
   }
-  // hipMemcpyAsync from pageable host memory returns once the source has been consumed.
-  HIP_TRY(hipMemcpyAsync(c.ws + c.o.Tables, tab.data(), tab.size() * sizeof(GemmGroup), hipMemcpyHostToDevice, c.st));
-  HIP_TRY(hipMemcpyAsync(c.ws + c.o.Aux, aux.data(), aux.size() * sizeof(LayerAux), hipMemcpyHostToDevice, c.st));
-  HIP_TRY(hipStreamSynchronize(c.st));
+  ARMT_TRY(upload_bytes(c.st, c.ws + c.o.Tables, tab.data(), tab.size() * sizeof(GemmGroup)));
+  ARMT_TRY(upload_bytes(c.st, c.ws + c.o.Aux, aux.data(), aux.size() * sizeof(LayerAux)));
   c.tables = c.at<GemmGroup>(c.o.Tables);
   c.aux = c.at<LayerAux>(c.o.Aux);
   return ARMT_OK;
@@ -250,21 +286,28 @@ struct Profile {
   int64_t groups = 0;            // groups (cells) covered by the recorded launches
 } g_prof;
 
+// Bracket the launches between prof_start and prof_stop with a pair of events if their kind is the one being timed.
+inline bool prof_start(int tag, hipStream_t st) {
+  if (g_prof.kind < 0 || g_prof.kind != tag || g_prof.used + 2 > g_prof.ev.size()) return false;
+  return hipEventRecord(g_prof.ev[g_prof.used], st) == hipSuccess;
+}
+inline void prof_stop(bool timed, hipStream_t st, int g) {
+  if (!timed) return;
+  (void)hipEventRecord(g_prof.ev[g_prof.used + 1], st);
+  g_prof.used += 2;
+  g_prof.groups += g;
+}
+
 template <typename T>
 armt_status gemm(hipStream_t st, const GemmGroup* table, int first, int g, const GemmShape& s) {
   if (g <= 0) return ARMT_OK;
-  const bool timed = (g_prof.kind >= 0 && g_prof.kind == s.tag && g_prof.used + 2 <= g_prof.ev.size());
-  if (timed) HIP_TRY(hipEventRecord(g_prof.ev[g_prof.used], st));
+  const bool timed = prof_start(s.tag, st);
   if (std::is_same<T, bf16>::value && !debug_generic()) {
     HIP_TRY(launch_gemm_mfma(table, first, g, s, st, g_gemm_tile_config));
   } else {
     HIP_TRY(launch_gemm_generic<T>(table, first, g, s, st));
   }
-  if (timed) {
-    HIP_TRY(hipEventRecord(g_prof.ev[g_prof.used + 1], st));
-    g_prof.used += 2;
-    g_prof.groups += g;
-  }
+  prof_stop(timed, st, g);
   return ARMT_OK;
 }
 
@@ -277,8 +320,12 @@ armt_status step_assoc_read(hipStream_t st, const GemmGroup* t_mq, const GemmSha
                             float eps, float* Qm, T* Fphi, float* RDen) {
   if (g <= 0) return ARMT_OK;
   ARMT_TRY(gemm<T>(st, t_mq, first, g, s_mq));
-  dpfp_read_kernel<T><<<dim3(Trows, g), 128, (dm + 17) * 4, st>>>(Qm, aux, first, Trows, dm, nu, eps, Fphi, RDen);
-  HIP_TRY(hipGetLastError());
+  if (s_mq.epi != EPI_DPFP_READ) {       // feature map and denominator not yet produced by the projection's epilogue
+    const bool timed = prof_start(PK_DPFP_READ, st);
+    dpfp_read_kernel<T><<<dim3(Trows, g), 128, (dm + 17) * 4, st>>>(Qm, aux, first, Trows, dm, nu, eps, Fphi, RDen);
+    prof_stop(timed, st, g);
+    HIP_TRY(hipGetLastError());
+  }
   return gemm<T>(st, t_read, first, g, s_read);
 }
 
@@ -293,7 +340,9 @@ armt_status step_attention(hipStream_t st, T* QKV, T* Att, bf16* Vt, const float
     HIP_TRY(hipGetLastError());
   }
   if (std::is_same<T, bf16>::value && !debug_generic()) {
+    const bool timed = prof_start(PK_ATTENTION, st);
     HIP_TRY(launch_attention_mfma((const bf16*)QKV, Vt, (bf16*)Att, first, g, Trows, H, Hkv, dh, vt_ready, st));
+    prof_stop(timed, st, g);
     return ARMT_OK;
   }
   attention_generic_kernel<T><<<dim3(Trows, H, g), 64, (dh + Trows) * 4, st>>>(QKV, Att, first, Trows, H, Hkv, dh,
@@ -310,9 +359,12 @@ armt_status step_assoc_update(hipStream_t st, const GemmGroup* t_mkv, const Gemm
   if (g <= 0) return ARMT_OK;
   const int Phi = 2 * nu * dm;
   ARMT_TRY(gemm<T>(st, t_mkv, first, g, s_mkv));
+  bool timed = prof_start(PK_UPD_PREP, st);
   memupd_prep_kernel<T><<<dim3(m, g), 128, (dm + 17) * 4, st>>>(KVm, Y0, y_stride, aux, first, empty_lo, empty_hi, m, d, dm, nu,
                                                                eps, Fm, Coef);
+  prof_stop(timed, st, g);
   HIP_TRY(hipGetLastError());
+  timed = prof_start(PK_DELTA_RULE, st);
   if (m == 16 && Phi % 64 == 0 && Phi <= 512) {
     const int rows_per_block = 32;
     const dim3 grid((d + rows_per_block - 1) / rows_per_block, g);
@@ -338,6 +390,7 @@ armt_status step_assoc_update(hipStream_t st, const GemmGroup* t_mkv, const Gemm
     delta_rule_kernel<8><<<dim3((d + rows_per_block - 1) / rows_per_block, g), 256, lds, st>>>(KVm, Fm, Coef, aux, first,
                                                                                              m, d, dm, Phi);
   }
+  prof_stop(timed, st, g);
   HIP_TRY(hipGetLastError());
   return ARMT_OK;
 }
@@ -408,7 +461,7 @@ armt_status save_tape(const Ctx& c, int lo, int hi, int t) {
 
 template <typename T>
 armt_status forward_typed(Ctx& c, const void* mem_emb, const void* x, int64_t N, bool carry_in, void* hidden_out,
-                          bool diagonal) {
+                          bool diagonal, int split_upto) {
   const Dims& D = c.D;
   const int L = D.Lr;
   const size_t seq = (size_t)N * D.S * D.d;      // elements of one sequence of x / hidden_out
@@ -459,7 +512,15 @@ armt_status forward_typed(Ctx& c, const void* mem_emb, const void* x, int64_t N,
       // only the cell of segment 0 (layer t, while t < L) can meet an empty memory
       const bool top_empty = (!carry_in && t < L);
       ARMT_TRY(save_tape(c, lo, hi, (int)t));
-      ARMT_TRY(run_group<T>(c, lo, hi, top_empty ? hi - 1 : hi, top_empty ? hi : -1));
+      if (hi - lo + 1 <= split_upto) {
+        // the cells of a small group one at a time, highest layer first: cell l writes slot l + 1, the input of cell l + 1
+        for (int l = hi; l >= lo; --l) {
+          const bool e = top_empty && l == hi;
+          ARMT_TRY(run_group<T>(c, l, l, e ? l - 1 : l, e ? l : -1));
+        }
+      } else {
+        ARMT_TRY(run_group<T>(c, lo, hi, top_empty ? hi - 1 : hi, top_empty ? hi : -1));
+      }
       if (hi == L - 1) ARMT_TRY(emit(t - (L - 1)));
     }
   }
@@ -469,7 +530,7 @@ armt_status forward_typed(Ctx& c, const void* mem_emb, const void* x, int64_t N,
 armt_status forward_impl(const armt_config* cfg, const armt_layer_weights* layers, const void* mem_emb, const void* x,
                          int32_t batch, int64_t n_tokens, const float* A_in, const float* z_in, void* hidden_out, float* A_out,
                          float* z_out, void* workspace, size_t workspace_bytes, void* hip_stream, bool diagonal,
-                         float* tape = nullptr, size_t rec_floats = 0) {
+                         float* tape = nullptr, size_t rec_floats = 0, int split_upto = 0) {
   Ctx c;
   c.tape = tape;
   c.rec_floats = rec_floats;
@@ -510,8 +571,8 @@ armt_status forward_impl(const armt_config* cfg, const armt_layer_weights* layer
     HIP_TRY(hipGetLastError());
   }
   ARMT_TRY(upload_tables(c, layers, A_out, z_out));
-  if (D.bf16) return forward_typed<bf16>(c, mem_emb, x, N, A_in != nullptr, hidden_out, diagonal);
-  return forward_typed<float>(c, mem_emb, x, N, A_in != nullptr, hidden_out, diagonal);
+  if (D.bf16) return forward_typed<bf16>(c, mem_emb, x, N, A_in != nullptr, hidden_out, diagonal, split_upto);
+  return forward_typed<float>(c, mem_emb, x, N, A_in != nullptr, hidden_out, diagonal, split_upto);
 }
 
 }  // namespace
@@ -531,11 +592,8 @@ armt_status step_prologue(const armt_config* cfg, int32_t g, void* workspace, si
 }
 
 armt_status upload(Ctx& c, const std::vector<GemmGroup>& tab, const std::vector<LayerAux>& aux) {
-  if (!tab.empty())
-    HIP_TRY(hipMemcpyAsync(c.ws + c.o.Tables, tab.data(), tab.size() * sizeof(GemmGroup), hipMemcpyHostToDevice, c.st));
-  if (!aux.empty())
-    HIP_TRY(hipMemcpyAsync(c.ws + c.o.Aux, aux.data(), aux.size() * sizeof(LayerAux), hipMemcpyHostToDevice, c.st));
-  HIP_TRY(hipStreamSynchronize(c.st));
+  if (!tab.empty()) ARMT_TRY(upload_bytes(c.st, c.ws + c.o.Tables, tab.data(), tab.size() * sizeof(GemmGroup)));
+  if (!aux.empty()) ARMT_TRY(upload_bytes(c.st, c.ws + c.o.Aux, aux.data(), aux.size() * sizeof(LayerAux)));
   c.tables = c.at<GemmGroup>(c.o.Tables);
   c.aux = c.at<LayerAux>(c.o.Aux);
   return ARMT_OK;
@@ -579,8 +637,7 @@ armt_status lm_head_typed(const Dims& D, const HeadLayout& h, const void* hidden
     const size_t r0 = (size_t)i * kHeadRows;
     tab[i].A = xg + r0 * D.d; tab[i].B0 = w_lm; tab[i].C = logits + r0 * (size_t)vocab; tab[i].rowscale = rstd + r0;
   }
-  HIP_TRY(hipMemcpyAsync(ws + h.table, tab.data(), tab.size() * sizeof(GemmGroup), hipMemcpyHostToDevice, st));
-  HIP_TRY(hipStreamSynchronize(st));
+  ARMT_TRY(upload_bytes(st, ws + h.table, tab.data(), tab.size() * sizeof(GemmGroup)));
   GemmShape s;
   s.M = (int)kHeadRows; s.N = vocab; s.K = D.d; s.lda = D.d; s.ldc = vocab; s.ldc2 = 0; s.ldr = 0; s.n0 = vocab; s.n1 = 0;
   s.epi = EPI_STORE_F32; s.tag = -1; s.dbg = g_gemm_dbg; s.ldb = s.K;
@@ -617,6 +674,35 @@ armt_status armt_forward_diagonal(const armt_config* cfg, const armt_layer_weigh
                                   size_t workspace_bytes, void* hip_stream) {
   return forward_impl(cfg, layers, mem_emb, x, 1, n_tokens, A_in, z_in, hidden_out, A_out, z_out, workspace,
                       workspace_bytes, hip_stream, true);
+}
+
+armt_status armt_forward_diagonal_split(const armt_config* cfg, const armt_layer_weights* layers, const void* mem_emb,
+                                        const void* x, int64_t n_tokens, const float* A_in, const float* z_in,
+                                        void* hidden_out, float* A_out, float* z_out, void* workspace,
+                                        size_t workspace_bytes, void* hip_stream, int32_t split_upto) {
+  if (split_upto < 0) return ARMT_ERR_SHAPE;
+  return forward_impl(cfg, layers, mem_emb, x, 1, n_tokens, A_in, z_in, hidden_out, A_out, z_out, workspace,
+                      workspace_bytes, hip_stream, true, nullptr, 0, split_upto);
+}
+
+int32_t armt_auto_order(const armt_config* cfg, int64_t n_tokens) {
+  Dims D;
+  if (check_config(cfg, &D) != ARMT_OK || n_tokens <= 0 || n_tokens % D.S != 0) return -1;
+  // One segment: every anti-diagonal holds one cell and the two orders launch the same kernels; take the plain one.
+  // From two segments on a step of the diagonal order does the work of up to min(L, N) sequential cell executions with
+  // the same kernels on larger launches: it was faster at every length and segment size measured, the paper's
+  // 4096-token column included.
+  return (n_tokens / D.S >= 2 && D.Lr >= 2) ? 1 : 0;
+}
+
+armt_status armt_forward_auto(const armt_config* cfg, const armt_layer_weights* layers, const void* mem_emb,
+                              const void* x, int64_t n_tokens, const float* A_in, const float* z_in,
+                              void* hidden_out, float* A_out, float* z_out, void* workspace,
+                              size_t workspace_bytes, void* hip_stream, int32_t* order_used) {
+  const int32_t order = armt_auto_order(cfg, n_tokens);
+  if (order_used && order >= 0) *order_used = order;
+  return forward_impl(cfg, layers, mem_emb, x, 1, n_tokens, A_in, z_in, hidden_out, A_out, z_out, workspace,
+                      workspace_bytes, hip_stream, order == 1);
 }
 
 size_t armt_workspace_bytes_batched(const armt_config* cfg, int32_t batch) {
@@ -662,8 +748,7 @@ armt_status armt_grouped_gemm(int32_t dtype, int32_t g, int32_t M, int32_t N, in
     tab[i].A = a[i]; tab[i].B0 = b[i]; tab[i].C = c[i];
   }
   hipStream_t st = (hipStream_t)hip_stream;
-  HIP_TRY(hipMemcpyAsync(workspace, tab.data(), tab.size() * sizeof(GemmGroup), hipMemcpyHostToDevice, st));
-  HIP_TRY(hipStreamSynchronize(st));
+  ARMT_TRY(upload_bytes(st, workspace, tab.data(), tab.size() * sizeof(GemmGroup)));
   GemmShape s;
   s.M = M; s.N = N; s.K = K; s.lda = K; s.ldc = N; s.ldc2 = 0; s.ldr = 0; s.n0 = N; s.n1 = 0; s.epi = EPI_STORE_ACT;
   s.tag = -1;
@@ -748,6 +833,10 @@ armt_status armt_assoc_read(const armt_config* cfg, int32_t g, float* x, const v
     q->A = D.bf16 ? (const void*)(c.at<bf16>(c.o.Xb) + i * T * D.d) : (const void*)(x + i * T * D.d);
     q->B0 = wm_q[i];
     q->C = c.ws + c.o.Qm + i * T * D.dm * 4;
+    if (c.fused_dpfp) {
+      q->C = c.ws + c.o.Fphi + i * T * D.Phi * D.esz; q->C2 = c.ws + c.o.RDen + i * T * 4;
+      q->R = z + (size_t)i * D.Phi;
+    }
     GemmGroup* r = &tab[K_READ * L + i];
     r->A = c.ws + c.o.Fphi + i * T * D.Phi * D.esz;
     r->B0 = D.bf16 ? (const void*)(c.at<bf16>(c.o.A16) + (size_t)i * D.d * D.Phi) : (const void*)(A + (size_t)i * D.d * D.Phi);
@@ -815,12 +904,12 @@ int32_t armt_set_gemm_tile_config(int32_t config) {
   const int32_t old = g_gemm_tile_config;
   g_gemm_dbg = config >= 100 ? config / 100 : 0;
   if (config >= 100) config %= 100;
-  g_gemm_tile_config = (config >= 0 && config < MF_NUM_CONFIGS) ? config : -1;
+  g_gemm_tile_config = (config == 1 || config == 2 || config == 5 || config == 6) ? config : -1;
   return old;
 }
 
 armt_status armt_profile_begin(int32_t gemm_kind, int32_t max_launches) {
-  if (gemm_kind < 0 || gemm_kind >= K_COUNT || max_launches < 1) return ARMT_ERR_SHAPE;
+  if (gemm_kind < 0 || gemm_kind >= PK_COUNT || max_launches < 1) return ARMT_ERR_SHAPE;
   armt_profile_end(nullptr, nullptr, nullptr);
   g_prof.ev.resize((size_t)max_launches * 2);
   for (size_t i = 0; i < g_prof.ev.size(); ++i) {

@@ -274,10 +274,9 @@ armt_status upload_train_tables(BCtx& c, const armt_layer_weights* W, const armt
     a.A16 = D.bf16 ? (bf16*)(ws + o.A16w + l * d * D.Phi * 2) : nullptr;
     ptrs[l] = gw.rms1; ptrs[L + l] = gw.rms2; ptrs[2 * L + l] = gw.wm_b;
   }
-  HIP_TRY(hipMemcpyAsync(ws + o.Tables, tab.data(), tab.size() * sizeof(GemmGroup), hipMemcpyHostToDevice, c.st));
-  HIP_TRY(hipMemcpyAsync(ws + o.Aux, aux.data(), aux.size() * sizeof(LayerAux), hipMemcpyHostToDevice, c.st));
-  HIP_TRY(hipMemcpyAsync(ws + o.Ptrs, ptrs.data(), ptrs.size() * sizeof(float*), hipMemcpyHostToDevice, c.st));
-  HIP_TRY(hipStreamSynchronize(c.st));
+  ARMT_TRY(upload_bytes(c.st, ws + o.Tables, tab.data(), tab.size() * sizeof(GemmGroup)));
+  ARMT_TRY(upload_bytes(c.st, ws + o.Aux, aux.data(), aux.size() * sizeof(LayerAux)));
+  ARMT_TRY(upload_bytes(c.st, ws + o.Ptrs, ptrs.data(), ptrs.size() * sizeof(float*)));
   c.tables = c.at<GemmGroup>(o.Tables);
   c.aux = c.at<LayerAux>(o.Aux);
   c.dg1 = c.at<float*>(o.Ptrs); c.dg2 = c.dg1 + L; c.dwb = c.dg1 + 2 * L;
@@ -814,8 +813,7 @@ armt_status lm_head_backward_typed(const Dims& D, const HeadBwdLayout& h, const 
   memset(tab.data(), 0, tab.size() * sizeof(GemmGroup));
   tab[0].A = DLb; tab[0].B0 = WT; tab[0].C = U;                               // u = dL W
   tab[1].A = DLT; tab[1].B0 = NT; tab[1].C = d_w; tab[1].R = d_w;             // dW += dL^T n
-  HIP_TRY(hipMemcpyAsync(ws + h.table, tab.data(), tab.size() * sizeof(GemmGroup), hipMemcpyHostToDevice, st));
-  HIP_TRY(hipStreamSynchronize(st));
+  ARMT_TRY(upload_bytes(st, ws + h.table, tab.data(), tab.size() * sizeof(GemmGroup)));
   const GemmGroup* table = (const GemmGroup*)(ws + h.table);
   GemmShape su, sw;
   su.M = 0; su.N = D.d; su.K = h.Vp; su.lda = h.Vp; su.ldb = h.Vp; su.ldc = D.d; su.ldc2 = 0; su.ldr = 0; su.n0 = D.d; su.n1 = 0;

@@ -72,6 +72,10 @@ enum GemmEpilogue : int {
   EPI_STORE_F32 = 1,   // C (fp32) = acc * rowscale[row]
   EPI_RESID_F32 = 2,   // C (fp32) = R + acc * rowscale[row]; C2 (activation type) = same, if given
   EPI_SWIGLU = 3,      // C (activation type) = silu(rs * acc over B0) * (rs * acc over B1), rs = rowscale[row]; N = rows of B0
+  EPI_DPFP_READ = 5,   // read side of the associative memory (Eq. 6) fused behind the W_Q projection: the N = n0 = d_mem result
+                       // columns q of a row never leave the workgroup; written are phi(q) (DPFP-nu, nu = ldr; activation
+                       // type, C [M][ldc], ldc >= 2 nu d_mem) and 1 / (z . phi(q) + fparam) (fp32, C2 [M]); z = R [2 nu d_mem].
+                       // All N columns must lie in one output tile.
   EPI_QKV_ROPE = 4     // EPI_STORE_ACT of the fused q | k | v projection with the rotary embedding applied to the q and k
                        // columns [0, n0 + n1): heads of ldr columns, rotate-half pairing, position = row; R = cos/sin table
                        // [M][ldr / 2][2].  Heads must not straddle output tiles (tile width a multiple of ldr).
@@ -88,6 +92,7 @@ struct GemmShape {
   int dbg;              // A/B switches for benchmarks: bit 5 (32) multiplies the 16 memory rows as a tile of their own
                         // instead of a strip of the last M-tile (same results up to rounding order)
   int ldb;              // row stride of the weight blocks in elements (>= K); the weights of the model are dense: ldb = K
+  float fparam = 0.f;   // EPI_DPFP_READ: assoc_eps
   int a_rows = 0;       // rows of A that may be READ in every group (0: M).  Operand buffers that are padded to whole
                         // tiles let a ragged M take the copies without per-lane clamping; rows >= M are never stored
 };

@@ -17,10 +17,11 @@
 // group-major tile sequence: with 16 groups every XCD streams the weights of 2 layers through its
 // own L2, and the M-tiles sharing a weight panel run back to back.
 // Template parameters of the kernel: BM x BN tile, WGM x WGN waves, REG (see above), EPI (GemmEpilogue),
-// TAIL (see below), NS (LDS stages), BK (k-tile: 64, or 32 = 64-byte tile rows, four chunks, REG only: half the bytes
-// per stage, so that twice the stages fit and more copies are in flight at a barrier).  The launcher picks the configuration from the shape and the
-// number of tiles of the launch (mfma_pick_config).
+// TAIL (see below), NS (LDS stages).  The launcher picks the configuration from the shape and the number of tiles of
+// the launch (mfma_pick_config).
 #pragma once
+
+#include <atomic>
 
 #include "common.h"
 #include "gemm_generic.h"
@@ -29,14 +30,10 @@ namespace armt {
 
 constexpr int MF_BK = 64;                 // k-tile (bf16 elements): 128 bytes per tile row
 constexpr int MF_ROW_BYTES = MF_BK * 2;
-constexpr int MF_NUM_CONFIGS = 9;         // tile configurations of launch_gemm_mfma_epi
+constexpr int MF_NUM_CONFIGS = 7;         // tile configuration numbers of launch_gemm_mfma_epi lie below this
 
 // swizzle of the 16-byte chunk index inside a 128-byte tile row; depends on row bits 0..3 only
 __device__ __forceinline__ int mf_swz(int row) { return ((row >> 1) & 7) ^ ((row & 1) << 2); }
-// ... and inside a 64-byte tile row (four chunks): rows r, r + 4, r + 8, r + 12 share their LDS banks, so they take
-// different chunks; depends on row bits 2..3 only
-template <int BK>
-__device__ __forceinline__ int mf_swz_bk(int row) { return BK == 64 ? mf_swz(row) : ((row >> 2) & 3); }
 
 template <int N>
 __device__ __forceinline__ void mf_wait_vmcnt() {      // s_waitcnt vmcnt(N) only (N <= 63)
@@ -46,11 +43,11 @@ __device__ __forceinline__ void mf_wait_vmcnt() {      // s_waitcnt vmcnt(N) onl
 // TAIL: the last M-tile of every group also owns the 16 rows that follow it (M = tiles_m * BM + 16).  With
 // T = seg_len + 16 memory rows and seg_len a multiple of BM this removes the nearly empty fifth tile a
 // 1040-row cell would otherwise need: the 16 memory rows ride along as one extra strip of 16x16x32 MFMAs.
-template <int BM, int BN, int WGM, int WGN, bool REG, int EPI, bool TAIL, int NS, int BK = MF_BK, bool EARLY = false>
+template <int BM, int BN, int WGM, int WGN, bool REG, int EPI, bool TAIL, int NS>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGroup* __restrict__ table, int first,
                                                                   GemmShape s, int tiles_m, int tiles_n,
                                                                   int total_tiles) {
-  constexpr int NW = WGM * WGN;
+  constexpr int NW = WGM * WGN, BK = MF_BK;
   constexpr int WROWS = BM / WGM, WCOLS = BN / WGN;       // wave tile
   constexpr int TM = WROWS / 16, TN = WCOLS / 16;         // 16x16 MFMA tiles per wave
   constexpr int ROWB = BK * 2;                            // bytes of a tile row
@@ -59,7 +56,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   constexpr int TAIL_SLABS = 16 / RPS;                    // slabs of the 16 tail rows, copied by the first waves
   constexpr int A_ROWS = TAIL ? BM + 16 : BM;
   constexpr int A_BYTES = A_ROWS * ROWB, B_BYTES = BN * ROWB;
-  static_assert(BK == 64 || (BK == 32 && REG), "64-byte tile rows are written for the scalar-addressed copies only");
   constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;   // output columns per tile
   static_assert(BM % (WGM * 32) == 0 && BN % (WGN * 32) == 0, "wave tile must be a multiple of 32x32");
   static_assert(EPI != EPI_SWIGLU || WCOLS % 64 == 0, "SwiGLU: a wave owns whole gate/up pairs of 32-row weight blocks");
@@ -140,11 +136,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
 #pragma unroll
     for (int j = 0; j < (KEEP_PTRS ? B_DMA : 0); ++j) bp[j] = b_src(j);
   } else {
-    // lane i fills row i / (ROWB / 16), physical chunk i % (ROWB / 16) of its slab
-    const int rR = BK == 64 ? dR : (lane >> 2), rc = BK == 64 ? dpc : (lane & 3);
-    const int chunk = (rc ^ mf_swz_bk<BK>(BK == 64 ? (wave & 1) * 8 + rR : rR)) << 4;   // BK = 32: the same for every slab
-    a_off0 = (unsigned)rR * (unsigned)s.lda * 2u + chunk;
-    b_off0 = (unsigned)rR * (unsigned)s.ldb * 2u + chunk;
+    // lane i fills row i / 8, physical chunk i % 8 of its slab
+    const int chunk = (dpc ^ mf_swz((wave & 1) * 8 + dR)) << 4;
+    a_off0 = (unsigned)dR * (unsigned)s.lda * 2u + chunk;
+    b_off0 = (unsigned)dR * (unsigned)s.ldb * 2u + chunk;
   }
   // scalar source of the first row of slab `slab` (REG only)
   auto a_base = [&](int slab) -> const char* { return (const char*)g.A + (size_t)(m0 + RPS * slab) * s.lda * 2; };
@@ -191,7 +186,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   // register-only loops): lane reads tile row (lane % 16) of each 16-row block, 16-byte chunk 4 * ks2 + lane / 16
   // of the 128-byte row; a 16x16 result tile has lane = column lane % 16 and registers = rows 4 * (lane / 16) + r.
   constexpr int KS2 = BK / 32;                 // MFMA k-steps per k-tile
-  const int t_sw = mf_swz_bk<BK>(lane & 15), t_q = lane >> 4;
+  const int t_sw = mf_swz(lane & 15), t_q = lane >> 4;
   int koff[KS2];
 #pragma unroll
   for (int ks2 = 0; ks2 < KS2; ++ks2) koff[ks2] = ((4 * ks2 + t_q) ^ t_sw) << 4;
@@ -211,73 +206,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
     for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
   f32x4 tacc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 
-  if constexpr (EARLY) {
-    // main loop with two tile buffers and two barriers per k-tile.  A buffer is free as soon as every wave holds the
-    // fragments of the tile's last k-step in registers, which is before the MFMAs of that k-step run: the first
-    // barrier sits there and the copy of k-tile kt + 2 goes out behind it, half a k-tile of arithmetic earlier than
-    // with one barrier at the end.  The second barrier, after those MFMAs, makes k-tile kt + 1 visible.
-    static_assert(!EARLY || (NS == 2 && KS2 == 2), "written for two buffers and two k-steps per tile");
-    constexpr int CNT = A_DMA + B_DMA;
-    const bool extra = TAIL && tail_blk && wave < TAIL_SLABS;
-    const int nk = s.K / BK;
-    issue_tile(0, 0);
-    if (nk > 1) {
-      issue_tile(1, 1);
-      if (extra) mf_wait_vmcnt<CNT + 1>(); else mf_wait_vmcnt<CNT>();
-    } else {
-      mf_wait_vmcnt<0>();
-    }
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-      const int cur = kt & 1;
-      const unsigned char* As = smem + cur * A_BYTES;
-      const unsigned char* Bs = smem + NS * A_BYTES + cur * B_BYTES;
-      {
-        bf16x8 af[TM], bfr[TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8*)(As + a_frag + i * 16 * ROWB + koff[0]);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8*)(Bs + b_frag + j * 16 * ROWB + koff[0]);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-      }
-      if (TAIL && tail) {       // the strip of memory rows, both k-steps, while the buffer is still held
-#pragma unroll
-        for (int ks2 = 0; ks2 < KS2; ++ks2) {
-          const int ko = koff[ks2];
-          const bf16x8 ta = *(const bf16x8*)(As + t_a + ko);
-#pragma unroll
-          for (int t = 0; t < 2; ++t) {
-            const bf16x8 tb = *(const bf16x8*)(Bs + t_b + t * 32 * ROWB + ko);
-            tacc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ta, tb, tacc[t], 0, 0, 0);
-          }
-        }
-      }
-      bf16x8 af[TM], bfr[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8*)(As + a_frag + i * 16 * ROWB + koff[1]);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) bfr[j] = *(const bf16x8*)(Bs + b_frag + j * 16 * ROWB + koff[1]);
-      __syncthreads();          // (waits for the fragment reads) nobody reads buffer cur any more
-      if (kt + 2 < nk) issue_tile(kt + 2, cur);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-      // k-tile kt + 1 (copied into the other buffer half a k-tile ago or more) must have landed; the copy just issued stays in flight
-      if (kt + 2 < nk) {
-        if (extra) mf_wait_vmcnt<CNT + 1>(); else mf_wait_vmcnt<CNT>();
-      } else {
-        mf_wait_vmcnt<0>();
-      }
-      __syncthreads();
-    }
-  } else {
+  {
     // main loop: NS tile buffers; the copies of k-tiles kt+1 .. kt+NS-1 are in flight while k-tile kt is
     // multiplied (copies complete in issue order, so waiting for tile kt+1 leaves the younger ones outstanding);
     // one barrier per k-tile
@@ -352,6 +281,35 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   auto row_scale = [&](int m) { return rs_lds[m - m0]; };
   // walk nrows staged rows; staged row sr is output row m_of(sr)
   auto drain = [&](int nrows, auto m_of) {
+    if constexpr (EPI == EPI_DPFP_READ) {
+      // One wave per staged row: the row's d_mem values q sit in the staging tile; lane L computes the features
+      // L, L + 64, ... of phi(q) = r[i] r[(i - j) mod 2 d_mem], r = [relu(q), relu(-q)], j = 1..nu (the untrained
+      // feature map of Section 2.1), stores them in the activation type and adds up its share of z . phi(q).
+      // The summation order (lane-strided partial sums, then the wave reduction) does not depend on the tile
+      // configuration, so every configuration produces the same bits.
+      const int dm = s.n0, n2 = 2 * dm, Phi = s.ldr * n2;
+      const float* __restrict__ z = g.R;
+      for (int sr = wave; sr < nrows; sr += NW) {
+        const int m = m_of(sr);
+        if (m >= s.M) continue;                          // wave-uniform
+        const float* q = stg + sr * SLD;
+        float den = 0.f;
+        for (int idx = lane; idx < Phi; idx += 64) {
+          const int j = idx / n2 + 1, i = idx - (j - 1) * n2;
+          int i2 = i - j;
+          if (i2 < 0) i2 += n2;
+          const float a = i < dm ? fmaxf(q[i], 0.f) : fmaxf(-q[i - dm], 0.f);
+          const float b = i2 < dm ? fmaxf(q[i2], 0.f) : fmaxf(-q[i2 - dm], 0.f);
+          const float f = a * b;
+          den = fmaf(f, z[idx], den);
+          ((bf16*)g.C)[(size_t)m * s.ldc + idx] = (bf16)f;
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) den += __shfl_xor(den, off, kWave);
+        if (lane == 0) ((float*)g.C2)[m] = 1.0f / (den + s.fparam);
+      }
+      return;
+    }
     for (int q = tid; q < nrows * C4; q += NT) {
       const int sr = q / C4, c4 = q - sr * C4;
       const int m = m_of(sr), n = n0 + c4 * 4;
@@ -495,19 +453,25 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool REG, int EPI, bool TAIL, int NS, int BK = MF_BK, bool EARLY = false>
+template <int BM, int BN, int WGM, int WGN, bool REG, int EPI, bool TAIL, int NS>
 inline hipError_t launch_mfma_tail(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st) {
   constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
-  constexpr int LDS = NS * ((TAIL ? BM + 16 : BM) + BN) * BK * 2 + (BM + 16) * 4;
+  constexpr int LDS = NS * ((TAIL ? BM + 16 : BM) + BN) * MF_BK * 2 + (BM + 16) * 4;
   const int tiles_m = TAIL ? s.M / BM : (s.M + BM - 1) / BM, tiles_n = (s.N + BN_OUT - 1) / BN_OUT;
   const int total = g * tiles_m * tiles_n;
   const int grid = ((total + 7) / 8) * 8;
-  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, REG, EPI, TAIL, NS, BK, EARLY>;
-  static bool attr_set = false;            // raising the dynamic-LDS limit is a per-function, idempotent setting
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, REG, EPI, TAIL, NS>;
+  // raising the dynamic-LDS limit is a per-function, per-device, idempotent setting: done once per device (a second
+  // thread that gets here first merely repeats it)
+  static std::atomic<uint64_t> attr_set{0};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (!(attr_set.load(std::memory_order_acquire) & bit)) {
+    e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_set.fetch_or(bit, std::memory_order_release);
   }
   kern<<<grid, WGM * WGN * 64, LDS, st>>>(table, first, s, tiles_m, tiles_n, total);
   return hipGetLastError();
@@ -524,13 +488,13 @@ inline bool mfma_regular_shape(const GemmShape& s) {
   return m_ok && s.N % BN_OUT == 0 && w_ok && s.K % MF_BK == 0;
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, bool REG = false, int NS = 2, int BK = MF_BK, bool EARLY = false>
+template <int BM, int BN, int WGM, int WGN, int EPI, bool REG = false, int NS = 2>
 inline hipError_t launch_mfma_cfg(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st) {
   if constexpr (BN <= WGM * WGN * 32) {
     if (s.M > BM && s.M % BM == 16 && !(s.dbg & 32))
-      return launch_mfma_tail<BM, BN, WGM, WGN, REG, EPI, true, NS, BK, EARLY>(table, first, g, s, st);
+      return launch_mfma_tail<BM, BN, WGM, WGN, REG, EPI, true, NS>(table, first, g, s, st);
   }
-  return launch_mfma_tail<BM, BN, WGM, WGN, REG, EPI, false, NS, BK, EARLY>(table, first, g, s, st);
+  return launch_mfma_tail<BM, BN, WGM, WGN, REG, EPI, false, NS>(table, first, g, s, st);
 }
 
 // Big tiles move the fewest bytes per flop, but a launch needs about one tile per CU to use the chip: a single
@@ -553,20 +517,11 @@ inline hipError_t launch_gemm_mfma_epi(const GemmGroup* table, int first, int g,
                                        int force_cfg) {
   const int cfg = mfma_pick_config(s, g, force_cfg);
   switch (cfg) {
-    case 0: return launch_mfma_cfg<256, 256, 2, 4, EPI>(table, first, g, s, st);
     case 1: return launch_mfma_cfg<128, 128, 2, 2, EPI>(table, first, g, s, st);
-    case 3: return launch_mfma_cfg<128, 256, 2, 4, EPI>(table, first, g, s, st);
-    case 4: return launch_mfma_cfg<256, 256, 4, 4, EPI>(table, first, g, s, st);
-    case 5:   // as 4, copies addressed by scalar base + lane offset
+    case 5:   // 256 x 256, 16 waves, copies addressed by scalar base + lane offset where the shape allows
       if (mfma_regular_shape<256, 256, EPI>(s)) return launch_mfma_cfg<256, 256, 4, 4, EPI, true>(table, first, g, s, st);
       return launch_mfma_cfg<256, 256, 4, 4, EPI>(table, first, g, s, st);
-    case 7:   // as 5 with k-tiles of 32 in four stages (three tiles in flight at a barrier instead of one)
-      if (mfma_regular_shape<256, 256, EPI>(s)) return launch_mfma_cfg<256, 256, 4, 4, EPI, true, 4, 32>(table, first, g, s, st);
-      return launch_mfma_cfg<256, 256, 4, 4, EPI>(table, first, g, s, st);
-    case 8:   // as 5 with the buffer released (and refilled) before the MFMAs of a tile's last k-step
-      if (mfma_regular_shape<256, 256, EPI>(s)) return launch_mfma_cfg<256, 256, 4, 4, EPI, true, 2, 64, true>(table, first, g, s, st);
-      return launch_mfma_cfg<256, 256, 4, 4, EPI>(table, first, g, s, st);
-    case 6:   // as 1, copies addressed by scalar base + lane offset
+    case 6:   // as 1, copies addressed by scalar base + lane offset where the shape allows
       if (mfma_regular_shape<128, 128, EPI>(s)) return launch_mfma_cfg<128, 128, 2, 2, EPI, true>(table, first, g, s, st);
       return launch_mfma_cfg<128, 128, 2, 2, EPI>(table, first, g, s, st);
     default: break;
@@ -582,6 +537,10 @@ inline hipError_t launch_gemm_mfma(const GemmGroup* table, int first, int g, con
     case EPI_STORE_F32: return launch_gemm_mfma_epi<EPI_STORE_F32>(table, first, g, s, st, force_cfg);
     case EPI_RESID_F32: return launch_gemm_mfma_epi<EPI_RESID_F32>(table, first, g, s, st, force_cfg);
     case EPI_SWIGLU: return launch_gemm_mfma_epi<EPI_SWIGLU>(table, first, g, s, st, force_cfg);
+    case EPI_DPFP_READ:
+      // all d_mem columns of a row in one output tile (the narrowest tile is 128 wide)
+      if (s.N != s.n0 || s.N > 128 || s.ldr < 1 || s.ldc < 2 * s.ldr * s.n0) return hipErrorInvalidValue;
+      return launch_gemm_mfma_epi<EPI_DPFP_READ>(table, first, g, s, st, force_cfg);
     case EPI_QKV_ROPE:
       // the rotation reads its partner column from the staged tile: heads must not straddle tiles (128 or 256 wide)
       if (s.ldr <= 0 || 128 % s.ldr != 0 || (s.N & 3) || (s.ldc & 3)) return hipErrorInvalidValue;

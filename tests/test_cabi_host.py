@@ -64,6 +64,28 @@ def test_diagonal_schedule_matches_lemma_fixture(lib):
     assert lib.armt_diagonal_group(16, 128, 20, None, None) == 16
 
 
+def test_auto_order_rule(lib):
+    """One segment or one layer: sequential (the two orders coincide); otherwise diagonal; invalid input: -1."""
+    tiny = S.get_shape("tiny")
+    cfg = _cfg(tiny)
+    assert lib.armt_auto_order(C.byref(cfg), tiny.seg_len) == 0
+    assert lib.armt_auto_order(C.byref(cfg), 2 * tiny.seg_len) == 1
+    assert lib.armt_auto_order(C.byref(cfg), 128 * tiny.seg_len) == 1
+    assert lib.armt_auto_order(C.byref(cfg), tiny.seg_len + 1) == -1
+    assert lib.armt_auto_order(C.byref(cfg), 0) == -1
+    one_layer = _cfg(tiny.replace(n_layers=1))
+    assert lib.armt_auto_order(C.byref(one_layer), 5 * tiny.seg_len) == 0
+    assert lib.armt_auto_order(None, tiny.seg_len) == -1
+    used = C.c_int32(-5)
+    # argument errors of the call itself come back as status codes before anything is launched
+    rc = lib.armt_forward_auto(C.byref(cfg), None, None, None, tiny.seg_len, None, None, None, None, None, None, 0, None,
+                               C.byref(used))
+    assert rc == 1
+    rc = lib.armt_forward_diagonal_split(C.byref(cfg), None, None, None, tiny.seg_len, None, None, None, None, None, None,
+                                         0, None, -1)
+    assert rc == 2
+
+
 def test_earliest_group_property(lib):
     """Each cell's group index s + l is one more than the latest of its two predecessors (s, l-1),
     (s-1, l): no cell could run earlier (Lemma 3.1)."""
