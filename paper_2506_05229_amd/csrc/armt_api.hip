@@ -624,20 +624,20 @@ HeadLayout head_layout(const Dims& D, int64_t n_rows) {
 
 template <typename T>
 armt_status lm_head_typed(const Dims& D, const HeadLayout& h, const void* hidden, int64_t n_rows, const void* gain,
-                          const void* w_lm, int32_t vocab, float* logits, char* ws, hipStream_t st) {
+                          const void* w_lm, int32_t vocab, float* logits, char* ws, hipStream_t st,
+                          GemmGroup* tab /* host, h.groups + 1 entries */) {
   T* xg = (T*)(ws + h.xg);
   float* rstd = (float*)(ws + h.rstd);
   final_norm_kernel<T><<<(unsigned)n_rows, 256, 0, st>>>((const T*)hidden, (const T*)gain, D.d, D.rms_eps, xg, rstd);
   HIP_TRY(hipGetLastError());
   // the rows go through the grouped GEMM in groups of kHeadRows that all point at the same weight: the
   // tile order then keeps the four M-tiles of a weight panel side by side, as for a cell
-  std::vector<GemmGroup> tab(h.groups + 1);
-  memset(tab.data(), 0, tab.size() * sizeof(GemmGroup));
+  memset(tab, 0, (size_t)(h.groups + 1) * sizeof(GemmGroup));
   for (int64_t i = 0; i <= h.groups; ++i) {
     const size_t r0 = (size_t)i * kHeadRows;
     tab[i].A = xg + r0 * D.d; tab[i].B0 = w_lm; tab[i].C = logits + r0 * (size_t)vocab; tab[i].rowscale = rstd + r0;
   }
-  ARMT_TRY(upload_bytes(st, ws + h.table, tab.data(), tab.size() * sizeof(GemmGroup)));
+  ARMT_TRY(upload_bytes(st, ws + h.table, tab, (size_t)(h.groups + 1) * sizeof(GemmGroup)));
   GemmShape s;
   s.M = (int)kHeadRows; s.N = vocab; s.K = D.d; s.lda = D.d; s.ldc = vocab; s.ldc2 = 0; s.ldr = 0; s.n0 = vocab; s.n1 = 0;
   s.epi = EPI_STORE_F32; s.tag = -1; s.dbg = g_gemm_dbg; s.ldb = s.K;
@@ -790,9 +790,10 @@ armt_status armt_lm_head(const armt_config* cfg, const void* hidden, int64_t n_r
   const HeadLayout h = head_layout(D, n_rows);
   if (!workspace || ((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < h.total) return ARMT_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)hip_stream;
+  std::vector<GemmGroup> tab((size_t)h.groups + 1);
   if (D.bf16)
-    return lm_head_typed<bf16>(D, h, hidden, n_rows, final_gain, w_lm, vocab, logits, (char*)workspace, st);
-  return lm_head_typed<float>(D, h, hidden, n_rows, final_gain, w_lm, vocab, logits, (char*)workspace, st);
+    return lm_head_typed<bf16>(D, h, hidden, n_rows, final_gain, w_lm, vocab, logits, (char*)workspace, st, tab.data());
+  return lm_head_typed<float>(D, h, hidden, n_rows, final_gain, w_lm, vocab, logits, (char*)workspace, st, tab.data());
 }
 
 armt_status armt_segment_attention(const armt_config* cfg, int32_t g, void* qkv, void* out, void* workspace,
