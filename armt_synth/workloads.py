@@ -84,7 +84,7 @@ _MEM_SCALES = _mem_scales(-7)
 _1B = dict(n_layers=16, d_model=2048, n_heads=32, n_kv_heads=8, head_dim=64, d_ff=8192,
            seg_len=1024, n_mem=16, d_mem=64, dtype="bf16", **_MEM_SCALES)
 _3B = dict(n_layers=28, d_model=3072, n_heads=24, n_kv_heads=8, head_dim=128, d_ff=8192,
-           seg_len=1024, n_mem=16, d_mem=64, dtype="bf16", **_mem_scales(-8))
+           seg_len=1024, n_mem=16, d_mem=64, dtype="bf16", **_mem_scales(-9))
 
 # LLaMA-160M (12 layers of width 768, 12 heads without grouping): the small model of the paper's tables
 _160M = dict(n_layers=12, d_model=768, n_heads=12, n_kv_heads=12, head_dim=64, d_ff=3072,

@@ -208,6 +208,9 @@ def main():
                    "diagonal_steps": shape.n_layers + shape.n_segments - 1,
                    "algorithmic_tflop": total_flops / 1e12},
         "mfma_fraction_end_to_end": total_flops / (ms / 1e3) / 1e12 / MFMA_PEAK_TFLOPS,
+        "outputs_finite": bool(torch.isfinite(out[0].float()).all() and torch.isfinite(out[1]).all()),
+        "hidden_rms_first_last_segment": [float(out[0][..., :shape.seg_len, :].float().pow(2).mean().sqrt()),
+                                          float(out[0][..., -shape.seg_len:, :].float().pow(2).mean().sqrt())],
     }
     # roofline of the dominant kernel: the gate/up grouped GEMM with the SwiGLU epilogue
     k_ms, k_launches, k_groups = prof

@@ -279,30 +279,46 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   const bool vec_ok = ((s.N | s.ldc | s.ldr | s.ldc2) & 3) == 0;
   auto silu_mul = [](float gt, float up) { return gt / (1.f + __expf(-gt)) * up; };
   auto row_scale = [&](int m) { return rs_lds[m - m0]; };
+  // EPI_DPFP_READ: feature idx = lane + 64 k of phi(q) = r[i] r[(i - j) mod 2 d_mem], r = [relu(q), relu(-q)], j = 1..nu
+  // (the untrained feature map of Section 2.1) is max(sa q[ia], 0) max(sb q[ib], 0); which columns and signs, and the
+  // lane's entries of z, are the same for every row: set up once per thread
+  constexpr int DP_MAXK = (EPI == EPI_DPFP_READ) ? 8 : 1;      // 2 nu d_mem <= 512 features
+  int dp_ia[DP_MAXK], dp_ib[DP_MAXK], dp_phi = 0;
+  float dp_sa[DP_MAXK], dp_sb[DP_MAXK], dp_z[DP_MAXK];
+  if constexpr (EPI == EPI_DPFP_READ) {
+    const int dm = s.n0, n2 = 2 * dm;
+    dp_phi = s.ldr * n2;
+#pragma unroll
+    for (int k = 0; k < DP_MAXK; ++k) {
+      const int idx = min(k * 64 + lane, dp_phi - 1);
+      const int j = idx / n2 + 1, i = idx - (j - 1) * n2;
+      int i2 = i - j;
+      if (i2 < 0) i2 += n2;
+      dp_ia[k] = i < dm ? i : i - dm;   dp_sa[k] = i < dm ? 1.f : -1.f;
+      dp_ib[k] = i2 < dm ? i2 : i2 - dm; dp_sb[k] = i2 < dm ? 1.f : -1.f;
+      dp_z[k] = g.R[idx];
+    }
+  }
   // walk nrows staged rows; staged row sr is output row m_of(sr)
   auto drain = [&](int nrows, auto m_of) {
     if constexpr (EPI == EPI_DPFP_READ) {
       // One wave per staged row: the row's d_mem values q sit in the staging tile; lane L computes the features
-      // L, L + 64, ... of phi(q) = r[i] r[(i - j) mod 2 d_mem], r = [relu(q), relu(-q)], j = 1..nu (the untrained
-      // feature map of Section 2.1), stores them in the activation type and adds up its share of z . phi(q).
+      // L, L + 64, ... of phi(q) (dp_* above), stores them in the activation type and adds up its share of z . phi(q).
       // The summation order (lane-strided partial sums, then the wave reduction) does not depend on the tile
       // configuration, so every configuration produces the same bits.
-      const int dm = s.n0, n2 = 2 * dm, Phi = s.ldr * n2;
-      const float* __restrict__ z = g.R;
       for (int sr = wave; sr < nrows; sr += NW) {
         const int m = m_of(sr);
         if (m >= s.M) continue;                          // wave-uniform
         const float* q = stg + sr * SLD;
+        bf16* frow = (bf16*)g.C + (size_t)m * s.ldc + lane;
         float den = 0.f;
-        for (int idx = lane; idx < Phi; idx += 64) {
-          const int j = idx / n2 + 1, i = idx - (j - 1) * n2;
-          int i2 = i - j;
-          if (i2 < 0) i2 += n2;
-          const float a = i < dm ? fmaxf(q[i], 0.f) : fmaxf(-q[i - dm], 0.f);
-          const float b = i2 < dm ? fmaxf(q[i2], 0.f) : fmaxf(-q[i2 - dm], 0.f);
-          const float f = a * b;
-          den = fmaf(f, z[idx], den);
-          ((bf16*)g.C)[(size_t)m * s.ldc + idx] = (bf16)f;
+#pragma unroll
+        for (int k = 0; k < DP_MAXK; ++k) {
+          if (k * 64 + lane < dp_phi) {
+            const float f = fmaxf(dp_sa[k] * q[dp_ia[k]], 0.f) * fmaxf(dp_sb[k] * q[dp_ib[k]], 0.f);
+            den = fmaf(f, dp_z[k], den);
+            frow[k * 64] = (bf16)f;
+          }
         }
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) den += __shfl_xor(den, off, kWave);
@@ -539,7 +555,7 @@ inline hipError_t launch_gemm_mfma(const GemmGroup* table, int first, int g, con
     case EPI_SWIGLU: return launch_gemm_mfma_epi<EPI_SWIGLU>(table, first, g, s, st, force_cfg);
     case EPI_DPFP_READ:
       // all d_mem columns of a row in one output tile (the narrowest tile is 128 wide)
-      if (s.N != s.n0 || s.N > 128 || s.ldr < 1 || s.ldc < 2 * s.ldr * s.n0) return hipErrorInvalidValue;
+      if (s.N != s.n0 || s.N > 128 || s.ldr < 1 || s.ldc < 2 * s.ldr * s.n0 || 2 * s.ldr * s.n0 > 512) return hipErrorInvalidValue;
       return launch_gemm_mfma_epi<EPI_DPFP_READ>(table, first, g, s, st, force_cfg);
     case EPI_QKV_ROPE:
       // the rotation reads its partner column from the staged tile: heads must not straddle tiles (128 or 256 wide)
