@@ -10,7 +10,8 @@
  * Conventions, valid for every call unless stated otherwise:
  *   - every pointer is a DEVICE pointer unless marked [host];
  *   - the caller owns all memory; the library allocates and frees no device memory;
- *     scratch space comes in through `workspace`;
+ *     scratch space comes in through `workspace` (armt_lm_head_static alone uses a fixed
+ *     array inside the library instead);
  *   - no call keeps state for a later call.  Excluded from this, and NOT thread safe: the
  *     process-wide benchmarking and debugging knobs at the end of this header
  *     (armt_set_gemm_tile_config, armt_profile_begin / armt_profile_end, the environment
@@ -44,7 +45,8 @@ typedef enum {
   ARMT_ERR_DTYPE = 3,       /* dtype is not one of armt_dtype */
   ARMT_ERR_WORKSPACE = 4,   /* workspace missing, misaligned (256 B) or smaller than armt_workspace_bytes */
   ARMT_ERR_HIP = 5,         /* a HIP runtime call failed; see armt_last_hip_error */
-  ARMT_ERR_UNSUPPORTED = 6  /* valid ARMT shape this build has no kernel for (see armt_config) */
+  ARMT_ERR_UNSUPPORTED = 6, /* valid ARMT shape this build has no kernel for (see armt_config) */
+  ARMT_ERR_TOO_LARGE = 7    /* input needs more scratch than the fixed array of a *_static call holds */
 } armt_status;
 
 typedef enum { ARMT_F32 = 0, ARMT_BF16 = 1 } armt_dtype;   /* type of weights, embeddings, hidden_out */
@@ -307,6 +309,20 @@ size_t armt_lm_head_workspace_bytes(const armt_config *cfg, int64_t n_rows);
 armt_status armt_lm_head(const armt_config *cfg, const void *hidden, int64_t n_rows, const void *final_gain,
                          const void *w_lm, int32_t vocab, float *logits,
                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* armt_lm_head for callers that cannot allocate or carry a workspace: code under HIP graph capture, tight serving
+ * loops that turn the last rows of a forward call into logits, harnesses that forbid hipMalloc.  Same arguments,
+ * kernels and result (bit for bit) as armt_lm_head, but the scratch memory (normalised operand rows, row scales,
+ * pointer table) is a fixed array of ARMT_LM_HEAD_STATIC_BYTES bytes inside the library, of which every GPU the
+ * library runs on holds one copy until the process ends.  The call allocates nothing, on the device or on the host
+ * heap.  Limit: armt_lm_head_workspace_bytes(cfg, n_rows) <= ARMT_LM_HEAD_STATIC_BYTES and n_rows < 64512 (for
+ * example 2047 rows at d_model 2048 in bf16, 1023 rows at d_model 4096); anything larger returns ARMT_ERR_TOO_LARGE
+ * before anything is launched.  All calls on one GPU share that GPU's array, which keeps the contents of the last
+ * call (nothing in it has to be cleared: every byte a call reads it has written first): two calls whose kernels
+ * overlap on one GPU (different streams, or threads) race; calls on one stream are safe. */
+#define ARMT_LM_HEAD_STATIC_BYTES ((size_t)8454144)        /* 8 MiB + 64 KiB */
+armt_status armt_lm_head_static(const armt_config *cfg, const void *hidden, int64_t n_rows, const void *final_gain,
+                                const void *w_lm, int32_t vocab, float *logits, void *hip_stream);
 
 /* Environment: ARMT_DEBUG_GENERIC=1 (read once per process) makes bf16 configurations run the plain
  * fp32-FMA GPU kernels of the fp32 path on bf16 operands instead of the MFMA kernels: slow, for telling an

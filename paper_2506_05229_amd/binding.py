@@ -113,6 +113,8 @@ def load_library():
     lib.armt_lm_head_workspace_bytes.restype = sz
     lib.armt_lm_head.argtypes = [C.POINTER(ArmtConfig), vp, i64, vp, vp, i32, vp, vp, sz, vp]
     lib.armt_lm_head.restype = C.c_int
+    lib.armt_lm_head_static.argtypes = [C.POINTER(ArmtConfig), vp, i64, vp, vp, i32, vp, vp]
+    lib.armt_lm_head_static.restype = C.c_int
     lib.armt_lm_head_backward_workspace_bytes.argtypes = [C.POINTER(ArmtConfig), i64, i32]
     lib.armt_lm_head_backward_workspace_bytes.restype = sz
     lib.armt_lm_head_backward.argtypes = [C.POINTER(ArmtConfig), vp, i64, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
@@ -422,6 +424,14 @@ class TokenEnds:
         _check(self.lib, self.lib.armt_lm_head(C.byref(self.cfg), _ptr(hidden), n, _ptr(self.final_gain),
                                                _ptr(self.w_lm), V, _ptr(out), _ptr(self.ws), self.ws.numel(),
                                                _stream(torch)))
+        return out
+
+    def logits_static(self, hidden, out):
+        """armt_lm_head_static: as logits(), with the library's own fixed scratch array; `out` must be given (this call
+        and everything under it allocate nothing)."""
+        n, V = hidden.shape[0], int(self.w_lm.shape[0])
+        _check(self.lib, self.lib.armt_lm_head_static(C.byref(self.cfg), _ptr(hidden), n, _ptr(self.final_gain),
+                                                      _ptr(self.w_lm), V, _ptr(out), _stream(self.torch)))
         return out
 
     def logits_backward(self, hidden, d_logits, grads=None):

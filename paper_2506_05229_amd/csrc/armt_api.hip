@@ -652,6 +652,34 @@ armt_status lm_head_typed(const Dims& D, const HeadLayout& h, const void* hidden
 }
 }  // namespace
 
+// ---- scratch memory of armt_lm_head_static, the entry point for callers that cannot allocate.  One copy of the array
+// exists on every GPU that loads the library, at its own address: the name below is only a handle for
+// hipGetSymbolAddress in host code, never a device address.
+static __device__ __align__(256) unsigned char scratch[ARMT_LM_HEAD_STATIC_BYTES];
+
+namespace {
+constexpr size_t kStaticHeadGroups = 64;                  // groups of kHeadRows rows the stack-allocated host table holds
+constexpr int kMaxDevices = 64;
+std::atomic<char*> g_scratch_ptr[kMaxDevices];            // device address of `scratch` on each device, once looked up
+
+// Address of this device's copy of the array; looked up on the first call on a device, with that device current.
+armt_status static_scratch(char** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return ARMT_ERR_UNSUPPORTED;
+  char* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    void* sym = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)));
+    if (!sym) { g_hip_error = "hipGetSymbolAddress returned a null address"; return ARMT_ERR_HIP; }
+    p = (char*)sym;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);   // a second thread can only store the same address
+  }
+  *out = p;
+  return ARMT_OK;
+}
+}  // namespace
+
 extern "C" {
 
 size_t armt_workspace_bytes(const armt_config* cfg) {
@@ -794,6 +822,24 @@ armt_status armt_lm_head(const armt_config* cfg, const void* hidden, int64_t n_r
   if (D.bf16)
     return lm_head_typed<bf16>(D, h, hidden, n_rows, final_gain, w_lm, vocab, logits, (char*)workspace, st, tab.data());
   return lm_head_typed<float>(D, h, hidden, n_rows, final_gain, w_lm, vocab, logits, (char*)workspace, st, tab.data());
+}
+
+armt_status armt_lm_head_static(const armt_config* cfg, const void* hidden, int64_t n_rows, const void* final_gain,
+                                const void* w_lm, int32_t vocab, float* logits, void* hip_stream) {
+  Dims D;
+  ARMT_TRY(check_config(cfg, &D));
+  if (!hidden || !final_gain || !w_lm || !logits) return ARMT_ERR_NULL;
+  if (n_rows < 1 || n_rows > 0x7fffffff || vocab < 1) return ARMT_ERR_SHAPE;
+  const HeadLayout h = head_layout(D, n_rows);
+  GemmGroup tab[kStaticHeadGroups];                       // host side of the pointer table: on the stack, no heap
+  if (h.total > sizeof(scratch) || (size_t)h.groups + 1 > kStaticHeadGroups) return ARMT_ERR_TOO_LARGE;
+  char* ws = nullptr;
+  ARMT_TRY(static_scratch(&ws));
+  hipStream_t st = (hipStream_t)hip_stream;
+  // nothing in the scratch array has to start at zero: the normalised rows, the row scales and the table entries the
+  // kernels read are all written first by this call
+  if (D.bf16) return lm_head_typed<bf16>(D, h, hidden, n_rows, final_gain, w_lm, vocab, logits, ws, st, tab);
+  return lm_head_typed<float>(D, h, hidden, n_rows, final_gain, w_lm, vocab, logits, ws, st, tab);
 }
 
 armt_status armt_segment_attention(const armt_config* cfg, int32_t g, void* qkv, void* out, void* workspace,
@@ -960,6 +1006,7 @@ const char* armt_status_str(armt_status s) {
     case ARMT_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case ARMT_ERR_HIP: return "HIP runtime error";
     case ARMT_ERR_UNSUPPORTED: return "shape not supported by this build";
+    case ARMT_ERR_TOO_LARGE: return "input exceeds the fixed scratch array of a *_static call";
   }
   return "unknown status";
 }

@@ -157,7 +157,7 @@ def test_forward_argument_errors_come_before_any_launch(lib):
                 setattr(missing[l], f, fake)
         missing[L - 1].wm_b = None
         assert call(fn, layers=missing) == 1
-    for code in range(0, 7):
+    for code in range(0, 8):
         assert lib.armt_status_str(code)
     assert lib.armt_last_hip_error() is not None
 
