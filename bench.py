@@ -145,6 +145,8 @@ def main():
     ap.add_argument("--cpu-segments", type=int, default=4)
     ap.add_argument("--no-train", action="store_true",
                     help="skip the training leg (forward with tape + backward pass; reported under `training`, not in `value`)")
+    ap.add_argument("--no-memory-ops", action="store_true",
+                    help="skip the per-kernel timing passes of the associative-memory kernels (reported under `memory_ops`)")
     ap.add_argument("--no-configs", action="store_true",
                     help="skip the short runs of the other named configurations (reported under `configs`)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -236,7 +238,7 @@ def main():
         sms, swall, _ = timed(False, max(1, min(args.steps, 2)), 1)      # one warm-up pass: one-off costs of its tile configurations
         res["sequential_tokens_per_s"] = n_tok / (swall / 1e3)
         res["speedup_vs_sequential"] = swall / wall_ms
-    if B == 1:
+    if B == 1 and not args.no_memory_ops:
         # Kernels of the associative memory: HIP-event time of each over one more pass (one kind per pass), against the
         # bytes each must move at least.  The 16 A matrices of the 1B shape (50 MB) fit the chip's last-level cache, so
         # "achieved" is a rate against the HBM peak, not a claim that the bytes came from HBM.
