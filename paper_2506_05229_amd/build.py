@@ -15,9 +15,14 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> str:
+TIMELINE_LIB = os.path.join(HERE, "libarmt_hip_timeline.so")
+
+
+def build(verbose: bool = False, timeline: bool = False) -> str:
+    """timeline=True builds the probe variant of the library (see timeline.py) next to the product library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-o", LIB, os.path.join(CSRC, "armt_api.hip")]
+    out = TIMELINE_LIB if timeline else LIB
+    cmd = [hipcc, *HIPCC_FLAGS, *(["-DARMT_GEMM_TIMELINE"] if timeline else []), "-o", out, os.path.join(CSRC, "armt_api.hip")]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -27,8 +32,9 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    print(build(verbose=True, timeline="--timeline" in sys.argv))

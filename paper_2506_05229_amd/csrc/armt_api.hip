@@ -1013,6 +1013,14 @@ const char* armt_status_str(armt_status s) {
 
 const char* armt_last_hip_error(void) { return g_hip_error.c_str(); }
 
+#ifdef ARMT_GEMM_TIMELINE
+// probe build only: arm the n-th next launch of a GEMM kind; read the records back (8 x 64 bits per workgroup)
+void armt_timeline_arm(int32_t kind, int32_t nth) { g_tl_kind = kind; g_tl_countdown = nth; }
+int32_t armt_timeline_read(unsigned long long* host, int64_t n_words) {
+  return (int32_t)hipMemcpyFromSymbol(host, HIP_SYMBOL(armt_timeline), (size_t)n_words * 8, 0, hipMemcpyDeviceToHost);
+}
+#endif
+
 }  // extern "C"
 
 #include "backward_host.h"

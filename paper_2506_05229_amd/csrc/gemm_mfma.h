@@ -22,6 +22,7 @@
 #pragma once
 
 #include <atomic>
+#include <type_traits>
 
 #include "common.h"
 #include "gemm_generic.h"
@@ -38,6 +39,29 @@ __device__ __forceinline__ int mf_swz(int row) { return ((row >> 1) & 7) ^ ((row
 template <int N>
 __device__ __forceinline__ void mf_wait_vmcnt() {      // s_waitcnt vmcnt(N) only (N <= 63)
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
+
+#ifdef ARMT_GEMM_TIMELINE
+// Probe build (paper_2506_05229_amd.build.build_timeline, never the product library): one armed launch records, per
+// workgroup, where its time goes: [0] hardware id, [1] / [6] wall clock (100 MHz) at start / end, [2] .. [5] shader
+// clock at start, after the first k-tile has landed, after the main loop, after the epilogue.
+__device__ unsigned long long armt_timeline[8 * 65536];
+inline int g_tl_kind = -2, g_tl_countdown = -1;      // host: the n-th next launch of this kind is the armed one
+#define TL_STAMP(i)                                                     \
+  do {                                                                  \
+    if (tl_on && threadIdx.x == 0) tl[i] = __builtin_readcyclecounter(); \
+  } while (0)
+#else
+#define TL_STAMP(i) do {} while (0)
+#endif
+
+// LDS bytes of the tile buffers of a configuration: NS buffers of a k-tile (A rows, B rows), and at least the two fp32
+// staging tiles [WGM * 16][tile columns + 4] of the epilogue, which reuse them.
+template <int BM, int BN, int WGM, int EPI, bool TAIL, int NS>
+constexpr int mfma_tile_lds_bytes() {
+  const int tiles = NS * ((TAIL ? BM + 16 : BM) + BN) * MF_ROW_BYTES;
+  const int stg = 2 * WGM * 16 * (((EPI == EPI_SWIGLU) ? BN / 2 : BN) + 4) * 4;
+  return ((tiles > stg ? tiles : stg) + 255) / 256 * 256;
 }
 
 // TAIL: the last M-tile of every group also owns the 16 rows that follow it (M = tiles_m * BM + 16).  With
@@ -64,6 +88,18 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
 
   extern __shared__ __align__(16) unsigned char smem[];   // [NS][A_BYTES], [NS][B_BYTES], then A_ROWS row scales
 
+#ifdef ARMT_GEMM_TIMELINE
+  const bool tl_on = (s.dbg >> 20) & 1;
+  unsigned long long* tl = armt_timeline + 8 * (size_t)(blockIdx.x & 65535);
+  if (tl_on && threadIdx.x == 0) {
+    unsigned hw, xcc;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    tl[0] = ((unsigned long long)xcc << 32) | hw;
+    tl[1] = __builtin_amdgcn_s_memrealtime();
+    tl[2] = __builtin_readcyclecounter();
+  }
+#endif
   // XCD-aware tile order: workgroup b runs on XCD b % 8; give each XCD a contiguous range.
   const int per_xcd = (total_tiles + 7) >> 3;
   const int lid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
@@ -79,7 +115,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // per-row scale of the result (1 / rms of a fused RMSNorm, or 1 / denominator of the associative read),
   // fetched once; visible to everybody after the first barrier of the main loop
-  float* rs_lds = (float*)(smem + NS * A_BYTES + NS * B_BYTES);
+  float* rs_lds = (float*)(smem + mfma_tile_lds_bytes<BM, BN, WGM, EPI, TAIL, NS>());
   for (int r = tid; r < A_ROWS; r += NW * 64) rs_lds[r] = (g.rowscale && m0 + r < s.M) ? g.rowscale[m0 + r] : 1.f;
   const int wm = wave / WGN, wn = wave % WGN;
   const bool tail = tail_blk && wave < (TAIL ? BN / 32 : 0);   // wave-uniform: this wave computes part of the strip
@@ -88,6 +124,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   // bytes into 1 KB of consecutive LDS = 8 tile rows.  Lane i fills row i / 8, physical chunk i % 8 of the
   // slab, so it fetches the logical chunk (i % 8) ^ swz(row) of that row from global memory.
   // first element of row `row` of this block's weight tile
+  // row n of the logical [N, K] weight, which comes in up to three blocks (selected by value: the table entry must not
+  // be indexed dynamically, or it ends up in scratch memory instead of scalar registers)
+  const bf16 *wB0 = (const bf16*)g.B0, *wB1 = (const bf16*)g.B1, *wB2 = (const bf16*)g.B2;
+  auto w_row = [&](int n) -> const bf16* {
+    if (n < s.n0) return wB0 + (size_t)n * s.ldb;
+    n -= s.n0;
+    if (n < s.n1) return wB1 + (size_t)n * s.ldb;
+    return wB2 + (size_t)(n - s.n1) * s.ldb;
+  };
   auto b_row = [&](int row) -> const bf16* {
     if (EPI == EPI_SWIGLU) {
       // tile rows come in 32-row blocks: even blocks from the gate weight, odd from the up weight,
@@ -96,7 +141,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       const int n = min(n0 + (blk >> 1) * 32 + (row & 31), s.N - 1);
       return (const bf16*)((blk & 1) ? g.B1 : g.B0) + (size_t)n * s.ldb;
     }
-    return weight_row<bf16>(g, s, min(n0 + row, s.N - 1));
+    return w_row(min(n0 + row, s.N - 1));
   };
   const int dR = lane >> 3, dpc = lane & 7;
   // source of this lane for A slab j / the tail slab / B slab j, at k = 0
@@ -149,7 +194,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       const int n = n0 + (blk >> 1) * 32 + (row & 31);
       return (const char*)((blk & 1) ? g.B1 : g.B0) + (size_t)n * s.ldb * 2;
     }
-    return (const char*)weight_row<bf16>(g, s, n0 + RPS * slab);
+    return (const char*)w_row(n0 + RPS * slab);
   };
   const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) void*)smem;
   // one copy: 64 lanes x 16 bytes from base + lane offset to LDS address `lds` (M0) onwards; scalar operands only
@@ -222,6 +267,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       mf_wait_vmcnt<0>();
     }
     __syncthreads();
+    TL_STAMP(3);
     int cur = 0, nxt = NS - 1;                           // buffers of tile kt and of tile kt + NS - 1
     for (int kt = 0; kt < nk; ++kt) {
       // buffer nxt was last read in iteration kt - 1, which ended with a barrier
@@ -265,19 +311,25 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
     }
   }
 
+  TL_STAMP(4);
   // ---- epilogue, staged through LDS so that global memory sees whole rows: a 16x16 result tile has lane =
   // column (lane % 16) and registers = rows 4 * (lane / 16) + r, which written directly would touch global
   // memory in 32- or 64-byte pieces.  Instead, in TM passes every wave drops one 16-row block of its tile into
   // a fp32 staging tile [WGM * 16][BN_OUT + 4] (the +4 puts the four row groups of a wave on different banks),
   // and all threads then walk the staging tile row-major, C4 = BN_OUT / 4 lanes per row: 16-byte accesses, full rows
   // of R, C, C2.  The tail strip goes through the same path as one more pass of 16 rows.
-  // The tile buffers are free here: the main loop ended with a barrier.
+  // There are two staging tiles (the tile buffers are free: the main loop ended with a barrier): pass p + 1 is staged
+  // while pass p is still being drained, so a pass costs one barrier, and nothing of it waits for global memory
+  // between the barriers: what a pass reads from global memory (residual rows, rotary table) is requested before its
+  // staging writes, and the barriers wait for LDS traffic only.
   constexpr int SLD = BN_OUT + 4, SR = WGM * 16, C4 = BN_OUT / 4, NT = NW * 64;
-  static_assert(SR * SLD * 4 <= NS * (A_BYTES + B_BYTES), "staging tile must fit in the tile buffers");
+  constexpr int STG_FLOATS = SR * SLD;
+  static_assert(2 * STG_FLOATS * 4 <= mfma_tile_lds_bytes<BM, BN, WGM, EPI, TAIL, NS>(), "two staging tiles must fit in the tile buffers");
   static_assert(C4 == 16 || C4 == 32 || C4 == 64, "a staged row is handled by 16, 32 or 64 consecutive lanes");
-  float* stg = (float*)smem;
+  static_assert(NT % C4 == 0, "a thread keeps its columns from one row of the walk to the next");
   const bool vec_ok = ((s.N | s.ldc | s.ldr | s.ldc2) & 3) == 0;
-  auto silu_mul = [](float gt, float up) { return gt / (1.f + __expf(-gt)) * up; };
+  // silu(gate) * up; the reciprocal is the hardware's (1 ulp), the result is rounded to bf16 afterwards
+  auto silu_mul = [](float gt, float up) { return gt * __builtin_amdgcn_rcpf(1.f + __expf(-gt)) * up; };
   auto row_scale = [&](int m) { return rs_lds[m - m0]; };
   // EPI_DPFP_READ: feature idx = lane + 64 k of phi(q) = r[i] r[(i - j) mod 2 d_mem], r = [relu(q), relu(-q)], j = 1..nu
   // (the untrained feature map of Section 2.1) is max(sa q[ia], 0) max(sb q[ib], 0); which columns and signs, and the
@@ -299,14 +351,59 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       dp_z[k] = g.R[idx];
     }
   }
-  // walk nrows staged rows; staged row sr is output row m_of(sr)
-  auto drain = [&](int nrows, auto m_of) {
+  // The walk: thread tid takes column group c4 = tid % C4 (4 columns) of the staged rows tid / C4 + it * (NT / C4).
+  const int c4 = tid % C4, sr_first = tid / C4;
+  const int n = n0 + c4 * 4;
+  // per-thread constants of the walk: the gain of its four columns (EPI_RESID_F32 with a normalised copy)
+  f32x4 gq = {1.f, 1.f, 1.f, 1.f};
+  if (EPI == EPI_RESID_F32 && g.C2 && g.gain) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) gq[e] = (float)((const bf16*)g.gain)[min(n + e, s.N - 1)];
+  }
+  // sum over the 32 lanes that hold 128 consecutive columns of a row: four steps inside a row of 16 lanes with
+  // data-parallel moves (no LDS), one exchange between the two rows
+  auto sum32 = [](float v) __attribute__((always_inline)) {
+    auto dpp = [](float x, auto ctrl) {
+      return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value, 0xF, 0xF, true));
+    };
+    v += dpp(v, std::integral_constant<int, 0xB1>{});      // quad_perm [1, 0, 3, 2]
+    v += dpp(v, std::integral_constant<int, 0x4E>{});      // quad_perm [2, 3, 0, 1]
+    v += dpp(v, std::integral_constant<int, 0x141>{});     // row_half_mirror
+    v += dpp(v, std::integral_constant<int, 0x140>{});     // row_mirror
+    v += __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));   // lane ^ 16
+    return v;
+  };
+  // What one pass of the walk reads from global memory, requested ahead of the pass.
+  constexpr int MAX_ITER = (SR * C4 + NT - 1) / NT;
+  struct Pre { f32x4 r[MAX_ITER]; };
+  auto prefetch = [&](auto nrows_c, auto m_of, Pre& pre) __attribute__((always_inline)) {
+    constexpr int NROWS = decltype(nrows_c)::value, ITER = (NROWS * C4 + NT - 1) / NT;
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+      const int sr = sr_first + it * (NT / C4);
+      const int m = m_of(min(sr, NROWS - 1));
+      const bool valid = sr < NROWS && m < s.M && n < s.N;
+      pre.r[it] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (EPI == EPI_RESID_F32 && g.R && valid) {
+        if (vec_ok) {
+          pre.r[it] = *(const f32x4*)(g.R + (size_t)m * s.ldr + n);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (n + e < s.N) pre.r[it][e] = g.R[(size_t)m * s.ldr + n + e];
+        }
+      }
+    }
+  };
+  // walk NROWS staged rows of staging tile stg; staged row sr is output row m_of(sr)
+  auto drain = [&](const float* stg, auto nrows_c, auto m_of, const Pre& pre) __attribute__((always_inline)) {
+    constexpr int NROWS = decltype(nrows_c)::value, ITER = (NROWS * C4 + NT - 1) / NT;
     if constexpr (EPI == EPI_DPFP_READ) {
       // One wave per staged row: the row's d_mem values q sit in the staging tile; lane L computes the features
       // L, L + 64, ... of phi(q) (dp_* above), stores them in the activation type and adds up its share of z . phi(q).
       // The summation order (lane-strided partial sums, then the wave reduction) does not depend on the tile
       // configuration, so every configuration produces the same bits.
-      for (int sr = wave; sr < nrows; sr += NW) {
+      for (int sr = wave; sr < NROWS; sr += NW) {
         const int m = m_of(sr);
         if (m >= s.M) continue;                          // wave-uniform
         const float* q = stg + sr * SLD;
@@ -326,36 +423,47 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       }
       return;
     }
-    for (int q = tid; q < nrows * C4; q += NT) {
-      const int sr = q / C4, c4 = q - sr * C4;
-      const int m = m_of(sr), n = n0 + c4 * 4;
-      const bool valid = m < s.M && n < s.N;
+    // EPI_QKV_ROPE: the cos / sin pairs of all rows of the walk first (stores to C could alias the table as far as
+    // the compiler knows, so loads placed between the stores would wait for one another)
+    f32x4 rc0[EPI == EPI_QKV_ROPE ? ITER : 1], rc1[EPI == EPI_QKV_ROPE ? ITER : 1];
+    if constexpr (EPI == EPI_QKV_ROPE) {
+      const int hd = s.ldr >> 1, j = n % s.ldr;
+#pragma unroll
+      for (int it = 0; it < ITER; ++it) {
+        const int sr = sr_first + it * (NT / C4);
+        const int m = m_of(min(sr, NROWS - 1));
+        rc0[it] = rc1[it] = f32x4{1.f, 0.f, 1.f, 0.f};
+        if (sr < NROWS && m < s.M && n < s.n0 + s.n1 && n < s.N) {
+          const float* cs = g.R + 2 * ((size_t)m * hd + (j - (j < hd ? 0 : hd)));
+          rc0[it] = *(const f32x4*)cs;                   // c0 s0 c1 s1 | c2 s2 c3 s3
+          rc1[it] = *(const f32x4*)(cs + 4);
+        }
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < ITER; ++it) {
+      const int sr = sr_first + it * (NT / C4);
+      const int m = m_of(min(sr, NROWS - 1));
+      const bool valid = sr < NROWS && m < s.M && n < s.N;
       f32x4 o = {0.f, 0.f, 0.f, 0.f};
       if (valid) {
         o = *(const f32x4*)(stg + sr * SLD + c4 * 4);
         if (EPI != EPI_SWIGLU) o *= row_scale(m);        // SwiGLU applied it before the nonlinearity
-        if (EPI == EPI_QKV_ROPE && n < s.n0 + s.n1) {
-          // rotary embedding (rotate-half): column j of a head pairs with j +- dh/2, which lies in the same
-          // staged row; out_j = x_j cos_j' - x_{j+h} sin_j' (j < h), x_j cos_j' + x_{j-h} sin_j' (j >= h), j' = j mod h
-          const int dh = s.ldr, hd = dh >> 1, j = n % dh, lo = j < hd;
-          const f32x4 p = *(const f32x4*)(stg + sr * SLD + c4 * 4 + (lo ? hd : -hd)) * row_scale(m);
-          const float* cs = g.R + 2 * ((size_t)m * hd + (j - (lo ? 0 : hd)));
-          const f32x4 cs0 = *(const f32x4*)cs, cs1 = *(const f32x4*)(cs + 4);     // c0 s0 c1 s1 | c2 s2 c3 s3
-          const float sg = lo ? -1.f : 1.f;
-          o[0] = o[0] * cs0[0] + sg * p[0] * cs0[1];
-          o[1] = o[1] * cs0[2] + sg * p[1] * cs0[3];
-          o[2] = o[2] * cs1[0] + sg * p[2] * cs1[1];
-          o[3] = o[3] * cs1[2] + sg * p[3] * cs1[3];
-        }
-        if (EPI == EPI_RESID_F32 && g.R) {
-          if (vec_ok) {
-            o += *(const f32x4*)(g.R + (size_t)m * s.ldr + n);
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (n + e < s.N) o[e] += g.R[(size_t)m * s.ldr + n + e];
+        if constexpr (EPI == EPI_QKV_ROPE) {
+          if (n < s.n0 + s.n1) {
+            // rotary embedding (rotate-half): column j of a head pairs with j +- dh/2, which lies in the same
+            // staged row; out_j = x_j cos_j' - x_{j+h} sin_j' (j < h), x_j cos_j' + x_{j-h} sin_j' (j >= h), j' = j mod h
+            const int dh = s.ldr, hd = dh >> 1, j = n % dh, lo = j < hd;
+            const f32x4 p = *(const f32x4*)(stg + sr * SLD + c4 * 4 + (lo ? hd : -hd)) * row_scale(m);
+            const f32x4 cs0 = rc0[it], cs1 = rc1[it];
+            const float sg = lo ? -1.f : 1.f;
+            o[0] = o[0] * cs0[0] + sg * p[0] * cs0[1];
+            o[1] = o[1] * cs0[2] + sg * p[1] * cs0[3];
+            o[2] = o[2] * cs1[0] + sg * p[2] * cs1[1];
+            o[3] = o[3] * cs1[2] + sg * p[3] * cs1[3];
           }
         }
+        if (EPI == EPI_RESID_F32) o += pre.r[it];        // zeros without a residual
         if (!vec_ok) {
 #pragma unroll
           for (int e = 0; e < 4; ++e)
@@ -365,12 +473,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
 #pragma unroll
         for (int e = 0; e < 4; ++e) ob[e] = (bf16)o[e];
         if (EPI == EPI_RESID_F32 && g.C2) {
-          if (g.gain) {      // the copy is the un-normalised input of the next RMSNorm: x * gain
+          // with a gain the copy is the un-normalised input of the next RMSNorm: x * gain
 #pragma unroll
-            for (int e = 0; e < 4; ++e) og[e] = (bf16)(o[e] * (float)((const bf16*)g.gain)[min(n + e, s.N - 1)]);
-          } else {
-            og = ob;
-          }
+          for (int e = 0; e < 4; ++e) og[e] = g.gain ? (bf16)(o[e] * gq[e]) : ob[e];
         }
         if (vec_ok) {
           if (EPI == EPI_STORE_ACT || EPI == EPI_SWIGLU || EPI == EPI_QKV_ROPE) {
@@ -394,13 +499,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       }
       if (EPI == EPI_RESID_F32 && g.ssq_out) {
         // sum of squares of this row for the RMSNorm that consumes the row: one partial per (row, 128 columns),
-        // summed later in column order (deterministic, no atomics).  The granularity is fixed, not the tile
-        // width, so that every tile configuration produces the same partials bit for bit.
+        // summed later in column order (deterministic, no atomics).  The granularity and the order of the additions
+        // are fixed, not tied to the tile width, so that every tile configuration produces the same partials bit for bit.
         static_assert(EPI != EPI_RESID_F32 || BN_OUT % 128 == 0, "partials cover 128 columns = 32 lanes");
-        float part = o[0] * o[0] + o[1] * o[1] + o[2] * o[2] + o[3] * o[3];
-#pragma unroll
-        for (int off = 16; off > 0; off >>= 1) part += __shfl_xor(part, off, kWave);
-        if ((c4 & 31) == 0 && m < s.M)
+        const float part = sum32(o[0] * o[0] + o[1] * o[1] + o[2] * o[2] + o[3] * o[3]);
+        if ((c4 & 31) == 0 && sr < NROWS && m < s.M)
           g.ssq_out[(size_t)m * ((s.N + 127) >> 7) + tn * (BN_OUT / 128) + (c4 >> 5)] = part;
       }
     }
@@ -408,7 +511,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   // EPI_QKV_ROPE, tiles of the v columns: the attention kernel wants V transposed ([column][row], row stride ldc2),
   // so these tiles are drained column-wise: a thread takes 8 consecutive rows of one column, 16 bytes per store.
   const bool vt_tile = EPI == EPI_QKV_ROPE && s.ldc2 > 0 && n0 >= s.n0 + s.n1;      // block-uniform
-  auto drain_vt = [&](int nrows, auto m_of) {
+  auto drain_vt = [&](const float* stg, int nrows, auto m_of) __attribute__((always_inline)) {
     bf16* vt = (bf16*)g.C2 + (size_t)(n0 - (s.n0 + s.n1)) * s.ldc2;
     for (int u = tid; u < (nrows >> 3) * BN_OUT; u += NT) {
       const int rg = u / BN_OUT, col = u - rg * BN_OUT;
@@ -422,9 +525,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
     }
   };
   const int col_in = lane & 15;
+  Pre pre;
 #pragma unroll
   for (int pass = 0; pass < TM; ++pass) {
     const int i = pass;
+    float* stg = (float*)smem + (pass & 1) * STG_FLOATS;
+    auto pass_row = [&](int sr) { return m0 + (sr >> 4) * WROWS + i * 16 + (sr & 15); };
+    if (EPI == EPI_RESID_F32) prefetch(std::integral_constant<int, SR>{}, pass_row, pre);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int row16 = 4 * t_q + r;
@@ -442,13 +549,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
         for (int j = 0; j < TN; ++j) dst[wn * WCOLS + j * 16] = acc[i][j][r];
       }
     }
-    __syncthreads();
-    auto pass_row = [&](int sr) { return m0 + (sr >> 4) * WROWS + i * 16 + (sr & 15); };
-    if (vt_tile) drain_vt(SR, pass_row);
-    else drain(SR, pass_row);
-    __syncthreads();
+    __syncthreads();         // pass p is staged; everybody has left the walk of pass p - 1, whose tile pass p + 1 reuses
+    if (vt_tile) drain_vt(stg, SR, pass_row);
+    else drain(stg, std::integral_constant<int, SR>{}, pass_row, pre);
   }
   if (TAIL && tail_blk) {     // 16x16 result tile: lane holds column lane % 16, rows 4*(lane/16) + r
+    float* stg = (float*)smem + (TM & 1) * STG_FLOATS;
+    auto tail_row = [&](int sr) { return m0 + BM + sr; };
+    if (EPI == EPI_RESID_F32) prefetch(std::integral_constant<int, 16>{}, tail_row, pre);
     if (tail) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
@@ -463,16 +571,18 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       }
     }
     __syncthreads();
-    auto tail_row = [&](int sr) { return m0 + BM + sr; };
-    if (vt_tile) drain_vt(16, tail_row);
-    else drain(16, tail_row);
+    if (vt_tile) drain_vt(stg, 16, tail_row);
+    else drain(stg, std::integral_constant<int, 16>{}, tail_row, pre);
   }
+#ifdef ARMT_GEMM_TIMELINE
+  if (tl_on && threadIdx.x == 0) { tl[5] = __builtin_readcyclecounter(); tl[6] = __builtin_amdgcn_s_memrealtime(); }
+#endif
 }
 
 template <int BM, int BN, int WGM, int WGN, bool REG, int EPI, bool TAIL, int NS>
 inline hipError_t launch_mfma_tail(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st) {
   constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
-  constexpr int LDS = NS * ((TAIL ? BM + 16 : BM) + BN) * MF_BK * 2 + (BM + 16) * 4;
+  constexpr int LDS = mfma_tile_lds_bytes<BM, BN, WGM, EPI, TAIL, NS>() + (BM + 16) * 4;
   const int tiles_m = TAIL ? s.M / BM : (s.M + BM - 1) / BM, tiles_n = (s.N + BN_OUT - 1) / BN_OUT;
   const int total = g * tiles_m * tiles_n;
   const int grid = ((total + 7) / 8) * 8;
@@ -489,6 +599,14 @@ inline hipError_t launch_mfma_tail(const GemmGroup* table, int first, int g, con
     if (e != hipSuccess) return e;
     attr_set.fetch_or(bit, std::memory_order_release);
   }
+#ifdef ARMT_GEMM_TIMELINE
+  if (s.tag == g_tl_kind && g_tl_countdown >= 0 && g_tl_countdown-- == 0) {
+    GemmShape s_tl = s;
+    s_tl.dbg |= 1 << 20;
+    kern<<<grid, WGM * WGN * 64, LDS, st>>>(table, first, s_tl, tiles_m, tiles_n, total);
+    return hipGetLastError();
+  }
+#endif
   kern<<<grid, WGM * WGN * 64, LDS, st>>>(table, first, s, tiles_m, tiles_n, total);
   return hipGetLastError();
 }
