@@ -107,7 +107,9 @@ CONFIGS = {
     "8b_128k": ArmtShape("8b_128k", n_tokens=131072, **_8B),
     "160m_128k": ArmtShape("160m_128k", n_tokens=131072, **_160M),
     # the shape of the paper's timing tables: 4096-token segments with 128 memory tokens
-    "1b_128k_s4096_m128": ArmtShape("1b_128k_s4096_m128", n_tokens=131072, **{**_1B, "seg_len": 4096, "n_mem": 128}),
+    # (128 keys written together are more strongly correlated: key scale 2^-9)
+    "1b_128k_s4096_m128": ArmtShape("1b_128k_s4096_m128", n_tokens=131072,
+                                    **{**_1B, "seg_len": 4096, "n_mem": 128, **_mem_scales(-9)}),
 }
 
 

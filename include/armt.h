@@ -176,6 +176,9 @@ armt_status armt_forward_diagonal_batched(const armt_config *cfg, const armt_lay
  * sequence, and in addition records in `tape`, per (segment, layer) cell, the cell's input [T][d_model] and the layer's
  * A, z from before the cell's update (fp32; armt_tape_bytes(cfg, n_tokens) bytes, 256-byte aligned, device memory
  * owned by the caller; 0 = configuration rejected).  Same results as the inference calls.
+ * Tape layout (one sequence): record (s, l) starts at float ((s * n_layers + l) * R), R = T * d_model + d_model * Phi + Phi
+ * rounded up to a multiple of 64, and holds the cell input [T][d_model], then A^l [d_model][Phi], then z^l [Phi]; a caller
+ * may fill a tape itself (from another forward implementation, or a checkpoint) and hand it to armt_backward.
  *
  * armt_backward consumes the tape: for J = <hidden_out, d_hidden> + <A_out, dA_out> + <z_out, dz_out> it ADDS dJ/dW to
  * the caller's fp32 gradient buffers (`grads[l]` mirrors `layers[l]`: one device pointer per weight, same shapes; the

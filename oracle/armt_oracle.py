@@ -196,10 +196,12 @@ def _prepare(cfg, layers, mem_emb, x, A_in, z_in):
     return x, W, mem_emb, A, z, empty
 
 
-def armt_forward_sequential(cfg, layers, mem_emb, x, A_in=None, z_in=None, stats=None):
+def armt_forward_sequential(cfg, layers, mem_emb, x, A_in=None, z_in=None, stats=None, trace=None):
     """Sequential ARMT forward: for each segment, for each layer (Section 3.1).
     x [n_tokens, d] token embeddings; returns (hidden [n_tokens, d], A [L, d, Phi], z [L, Phi]).
-    stats, if a list, receives per-cell conditioning figures of the associative read and update."""
+    stats, if a list, receives per-cell conditioning figures of the associative read and update; trace, if a list,
+    receives per cell (s, l, cell input [T, d] before the read, A^l and z^l before the update): what a backward pass has
+    to be given about the forward pass."""
     x, W, mem_emb, A, z, empty = _prepare(cfg, layers, mem_emb, x, A_in, z_in)
     S = cfg.seg_len
     N = x.shape[0] // S
@@ -215,6 +217,8 @@ def armt_forward_sequential(cfg, layers, mem_emb, x, A_in=None, z_in=None, stats
                                   max_abs_read=float(np.abs((f @ A[l].T) / (den + cfg.assoc_eps)[:, None]).max()),
                                   max_abs_A=float(np.abs(A[l]).max()), max_abs_z=float(np.abs(z[l]).max())))
             was_empty, A_old, z_old = empty[l], A[l], z[l]
+            if trace is not None:
+                trace.append((s, l, U, A_old, z_old))
             U, A[l], z[l] = armt_cell(U, A[l], z[l], empty[l], W[l], cfg)
             if stats is not None and not was_empty:      # the update side of the same cell (U is the cell's output here)
                 stats[-1].update(update_conditioning(U[S:], A_old, z_old, W[l], cfg.assoc_eps, cfg.dpfp_nu))

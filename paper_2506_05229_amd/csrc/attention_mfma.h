@@ -46,7 +46,7 @@ __global__ __launch_bounds__(256) void v_transpose_kernel(const bf16* __restrict
 // QKV: [L][T][(H + 2 Hkv) dh] with q, k already rotated; Vt as above; Out: [L][T][H dh]; lse2: optional, see the end.
 // grid: (ceil(T / (32 NQ)), Hkv, g), block: NQ * GROUP * 64 with GROUP = H / Hkv.
 template <int DH>
-__global__ __launch_bounds__(512) void attention_mfma_kernel(const bf16* __restrict__ QKV, const bf16* __restrict__ Vt,
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(DH == 64 ? 4 : 3))) void attention_mfma_kernel(const bf16* __restrict__ QKV, const bf16* __restrict__ Vt,
                                                              bf16* __restrict__ Out, int first, int Trows, int Tp,
                                                              int H, int Hkv, int nq, float scale_log2e,
                                                              float* __restrict__ lse2) {
@@ -126,66 +126,66 @@ __global__ __launch_bounds__(512) void attention_mfma_kernel(const bf16* __restr
     const unsigned char* Vs = Ks + K_BYTES;
     if (live && k0 < q0 + AT_QT) {                 // wave-uniform: the tile holds keys this wave's rows may see
 
-    // S^T[key][query] for the two 32-key halves of the tile
-    f32x16 s[2];
+    // The tile's two 32-key halves one after the other: S^T[key][query] of a half, its share of the online softmax,
+    // its share of O^T.  (A half at a time keeps 16 instead of 32 score registers and 2 instead of 4 P fragments
+    // alive: under 128 registers per lane, four waves per SIMD.)
 #pragma unroll
     for (int jj = 0; jj < 2; ++jj) {
+      if (k0 + jj * 32 >= q0 + AT_QT) continue;      // wave-uniform: every key of this half lies after the wave's rows
+      f32x16 sc;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[jj][r] = 0.f;
+      for (int r = 0; r < 16; ++r) sc[r] = 0.f;
       const unsigned char* krow = Ks + (jj * 32 + (lane & 31)) * MF_ROW_BYTES;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         const bf16x8 kf = *(const bf16x8*)(krow + (ks >> 2) * (AT_KT * MF_ROW_BYTES) + (((2 * (ks & 3) + half) ^ fl) << 4));
-        s[jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[jj], 0, 0, 0);
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sc, 0, 0, 0);
       }
-    }
-    if (k0 + AT_KT - 1 > q0) {     // tile crosses the diagonal: mask keys after the query
-      const int qi = q0 + qcol;
-#pragma unroll
-      for (int jj = 0; jj < 2; ++jj)
+      if (k0 + jj * 32 + 31 > q0) {     // the half crosses the diagonal: mask keys after the query
+        const int qi = q0 + qcol;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int key = k0 + jj * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-          if (key > qi) s[jj][r] = -INFINITY;
+          if (key > qi) sc[r] = -INFINITY;
         }
-    }
-    // online softmax: every lane owns one query column; its 32 keys here, the other 32 in lane ^ 32
-    float mx = s[0][0];
-#pragma unroll
-    for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[jj][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-    // m is the reference maximum of the exponents, not the running maximum: it only moves when some score of the
-    // wave exceeds it by more than 2^AT_LAZY, so that most tiles skip rescaling O and the sum (the result does not
-    // depend on the reference: numerator and denominator carry the same factor; p stays below 2^AT_LAZY)
-    if (__builtin_amdgcn_ballot_w64(mx * scale_log2e > fmaf(m, scale_log2e, AT_LAZY)) != 0) {
-      const float m_new = fmaxf(m, mx);
-      const float alpha = __builtin_amdgcn_exp2f((m - m_new) * scale_log2e);
-      m = m_new;
-      lsum *= alpha;
-#pragma unroll
-      for (int t = 0; t < OT; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[t][r] *= alpha;
-    }
-    const float mc = m * scale_log2e;
-    bf16x8 pf[2][2];
-#pragma unroll
-    for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(s[jj][r], scale_log2e, -mc));
-        lsum += p;
-        pf[jj][r >> 3][r & 7] = (bf16)p;
       }
-    // O^T[dim][query] += V^T[dim][key] P^T[key][query]; k-step ss of half jj covers keys
-    // jj*32 + 16*ss + {4*half + 0..3, 8 + 4*half + 0..3}: exactly what registers 8*ss .. 8*ss+7 of s[jj] hold
+      // online softmax: every lane owns one query column; 16 of the half's keys here, the other 16 in lane ^ 32
+      float mx = sc[0];
 #pragma unroll
-    for (int t = 0; t < OT; ++t) {
-      const unsigned char* vrow = Vs + (t * 32 + (lane & 31)) * MF_ROW_BYTES + 8 * half;
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+      // m is the reference maximum of the exponents, not the running maximum: it only moves when some score of the
+      // wave exceeds it by more than 2^AT_LAZY, so that most tiles skip rescaling O and the sum (the result does not
+      // depend on the reference: numerator and denominator carry the same factor; p stays below 2^AT_LAZY)
+      if (__builtin_amdgcn_ballot_w64(mx * scale_log2e > fmaf(m, scale_log2e, AT_LAZY)) != 0) {
+        const float m_new = fmaxf(m, mx);
+        const float alpha = __builtin_amdgcn_exp2f((m - m_new) * scale_log2e);
+        m = m_new;
+        lsum *= alpha;
 #pragma unroll
-      for (int jj = 0; jj < 2; ++jj)
+        for (int t = 0; t < OT; ++t)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[t][r] *= alpha;
+      }
+      const float mc = m * scale_log2e;
+      // P^T as the B operand of the second product: two 16-key k-steps, packed to bf16 in pairs
+      bf16x8 pf[2];
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[r], scale_log2e, -mc));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[r + 1], scale_log2e, -mc));
+        lsum += p0 + p1;
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        const bf16x2 pk = __builtin_convertvector(f32x2{p0, p1}, bf16x2);
+        pf[r >> 3][r & 7] = pk[0];
+        pf[r >> 3][(r & 7) + 1] = pk[1];
+      }
+      // O^T[dim][query] += V^T[dim][key] P^T[key][query]; k-step ss of half jj covers keys
+      // jj*32 + 16*ss + {4*half + 0..3, 8 + 4*half + 0..3}: exactly what registers 8*ss .. 8*ss+7 of sc hold
+#pragma unroll
+      for (int t = 0; t < OT; ++t) {
+        const unsigned char* vrow = Vs + (t * 32 + (lane & 31)) * MF_ROW_BYTES + 8 * half;
 #pragma unroll
         for (int ss = 0; ss < 2; ++ss) {
           const int ch = jj * 4 + 2 * ss;
@@ -194,8 +194,9 @@ __global__ __launch_bounds__(512) void attention_mfma_kernel(const bf16* __restr
           bf16x8 vf;
           vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
           vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
-          o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[jj][ss], o[t], 0, 0, 0);
+          o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ss], o[t], 0, 0, 0);
         }
+      }
     }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);

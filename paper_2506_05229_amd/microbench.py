@@ -4,6 +4,7 @@ the figures on grouped-GEMM FLOPS vs group size and attention vs batch size), on
     python -m paper_2506_05229_amd.microbench gemm      [--workload 1b_128k] [--data randn|zeros] [--iters 30]
     python -m paper_2506_05229_amd.microbench attention [--workload 1b_128k] [--iters 30]
     python -m paper_2506_05229_amd.microbench head      [--workload 1b_128k] [--iters 10]
+    python -m paper_2506_05229_amd.microbench orders    [--workload 1b_8k]   [--iters 5]
 
 `gemm` times the four big linear shapes of one cell (QKV, attention output, gate/up as one N = 2 d_ff problem,
 down) as one grouped launch of g = 1, 2, 4, 8, n_layers groups, every group with its own weight, through the
@@ -13,6 +14,11 @@ the arithmetic is the same but nothing toggles, which shows how much of the rate
 `attention` times the fused segment attention (RoPE + GQA + causal softmax) for g = 1 ... n_layers cells.
 
 `head` times the final RMSNorm + linear head over the LLaMA-3 vocabulary (128256) for 1, 4 and 16 segments of rows.
+
+`orders` is the short-input comparison behind armt_forward_auto (the 4096 - 16384-token columns of the paper's timing
+tables, where its implementation is slower than its baseline): the widths of the workload with segments of 512 ...
+4096 tokens and 16 or 128 memory tokens, both orders, the order the library picks, and the split-group hybrid with
+groups of at most 1, 2 and 4 cells launched cell by cell; one markdown table row per case.
 
 Everything is timed with device events after a warm-up in the same process; one JSON line per measurement.
 """
@@ -111,9 +117,34 @@ def bench_head(shape, iters: int, warmup: int):
         del h, out
 
 
+def bench_orders(shape, iters: int):
+    import numpy as np
+    import torch
+    import armt_synth as S
+    from . import Armt
+    layers, _ = S.make_weights(shape, seed=0)
+    print("| tokens | segment + memory | segments | diagonal ms | sequential ms | seq / diag | auto picks | split<=1 ms | split<=2 ms | split<=4 ms |")
+    print("|---|---|---|---|---|---|---|---|---|---|")
+    for n_mem in (16, 128):
+        for tokens in (4096, 8192, 16384):
+            for seg in (512, 1024, 2048, 4096):
+                sh = shape.replace(seg_len=seg, n_mem=n_mem, n_tokens=tokens)
+                model = Armt(sh, layers, S.make_weights(sh, seed=0, n_layers=0)[1])
+                xd = model.embed(S.make_embeddings(sh, seed=0))
+                out = model.forward(xd, diagonal=True)
+                t = lambda **kw: _time(torch, lambda: model.forward(xd, out=out, **kw), iters, 1)
+                d, q = t(diagonal=True), t(diagonal=False)
+                model.forward(xd, diagonal="auto", out=out)
+                sp = [t(split_upto=k) for k in (1, 2, 4)]
+                print(f"| {tokens} | {seg} + {n_mem} | {tokens // seg} | {d:.2f} | {q:.2f} | {q / d:.2f} | "
+                      f"{'diagonal' if model.order_used else 'sequential'} | " + " | ".join(f"{v:.2f}" for v in sp) + " |", flush=True)
+                del model, xd, out
+                torch.cuda.empty_cache()
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("op", choices=["gemm", "attention", "head"])
+    ap.add_argument("op", choices=["gemm", "attention", "head", "orders"])
     ap.add_argument("--workload", default="1b_128k")
     ap.add_argument("--data", choices=["randn", "zeros"], default="randn")
     ap.add_argument("--iters", type=int, default=30)
@@ -133,6 +164,8 @@ def main(argv=None) -> int:
         bench_gemm(shape, args.data, args.iters, args.warmup)
     elif args.op == "attention":
         bench_attention(shape, args.iters, args.warmup)
+    elif args.op == "orders":
+        bench_orders(shape, min(args.iters, 5))
     else:
         bench_head(shape, min(args.iters, 10), args.warmup)
     return 0

@@ -4,9 +4,16 @@ fp32 configurations: <= 2e-4.
 bf16 configurations: <= 5e-2 for the decoder block's weights, the embeddings and W_V, W_beta of the memory (every
 gradient GEMM takes bf16 operands and accumulates in fp32, the attention backward rounds P and dS to bf16 like the
 forward rounds P; measured 0.5 - 3.5 %, growing by about 0.5 % per layer the gradient crosses; the same cases through
-fp32 arithmetic on the same bf16-stored tensors give 0.7 - 2.7 %); <= 1.5e-1 (measured 3 - 10 %) for W_Q and W_K of the memory and for the carried-in state: these gradients are linear in the
-memory matrix A and in its gradient, which the bf16 forward itself only reproduces to a few per cent (the forward
-tolerance on A and z is 5e-2), and they pass through the rank-one cancellation d(num / den)."""
+fp32 arithmetic on the same bf16-stored tensors give 0.7 - 2.7 %); <= 1.5e-1 (measured 2 - 11 %) for W_Q and W_K of the
+memory.  Where that looser bound comes from is measured by test_bf16_backward_kernels_on_an_oracle_tape, which hands
+armt_backward a tape from the float64 forward oracle, so that the deviation of the bf16 forward pass between cells is
+out of the comparison: then the gradients of the carried-in state are good to 1.4e-2 / 5e-3 and are held to 5e-2 like
+everything else, W_Q comes out at 4e-2 and W_K at 7e-2.  So about two thirds of the W_K error are the backward pass's own:
+its gradient runs through gamma = 1 - z.phi / (|phi|^2 + eps) and v - v_bar (Eq. 4), differences whose relative error is
+that of phi(k) -- twice the bf16 error of the memory rows the step recomputes -- divided by gamma, and the test inputs sit
+on purpose at the edge of the well-conditioned range, where gamma comes close to zero; the rest is the forward's bf16
+deviation in A and z between cells, which these gradients are linear in.  Bound: 1e-1 on an oracle tape, 1.5e-1 end to
+end (margin over the measured 7e-2 and 1.1e-1)."""
 import numpy as np
 import pytest
 
@@ -19,6 +26,7 @@ pytestmark = pytest.mark.gpu
 F32_REL = 2e-4
 BF16_REL = 5e-2
 BF16_REL_MEM = 1.5e-1
+BF16_REL_TAPE = 1e-1
 
 
 def upstream(shape, seed, with_state):
@@ -151,6 +159,54 @@ def test_many_memory_tokens_backward_matches_oracle(dtype):
         compare(got, want, F32_REL, "f32 n_mem 40")
     else:
         compare(got, want, BF16_REL, "bf16 n_mem 48", tol_mem=BF16_REL_MEM)
+
+
+def _oracle_tape(shape, layers, mem_emb, x, A_in=None, z_in=None):
+    """The tape of include/armt.h filled from the float64 forward oracle (rounded to fp32 once)."""
+    from oracle import armt_oracle as O
+    trace = []
+    O.armt_forward_sequential(shape, layers, mem_emb, x, A_in=A_in, z_in=z_in, trace=trace)
+    T, d, P = shape.T, shape.d_model, shape.phi
+    R = (T * d + d * P + P + 63) // 64 * 64
+    tape = np.zeros((shape.n_segments * shape.n_layers, R), dtype=np.float32)
+    for (s, l, U, A, z) in trace:
+        rec = tape[s * shape.n_layers + l]
+        rec[:T * d] = U.reshape(-1)
+        rec[T * d:T * d + d * P] = A.reshape(-1)
+        rec[T * d + d * P:T * d + d * P + P] = z
+    return tape
+
+
+@pytest.mark.parametrize("diagonal", [False, True])
+def test_bf16_backward_kernels_on_an_oracle_tape(diagonal):
+    """The backward kernels alone: armt_backward is given a tape built from the float64 forward oracle (cell inputs and
+    memory states rounded to fp32 once), so that the deviation of the bf16 FORWARD pass is out of the comparison.  Then
+    every gradient, those of the carried-in state included, is held to the 5e-2 of the other tensors, W_Q and W_K of the
+    memory to 1e-1 (see the header of this file).  The state is carried in from an oracle run over two earlier segments (a well-conditioned state)."""
+    import torch
+    import paper_2506_05229_amd as P
+    from oracle import armt_oracle as O
+    shape, layers, mem_emb, x = well_conditioned(S.get_shape("tiny").replace(**dict(SMALL_BF16, n_tokens=144 * 6)), seed=11)
+    Sg = shape.seg_len
+    _, A0, z0 = O.armt_forward_sequential(shape, layers, mem_emb, x[:2 * Sg])
+    A0, z0 = A0.astype(np.float32), z0.astype(np.float32)
+    rest = shape.replace(n_tokens=4 * Sg)
+    xr = x[2 * Sg:]
+    Gs = upstream(rest, 11, with_state=True)
+    want = G.armt_grad(rest, layers, mem_emb, xr, *Gs, A_in=A0, z_in=z0)
+    tape = torch.from_numpy(_oracle_tape(rest, layers, mem_emb, xr, A_in=A0.astype(np.float64), z_in=z0.astype(np.float64))).cuda()
+    model = P.Armt(rest, layers, mem_emb)
+    dev = lambda a: torch.as_tensor(a, dtype=torch.float32).cuda().contiguous()
+    g = model.backward(tape.view(torch.uint8).reshape(-1), rest.n_tokens, model.embed(Gs[0]), dev(Gs[1]), dev(Gs[2]), carry_in=True,
+                       diagonal=diagonal)
+    torch.cuda.synchronize()
+    np_ = lambda t: t.float().cpu().numpy()
+    got = {"layers": [{k: np_(v) for k, v in lw.items()} for lw in g["layers"]], "mem_emb": np_(g["mem_emb"]),
+           "x": np_(g["x"]), "A_in": np_(g["A_in"]), "z_in": np_(g["z_in"]),
+           "hidden": want["hidden"], "A": want["A"], "z": want["z"]}      # the forward is the oracle's own here
+    # the carried-in state's gradients are held to the bound of every other tensor here; W_Q, W_K of the memory to 1e-1
+    compare(got, want, BF16_REL, f"bf16 backward on an oracle tape, diag={diagonal}", tol_mem=BF16_REL_TAPE)
+    assert rel_fro(got["A_in"], want["A_in"]) <= BF16_REL and rel_fro(got["z_in"], want["z_in"]) <= BF16_REL
 
 
 def test_backward_orders_agree():
