@@ -403,23 +403,35 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
       // L, L + 64, ... of phi(q) (dp_* above), stores them in the activation type and adds up its share of z . phi(q).
       // The summation order (lane-strided partial sums, then the wave reduction) does not depend on the tile
       // configuration, so every configuration produces the same bits.
-      for (int sr = wave; sr < NROWS; sr += NW) {
-        const int m = m_of(sr);
-        if (m >= s.M) continue;                          // wave-uniform
+      // A wave takes the staged rows wave, wave + NW, ...: all of them side by side (features of every row first, then the
+      // row sums, then the stores), so that the LDS reads and the wave reductions of different rows overlap.
+      constexpr int RW = (NROWS + NW - 1) / NW;           // rows per wave
+      float f[RW][DP_MAXK], den[RW];
+      int mrow[RW];
+#pragma unroll
+      for (int j = 0; j < RW; ++j) {
+        const int sr = min(wave + j * NW, NROWS - 1);
+        mrow[j] = (wave + j * NW < NROWS) ? m_of(sr) : s.M;      // rows past the tile or past M are skipped below
         const float* q = stg + sr * SLD;
-        bf16* frow = (bf16*)g.C + (size_t)m * s.ldc + lane;
-        float den = 0.f;
+        den[j] = 0.f;
 #pragma unroll
         for (int k = 0; k < DP_MAXK; ++k) {
-          if (k * 64 + lane < dp_phi) {
-            const float f = fmaxf(dp_sa[k] * q[dp_ia[k]], 0.f) * fmaxf(dp_sb[k] * q[dp_ib[k]], 0.f);
-            den = fmaf(f, dp_z[k], den);
-            frow[k * 64] = (bf16)f;
-          }
+          f[j][k] = fmaxf(dp_sa[k] * q[dp_ia[k]], 0.f) * fmaxf(dp_sb[k] * q[dp_ib[k]], 0.f);
+          if (k * 64 + lane < dp_phi) den[j] = fmaf(f[j][k], dp_z[k], den[j]);
         }
+      }
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) den += __shfl_xor(den, off, kWave);
-        if (lane == 0) ((float*)g.C2)[m] = 1.0f / (den + s.fparam);
+      for (int off = 32; off > 0; off >>= 1)
+#pragma unroll
+        for (int j = 0; j < RW; ++j) den[j] += __shfl_xor(den[j], off, kWave);
+#pragma unroll
+      for (int j = 0; j < RW; ++j) {
+        if (mrow[j] >= s.M) continue;                    // wave-uniform
+        bf16* frow = (bf16*)g.C + (size_t)mrow[j] * s.ldc + lane;
+#pragma unroll
+        for (int k = 0; k < DP_MAXK; ++k)
+          if (k * 64 + lane < dp_phi) frow[k * 64] = (bf16)f[j][k];
+        if (lane == 0) ((float*)g.C2)[mrow[j]] = 1.0f / (den[j] + s.fparam);
       }
       return;
     }
