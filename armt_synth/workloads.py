@@ -92,11 +92,12 @@ _160M = dict(n_layers=12, d_model=768, n_heads=12, n_kv_heads=12, head_dim=64, d
              seg_len=1024, n_mem=16, d_mem=64, dtype="bf16", **_mem_scales(-4))
 
 # LLaMA-3.1-8B: 32 layers of width 4096, 32 / 8 heads of 128, d_ff 14336 (the large model of the paper's tables).
-# Its key scale is NOT searched: the float64 oracle of all 32 layers needs 64 GB for the weights alone.  2^-10
-# continues the trend of the searched shapes (16 layers of width 2048: 2^-7, 28 layers of width 3072: 2^-9); the
-# parity tests at this width run 2 layers with the scale searched for that depth.
+# Its key scale is NOT searched: the float64 oracle of all 32 layers needs 64 GB for the weights alone.  2^-11
+# continues the trend of the searched shapes (16 layers of width 2048: 2^-7, 28 layers of width 3072: 2^-9; at 2^-10
+# the hidden states of the 131072-token run drift upwards by 9 %, at 2^-11 they are stationary); the parity tests at
+# this width run 2 layers with the scale searched for that depth.
 _8B = dict(n_layers=32, d_model=4096, n_heads=32, n_kv_heads=8, head_dim=128, d_ff=14336,
-           seg_len=1024, n_mem=16, d_mem=64, dtype="bf16", **_mem_scales(-10))
+           seg_len=1024, n_mem=16, d_mem=64, dtype="bf16", **_mem_scales(-11))
 
 CONFIGS = {
     # correctness-only fp32 case
@@ -105,7 +106,9 @@ CONFIGS = {
     "1b_8k": ArmtShape("1b_8k", n_tokens=8192, **_1B),
     "1b_32k": ArmtShape("1b_32k", n_tokens=32768, **_1B),
     "1b_128k": ArmtShape("1b_128k", n_tokens=131072, **_1B),
-    "1b_128k_s512": ArmtShape("1b_128k_s512", n_tokens=131072, **{**_1B, "seg_len": 512}),
+    # 256 segments: at 2^-7 the oracle is stable over the first segments but the run leaves the stable regime near
+    # segment 240 (z turns negative), so this workload takes the next smaller scale
+    "1b_128k_s512": ArmtShape("1b_128k_s512", n_tokens=131072, **{**_1B, "seg_len": 512, **_mem_scales(-8)}),
     "1b_128k_s2048": ArmtShape("1b_128k_s2048", n_tokens=131072, **{**_1B, "seg_len": 2048}),
     "3b_128k": ArmtShape("3b_128k", n_tokens=131072, **_3B),
     "8b_128k": ArmtShape("8b_128k", n_tokens=131072, **_8B),
