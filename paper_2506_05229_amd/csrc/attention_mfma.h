@@ -22,6 +22,23 @@ constexpr int AT_KT = 64;      // keys per tile
 constexpr int AT_QT = 32;      // query rows per wave / workgroup
 constexpr float AT_LAZY = 8.f; // log2 of the largest unnormalised probability the online softmax lets through
 
+// Which key of a 64-key tile sits in LDS row `row` of the K tile.  The 32 x 32 MFMA leaves S^T[row][query] of a lane in
+// registers r = 0..15 <-> rows 8 (r / 4) + 4 half + r % 4, and registers 8 ss .. 8 ss + 7 become the lane's B operand
+// of k-step ss of the second product.  With the rows of every 16-row group holding the keys in 4-key blocks ordered
+// 0, 2, 1, 3, those eight registers are the eight CONSECUTIVE keys 16 ss + 8 half .. + 7, so the matching A operand is one
+// 16-byte piece of a V^T row.  The permutation costs nothing: it only changes which global row a copy lane reads.
+// max of a value over the two half-waves (lanes i and i ^ 32), in every lane: one lane-half swap instead of a
+// round trip through the LDS crossbar
+__device__ __forceinline__ float at_max_halves(float v) {
+  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+__device__ __forceinline__ int at_key_of_row(int row) {
+  return (row & ~12) | ((row & 4) << 1) | ((row & 8) >> 1);
+}
+
 // V of every cell transposed: Vt[l][kvh][c][j] = V[l][j][kvh*dh + c], j padded with zeros to Tp.
 // grid: (Tp / 64, Hkv, g), block: 256.
 __global__ __launch_bounds__(256) void v_transpose_kernel(const bf16* __restrict__ QKV, bf16* __restrict__ Vt,
@@ -94,8 +111,8 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(DH == 64 ? 
     const int k0 = kt * AT_KT;
     for (int sl = wave; sl < K_SLABS + V_SLABS; sl += nw) {
       if (sl < K_SLABS) {
-        const int sub = sl >> 3, row = (sl & 7) * 8 + R;               // key row inside the tile
-        const int key = min(k0 + row, Trows - 1);                      // keys past T are masked by causality
+        const int sub = sl >> 3, row = (sl & 7) * 8 + R;               // row of the tile in LDS
+        const int key = min(k0 + at_key_of_row(row), Trows - 1);       // keys past T are masked by causality
         const char* src = kbase + ((size_t)key * ldq + sub * 64 + ((pc ^ mf_swz(row)) << 3)) * 2;
         __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(Ks + sl * 1024), 16, 0, 0);
       } else {
@@ -112,7 +129,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(DH == 64 ? 
   for (int t = 0; t < OT; ++t)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[t][r] = 0.f;
-  float m = -INFINITY, lsum = 0.f;
+  float m = -INFINITY, lsum = 0.f, lsum1 = 0.f;
 
   const int nkt = (min((qt + 1) * nq * AT_QT, Trows) + AT_KT - 1) / AT_KT;   // key tiles of the workgroup's last rows
   issue_tile(0, 0);
@@ -145,7 +162,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(DH == 64 ? 
         const int qi = q0 + qcol;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int key = k0 + jj * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+          const int key = k0 + jj * 32 + 16 * (r >> 3) + 8 * half + (r & 7);   // see at_key_of_row
           if (key > qi) sc[r] = -INFINITY;
         }
       }
@@ -153,7 +170,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(DH == 64 ? 
       float mx = sc[0];
 #pragma unroll
       for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+      mx = at_max_halves(mx);
       // m is the reference maximum of the exponents, not the running maximum: it only moves when some score of the
       // wave exceeds it by more than 2^AT_LAZY, so that most tiles skip rescaling O and the sum (the result does not
       // depend on the reference: numerator and denominator carry the same factor; p stays below 2^AT_LAZY)
@@ -162,6 +179,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(DH == 64 ? 
         const float alpha = __builtin_amdgcn_exp2f((m - m_new) * scale_log2e);
         m = m_new;
         lsum *= alpha;
+        lsum1 *= alpha;
 #pragma unroll
         for (int t = 0; t < OT; ++t)
 #pragma unroll
@@ -174,26 +192,24 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(DH == 64 ? 
       for (int r = 0; r < 16; r += 2) {
         const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[r], scale_log2e, -mc));
         const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[r + 1], scale_log2e, -mc));
-        lsum += p0 + p1;
         typedef float f32x2 __attribute__((ext_vector_type(2)));
         typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
         const bf16x2 pk = __builtin_convertvector(f32x2{p0, p1}, bf16x2);
+        // the row sum adds up the ROUNDED probabilities, the ones the second product uses (one dot instruction per pair)
+        // (two running sums, so that consecutive dot instructions do not wait for each other)
+        if (r & 2) lsum1 = __builtin_amdgcn_fdot2_f32_bf16(pk, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, lsum1, false);
+        else lsum = __builtin_amdgcn_fdot2_f32_bf16(pk, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, lsum, false);
         pf[r >> 3][r & 7] = pk[0];
         pf[r >> 3][(r & 7) + 1] = pk[1];
       }
-      // O^T[dim][query] += V^T[dim][key] P^T[key][query]; k-step ss of half jj covers keys
-      // jj*32 + 16*ss + {4*half + 0..3, 8 + 4*half + 0..3}: exactly what registers 8*ss .. 8*ss+7 of sc hold
+      // O^T[dim][query] += V^T[dim][key] P^T[key][query]; k-step ss of half jj covers the keys
+      // jj*32 + 16*ss + 8*half + 0..7 (see at_key_of_row): registers 8*ss .. 8*ss+7 of sc, one 16-byte piece of a V^T row
 #pragma unroll
       for (int t = 0; t < OT; ++t) {
-        const unsigned char* vrow = Vs + (t * 32 + (lane & 31)) * MF_ROW_BYTES + 8 * half;
+        const unsigned char* vrow = Vs + (t * 32 + (lane & 31)) * MF_ROW_BYTES;
 #pragma unroll
         for (int ss = 0; ss < 2; ++ss) {
-          const int ch = jj * 4 + 2 * ss;
-          const bf16x4 lo = *(const bf16x4*)(vrow + ((ch ^ fl) << 4));
-          const bf16x4 hi = *(const bf16x4*)(vrow + (((ch + 1) ^ fl) << 4));
-          bf16x8 vf;
-          vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
-          vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
+          const bf16x8 vf = *(const bf16x8*)(vrow + (((jj * 4 + 2 * ss + half) ^ fl) << 4));
           o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ss], o[t], 0, 0, 0);
         }
       }
@@ -203,6 +219,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(DH == 64 ? 
     __syncthreads();
   }
 
+  lsum += lsum1;
   lsum += __shfl_xor(lsum, 32, kWave);
   const float inv = 1.0f / lsum;
   const int qi = q0 + qcol;
