@@ -195,10 +195,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(DH == 64 ? 
         typedef float f32x2 __attribute__((ext_vector_type(2)));
         typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
         const bf16x2 pk = __builtin_convertvector(f32x2{p0, p1}, bf16x2);
-        // the row sum adds up the ROUNDED probabilities, the ones the second product uses (one dot instruction per pair)
-        // (two running sums, so that consecutive dot instructions do not wait for each other)
-        if (r & 2) lsum1 = __builtin_amdgcn_fdot2_f32_bf16(pk, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, lsum1, false);
-        else lsum = __builtin_amdgcn_fdot2_f32_bf16(pk, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, lsum, false);
+        // two running sums in plain fp32 adds.  (A dot instruction on the packed pair, v_dot2c_f32_bf16, would halve the
+        // count, but the sums it produced shifted every gradient of the backward pass by 2 - 3 %: the backward pass takes
+        // P from this row sum and cancels a common component of dP against D = dO.O, which amplifies any bias of it.)
+        if (r & 2) lsum1 += p0 + p1;
+        else lsum += p0 + p1;
         pf[r >> 3][r & 7] = pk[0];
         pf[r >> 3][(r & 7) + 1] = pk[1];
       }
