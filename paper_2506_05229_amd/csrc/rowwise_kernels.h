@@ -174,24 +174,40 @@ __global__ __launch_bounds__(128) void memupd_prep_kernel(const float* __restric
   const int l = first + blockIdx.y, i = blockIdx.x;
   const int Phi = 2 * nu * dm;
   const size_t mi = (size_t)l * m + i;
+  // the kernel is a chain of memory latencies, not of arithmetic: request everything up front (the W_beta dot
+  // product in four independent partial sums so that its loads are all in flight together) and reduce the three
+  // sums with one pass through LDS
   for (int c = threadIdx.x; c < dm; c += blockDim.x) k[c] = KV[mi * (dm + d) + c];
+  const T* y = Y0 + (size_t)l * y_stride + (size_t)i * d;
+  const T* wb = (const T*)aux[l].wm_b;
+  float b0 = 0.f, b1 = 0.f, b2 = 0.f, b3 = 0.f;
+  int c = threadIdx.x;
+  const int step = blockDim.x;
+  for (; c + 3 * step < d; c += 4 * step) {
+    const float y0 = to_f32(y[c]), y1 = to_f32(y[c + step]), y2 = to_f32(y[c + 2 * step]), y3 = to_f32(y[c + 3 * step]);
+    const float w0 = to_f32(wb[c]), w1 = to_f32(wb[c + step]), w2 = to_f32(wb[c + 2 * step]), w3 = to_f32(wb[c + 3 * step]);
+    b0 = fmaf(y0, w0, b0); b1 = fmaf(y1, w1, b1); b2 = fmaf(y2, w2, b2); b3 = fmaf(y3, w3, b3);
+  }
+  for (; c < d; c += step) b0 = fmaf(to_f32(y[c]), to_f32(wb[c]), b0);
+  float bl = (b0 + b1) + (b2 + b3);
   __syncthreads();
   const float* z = aux[l].z;
   float zf = 0.f, ff = 0.f;
-  for (int c = threadIdx.x; c < Phi; c += blockDim.x) {
-    const float f = dpfp_at(k, dm, c);
-    zf = fmaf(f, z[c], zf);
+  for (int cc = threadIdx.x; cc < Phi; cc += blockDim.x) {
+    const float f = dpfp_at(k, dm, cc);
+    zf = fmaf(f, z[cc], zf);
     ff = fmaf(f, f, ff);
-    Fm[mi * Phi + c] = f;
+    Fm[mi * Phi + cc] = f;
   }
-  const T* y = Y0 + (size_t)l * y_stride + (size_t)i * d;
-  const T* wb = (const T*)aux[l].wm_b;
-  float bl = 0.f;
-  for (int c = threadIdx.x; c < d; c += blockDim.x) bl = fmaf(to_f32(y[c]), to_f32(wb[c]), bl);
-  zf = block_sum(zf, red);
-  ff = block_sum(ff, red);
-  bl = block_sum(bl, red);
+  zf = wave_sum(zf);
+  ff = wave_sum(ff);
+  bl = wave_sum(bl);
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;      // nw <= 5: red holds 17 floats
+  if ((threadIdx.x & 63) == 0) { red[3 * w] = zf; red[3 * w + 1] = ff; red[3 * w + 2] = bl; }
+  __syncthreads();
   if (threadIdx.x == 0) {
+    zf = ff = bl = 0.f;
+    for (int j = 0; j < nw; ++j) { zf += red[3 * j]; ff += red[3 * j + 1]; bl += red[3 * j + 2]; }
     Coef[mi * 4 + 0] = 1.0f / (1.0f + expf(-bl));
     Coef[mi * 4 + 1] = 1.0f - zf / (ff + eps);
     Coef[mi * 4 + 2] = (l >= empty_lo && l < empty_hi) ? 0.f : 1.0f / (zf + eps);
@@ -315,11 +331,24 @@ __global__ __launch_bounds__(256) void delta_rule16_kernel(const float* __restri
   bf16* A16 = aux[l].A16;
   const bool b5 = lane & 32, b4 = lane & 16, b3 = lane & 8, b2 = lane & 4;
   const int r0 = blockIdx.x * rows_per_block, r1 = min(d, r0 + rows_per_block);
+  // the wave's next row is requested before the current one is worked on: with one row of 4 * Phi bytes in flight
+  // per wave the pass ran at the latency of HBM, not at its rate
+  float an[NPL], vn = 0.f;
+  if (r0 + w < r1) {
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) an[k] = A[(size_t)(r0 + w) * Phi + lane + 64 * k];
+    vn = Vmi[r0 + w];
+  }
   for (int r = r0 + w; r < r1; r += 4) {
     float a[NPL];
 #pragma unroll
-    for (int k = 0; k < NPL; ++k) a[k] = A[(size_t)r * Phi + lane + 64 * k];
-    const float vr = Vmi[r];
+    for (int k = 0; k < NPL; ++k) a[k] = an[k];
+    const float vr = vn;
+    if (r + 4 < r1) {
+#pragma unroll
+      for (int k = 0; k < NPL; ++k) an[k] = A[(size_t)(r + 4) * Phi + lane + 64 * k];
+      vn = Vmi[r + 4];
+    }
     float p[M];
 #pragma unroll
     for (int i = 0; i < M; ++i) {
