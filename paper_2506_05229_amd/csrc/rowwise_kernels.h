@@ -305,6 +305,24 @@ __global__ __launch_bounds__(256) void delta_rule_kernel(const float* __restrict
   }
 }
 
+// Lanes < 32 get a + (a of lane + 32), lanes >= 32 get b + (b of lane - 32): the level "lane ^ 32" of a transposing
+// butterfly in one swap.  dr_swap_add16: the same for "lane ^ 16" (lanes with bit 4 clear get the sum of a).
+__device__ __forceinline__ float dr_swap_add32(float a, float b) {
+  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float dr_swap_add16(float a, float b) {
+  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+  const u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+// value of another lane of the same row of 16 (CTRL 0x128: lane ^ 8 as a rotation by 8, 0x4E: lane ^ 2, 0xB1: lane ^ 1)
+template <int CTRL>
+__device__ __forceinline__ float dr_dpp(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
 // Fast path of the delta rule for n_mem = 16 and Phi = 64 * NPL: phi(k_i) lives in registers (lane owns columns
 // lane + 64 k), the 16 dot products of a row are reduced with a transposing butterfly (17 exchanges instead of
 // 16 full wave reductions; afterwards lane L holds the complete dot product for i = (L >> 2) & 15), and the 16
@@ -329,7 +347,7 @@ __global__ __launch_bounds__(256) void delta_rule16_kernel(const float* __restri
   const float* Vmi = KV + (size_t)l * M * (dm + d) + (size_t)mi * (dm + d) + dm;
   float* A = aux[l].A;
   bf16* A16 = aux[l].A16;
-  const bool b5 = lane & 32, b4 = lane & 16, b3 = lane & 8, b2 = lane & 4;
+  const bool b3 = lane & 8, b2 = lane & 4;
   const int r0 = blockIdx.x * rows_per_block, r1 = min(d, r0 + rows_per_block);
   // the wave's next row is requested before the current one is worked on: with one row of 4 * Phi bytes in flight
   // per wave the pass ran at the latency of HBM, not at its rate
@@ -357,16 +375,18 @@ __global__ __launch_bounds__(256) void delta_rule16_kernel(const float* __restri
       for (int k = 0; k < NPL; ++k) t = fmaf(a[k], f[i][k], t);
       p[i] = t;
     }
+    // transposing butterfly: the first two levels are lane-half / lane-row swaps (one instruction exchanges what the two
+    // sides of a level send each other), the others data-parallel moves inside a row; sums as in the plain exchange
     float q8[8], q4[4], q2[2];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) q8[j] = (b5 ? p[j + 8] : p[j]) + __shfl_xor(b5 ? p[j] : p[j + 8], 32, kWave);
+    for (int j = 0; j < 8; ++j) q8[j] = dr_swap_add32(p[j], p[j + 8]);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) q4[j] = (b4 ? q8[j + 4] : q8[j]) + __shfl_xor(b4 ? q8[j] : q8[j + 4], 16, kWave);
+    for (int j = 0; j < 4; ++j) q4[j] = dr_swap_add16(q8[j], q8[j + 4]);
 #pragma unroll
-    for (int j = 0; j < 2; ++j) q2[j] = (b3 ? q4[j + 2] : q4[j]) + __shfl_xor(b3 ? q4[j] : q4[j + 2], 8, kWave);
+    for (int j = 0; j < 2; ++j) q2[j] = (b3 ? q4[j + 2] : q4[j]) + dr_dpp<0x128>(b3 ? q4[j] : q4[j + 2]);   // lane ^ 8
     float dot = (b2 ? q2[1] : q2[0]) + __shfl_xor(b2 ? q2[0] : q2[1], 4, kWave);
-    dot += __shfl_xor(dot, 2, kWave);
-    dot += __shfl_xor(dot, 1, kWave);
+    dot += dr_dpp<0x4E>(dot);      // lane ^ 2
+    dot += dr_dpp<0xB1>(dot);      // lane ^ 1
     const float coef = beta * (vr - dot * rden);      // beta_i (v_i[r] - v_bar_i[r])
     float upd[NPL] = {};
 #pragma unroll
