@@ -334,7 +334,8 @@ armt_status armt_lm_head_static(const armt_config *cfg, const void *hidden, int6
 /* ---- process-wide benchmarking and debugging knobs (not part of the re-entrant contract above, not thread safe) ---- */
 
 /* Force the tile configuration of the bf16 grouped GEMM for all later calls of this process (1: 128x128 tile, 4 waves;
- * 2: 64x128, 4 waves; 3: 64x64, 4 waves, for the plain fp32 store only (other epilogues run 2 instead);
+ * 2: 64x128, 4 waves; 3: 64x64, 4 waves, for the plain fp32 store only, and 4: 32x128, 4 waves, for the feature-map
+ * epilogue of the W_Q projection only (other epilogues run 2 instead);
  * 5: 256x256, 16 waves; 6: as 1; 5 and 6 address the tile copies by scalar base + lane offset
  * where the shape allows; anything else below 100: choose by shape and tile count, the default).  config = 100 *
  * switches + tile configuration (or + 99 for the default choice) additionally turns fusions off, for A/B timing:

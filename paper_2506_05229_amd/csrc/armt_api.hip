@@ -951,7 +951,7 @@ int32_t armt_set_gemm_tile_config(int32_t config) {
   const int32_t old = g_gemm_tile_config;
   g_gemm_dbg = config >= 100 ? config / 100 : 0;
   if (config >= 100) config %= 100;
-  g_gemm_tile_config = (config == 1 || config == 2 || config == 3 || config == 5 || config == 6) ? config : -1;
+  g_gemm_tile_config = (config >= 1 && config <= 6) ? config : -1;
   return old;
 }
 

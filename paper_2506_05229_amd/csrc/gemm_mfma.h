@@ -650,6 +650,9 @@ inline int mfma_pick_config(const GemmShape& s, int g, int force_cfg) {
   // a few rows against wide weights (W_K | W_V on the memory rows): the launch streams the weights once and is bound
   // by how many bytes a CU has in flight, so narrow tiles that give every CU two workgroups
   if (s.M <= 64 && s.epi == EPI_STORE_F32 && (long)g * ((s.N + 127) / 128) < 512) return 3;
+  // W_Q of the read with the feature map as its epilogue: one d_mem-wide tile column, so the workgroups are the M-tiles;
+  // 32-row tiles put two or more workgroups on a CU, whose waves then fill each other's waits
+  if (s.epi == EPI_DPFP_READ && s.M >= 64 && (long)g * ((s.M + 63) / 64) < 1024) return 4;
   if (s.M < 96 || s.N < 96) return 2;
   const int tm = (s.M > 256 && s.M % 256 == 16) ? s.M / 256 : (s.M + 255) / 256;
   const int bn_out = (s.epi == EPI_SWIGLU) ? 128 : 256;
@@ -669,6 +672,9 @@ inline hipError_t launch_gemm_mfma_epi(const GemmGroup* table, int first, int g,
     case 1: return launch_mfma_cfg<128, 128, 2, 2, EPI>(table, first, g, s, st);
     case 3:   // 64 x 64: only instantiated for the plain fp32 store
       if constexpr (EPI == EPI_STORE_F32) return launch_mfma_cfg<64, 64, 2, 2, EPI>(table, first, g, s, st);
+      break;
+    case 4:   // 32 x 128, waves side by side: only instantiated for the feature-map epilogue of the W_Q projection
+      if constexpr (EPI == EPI_DPFP_READ) return launch_mfma_cfg<32, 128, 1, 4, EPI>(table, first, g, s, st);
       break;
     case 5:   // 256 x 256, 16 waves, copies addressed by scalar base + lane offset where the shape allows
       if (mfma_regular_shape<256, 256, EPI>(s)) return launch_mfma_cfg<256, 256, 4, 4, EPI, true>(table, first, g, s, st);

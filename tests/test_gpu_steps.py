@@ -31,7 +31,7 @@ def _rand(rng, shape, std, bf16):
     (5, 300, 2112, 192),      # N = d_mem + d of the update projections, several tiles and a tail
     (16, 130, 96, 64),        # group = number of layers
 ])
-@pytest.mark.parametrize("tile_cfg", [-1, 1, 2, 3, 5, 6])
+@pytest.mark.parametrize("tile_cfg", [-1, 1, 2, 3, 4, 5, 6])
 def test_grouped_gemm(dtype, g, M, N, K, tile_cfg):
     import paper_2506_05229_amd as P
     if dtype == "f32" and tile_cfg != -1:
