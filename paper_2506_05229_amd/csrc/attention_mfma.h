@@ -20,7 +20,7 @@ namespace armt {
 
 constexpr int AT_KT = 64;      // keys per tile
 constexpr int AT_QT = 32;      // query rows per wave / workgroup
-constexpr float AT_LAZY = 8.f; // log2 of the largest unnormalised probability the online softmax lets through
+constexpr float AT_LAZY_SUM = 4096.f;  // the online softmax lets a lane's 16 unnormalised probabilities of a half-tile add up to this
 
 // Which key of a 64-key tile sits in LDS row `row` of the K tile.  The 32 x 32 MFMA leaves S^T[row][query] of a lane in
 // registers r = 0..15 <-> rows 8 (r / 4) + 4 half + r % 4, and registers 8 ss .. 8 ss + 7 become the lane's B operand
@@ -166,15 +166,32 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(DH == 64 ? 
           if (key > qi) sc[r] = -INFINITY;
         }
       }
-      // online softmax: every lane owns one query column; 16 of the half's keys here, the other 16 in lane ^ 32
-      float mx = sc[0];
+      // online softmax: every lane owns one query column; 16 of the half's keys here, the other 16 in lane ^ 32.
+      // m is the REFERENCE of the exponents, not the running maximum (the result does not depend on it: numerator and
+      // denominator carry the same factor).  The common case does not look for the maximum at all: the probabilities
+      // are formed against the current reference, and only if some lane's 16 of them add up to more than AT_LAZY_SUM = 2^12
+      // (always so in a query's first half-tile, where the reference is still -inf and the sum comes out as inf or NaN)
+      // the wave takes the maximum, moves the reference, rescales O and the sums, and forms them again.
+      float pr[16], hs0, hs1;
+      auto form = [&](float mc) __attribute__((always_inline)) {
+        hs0 = hs1 = 0.f;
 #pragma unroll
-      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[r]);
-      mx = at_max_halves(mx);
-      // m is the reference maximum of the exponents, not the running maximum: it only moves when some score of the
-      // wave exceeds it by more than 2^AT_LAZY, so that most tiles skip rescaling O and the sum (the result does not
-      // depend on the reference: numerator and denominator carry the same factor; p stays below 2^AT_LAZY)
-      if (__builtin_amdgcn_ballot_w64(mx * scale_log2e > fmaf(m, scale_log2e, AT_LAZY)) != 0) {
+        for (int r = 0; r < 16; r += 2) {
+          pr[r] = __builtin_amdgcn_exp2f(fmaf(sc[r], scale_log2e, -mc));
+          pr[r + 1] = __builtin_amdgcn_exp2f(fmaf(sc[r + 1], scale_log2e, -mc));
+          // two running sums in plain fp32 adds.  (A dot instruction on the packed pair, v_dot2c_f32_bf16, would halve
+          // the count, but the sums it produced shifted every gradient of the backward pass by 2 - 3 %: the backward pass
+          // takes P from this row sum and cancels a common component of dP against D = dO.O, which amplifies any bias.)
+          if (r & 2) hs1 += pr[r] + pr[r + 1];
+          else hs0 += pr[r] + pr[r + 1];
+        }
+      };
+      form(m * scale_log2e);
+      if (__builtin_amdgcn_ballot_w64(!(hs0 + hs1 <= AT_LAZY_SUM)) != 0) {
+        float mx = sc[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[r]);
+        mx = at_max_halves(mx);
         const float m_new = fmaxf(m, mx);
         const float alpha = __builtin_amdgcn_exp2f((m - m_new) * scale_log2e);
         m = m_new;
@@ -184,22 +201,17 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(DH == 64 ? 
         for (int t = 0; t < OT; ++t)
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[t][r] *= alpha;
+        form(m * scale_log2e);
       }
-      const float mc = m * scale_log2e;
+      lsum += hs0;
+      lsum1 += hs1;
       // P^T as the B operand of the second product: two 16-key k-steps, packed to bf16 in pairs
       bf16x8 pf[2];
 #pragma unroll
       for (int r = 0; r < 16; r += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[r], scale_log2e, -mc));
-        const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[r + 1], scale_log2e, -mc));
         typedef float f32x2 __attribute__((ext_vector_type(2)));
         typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-        const bf16x2 pk = __builtin_convertvector(f32x2{p0, p1}, bf16x2);
-        // two running sums in plain fp32 adds.  (A dot instruction on the packed pair, v_dot2c_f32_bf16, would halve the
-        // count, but the sums it produced shifted every gradient of the backward pass by 2 - 3 %: the backward pass takes
-        // P from this row sum and cancels a common component of dP against D = dO.O, which amplifies any bias of it.)
-        if (r & 2) lsum1 += p0 + p1;
-        else lsum += p0 + p1;
+        const bf16x2 pk = __builtin_convertvector(f32x2{pr[r], pr[r + 1]}, bf16x2);
         pf[r >> 3][r & 7] = pk[0];
         pf[r >> 3][(r & 7) + 1] = pk[1];
       }
