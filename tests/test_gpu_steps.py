@@ -90,6 +90,47 @@ def test_segment_attention(dtype, kw):
             assert np.abs(got[i] - want).max() <= 2e-5
 
 
+@pytest.mark.parametrize("kind", ["growing", "huge", "tiny_then_huge"])
+def test_segment_attention_moving_maximum(kind):
+    """The matrix-core attention kernel keeps a reference exponent per query that it only moves when the unnormalised
+    probabilities of a half-tile get large.  Inputs that make it move all the time, or by a lot: keys whose scores grow
+    along the sequence (every later tile beats the reference), scores of magnitude 10^2 - 10^3 (exp2 of the difference
+    overflows unless the reference moves first), and a sequence whose first keys are tiny and whose later ones are huge."""
+    import paper_2506_05229_amd as P
+    kw = dict(n_heads=4, n_kv_heads=2, head_dim=64, d_model=256, d_ff=512, seg_len=400, n_mem=16, d_mem=32)
+    shape = S.get_shape("tiny").replace(dtype="bf16", n_layers=2, rope_theta=1000.0, **kw)
+    g, T, H, Hkv, dh = 2, shape.T, shape.n_heads, shape.n_kv_heads, shape.head_dim
+    rng = np.random.default_rng(7)
+    qkv = rng.standard_normal((g, T, (H + 2 * Hkv) * dh)).astype(np.float32)
+    ramp = np.ones(T, np.float32)
+    if kind == "growing":
+        ramp = 1.0 + np.arange(T, dtype=np.float32) / 16.0           # |k_j| grows 26-fold over the cell
+    elif kind == "huge":
+        ramp = np.full(T, 12.0, np.float32)                             # scores of a few hundred
+        qkv[:, :, :H * dh] *= 4.0
+    else:
+        ramp = np.where(np.arange(T) < 200, 1e-3, 30.0).astype(np.float32)
+    qkv[:, :, H * dh:(H + Hkv) * dh] *= ramp[None, :, None]
+    qkv = S.round_to_bf16(qkv)
+    steps = P.ArmtSteps(shape)
+    out = steps.segment_attention(_dev(qkv, steps.act_dtype))
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    assert np.isfinite(got).all()
+    for i in range(g):
+        q = qkv[i, :, :H * dh].reshape(T, H, dh).astype(np.float64)
+        k = qkv[i, :, H * dh:(H + Hkv) * dh].reshape(T, Hkv, dh).astype(np.float64)
+        v = qkv[i, :, (H + Hkv) * dh:].reshape(T, Hkv, dh).astype(np.float64)
+        # the entry point rotates q and k and rounds them to bf16 again before the kernel under test sees them; with scores
+        # of 10^2 - 10^3 that rounding alone changes the softmax, so the oracle gets the same rotated, rounded operands
+        qr = S.round_to_bf16(O.rope(q, shape.rope_theta).astype(np.float32)).astype(np.float64)
+        kr = S.round_to_bf16(O.rope(k, shape.rope_theta).astype(np.float32)).astype(np.float64)
+        want = O.causal_gqa_attention(qr, kr, v).reshape(T, H * dh)
+        err = rel_fro(got[i], want)
+        print(f"attention, {kind}: rel. Frobenius {err:.3e}", flush=True)
+        assert err <= 1e-2, (kind, err)
+
+
 # ---------------------------------------------------------------- associative read / update (Eq. 3-6)
 def _memory_problem(shape, g, rng, bf):
     d, dm, P_, m, T = shape.d_model, shape.d_mem, shape.phi, shape.n_mem, shape.T
