@@ -5,9 +5,9 @@ The float64 oracle cannot run 131072 tokens inside a test (272 TFLOP), so at LLa
         per segment, and the final memory state): the error-over-segments curve of the paper's Section 4.4;
   (ii)  against stored oracle samples over all 32 segments of the 32768-token workload (tests/golden, written by a
         script that calls only the oracle);
-  (iii) by a teacher-forced late window at 131072 tokens: the GPU exports (A, z) after segment 125, the oracle runs
+  (iii) by teacher-forced windows at 131072 tokens: the GPU exports (A, z) after segment 125, the oracle runs
         segments 126 and 127 from that state, and hidden states and final memory state must agree -- per-segment
-        correctness late in the sequence, with the oracle as the base;
+        correctness late in the sequence, with the oracle as the base; the same for the single segments 32, 64 and 96;
   (iv)  through properties that hold at any size: diagonal and sequential order give bit-identical results, and
         splitting the sequence with the exported memory state reproduces the full run bit for bit.
 By the dependency rule of Section 3.1 a prefix of a long run equals the run on that prefix, so (i) and (ii) are also
@@ -144,6 +144,22 @@ def _late_window(model, shape, layers, mem_emb, x, xd, hd, Ad, zd, k, what):
     _state_errors(Ad, zd, oA, oz, f"{what} final state (teacher-forced from segment {k})")
 
 
+def _mid_window(model, shape, layers, mem_emb, x, xd, hd, k, what):
+    """Teacher-forced single segment k in the middle of a run: the oracle computes it from the GPU's state after segment
+    k - 1; hidden states of the segment and the state after it (GPU: the run on the prefix [0, k + 1)) must agree."""
+    Sg = shape.seg_len
+    _, A0, z0 = model.forward(xd[:k * Sg].contiguous(), diagonal=True)
+    _, A1, z1 = model.forward(xd[:(k + 1) * Sg].contiguous(), diagonal=True)
+    torch.cuda.synchronize()
+    stats = []
+    oh, oA, oz = O.armt_forward_sequential(shape, layers, mem_emb, x[k * Sg:(k + 1) * Sg],
+                                           A_in=A0.cpu().numpy().astype(np.float64), z_in=z0.cpu().numpy().astype(np.float64),
+                                           stats=stats)
+    assert all(e["min_den"] > 0.0 and e["min_zf"] > 0.0 for e in stats), "ill-conditioned in the middle of the sequence"
+    assert_bf16_close(hd[k * Sg:(k + 1) * Sg].float().cpu().numpy(), oh, BF16_REL, f"{what} segment {k} (teacher-forced)")
+    _state_errors(A1, z1, oA, oz, f"{what} state after segment {k} (teacher-forced)")
+
+
 @pytest.mark.timeout(900)
 def test_1b_131072_tokens_bench_configuration():
     shape = S.get_shape("1b_128k")
@@ -179,6 +195,9 @@ def test_1b_131072_tokens_bench_configuration():
     del h1, h2
     # (iv) teacher-forced late window: segments 126 and 127 by the oracle from the GPU's state after segment 125
     _late_window(model, shape, layers, mem_emb, x, xd, hd, Ad, zd, shape.n_segments - 2, "1b_128k")
+    # (v) and single teacher-forced segments on the way there: per-segment correctness at a quarter, half and three quarters
+    for k in (32, 64, 96):
+        _mid_window(model, shape, layers, mem_emb, x, xd, hd, k, "1b_128k")
 
 
 @pytest.mark.timeout(900)
