@@ -258,18 +258,22 @@ def test_segment_sweep_full_length_is_stationary(name):
 
 
 @pytest.mark.timeout(900)
-def test_3b_late_window_against_oracle():
-    """The 3B shape (28 layers) late in its sequence: 12 segments on the GPU, the last two by the oracle from the GPU's
-    memory state after segment 9."""
+@pytest.mark.parametrize("n", [12, 128])
+def test_3b_late_window_against_oracle(n):
+    """The 3B shape (28 layers) late in its sequence: n segments on the GPU (128: the whole 131072-token workload), the
+    last two by the oracle from the GPU's memory state after segment n - 3 (two segments of this shape are 11 TFLOP in
+    float64, about half a minute on the machine's cores)."""
     shape = S.get_shape("3b_128k")
     model, layers, mem_emb = _model(shape)
-    n = 12
     x = S.make_embeddings(shape, seed=0, n_tokens=n * shape.seg_len)
     xd = model.embed(x)
     hd, Ad, zd = model.forward(xd, diagonal=True)
     torch.cuda.synchronize()
     assert torch.isfinite(hd.float()).all()
-    _late_window(model, shape.replace(n_tokens=n * shape.seg_len), layers, mem_emb, x, xd, hd, Ad, zd, n - 2, "3b, 12 segments")
+    rms = hd.float().reshape(n, -1).pow(2).mean(dim=1).sqrt().cpu().numpy()
+    print(f"3b, {n} segments: hidden rms per segment min {rms.min():.4f} max {rms.max():.4f}", flush=True)
+    assert np.abs(rms / rms[0] - 1.0).max() <= 0.1
+    _late_window(model, shape.replace(n_tokens=n * shape.seg_len), layers, mem_emb, x, xd, hd, Ad, zd, n - 2, f"3b, {n} segments")
 
 
 @pytest.mark.timeout(900)
