@@ -206,8 +206,12 @@ def test_1b_131072_tokens_bench_configuration():
 def test_other_shapes_prefix_against_oracle(name, n_seg_gpu):
     """Segment sweep (512 / 2048 + 16 memory tokens), the 3B shape (head_dim 128, 3 query heads per KV head) and
     the shape of the paper's timing tables (4096 + 128 memory tokens), the 160M model (no head grouping):
-    a few segments on the GPU, the first two checked against the oracle, diagonal == sequential."""
+    a few segments on the GPU, the first two checked against the oracle, diagonal == sequential.
+    (The 4096 + 128 shape runs 8 of its 16 layers here: two of its 4224-row segments cost the float64 oracle a minute
+    per 8 layers, and what the case is for -- 128 memory tokens, 4224-row cells -- does not depend on the depth.)"""
     shape = S.get_shape(name)
+    if name == "1b_128k_s4096_m128":
+        shape = shape.replace(n_layers=8)
     model, layers, mem_emb = _model(shape)
     x = S.make_embeddings(shape, seed=0, n_tokens=n_seg_gpu * shape.seg_len)
     xd = model.embed(x)
