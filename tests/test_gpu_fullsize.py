@@ -208,10 +208,11 @@ def test_other_shapes_prefix_against_oracle(name, n_seg_gpu):
     the shape of the paper's timing tables (4096 + 128 memory tokens), the 160M model (no head grouping):
     a few segments on the GPU, the first two checked against the oracle, diagonal == sequential.
     (The 4096 + 128 shape runs 8 of its 16 layers here: two of its 4224-row segments cost the float64 oracle a minute
-    per 8 layers, and what the case is for -- 128 memory tokens, 4224-row cells -- does not depend on the depth.)"""
+    per 8 layers, and what the case is for -- 128 memory tokens, 4224-row cells -- does not depend on the depth.  At 8
+    layers the search allows the key scale 2^-8, where gamma reaches -0.4: the chunked delta rule is live.)"""
     shape = S.get_shape(name)
     if name == "1b_128k_s4096_m128":
-        shape = shape.replace(n_layers=8)
+        shape = shape.replace(n_layers=8, mem_k_scale=2.0 ** -8)
     model, layers, mem_emb = _model(shape)
     x = S.make_embeddings(shape, seed=0, n_tokens=n_seg_gpu * shape.seg_len)
     xd = model.embed(x)
