@@ -61,12 +61,17 @@ __global__ __launch_bounds__(256) void v_transpose_kernel(const bf16* __restrict
 }
 
 // QKV: [L][T][(H + 2 Hkv) dh] with q, k already rotated; Vt as above; Out: [L][T][H dh]; lse2: optional, see the end.
-// grid: (ceil(T / (32 NQ)), Hkv, g), block: NQ * GROUP * 64 with GROUP = H / Hkv.
+// grid: 1-D, 8 * ceil(Hkv g / 8) * nqt workgroups with nqt = ceil(T / (32 NQ)); block: NQ * GROUP * 64 with GROUP = H / Hkv.
+// Workgroup b belongs to XCD b % 8 (the hardware deals consecutive workgroups round the 8 XCDs).  A (cell, KV head)
+// pair stays on ONE XCD, so its K / V tiles are fetched into one L2 only, and inside an XCD the workgroups are ordered
+// by their length over ALL pairs, longest (latest query rows) first: a workgroup of the last row tile runs 2 nqt / NQ
+// times as long as one of the first, and in a per-pair order the long workgroups of the last pairs would start when
+// most of the chip has already run dry.
 template <int DH>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(DH == 64 ? 4 : 3))) void attention_mfma_kernel(const bf16* __restrict__ QKV, const bf16* __restrict__ Vt,
                                                              bf16* __restrict__ Out, int first, int Trows, int Tp,
                                                              int H, int Hkv, int nq, float scale_log2e,
-                                                             float* __restrict__ lse2) {
+                                                             float* __restrict__ lse2, int nqt, int npairs) {
   // a K tile is DH / 64 sub-tiles [64 keys][64 dims] with 128-byte rows
   constexpr int K_BYTES = AT_KT * DH * 2;
   constexpr int V_BYTES = DH * AT_KT * 2;          // V^T tile: [DH dims][64 keys], 128-byte rows
@@ -76,9 +81,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(DH == 64 ? 
   constexpr int OT = DH / 32;                      // 32-row tiles of O^T
   extern __shared__ __align__(16) unsigned char smem[];   // [2][STAGE]
 
-  const int nqt = gridDim.x;
-  const int qt = nqt - 1 - blockIdx.x;             // long (late) query tiles first
-  const int kvh = blockIdx.y, l = first + blockIdx.z;
+  const int ppx = (npairs + 7) >> 3;               // pairs per XCD
+  const int xj = blockIdx.x >> 3;                  // index inside the XCD
+  const int qt = nqt - 1 - xj / ppx;               // long (late) query tiles first
+  const int pair = (xj % ppx) * 8 + (blockIdx.x & 7);
+  if (pair >= npairs) return;                      // padding of the last XCD round (whole workgroup)
+  const int kvh = pair % Hkv, l = first + pair / Hkv;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nw = blockDim.x >> 6, group = H / Hkv;
@@ -101,24 +109,43 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(DH == 64 ? 
     for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const bf16x8*)(qp + ks * 16);
   }
 
-  // ---- tile copies: slab = 8 rows x 128 bytes; lane i fills row i/8, physical chunk i%8
+  // ---- tile copies: slab = 8 rows x 128 bytes; lane i fills row i/8, physical chunk i%8.
+  // A copy is addressed as scalar base + one 32-bit lane offset: the LDS row of slab sl is 8 (sl % 8) + R, whose key
+  // (see at_key_of_row) splits into a part of R alone and a part of the slab alone, and whose swizzle depends on the
+  // slab only through its parity (bit 6 of the byte offset).  Issuing a copy then costs scalar instructions and one
+  // vector XOR instead of a dozen 64-bit vector operations per copy, which the SIMD would have to fit between the
+  // matrix instructions of its other waves.  Only the K rows of a cell's last tile (keys past T, clamped per lane) take the
+  // general form.
   const int R = lane >> 3, pc = lane & 7;
+  const unsigned chunk0 = (unsigned)((pc ^ mf_swz(R)) << 4);
+  const unsigned voffK = (unsigned)((R & 3) + ((R >> 2) << 3)) * (unsigned)ldq * 2u + chunk0;
+  const unsigned voffV = (unsigned)R * (unsigned)Tp * 2u + chunk0;
+  const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) void*)smem;
+  auto dma = [&](const char* base, unsigned voff, unsigned lds) {
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(lds) : "memory", "m0");
+  };
   auto issue_tile = [&](int kt, int buf) {
     typedef const __attribute__((address_space(1))) void* gptr_t;
     typedef __attribute__((address_space(3))) void* lptr_t;
     unsigned char* Ks = smem + buf * STAGE;
-    unsigned char* Vs = Ks + K_BYTES;
+    const unsigned ldsK = lds0 + buf * STAGE, ldsV = ldsK + K_BYTES;
     const int k0 = kt * AT_KT;
+    const bool whole = k0 + AT_KT <= Trows;          // wave-uniform: every key of the tile exists
     for (int sl = wave; sl < K_SLABS + V_SLABS; sl += nw) {
       if (sl < K_SLABS) {
-        const int sub = sl >> 3, row = (sl & 7) * 8 + R;               // row of the tile in LDS
-        const int key = min(k0 + at_key_of_row(row), Trows - 1);       // keys past T are masked by causality
-        const char* src = kbase + ((size_t)key * ldq + sub * 64 + ((pc ^ mf_swz(row)) << 3)) * 2;
-        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(Ks + sl * 1024), 16, 0, 0);
+        const int sub = sl >> 3, a = sl & 7;
+        if (whole) {
+          const int keyS = k0 + ((a & 1) << 2) + ((a >> 1) << 4);
+          dma(kbase + ((size_t)keyS * ldq + sub * 64) * 2, voffK ^ ((unsigned)(a & 1) << 6), ldsK + sl * 1024);
+        } else {
+          const int row = a * 8 + R;                                     // row of the tile in LDS
+          const int key = min(k0 + at_key_of_row(row), Trows - 1);       // keys past T are masked by causality
+          const char* src = kbase + ((size_t)key * ldq + sub * 64 + ((pc ^ mf_swz(row)) << 3)) * 2;
+          __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(Ks + sl * 1024), 16, 0, 0);
+        }
       } else {
-        const int vs = sl - K_SLABS, row = vs * 8 + R;                 // dim row of V^T
-        const char* src = vbase + ((size_t)row * Tp + k0 + ((pc ^ mf_swz(row)) << 3)) * 2;
-        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(Vs + vs * 1024), 16, 0, 0);
+        const int vs = sl - K_SLABS;                                     // dim rows 8 vs .. 8 vs + 7 of V^T
+        dma(vbase + ((size_t)vs * 8 * Tp + k0) * 2, voffV ^ ((unsigned)(vs & 1) << 6), ldsV + vs * 1024);
       }
     }
   };
@@ -270,11 +297,12 @@ inline hipError_t launch_attention_mfma(const bf16* QKV, bf16* Vt, bf16* Out, in
   }
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)dh);
   const int nq = group == 1 ? 4 : (group == 2 ? 2 : 1);       // row tiles per workgroup: at least 4 waves share the K / V tiles
-  const dim3 grid((Trows + nq * AT_QT - 1) / (nq * AT_QT), Hkv, g);
+  const int nqt = (Trows + nq * AT_QT - 1) / (nq * AT_QT), npairs = Hkv * g;
+  const dim3 grid(8 * ((npairs + 7) / 8) * nqt);
   if (dh == 64)
-    attention_mfma_kernel<64><<<grid, nq * group * 64, 2 * (64 * 64 * 2 * 2), st>>>(QKV, Vt, Out, first, Trows, Tp, H, Hkv, nq, scale_log2e, lse2);
+    attention_mfma_kernel<64><<<grid, nq * group * 64, 2 * (64 * 64 * 2 * 2), st>>>(QKV, Vt, Out, first, Trows, Tp, H, Hkv, nq, scale_log2e, lse2, nqt, npairs);
   else
-    attention_mfma_kernel<128><<<grid, nq * group * 64, 2 * (64 * 128 * 2 * 2), st>>>(QKV, Vt, Out, first, Trows, Tp, H, Hkv, nq, scale_log2e, lse2);
+    attention_mfma_kernel<128><<<grid, nq * group * 64, 2 * (64 * 128 * 2 * 2), st>>>(QKV, Vt, Out, first, Trows, Tp, H, Hkv, nq, scale_log2e, lse2, nqt, npairs);
   return hipGetLastError();
 }
 
