@@ -67,6 +67,16 @@ def test_grouped_gemm(dtype, g, M, N, K, tile_cfg):
     # one query head per KV head: four row tiles per workgroup, the last workgroup only partly inside the cell
     ("bf16", dict(n_heads=4, n_kv_heads=4, head_dim=64, d_model=256, d_ff=512, seg_len=200, n_mem=16, d_mem=32)),
     ("bf16", dict(n_heads=2, n_kv_heads=2, head_dim=128, d_model=256, d_ff=512, seg_len=1024, n_mem=16, d_mem=32)),
+    # the software-pipelined kernel (head_dim 64, 4 or 8 query heads per KV head) at its edges: a cell of one half-tile
+    # (T = 20: only the masked last step), of two (T = 33 + 16) and three half-tiles (T = 80 + 16, ragged last tile), an
+    # even and an odd number of half-tiles over several tiles, eight waves per workgroup
+    ("bf16", dict(n_heads=4, n_kv_heads=1, head_dim=64, d_model=256, d_ff=512, seg_len=4, n_mem=16, d_mem=32)),
+    ("bf16", dict(n_heads=4, n_kv_heads=1, head_dim=64, d_model=256, d_ff=512, seg_len=33, n_mem=16, d_mem=32)),
+    ("bf16", dict(n_heads=8, n_kv_heads=2, head_dim=64, d_model=512, d_ff=512, seg_len=80, n_mem=16, d_mem=32)),
+    ("bf16", dict(n_heads=8, n_kv_heads=2, head_dim=64, d_model=512, d_ff=512, seg_len=240, n_mem=16, d_mem=32)),
+    ("bf16", dict(n_heads=4, n_kv_heads=1, head_dim=64, d_model=256, d_ff=512, seg_len=300, n_mem=16, d_mem=32)),
+    ("bf16", dict(n_heads=8, n_kv_heads=1, head_dim=64, d_model=512, d_ff=512, seg_len=333, n_mem=16, d_mem=32)),
+    ("bf16", dict(n_heads=16, n_kv_heads=2, head_dim=64, d_model=1024, d_ff=512, seg_len=1024, n_mem=16, d_mem=32)),
 ])
 def test_segment_attention(dtype, kw):
     import paper_2506_05229_amd as P
@@ -86,18 +96,22 @@ def test_segment_attention(dtype, kw):
         want = O.causal_gqa_attention(O.rope(q, shape.rope_theta), O.rope(k, shape.rope_theta), v).reshape(T, H * dh)
         if bf:
             assert rel_fro(got[i], want) <= 1e-2, rel_fro(got[i], want)
+            # per query row as well: a wrong half-tile of one row tile hides in the norm over the cell
+            row_err = np.linalg.norm(got[i] - want, axis=1) / np.linalg.norm(want, axis=1)
+            assert row_err.max() <= 3e-2, (int(row_err.argmax()), float(row_err.max()))
         else:
             assert np.abs(got[i] - want).max() <= 2e-5
 
 
+@pytest.mark.parametrize("n_kv_heads", [2, 1])     # two / four query heads per KV head: the two kernels for head_dim 64
 @pytest.mark.parametrize("kind", ["growing", "huge", "tiny_then_huge"])
-def test_segment_attention_moving_maximum(kind):
+def test_segment_attention_moving_maximum(kind, n_kv_heads):
     """The matrix-core attention kernel keeps a reference exponent per query that it only moves when the unnormalised
     probabilities of a half-tile get large.  Inputs that make it move all the time, or by a lot: keys whose scores grow
     along the sequence (every later tile beats the reference), scores of magnitude 10^2 - 10^3 (exp2 of the difference
     overflows unless the reference moves first), and a sequence whose first keys are tiny and whose later ones are huge."""
     import paper_2506_05229_amd as P
-    kw = dict(n_heads=4, n_kv_heads=2, head_dim=64, d_model=256, d_ff=512, seg_len=400, n_mem=16, d_mem=32)
+    kw = dict(n_heads=4, n_kv_heads=n_kv_heads, head_dim=64, d_model=256, d_ff=512, seg_len=400, n_mem=16, d_mem=32)
     shape = S.get_shape("tiny").replace(dtype="bf16", n_layers=2, rope_theta=1000.0, **kw)
     g, T, H, Hkv, dh = 2, shape.T, shape.n_heads, shape.n_kv_heads, shape.head_dim
     rng = np.random.default_rng(7)
