@@ -32,7 +32,9 @@ def test_random_configuration_backward(case):
         stats = []
         for x in xs:
             O.armt_forward_sequential(shape, layers, mem_emb, x, stats=stats)
-        if not stats or (all(r["min_den"] > 0.0 for r in stats) and max(r["max_abs_read"] for r in stats) < 2.0):
+        # z . phi(q) = 0 exactly is as good as positive: with few features (nu = 1, d_mem of a dozen) a query's active
+        # features may share no support with any stored key, and its read is 0 / eps = 0 on both sides
+        if not stats or (all(r["min_den"] >= 0.0 for r in stats) and max(r["max_abs_read"] for r in stats) < 2.0):
             break
     else:
         pytest.skip("no well-conditioned key scale found")
