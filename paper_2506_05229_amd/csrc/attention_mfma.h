@@ -195,10 +195,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(DH == 64 ? 
       }
       // online softmax: every lane owns one query column; 16 of the half's keys here, the other 16 in lane ^ 32.
       // m is the REFERENCE of the exponents, not the running maximum (the result does not depend on it: numerator and
-      // denominator carry the same factor).  The common case does not look for the maximum at all: the probabilities
-      // are formed against the current reference, and only if some lane's 16 of them add up to more than AT_LAZY_SUM = 2^12
-      // (always so in a query's first half-tile, where the reference is still -inf and the sum comes out as inf or NaN)
-      // the wave takes the maximum, moves the reference, rescales O and the sums, and forms them again.
+      // denominator carry the same factor).  The first half-tile sets it to that half's maximum; after that the common
+      // case does not look for the maximum at all: the probabilities are formed against the current reference, and only
+      // if some lane's 16 of them add up to more than AT_LAZY_SUM = 2^12 (or the sum is not finite) the wave takes the
+      // maximum, moves the reference, rescales O and the sums, and forms them again.
       float pr[16], hs0, hs1;
       auto form = [&](float mc) __attribute__((always_inline)) {
         hs0 = hs1 = 0.f;
@@ -213,6 +213,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(DH == 64 ? 
           else hs0 += pr[r] + pr[r + 1];
         }
       };
+      if (jj == 0 && kt == 0) {         // a query's first half-tile: start the reference at its maximum (wave-uniform)
+        float mx = sc[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[r]);
+        m = at_max_halves(mx);
+      }
       form(m * scale_log2e);
       if (__builtin_amdgcn_ballot_w64(!(hs0 + hs1 <= AT_LAZY_SUM)) != 0) {
         float mx = sc[0];
