@@ -57,12 +57,13 @@ __global__ __launch_bounds__(256) void attention_dvec_kernel(const bf16* __restr
 // LSE2 (log2 domain), Dv: [cells][H][T]; dQKV: gradient rows, q columns written here.
 // As in the forward kernel a workgroup takes NQ consecutive 32-row tiles (NQ > 1 when a KV head has fewer than four
 // query heads): wave w handles query head kv * GROUP + w % GROUP and row tile w / GROUP.
-// grid: (ceil(T / (32 NQ)), Hkv, g), block: NQ * GROUP * 64; LDS: 2 stages of K, V, K^T tiles.
+// grid: 1-D, 8 * ceil(Hkv g / 8) * ceil(T / (32 NQ)) workgroups, block: NQ * GROUP * 64; LDS: 2 stages of K, V, K^T tiles.
 template <int DH>
 __global__ __launch_bounds__(512) void attention_bwd_dq_kernel(const bf16* __restrict__ QKV, const bf16* __restrict__ Kt,
                                                                const bf16* __restrict__ dO, const float* __restrict__ LSE2,
                                                                const float* __restrict__ Dv, bf16* __restrict__ dQKV,
-                                                               int first, int Trows, int Tp, int H, int Hkv, int nq, float scale) {
+                                                               int first, int Trows, int Tp, int H, int Hkv, int nq, float scale,
+                                                               int nqt, int npairs) {
   constexpr int K_BYTES = AT_KT * DH * 2;          // K and V tiles: DH / 64 sub-tiles [64 keys][64 dims], 128-byte rows
   constexpr int T_BYTES = DH * AT_KT * 2;          // K^T tile: [DH dims][64 keys]
   constexpr int STAGE = 2 * K_BYTES + T_BYTES;
@@ -70,9 +71,12 @@ __global__ __launch_bounds__(512) void attention_bwd_dq_kernel(const bf16* __res
   constexpr int KS = DH / 16, OT = DH / 32;
   extern __shared__ __align__(16) unsigned char smem[];   // [2][STAGE]
 
-  const int nqt = gridDim.x;
-  const int qt = nqt - 1 - blockIdx.x;
-  const int kvh = blockIdx.y, l = first + blockIdx.z;
+  // work order of the forward kernel: a (cell, KV head) pair stays on one XCD, longest row tiles first over all pairs
+  const int ppx = (npairs + 7) >> 3, xj = blockIdx.x >> 3;
+  const int qt = nqt - 1 - xj / ppx;
+  const int pair = (xj % ppx) * 8 + (blockIdx.x & 7);
+  if (pair >= npairs) return;
+  const int kvh = pair % Hkv, l = first + pair / Hkv;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nw = blockDim.x >> 6, group = H / Hkv;
@@ -213,21 +217,26 @@ __global__ __launch_bounds__(512) void attention_bwd_dq_kernel(const bf16* __res
 // as B operands) for the whole kernel and adds the contributions of all query heads of the KV group, one after the
 // other, in its registers: no reduction between waves or workgroups.  The eight waves share the tiles of the current
 // (query head, 64 query rows): Q and dO rows, Q^T and dO^T columns, the rows' log-sum-exp and D, double buffered in LDS.
-// grid: (ceil(T / 256), Hkv, g), block: 512; LDS: 2 stages of 4 tiles + 512 bytes.
+// grid: 1-D, 8 * ceil(Hkv g / 8) * ceil(T / 256) workgroups, block: 512; LDS: 2 stages of 4 tiles + 512 bytes.
 constexpr int DKV_WAVES = 8;
 template <int DH>
 __global__ __launch_bounds__(512) void attention_bwd_dkv_kernel(const bf16* __restrict__ QKV, const bf16* __restrict__ Qt,
                                                                 const bf16* __restrict__ dO, const bf16* __restrict__ dOt,
                                                                 const float* __restrict__ LSE2, const float* __restrict__ Dv,
                                                                 bf16* __restrict__ dQKV, int first, int Trows, int Tp, int H,
-                                                                int Hkv, float scale) {
+                                                                int Hkv, float scale, int npairs) {
   constexpr int Q_BYTES = 64 * DH * 2;             // one tile: 64 x DH or DH x 64 bf16
   constexpr int STAGE = 4 * Q_BYTES + 512;         // Q, dO, Q^T, dO^T, then lse[64], D[64]
   constexpr int Q_SLABS = Q_BYTES / 1024;
   constexpr int KS = DH / 16, OT = DH / 32;
   extern __shared__ __align__(16) unsigned char smem[];   // [2][STAGE]
 
-  const int kb = blockIdx.x, kvh = blockIdx.y, l = first + blockIdx.z;
+  // key block 0 meets every query row, the last one a few: longest first over all (cell, KV head) pairs, a pair on one XCD
+  const int ppx = (npairs + 7) >> 3, xj = blockIdx.x >> 3;
+  const int kb = xj / ppx;
+  const int pair = (xj % ppx) * 8 + (blockIdx.x & 7);
+  if (pair >= npairs) return;
+  const int kvh = pair % Hkv, l = first + pair / Hkv;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int group = H / Hkv;
@@ -397,23 +406,24 @@ inline hipError_t launch_attention_bwd_mfma(const bf16* QKV, const bf16* O, cons
   if (e != hipSuccess) return e;
   const float scale = 1.0f / sqrtf((float)dh);
   const int nq = group == 1 ? 4 : (group == 2 ? 2 : 1);       // row tiles per dQ workgroup, as in the forward kernel
-  const dim3 grid((Trows + 32 * nq - 1) / (32 * nq), Hkv, g), gkv((Trows + 32 * DKV_WAVES - 1) / (32 * DKV_WAVES), Hkv, g);
+  const int nqt = (Trows + 32 * nq - 1) / (32 * nq), nkb = (Trows + 32 * DKV_WAVES - 1) / (32 * DKV_WAVES), npairs = Hkv * g;
+  const dim3 grid(8 * ((npairs + 7) / 8) * nqt), gkv(8 * ((npairs + 7) / 8) * nkb);
   if (dh == 64) {
     attention_bwd_dq_kernel<64><<<grid, nq * group * 64, 2 * 3 * (64 * 64 * 2), st>>>(QKV, Kt, dO, LSE2, Dv, dQKV, first, Trows, Tp, H, Hkv,
-                                                                                   nq, scale);
+                                                                                   nq, scale, nqt, npairs);
     attention_bwd_dkv_kernel<64><<<gkv, 64 * DKV_WAVES, 2 * (4 * 64 * 64 * 2 + 512), st>>>(QKV, Qt, dO, Gt, LSE2, Dv, dQKV, first, Trows, Tp, H, Hkv,
-                                                                              scale);
+                                                                              scale, npairs);
   } else {
     hipError_t a = hipFuncSetAttribute((const void*)attention_bwd_dq_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        2 * 3 * (64 * 128 * 2));
     if (a != hipSuccess) return a;
     attention_bwd_dq_kernel<128><<<grid, nq * group * 64, 2 * 3 * (64 * 128 * 2), st>>>(QKV, Kt, dO, LSE2, Dv, dQKV, first, Trows, Tp, H,
-                                                                                     Hkv, nq, scale);
+                                                                                     Hkv, nq, scale, nqt, npairs);
     a = hipFuncSetAttribute((const void*)attention_bwd_dkv_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             2 * (4 * 64 * 128 * 2 + 512));
     if (a != hipSuccess) return a;
     attention_bwd_dkv_kernel<128><<<gkv, 64 * DKV_WAVES, 2 * (4 * 64 * 128 * 2 + 512), st>>>(QKV, Qt, dO, Gt, LSE2, Dv, dQKV, first, Trows, Tp, H,
-                                                                                Hkv, scale);
+                                                                                Hkv, scale, npairs);
   }
   return hipGetLastError();
 }
