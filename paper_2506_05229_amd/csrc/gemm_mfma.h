@@ -31,6 +31,7 @@ namespace armt {
 
 constexpr int MF_BK = 64;                 // k-tile (bf16 elements): 128 bytes per tile row
 constexpr int MF_ROW_BYTES = MF_BK * 2;
+constexpr int MF_CUS = 256;            // compute units of the chip: a round of one tile per unit
 constexpr int MF_NUM_CONFIGS = 7;         // tile configuration numbers of launch_gemm_mfma_epi lie below this
 
 // swizzle of the 16-byte chunk index inside a 128-byte tile row; depends on row bits 0..3 only
@@ -70,7 +71,7 @@ constexpr int mfma_tile_lds_bytes() {
 template <int BM, int BN, int WGM, int WGN, bool REG, int EPI, bool TAIL, int NS>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGroup* __restrict__ table, int first,
                                                                   GemmShape s, int tiles_m, int tiles_n,
-                                                                  int total_tiles) {
+                                                                  int total_tiles, int tile_begin) {
   constexpr int NW = WGM * WGN, BK = MF_BK;
   constexpr int WROWS = BM / WGM, WCOLS = BN / WGN;       // wave tile
   constexpr int TM = WROWS / 16, TN = WCOLS / 16;         // 16x16 MFMA tiles per wave
@@ -100,10 +101,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
     tl[2] = __builtin_readcyclecounter();
   }
 #endif
-  // XCD-aware tile order: workgroup b runs on XCD b % 8; give each XCD a contiguous range.
+  // XCD-aware tile order: workgroup b runs on XCD b % 8; give each XCD a contiguous range.  The launch covers the
+  // total_tiles tiles from tile_begin on of the order (group, N-tile, M-tile).
   const int per_xcd = (total_tiles + 7) >> 3;
-  const int lid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (lid >= total_tiles) return;
+  const int lid0 = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (lid0 >= total_tiles) return;
+  const int lid = tile_begin + lid0;
   const int per_group = tiles_m * tiles_n;
   const int grp = lid / per_group, rem = lid - grp * per_group;
   const int tn = rem / tiles_m, tm = rem - tn * tiles_m;    // M-tiles of one weight panel are adjacent
@@ -591,12 +594,26 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
 #endif
 }
 
+// Part of a launch's work, so that two tile sizes can share it: weight panels [begin, end) counted over the groups in
+// units of unit_cols output columns (units_per_group = N / unit_cols of them per group).  unit_cols = 0: everything.
+struct TileRange { int unit_cols = 0, units_per_group = 0, begin = 0, end = 0; };
+
 template <int BM, int BN, int WGM, int WGN, bool REG, int EPI, bool TAIL, int NS>
-inline hipError_t launch_mfma_tail(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st) {
+inline hipError_t launch_mfma_tail(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st,
+                                   const TileRange& rng) {
   constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   constexpr int LDS = mfma_tile_lds_bytes<BM, BN, WGM, EPI, TAIL, NS>() + (BM + 16) * 4;
   const int tiles_m = TAIL ? s.M / BM : (s.M + BM - 1) / BM, tiles_n = (s.N + BN_OUT - 1) / BN_OUT;
-  const int total = g * tiles_m * tiles_n;
+  const int all = g * tiles_m * tiles_n;
+  // a part of the launch's tiles, in units of whole weight panels (tiles_m M-tiles each) of this tile size
+  int begin = 0, total = all;
+  if (rng.unit_cols > 0) {
+    const int per_group = tiles_m * tiles_n, scale = rng.unit_cols / BN_OUT;    // this configuration's N-tiles per unit
+    const auto at = [&](int u) { return (u / rng.units_per_group) * per_group + (u % rng.units_per_group) * scale * tiles_m; };
+    begin = at(rng.begin);
+    total = (rng.end >= g * rng.units_per_group ? all : at(rng.end)) - begin;
+  }
+  if (total <= 0) return hipSuccess;
   const int grid = ((total + 7) / 8) * 8;
   auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, REG, EPI, TAIL, NS>;
   // raising the dynamic-LDS limit is a per-function, per-device, idempotent setting: done once per device (a second
@@ -615,11 +632,11 @@ inline hipError_t launch_mfma_tail(const GemmGroup* table, int first, int g, con
   if (s.tag == g_tl_kind && g_tl_countdown >= 0 && g_tl_countdown-- == 0) {
     GemmShape s_tl = s;
     s_tl.dbg |= 1 << 20;
-    kern<<<grid, WGM * WGN * 64, LDS, st>>>(table, first, s_tl, tiles_m, tiles_n, total);
+    kern<<<grid, WGM * WGN * 64, LDS, st>>>(table, first, s_tl, tiles_m, tiles_n, total, begin);
     return hipGetLastError();
   }
 #endif
-  kern<<<grid, WGM * WGN * 64, LDS, st>>>(table, first, s, tiles_m, tiles_n, total);
+  kern<<<grid, WGM * WGN * 64, LDS, st>>>(table, first, s, tiles_m, tiles_n, total, begin);
   return hipGetLastError();
 }
 
@@ -635,12 +652,13 @@ inline bool mfma_regular_shape(const GemmShape& s) {
 }
 
 template <int BM, int BN, int WGM, int WGN, int EPI, bool REG = false, int NS = 2>
-inline hipError_t launch_mfma_cfg(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st) {
+inline hipError_t launch_mfma_cfg(const GemmGroup* table, int first, int g, const GemmShape& s, hipStream_t st,
+                                  const TileRange& rng = TileRange()) {
   if constexpr (BN <= WGM * WGN * 32) {
     if (s.M > BM && s.M % BM == 16 && !(s.dbg & 32))
-      return launch_mfma_tail<BM, BN, WGM, WGN, REG, EPI, true, NS>(table, first, g, s, st);
+      return launch_mfma_tail<BM, BN, WGM, WGN, REG, EPI, true, NS>(table, first, g, s, st, rng);
   }
-  return launch_mfma_tail<BM, BN, WGM, WGN, REG, EPI, false, NS>(table, first, g, s, st);
+  return launch_mfma_tail<BM, BN, WGM, WGN, REG, EPI, false, NS>(table, first, g, s, st, rng);
 }
 
 // Big tiles move the fewest bytes per flop, but a launch needs about one tile per CU to use the chip: a single
@@ -677,7 +695,29 @@ inline hipError_t launch_gemm_mfma_epi(const GemmGroup* table, int first, int g,
       if constexpr (EPI == EPI_DPFP_READ) return launch_mfma_cfg<32, 128, 1, 4, EPI>(table, first, g, s, st);
       break;
     case 5:   // 256 x 256, 16 waves, copies addressed by scalar base + lane offset where the shape allows
-      if (mfma_regular_shape<256, 256, EPI>(s)) return launch_mfma_cfg<256, 256, 4, 4, EPI, true>(table, first, g, s, st);
+      if (mfma_regular_shape<256, 256, EPI>(s)) {
+        if constexpr (EPI != EPI_SWIGLU) {
+          // Whole rounds of the chip with 256 x 256 tiles; if what is left fills at most half of another round, it runs
+          // as 128 x 128 tiles (four times as many, two workgroups per CU: one short round instead of a long one
+          // that leaves most CUs idle).  Both tile sizes give the same bits (same order of the k-steps, row sums
+          // of squares at a fixed granularity), so where the cut falls does not show in the result.
+          const int tm = (s.M > 256 && s.M % 256 == 16) ? s.M / 256 : (s.M + 255) / 256, upg = s.N / 256;
+          const long tiles = (long)g * tm * upg;
+          const int rest_units = (int)((tiles % MF_CUS + tm - 1) / tm);   // weight panels of the last, partial round (rounded up)
+          const int units = g * upg;
+          if (force_cfg < 0 && tiles > MF_CUS && tiles % MF_CUS != 0 && tiles % MF_CUS <= MF_CUS / 2 && rest_units > 0 &&
+              mfma_regular_shape<128, 128, EPI>(s)) {
+            TileRange big, rest;
+            big.unit_cols = rest.unit_cols = 256;
+            big.units_per_group = rest.units_per_group = upg;
+            big.begin = 0; big.end = rest.begin = units - rest_units; rest.end = units;
+            hipError_t e = launch_mfma_cfg<256, 256, 4, 4, EPI, true>(table, first, g, s, st, big);
+            if (e != hipSuccess) return e;
+            return launch_mfma_cfg<128, 128, 2, 2, EPI, true>(table, first, g, s, st, rest);
+          }
+        }
+        return launch_mfma_cfg<256, 256, 4, 4, EPI, true>(table, first, g, s, st);
+      }
       return launch_mfma_cfg<256, 256, 4, 4, EPI>(table, first, g, s, st);
     case 6:   // as 1, copies addressed by scalar base + lane offset where the shape allows
       if (mfma_regular_shape<128, 128, EPI>(s)) return launch_mfma_cfg<128, 128, 2, 2, EPI, true>(table, first, g, s, st);

@@ -29,6 +29,11 @@ def _rand(rng, shape, std, bf16):
     (2, 1040, 512, 256),      # the real cell height: 4 full 256-row tiles and a 16-row tail
     (5, 300, 2112, 192),      # N = d_mem + d of the update projections, several tiles and a tail
     (16, 130, 96, 64),        # group = number of layers
+    # 256 x 256 tiles for whole rounds of the 256 CUs, the rest of the launch as 128 x 128 tiles: 9 x 4 x 8 = 288 tiles
+    # (a round and 32 tiles = one group), 7 x 4 x 12 = 336 (the cut falls inside a group), 66 x 1 x 4 = 264 (one M-tile)
+    (9, 1040, 2048, 128),
+    (7, 1040, 3072, 64),
+    (66, 256, 1024, 64),
 ])
 # tile configurations only exist for the bf16 MFMA kernel; -1 = the library's own choice
 @pytest.mark.parametrize("dtype,tile_cfg", [("f32", -1)] + [("bf16", c) for c in (-1, 1, 2, 3, 4, 5, 6)])
