@@ -204,21 +204,24 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_mfma_kernel(const GemmGrou
   auto dma = [&](const char* base, unsigned voff, unsigned lds) {
     asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(base), "s"(lds) : "memory", "m0");
   };
+  // the same copy from one 64-bit pointer per lane.  Written as an instruction like the one above: the compiler then
+  // does not count it among the outstanding memory operations, so the fence of a barrier does not wait for the
+  // copies of the younger k-tiles that are meant to stay in flight (the waits for the copies are explicit, below)
+  auto dma_ptr = [&](const char* src, unsigned lds) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds) : "memory", "m0");
+  };
   auto issue_tile = [&](int kt, int buf) {
-    typedef const __attribute__((address_space(1))) void* gptr_t;
-    typedef __attribute__((address_space(3))) void* lptr_t;
     const size_t ka = (size_t)kt * ROWB, kb = ka;
     if (KEEP_PTRS) {
-      unsigned char* As = smem + buf * A_BYTES;
-      unsigned char* Bs = smem + NS * A_BYTES + buf * B_BYTES;
+      const unsigned ldsA = lds0 + buf * A_BYTES, ldsB = lds0 + NS * A_BYTES + buf * B_BYTES;
 #pragma unroll
       for (int j = 0; j < A_DMA; ++j)
-        __builtin_amdgcn_global_load_lds((gptr_t)(ap[KEEP_PTRS ? j : 0] + ka), (lptr_t)(As + (wave + j * NW) * 1024), 16, 0, 0);
+        dma_ptr(ap[KEEP_PTRS ? j : 0] + ka, ldsA + (wave + j * NW) * 1024);
       if (TAIL && tail_blk && wave < 2)
-        __builtin_amdgcn_global_load_lds((gptr_t)(tp + ka), (lptr_t)(As + BM * MF_ROW_BYTES + wave * 1024), 16, 0, 0);
+        dma_ptr(tp + ka, ldsA + BM * MF_ROW_BYTES + wave * 1024);
 #pragma unroll
       for (int j = 0; j < B_DMA; ++j)
-        __builtin_amdgcn_global_load_lds((gptr_t)(bp[KEEP_PTRS ? j : 0] + kb), (lptr_t)(Bs + (wave + j * NW) * 1024), 16, 0, 0);
+        dma_ptr(bp[KEEP_PTRS ? j : 0] + kb, ldsB + (wave + j * NW) * 1024);
     } else {
       const unsigned As = lds0 + buf * A_BYTES, Bs = lds0 + NS * A_BYTES + buf * B_BYTES;
 #pragma unroll
@@ -689,10 +692,12 @@ inline hipError_t launch_gemm_mfma_epi(const GemmGroup* table, int first, int g,
   switch (cfg) {
     case 1: return launch_mfma_cfg<128, 128, 2, 2, EPI>(table, first, g, s, st);
     case 3:   // 64 x 64: only instantiated for the plain fp32 store
-      if constexpr (EPI == EPI_STORE_F32) return launch_mfma_cfg<64, 64, 2, 2, EPI>(table, first, g, s, st);
+      // four k-tiles in LDS: the loop of these small tiles is bound by the latency of a copy, not by its arithmetic
+      if constexpr (EPI == EPI_STORE_F32) return launch_mfma_cfg<64, 64, 2, 2, EPI, false, 4>(table, first, g, s, st);
       break;
     case 4:   // 32 x 128, waves side by side: only instantiated for the feature-map epilogue of the W_Q projection
-      if constexpr (EPI == EPI_DPFP_READ) return launch_mfma_cfg<32, 128, 1, 4, EPI>(table, first, g, s, st);
+      // three k-tiles in LDS (two workgroups still fit on a CU)
+      if constexpr (EPI == EPI_DPFP_READ) return launch_mfma_cfg<32, 128, 1, 4, EPI, false, 3>(table, first, g, s, st);
       break;
     case 5:   // 256 x 256, 16 waves, copies addressed by scalar base + lane offset where the shape allows
       if (mfma_regular_shape<256, 256, EPI>(s)) {
